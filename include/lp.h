@@ -1,0 +1,192 @@
+/*
+ * lp.h -- C ABI of the MI355X (gfx950) low-precision fixed-point forward library.
+ *
+ * The library runs the forward pass of the paper's low-precision layers
+ * (LPConvolution, LPInnerProduct, LPAct; Sec. 2 "Low-precision add-on for
+ * Caffe") on integer Qm.f codes, exactly: int8 MFMA products, int32 partial
+ * sums, int64 results.
+ *
+ * Notation (Sec. 2, footnote on Qm.f and the BD / AD parameters): a format is
+ * (n, m, f): n total bits, m integer bits INCLUDING the sign bit (BD), f
+ * fraction bits (AD), n = m + f.  A code q in [-2^(n-1), 2^(n-1)-1] stands for
+ * the real number q * 2^-f.
+ *
+ * General rules of this ABI
+ *   - Pointers named *_dev are device (HBM) pointers, *_host are host pointers.
+ *     The caller owns every buffer; the library allocates no device memory.
+ *   - Code storage: int8_t when n <= 8, int16_t when 9 <= n <= 16, sign-extended.
+ *   - Activations are NHWC, weights [Cout][R][S][Cin], FC inputs [M][K], FC
+ *     weights [Nout][K]: the contraction index is always contiguous.
+ *   - `stream` is a hipStream_t passed as void* (NULL = default stream).  Calls
+ *     only enqueue work and return, except lp_range / lp_range_acc, which wait
+ *     for the stream because they return a result on the host.
+ *   - Counters (zero_count_dev, sat_count_dev) are uint64 in device memory and
+ *     are ADDED to: the caller clears them when a fresh count is wanted.
+ *   - Every argument is validated before anything is launched; a call that
+ *     returns anything but LP_OK has launched nothing.  Errors are return codes
+ *     only.  Device pointers must be aligned to 16 bytes.
+ */
+#ifndef LP_H
+#define LP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct { int32_t n, m, f; } lp_qfmt; /* n == m + f, 1 <= m <= n, 2 <= n <= 16 */
+
+/* rounding_scheme of Sec. 2: deterministic (two tie rules offered, the paper
+ * names none) or stochastic (Sec. 2.4). */
+typedef enum {
+    LP_ROUND_NEAREST_AWAY = 0, /* halfway cases away from zero (default) */
+    LP_ROUND_NEAREST_EVEN = 1, /* halfway cases to the even code */
+    LP_ROUND_STOCHASTIC = 2    /* lp_quantize only; see lp_quantize */
+} lp_round;
+
+typedef enum {
+    LP_OK = 0,
+    LP_EINVAL = 1,       /* bad format, size, null or misaligned pointer */
+    LP_EUNSUPPORTED = 2, /* valid request outside what the kernels cover */
+    LP_EWORKSPACE = 3,   /* workspace / packed buffer too small */
+    LP_EDEVICE = 4       /* the HIP runtime reported an error */
+} lp_status;
+
+/* stride-s convolution with zero padding `pad` on all four sides;
+ * output is N x Ho x Wo x Cout, Ho = (H + 2*pad - R)/stride + 1. */
+typedef struct { int32_t N, H, W, Cin, Cout, R, S, stride, pad; } lp_conv_desc;
+
+const char *lp_status_string(lp_status s);
+
+/* Number of uint64 words of device scratch lp_range / lp_range_acc need. */
+#define LP_RANGE_WORKSPACE_WORDS 32
+
+/*
+ * lp_range -- layer-wise bit allocation from the dynamic range (Sec. 2.3
+ * "Layer-wise quantization").  With n fixed, a value is lost for m integer
+ * bits when |v| >= 2^(m-1).  Writes to *out_host the format with the smallest
+ * m in [1, n] whose lost share (lost / count) is <= loss_threshold (m = n if
+ * none); loss_threshold 0 places the point from max|v|.  NaN is never lost,
+ * +-Inf always.  lost_host (nullable) receives n+1 counts, lost_host[m] for
+ * m = 1..n (entry 0 unused).  workspace_dev: LP_RANGE_WORKSPACE_WORDS uint64.
+ * Synchronises the stream.  count == 0 yields m = 1.
+ */
+lp_status lp_range(const float *x_dev, size_t count, int n, double loss_threshold,
+                   lp_qfmt *out_host, uint64_t *lost_host, uint64_t *workspace_dev, void *stream);
+
+/*
+ * lp_range_acc -- the same rule for exact accumulators that stand for
+ * acc * 2^-f_acc (as lp_conv_fwd / lp_fc_fwd emit), after ReLU when relu != 0.
+ * Used to fix a layer's output format from a calibration batch (Sec. 2.1: the
+ * ranges are measured on a sample of inputs, then frozen).
+ */
+lp_status lp_range_acc(const int64_t *acc_dev, size_t count, int f_acc, int relu, int n,
+                       double loss_threshold, lp_qfmt *out_host, uint64_t *lost_host,
+                       uint64_t *workspace_dev, void *stream);
+
+/*
+ * lp_quantize -- the Qm.f quantizer of the low-precision layers (Sec. 2):
+ * code = clip(round(x * 2^f)) to the signed n-bit range (Sec. 2.5: values that
+ * do not fit saturate).  NaN gives code 0.  codes_dev: int8 (n <= 8) or int16.
+ * LP_ROUND_STOCHASTIC (Sec. 2.4): floor(x*2^f) + [u < frac], where u in [0,1)
+ * is 2^-32 * the first word of Philox4x32-10 (Salmon et al., SC'11) with key
+ * (seed lo, seed hi) and counter (i lo, i hi, 0, 0) for element index i; the
+ * other modes ignore `seed`.
+ * zero_count_dev / sat_count_dev (nullable): += number of zero codes / clipped values.
+ */
+lp_status lp_quantize(const float *x_dev, void *codes_dev, size_t count, lp_qfmt q, lp_round r,
+                      uint64_t seed, uint64_t *zero_count_dev, uint64_t *sat_count_dev,
+                      void *stream);
+
+/*
+ * lp_act -- LPAct followed by the activation function (Sec. 2.1: activations
+ * are quantized, then passed to ReLU; the two commute, so ReLU is applied to
+ * the accumulator first).  acc stands for acc * 2^-f_acc; the output code has
+ * qy.f fraction bits: code = clip(round(max(acc,0) / 2^(f_acc - qy.f))).
+ * |acc| must be below 2^62; -31 <= f_acc - qy.f <= 62.
+ * zero_count_dev (nullable): += number of zero output codes (Sec. 3.1 defines
+ * sparsity as zeros over elements).  r: NEAREST_AWAY or NEAREST_EVEN.
+ */
+lp_status lp_act(const int64_t *acc_dev, size_t count, int f_acc, lp_qfmt qy, int relu, lp_round r,
+                 void *y_codes_dev, uint64_t *zero_count_dev, void *stream);
+
+/*
+ * Weight packing for lp_conv_fwd / lp_fc_fwd.  Done once per layer, outside
+ * the timed path (the paper converts weight blobs offline, Sec. 2.1).  The
+ * packed buffer is opaque: int8 limb planes in the order the kernel streams
+ * them plus per-output-channel correction sums.  qx is needed because the
+ * layout depends on whether activations are 8- or 16-bit.
+ * lp_conv_packed_bytes writes the buffer size to *bytes_host.
+ */
+lp_status lp_conv_packed_bytes(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, size_t *bytes_host);
+lp_status lp_conv_pack_weights(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, const void *w_codes_dev,
+                               void *packed_dev, size_t packed_bytes, void *stream);
+
+/*
+ * lp_conv_plan_info -- how lp_conv_fwd will run this problem (host-only query, for
+ * reports and tests).  path: 0 = direct one-thread-per-output kernel, 1 = int8-MFMA
+ * implicit GEMM.  For path 1: limbs (1 = int8 codes, 2 = 16-bit codes as two int8
+ * limbs), the workgroup tile (128 output pixels = tile_rows consecutive rows of the
+ * N*Ho stacked output rows x tile_cols columns, times bn output channels), the staged
+ * input patch (patch_rows x patch_cols pixels), tile counts and LDS bytes per workgroup.
+ */
+typedef struct {
+    int32_t path, limbs, bn, tile_rows, tile_cols, patch_rows, patch_cols, tiles_m, tiles_n;
+    int32_t lds_bytes;
+} lp_plan_info;
+lp_status lp_conv_plan_info(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, lp_plan_info *out_host);
+
+/* Bytes of device workspace lp_conv_fwd needs for this problem (may be 0). */
+lp_status lp_conv_workspace_bytes(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, size_t *bytes_host);
+
+/*
+ * lp_conv_fwd -- LPConvolution forward (Sec. 2) with the LPAct + ReLU step
+ * fused (Sec. 2.1):
+ *   acc[n,y,x,co] = sum_{r,s,ci} X[n, y*stride+r-pad, x*stride+s-pad, ci] * W[co,r,s,ci]
+ *                   (+ bias[co] * 2^(qx.f + qw.f - qb.f)),   zero outside the image,
+ * exact in int64, fraction bits f_acc = qx.f + qw.f.
+ *   x_codes_dev   NHWC codes in format qx
+ *   w_packed_dev  from lp_conv_pack_weights (same d, qx, qw)
+ *   bias_codes_dev nullable; Cout codes in format qb (int8/int16 by qb.n), qb.f <= f_acc
+ *   acc_out_dev   nullable; receives the raw int64 accumulators, N x Ho x Wo x Cout
+ *   y_codes_dev   nullable; receives lp_act(acc) in format qy (see lp_act), same shape
+ *   zero_count_dev nullable; += zeros among the y codes written
+ * At least one of acc_out_dev / y_codes_dev must be given.
+ * LP_EUNSUPPORTED: R*S*Cin >= 65536 with 16-bit operands (int32 limb sums
+ * could overflow), tensors with 2^31 or more elements.
+ */
+lp_status lp_conv_fwd(const lp_conv_desc *d, const void *x_codes_dev, lp_qfmt qx,
+                      const void *w_packed_dev, lp_qfmt qw, const void *bias_codes_dev, lp_qfmt qb,
+                      int64_t *acc_out_dev, void *y_codes_dev, lp_qfmt qy, int relu, lp_round r,
+                      uint64_t *zero_count_dev, void *workspace_dev, size_t workspace_bytes,
+                      void *stream);
+
+/*
+ * lp_fc_fwd -- LPInnerProduct forward (Sec. 2) with the same fused tail:
+ *   acc[b,o] = sum_k X[b,k] * W[o,k] (+ bias), x [M][K], w packed from [Nout][K].
+ * Packing / workspace: the lp_fc_* functions below.  Other arguments as lp_conv_fwd.
+ */
+lp_status lp_fc_packed_bytes(int M, int K, int Nout, lp_qfmt qx, lp_qfmt qw, size_t *bytes_host);
+lp_status lp_fc_pack_weights(int M, int K, int Nout, lp_qfmt qx, lp_qfmt qw, const void *w_codes_dev,
+                             void *packed_dev, size_t packed_bytes, void *stream);
+lp_status lp_fc_workspace_bytes(int M, int K, int Nout, lp_qfmt qx, lp_qfmt qw, size_t *bytes_host);
+lp_status lp_fc_fwd(int M, int K, int Nout, const void *x_codes_dev, lp_qfmt qx,
+                    const void *w_packed_dev, lp_qfmt qw, const void *bias_codes_dev, lp_qfmt qb,
+                    int64_t *acc_out_dev, void *y_codes_dev, lp_qfmt qy, int relu, lp_round r,
+                    uint64_t *zero_count_dev, void *workspace_dev, size_t workspace_bytes,
+                    void *stream);
+
+/*
+ * lp_maxpool2x2 -- 2x2 max, stride 2, on NHWC codes (the pooling between VGG16
+ * blocks; "Pooling" column of Table 1).  H and W must be even.  n_bits selects
+ * int8 (<= 8) or int16 storage.  Output N x H/2 x W/2 x C.
+ */
+lp_status lp_maxpool2x2(const void *x_codes_dev, void *y_codes_dev, int N, int H, int W, int C,
+                        int n_bits, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LP_H */

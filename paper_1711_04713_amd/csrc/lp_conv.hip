@@ -1,0 +1,715 @@
+// LPConvolution / LPInnerProduct forward on Qm.f codes for gfx950 (Sec. 2 of the paper),
+// exact: int8 MFMA products, int32 limb sums, int64 results, fused LPAct+ReLU tail (Sec. 2.1).
+//
+// 16-bit codes are split into two int8 limbs, a = 256*ah + al + 128 with ah = a >> 8 and
+// al = (a & 255) - 128 in [-128, 127].  Over the K real positions of a dot product
+//     sum a*b = 2^16*HH + 2^8*(HL+LH) + LL + 128*sum(a) + 128*sum(b) - 16384*K
+// where HH = sum ah*bh etc. are int32 MFMA accumulators.  A tap outside the image is the
+// code 0, i.e. limbs (0, -128); channel padding is (0, 0) on both operands and drops out.
+// sum(b) - 128*K per output channel is folded into the packed weights; sum(a) per output
+// pixel comes from per-pixel channel sums gathered while the input patch is staged.
+//
+// Kernel shape: one 256-thread workgroup computes 128 output pixels x BN channels.  The
+// pixels are RH consecutive rows (of the N*Ho stacked output rows) x TW columns; the
+// input patch they need, (rows + R-1) x (TW + S-1) pixels x 64 channels, is staged in LDS
+// once per 64-channel chunk and every tap reads it at a shifted offset (implicit GEMM with
+// halo reuse).  Weights stream through LDS one (tap, chunk) slab at a time.
+#include <algorithm>
+#include <mutex>
+#include <utility>
+#include <vector>
+
+#include "lp_device.h"
+
+namespace lp {
+
+constexpr int BM = 128;      // output pixels per workgroup
+constexpr int CK = 64;       // channels (bytes per limb) per staged chunk
+constexpr int PS = 80;       // LDS bytes per staged pixel / weight row (64 + 16 pad)
+constexpr int kConvThreads = 256;
+
+enum { PATH_DIRECT = 0, PATH_MFMA = 1 };
+
+struct Plan {
+    int path;
+    int limbs;   // 1: int8 x int8, 2: 16-bit x 16-bit
+    int Ho, Wo, Hp, FR;
+    int nchunks, CoutP, BN;
+    int RH, TW, PW, PRA, NPIXA;
+    int tiles_r, tiles_c, tiles_m, tiles_n;
+    size_t lds_bytes;
+    size_t packed_bytes, corr_offset;
+};
+
+static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static bool desc_ok(const lp_conv_desc *d)
+{
+    return d && d->N > 0 && d->H > 0 && d->W > 0 && d->Cin > 0 && d->Cout > 0 && d->R > 0 &&
+           d->S > 0 && d->stride > 0 && d->pad >= 0 && d->H + 2 * d->pad >= d->R &&
+           d->W + 2 * d->pad >= d->S;
+}
+
+static size_t mfma_lds_bytes(int limbs, int npixa, int bn)
+{
+    size_t tables = round_up((size_t)(2 * npixa + 2 * BM) * 4, 16);
+    return tables + (size_t)limbs * npixa * PS + (size_t)limbs * bn * PS;
+}
+
+// virtual row (in the stack of zero-padded images, Hp rows each) of stacked output row fr
+static inline int vrow(int fr, int Ho, int Hp) { return (fr / Ho) * Hp + fr % Ho; }
+
+// Plans are pure functions of (descriptor, operand widths); the tile search costs tens of
+// microseconds, so results are remembered.
+struct PlanKey {
+    lp_conv_desc d;
+    int x16, w16;
+    bool operator==(const PlanKey &o) const
+    {
+        return d.N == o.d.N && d.H == o.d.H && d.W == o.d.W && d.Cin == o.d.Cin && d.Cout == o.d.Cout &&
+               d.R == o.d.R && d.S == o.d.S && d.stride == o.d.stride && d.pad == o.d.pad &&
+               x16 == o.x16 && w16 == o.w16;
+    }
+};
+static std::mutex g_plan_mutex;
+static std::vector<std::pair<PlanKey, Plan>> g_plan_cache;
+
+static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, Plan *pl);
+
+// Chooses path and tile geometry.  Returns LP_OK or the reason the problem is refused.
+static lp_status make_plan(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, Plan *pl)
+{
+    if (!desc_ok(d) || !fmt_ok(qx) || !fmt_ok(qw)) return LP_EINVAL;
+    const PlanKey key = {*d, qx.n > 8, qw.n > 8};
+    {
+        std::lock_guard<std::mutex> lock(g_plan_mutex);
+        for (const auto &e : g_plan_cache)
+            if (e.first == key) {
+                *pl = e.second;
+                return LP_OK;
+            }
+    }
+    const lp_status st = make_plan_uncached(d, qx, qw, pl);
+    if (st == LP_OK) {
+        std::lock_guard<std::mutex> lock(g_plan_mutex);
+        if (g_plan_cache.size() >= 256) g_plan_cache.clear();
+        g_plan_cache.emplace_back(key, *pl);
+    }
+    return st;
+}
+
+static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, Plan *pl)
+{
+    Plan p = {};
+    p.Ho = (d->H + 2 * d->pad - d->R) / d->stride + 1;
+    p.Wo = (d->W + 2 * d->pad - d->S) / d->stride + 1;
+    p.Hp = d->H + 2 * d->pad;
+    const long long in_elems = (long long)d->N * d->H * d->W * d->Cin;
+    const long long out_elems = (long long)d->N * p.Ho * p.Wo * d->Cout;
+    const long long w_elems = (long long)d->Cout * d->R * d->S * d->Cin;
+    const long long K = (long long)d->R * d->S * d->Cin;
+    if (in_elems >= (1LL << 31) || out_elems >= (1LL << 31) || w_elems >= (1LL << 31))
+        return LP_EUNSUPPORTED;
+    if (K >= 65536 && (qx.n > 8 || qw.n > 8)) return LP_EUNSUPPORTED;
+    if (K >= 131072) return LP_EUNSUPPORTED;
+    p.FR = d->N * p.Ho;
+    const bool x16 = qx.n > 8, w16 = qw.n > 8;
+    p.limbs = x16 ? 2 : 1;
+    p.path = PATH_DIRECT;
+    const int cvec = x16 ? 8 : 16; // codes per 16-byte load
+    if (d->stride == 1 && (x16 || !w16) && d->Cin % cvec == 0 && d->Cin >= 16) {
+        // tile search: RH x TW <= 128 output pixels, minimise wasted MFMA rows, then patch size
+        const int RS = d->R * d->S;
+        double best = 1e300;
+        for (int tw = 1; tw <= std::min(p.Wo, BM); ++tw)
+            for (int rh = std::min(BM / tw, p.FR); rh >= 1; --rh) {
+                const int tiles_c = (p.Wo + tw - 1) / tw, tiles_r = (p.FR + rh - 1) / rh;
+                const int pw = tw + d->S - 1;
+                // patch rows: the tile's rows, the R-1 halo, and R-1 more per image boundary
+                // the tile can straddle (none when tiles divide the image height)
+                const int cross = (p.Ho % rh == 0) ? 0 : std::min((rh - 1 + p.Ho - 1) / p.Ho, d->N - 1);
+                const int pra = rh + d->R - 1 + cross * (d->R - 1);
+                const int npixa = pra * pw;
+                if (mfma_lds_bytes(p.limbs, npixa, 128) > 72 * 1024) continue;
+                const double cost = (double)tiles_c * tiles_r * ((double)BM * RS + 0.5 * npixa);
+                if (cost < best) {
+                    best = cost;
+                    p.RH = rh; p.TW = tw; p.PW = pw; p.PRA = pra; p.NPIXA = npixa;
+                    p.tiles_r = tiles_r; p.tiles_c = tiles_c;
+                }
+            }
+        if (best < 1e300) p.path = PATH_MFMA;
+    }
+    if (p.path == PATH_MFMA) {
+        p.nchunks = (d->Cin + CK - 1) / CK;
+        p.CoutP = (int)round_up(d->Cout, 64);
+        p.BN = (p.CoutP % 128 == 0) ? 128 : 64;
+        p.tiles_m = p.tiles_r * p.tiles_c;
+        p.tiles_n = p.CoutP / p.BN;
+        p.lds_bytes = mfma_lds_bytes(p.limbs, p.NPIXA, p.BN);
+        p.corr_offset = round_up((size_t)d->R * d->S * p.nchunks * p.limbs * p.CoutP * CK, 256);
+        p.packed_bytes = p.corr_offset + (size_t)p.CoutP * sizeof(int64_t);
+    } else {
+        // direct path keeps a plain int16 copy of the weights
+        p.corr_offset = 0;
+        p.packed_bytes = round_up((size_t)w_elems * sizeof(int16_t), 256);
+    }
+    *pl = p;
+    return LP_OK;
+}
+
+// --------------------------------------------------------------------- weight packing
+
+// MFMA layout: [tap][chunk][limb][CoutP][64] int8.
+template <typename WT, int LIMBS>
+__global__ void pack_weights_kernel(const WT *__restrict__ w, unsigned char *__restrict__ out, int Cout,
+                                    int Cin, int RS, int nchunks, int CoutP, size_t total)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (size_t)gridDim.x * blockDim.x) {
+        const int kk = (int)(i % CK);
+        size_t t = i / CK;
+        const int co = (int)(t % CoutP);
+        t /= CoutP;
+        const int chunk = (int)(t % nchunks);
+        const int tap = (int)(t / nchunks);
+        const int ci = chunk * CK + kk;
+        int hi = 0, lo = 0;
+        if (co < Cout && ci < Cin) {
+            const int code = (int)w[((size_t)co * RS + tap) * Cin + ci];
+            if (LIMBS == 2) {
+                hi = code >> 8;
+                lo = (code & 255) - 128;
+            } else {
+                hi = code;
+            }
+        }
+        const size_t base = (((size_t)tap * nchunks + chunk) * LIMBS) * CoutP;
+        out[(base + co) * CK + kk] = (unsigned char)hi;
+        if (LIMBS == 2) out[(base + CoutP + co) * CK + kk] = (unsigned char)lo;
+    }
+}
+
+// corr[co] = 128 * sum_k w[co][k] - 16384 * K for the two-limb path, 0 otherwise.
+template <typename WT>
+__global__ void weight_corr_kernel(const WT *__restrict__ w, int64_t *__restrict__ corr, int Cout,
+                                   int CoutP, int K, int limbs)
+{
+    const int co = blockIdx.x * blockDim.x + threadIdx.x;
+    if (co >= CoutP) return;
+    int64_t v = 0;
+    if (limbs == 2 && co < Cout) {
+        int64_t s = 0;
+        for (int k = 0; k < K; ++k) s += (int64_t)w[(size_t)co * K + k];
+        v = 128 * s - (int64_t)16384 * K;
+    }
+    corr[co] = v;
+}
+
+template <typename WT>
+__global__ void widen_weights_kernel(const WT *__restrict__ w, int16_t *__restrict__ out, size_t total)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (size_t)gridDim.x * blockDim.x)
+        out[i] = (int16_t)w[i];
+}
+
+// --------------------------------------------------------------------- kernel arguments
+
+struct ConvArgs {
+    const void *x;
+    const unsigned char *wp;
+    const int64_t *corr;
+    const void *bias;
+    int bias16, bias_shift;
+    int64_t *acc_out;
+    void *y;
+    int y16;
+    unsigned long long *zero_count;
+    int N, H, W, Cin, Cout, R, S, stride, pad;
+    int Ho, Wo, Hp, FR;
+    int RH, TW, PW, NPIXA;
+    int tiles_c, tiles_n, CoutP, nchunks;
+    int total_work, per_xcd;
+    ActParams act;
+};
+
+__device__ __forceinline__ int64_t bias_term(const ConvArgs &a, int co)
+{
+    if (!a.bias) return 0;
+    const int b = a.bias16 ? (int)((const int16_t *)a.bias)[co] : (int)((const int8_t *)a.bias)[co];
+    return (int64_t)b * ((int64_t)1 << a.bias_shift);
+}
+
+// ------------------------------------------------------------------------ direct path
+// One thread per output value; any stride / kernel size / operand width.  Correctness
+// fallback for shapes the MFMA kernel does not take.
+template <typename XT>
+__global__ __launch_bounds__(256) void conv_direct_kernel(const ConvArgs a)
+{
+    const size_t total = (size_t)a.FR * a.Wo * a.Cout;
+    const XT *x = (const XT *)a.x;
+    const int16_t *w = (const int16_t *)a.wp;
+    unsigned zeros = 0;
+    for (size_t i0 = (size_t)blockIdx.x * 256; i0 < total; i0 += (size_t)gridDim.x * 256) {
+        const size_t i = i0 + threadIdx.x;
+        bool z = false;
+        if (i < total) {
+            const int co = (int)(i % a.Cout);
+            size_t t = i / a.Cout;
+            const int xo = (int)(t % a.Wo);
+            t /= a.Wo;
+            const int yo = (int)(t % a.Ho);
+            const int n = (int)(t / a.Ho);
+            int64_t acc = 0;
+            for (int r = 0; r < a.R; ++r) {
+                const int iy = yo * a.stride + r - a.pad;
+                if (iy < 0 || iy >= a.H) continue;
+                for (int s = 0; s < a.S; ++s) {
+                    const int ix = xo * a.stride + s - a.pad;
+                    if (ix < 0 || ix >= a.W) continue;
+                    const XT *xp = x + (((size_t)n * a.H + iy) * a.W + ix) * a.Cin;
+                    const int16_t *wq = w + (((size_t)co * a.R + r) * a.S + s) * a.Cin;
+                    for (int ci = 0; ci < a.Cin; ++ci) acc += (int64_t)((int)xp[ci] * (int)wq[ci]);
+                }
+            }
+            acc += bias_term(a, co);
+            if (a.acc_out) a.acc_out[i] = acc;
+            if (a.y) {
+                const int c = act_one(acc, a.act);
+                if (a.y16) ((int16_t *)a.y)[i] = (int16_t)c;
+                else ((int8_t *)a.y)[i] = (int8_t)c;
+                z = (c == 0);
+            }
+        }
+        zeros += wave_count(z);
+    }
+    if (a.zero_count && a.y && (threadIdx.x & 63) == 0 && zeros)
+        atomicAdd(a.zero_count, (unsigned long long)zeros);
+}
+
+// -------------------------------------------------------------------------- MFMA path
+
+__device__ __forceinline__ v16i mfma_i8(v4i a, v4i b, v16i c)
+{
+    return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+}
+
+// LIMBS: 1 (int8 codes) or 2 (16-bit codes as two int8 limbs).  NB: 32-column blocks per
+// wave; the workgroup covers BN = 64*NB output channels with 2x2 waves of 64 x 32*NB each.
+template <int LIMBS, int NB>
+__global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvArgs a)
+{
+    constexpr int BN = 64 * NB;
+    constexpr int NACC = (LIMBS == 2) ? 3 : 1;
+    extern __shared__ __align__(16) unsigned char smem[];
+
+    // XCD-aware work order: consecutive workgroup ids land on the 8 XCDs round-robin, so
+    // each XCD is handed one contiguous range of (pixel tile, channel tile) work items and
+    // the tiles sharing an input patch or a halo meet in the same L2.
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int wi = xcd * a.per_xcd + slot;
+    if (slot >= a.per_xcd || wi >= a.total_work) return;
+    const int mtile = wi / a.tiles_n, ntile = wi % a.tiles_n;
+    const int tile_r = mtile / a.tiles_c, tile_c = mtile % a.tiles_c;
+    const int fr0 = tile_r * a.RH, x0 = tile_c * a.TW;
+    const int vr0 = (fr0 / a.Ho) * a.Hp + fr0 % a.Ho;
+
+    const int NPIXA = a.NPIXA;
+    int *tab = (int *)smem;          // staged pixel -> input pixel index, -1 outside the image
+    int *psum = tab + NPIXA;         // per staged pixel: sum of its codes over all channels
+    int *outoff = psum + NPIXA;      // tile row -> output pixel index, -1 if not an output
+    int *abase_s = outoff + BM;      // tile row -> staged pixel of its (r=0, s=0) tap
+    unsigned char *Asm = smem + (((size_t)(2 * NPIXA + 2 * BM) * 4 + 15) & ~(size_t)15);
+    unsigned char *Bsm = Asm + (size_t)LIMBS * NPIXA * PS;
+    const int APL = NPIXA * PS;      // bytes per limb plane of the patch
+    constexpr int BPL = BN * PS;
+
+    const int tid = threadIdx.x;
+    for (int p = tid; p < NPIXA; p += kConvThreads) {
+        const int pr = p / a.PW, pc = p % a.PW;
+        const int vr = vr0 + pr;
+        const int n = vr / a.Hp, iy = vr % a.Hp - a.pad, ix = x0 - a.pad + pc;
+        const bool ok = n < a.N && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
+        tab[p] = ok ? (n * a.H + iy) * a.W + ix : -1;
+        psum[p] = 0;
+    }
+    for (int m = tid; m < BM; m += kConvThreads) {
+        const int j = m / a.TW, t = m % a.TW;
+        const int fr = fr0 + j, xo = x0 + t;
+        const bool ok = j < a.RH && fr < a.FR && xo < a.Wo;
+        outoff[m] = ok ? fr * a.Wo + xo : -1;
+        abase_s[m] = ok ? ((fr / a.Ho) * a.Hp + fr % a.Ho - vr0) * a.PW + t : 0;
+    }
+    __syncthreads();
+
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+    const int l32 = lane & 31, kg = lane >> 5;
+    int aoff[2], boff[NB];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) aoff[mb] = abase_s[wm * 64 + mb * 32 + l32] * PS + kg * 16;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) boff[nb] = (wn * (NB * 32) + nb * 32 + l32) * PS + kg * 16;
+
+    v16i acc[2][NB][NACC];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int q = 0; q < NACC; ++q)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mb][nb][q][v] = 0;
+
+    const int RS = a.R * a.S;
+    for (int cc = 0; cc < a.nchunks; ++cc) {
+        __syncthreads(); // all reads of the previous chunk's patch and weights are done
+        // ---- stage the input patch for channels [cc*64, cc*64+64)
+        if (LIMBS == 2) {
+            const int16_t *x = (const int16_t *)a.x;
+            for (int i = tid; i < NPIXA * 8; i += kConvThreads) {
+                const int p = i >> 3, c8 = i & 7, ch = cc * CK + c8 * 8;
+                const int g = tab[p];
+                v2i hi = {0, 0}, lo = {0, 0};
+                if (ch < a.Cin) {
+                    if (g >= 0) {
+                        const v4i v = *(const v4i *)(x + (size_t)g * a.Cin + ch);
+                        hi.x = (int)__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x07050301u);
+                        hi.y = (int)__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x07050301u);
+                        lo.x = (int)(__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x06040200u) ^ 0x80808080u);
+                        lo.y = (int)(__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x06040200u) ^ 0x80808080u);
+                        const int sum = ((v.x << 16) >> 16) + (v.x >> 16) + ((v.y << 16) >> 16) + (v.y >> 16) +
+                                        ((v.z << 16) >> 16) + (v.z >> 16) + ((v.w << 16) >> 16) + (v.w >> 16);
+                        if (sum) atomicAdd(&psum[p], sum);
+                    } else {
+                        lo.x = lo.y = (int)0x80808080u; // the code 0 outside the image
+                    }
+                }
+                *(v2i *)(Asm + p * PS + c8 * 8) = hi;
+                *(v2i *)(Asm + APL + p * PS + c8 * 8) = lo;
+            }
+        } else {
+            const int8_t *x = (const int8_t *)a.x;
+            for (int i = tid; i < NPIXA * 4; i += kConvThreads) {
+                const int p = i >> 2, c4 = i & 3, ch = cc * CK + c4 * 16;
+                const int g = tab[p];
+                v4i v = {0, 0, 0, 0};
+                if (ch < a.Cin && g >= 0) v = *(const v4i *)(x + (size_t)g * a.Cin + ch);
+                *(v4i *)(Asm + p * PS + c4 * 16) = v;
+            }
+        }
+        for (int tap = 0; tap < RS; ++tap) {
+            if (tap) __syncthreads(); // previous tap's weight reads are done
+            // ---- stage the weight slab of (tap, chunk): LIMBS x BN rows x 64 bytes
+            {
+                const unsigned char *src =
+                    a.wp + (((size_t)tap * a.nchunks + cc) * LIMBS * a.CoutP + (size_t)ntile * BN) * CK;
+#pragma unroll
+                for (int lb = 0; lb < LIMBS; ++lb)
+#pragma unroll
+                    for (int i = tid; i < BN * 4; i += kConvThreads) {
+                        const int row = i >> 2, q = i & 3;
+                        const v4i v = *(const v4i *)(src + ((size_t)lb * a.CoutP + row) * CK + q * 16);
+                        *(v4i *)(Bsm + lb * BPL + row * PS + q * 16) = v;
+                    }
+            }
+            __syncthreads();
+            // ---- 64 channels of this tap: two K=32 MFMA steps
+            const int r = tap / a.S, s = tap - r * a.S;
+            const int tapoff = (r * a.PW + s) * PS;
+#pragma unroll
+            for (int k32 = 0; k32 < 2; ++k32) {
+                v4i ah[2], al[2], bh[NB], bl[NB];
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb) {
+                    ah[mb] = *(const v4i *)(Asm + aoff[mb] + tapoff + k32 * 32);
+                    if (LIMBS == 2) al[mb] = *(const v4i *)(Asm + APL + aoff[mb] + tapoff + k32 * 32);
+                }
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    bh[nb] = *(const v4i *)(Bsm + boff[nb] + k32 * 32);
+                    if (LIMBS == 2) bl[nb] = *(const v4i *)(Bsm + BPL + boff[nb] + k32 * 32);
+                }
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        acc[mb][nb][0] = mfma_i8(ah[mb], bh[nb], acc[mb][nb][0]);
+                        if (LIMBS == 2) {
+                            acc[mb][nb][1] = mfma_i8(ah[mb], bl[nb], acc[mb][nb][1]);
+                            acc[mb][nb][2] = mfma_i8(al[mb], bl[nb], acc[mb][nb][2]);
+                        }
+                    }
+                if (LIMBS == 2) {
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            acc[mb][nb][1] = mfma_i8(al[mb], bh[nb], acc[mb][nb][1]);
+                }
+            }
+        }
+    }
+
+    // ---- per-row correction 128 * sum(a) over the window, from the staged channel sums
+    __syncthreads();
+    int64_t *rowterm = (int64_t *)Asm; // the patch is no longer needed
+    if (LIMBS == 2) {
+        for (int m = tid; m < BM; m += kConvThreads) {
+            const int base = abase_s[m];
+            int sum = 0;
+            for (int r = 0; r < a.R; ++r)
+                for (int s = 0; s < a.S; ++s) sum += psum[base + r * a.PW + s];
+            rowterm[m] = (int64_t)sum * 128;
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: combine limbs exactly, add corrections and bias, LPAct, count zeros.
+    // MFMA 32x32 result layout: lane holds column (lane & 31), rows 8*(v/4) + 4*(lane/32) + v%4.
+    unsigned zeros = 0;
+    int64_t colterm[NB];
+    int colg[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        colg[nb] = ntile * BN + wn * (NB * 32) + nb * 32 + l32;
+        colterm[nb] = 0;
+        if (colg[nb] < a.Cout) colterm[nb] = a.corr[colg[nb]] + bias_term(a, colg[nb]);
+    }
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = wm * 64 + mb * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+            const int oo = outoff[row];
+            const int64_t rt = (LIMBS == 2) ? rowterm[row] : 0;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                int64_t val;
+                if (LIMBS == 2)
+                    val = ((int64_t)acc[mb][nb][0][v] << 16) + ((int64_t)acc[mb][nb][1][v] << 8) +
+                          (int64_t)acc[mb][nb][2][v] + rt + colterm[nb];
+                else
+                    val = (int64_t)acc[mb][nb][0][v] + colterm[nb];
+                const bool ok = oo >= 0 && colg[nb] < a.Cout;
+                bool z = false;
+                if (ok) {
+                    const size_t idx = (size_t)oo * a.Cout + colg[nb];
+                    if (a.acc_out) a.acc_out[idx] = val;
+                    if (a.y) {
+                        const int c = act_one(val, a.act);
+                        if (a.y16) ((int16_t *)a.y)[idx] = (int16_t)c;
+                        else ((int8_t *)a.y)[idx] = (int8_t)c;
+                        z = (c == 0);
+                    }
+                }
+                zeros += wave_count(z);
+            }
+        }
+    if (a.zero_count && a.y && lane == 0 && zeros) atomicAdd(a.zero_count, (unsigned long long)zeros);
+}
+
+template <int LIMBS, int NB>
+static lp_status launch_mfma(const ConvArgs &a, const Plan &p, hipStream_t st)
+{
+    static bool attr_set = false; // raise the dynamic LDS limit once per kernel instance
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void *)conv_mfma_kernel<LIMBS, NB>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return LP_EDEVICE;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((conv_mfma_kernel<LIMBS, NB>), dim3(a.per_xcd * 8), dim3(kConvThreads),
+                       p.lds_bytes, st, a);
+    return launch_status();
+}
+
+static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, const void *wp,
+                              lp_qfmt qw, const void *bias, lp_qfmt qb, int64_t *acc_out, void *y,
+                              lp_qfmt qy, int relu, lp_round r, uint64_t *zero_count, void *stream)
+{
+    Plan p;
+    lp_status st = make_plan(d, qx, qw, &p);
+    if (st != LP_OK) return st;
+    if (!x || !wp || (!acc_out && !y) || !aligned16(x) || !aligned16(wp)) return LP_EINVAL;
+    if ((acc_out && !aligned16(acc_out)) || (y && !aligned16(y))) return LP_EINVAL;
+    const int f_acc = qx.f + qw.f;
+    if (bias && (!fmt_ok(qb) || qb.f > f_acc || f_acc - qb.f > 40)) return LP_EINVAL;
+    if (r != LP_ROUND_NEAREST_AWAY && r != LP_ROUND_NEAREST_EVEN) return LP_EINVAL;
+    ConvArgs a = {};
+    if (y) {
+        if (!fmt_ok(qy)) return LP_EINVAL;
+        const int s = f_acc - qy.f;
+        if (s > 62 || s < -31) return LP_EINVAL;
+        a.act = make_act_params(f_acc, qy, relu, r);
+        a.y16 = qy.n > 8;
+    }
+    a.x = x;
+    a.wp = (const unsigned char *)wp;
+    a.corr = (const int64_t *)((const unsigned char *)wp + p.corr_offset);
+    a.bias = bias;
+    a.bias16 = bias ? (qb.n > 8) : 0;
+    a.bias_shift = bias ? f_acc - qb.f : 0;
+    a.acc_out = acc_out;
+    a.y = y;
+    a.zero_count = (unsigned long long *)zero_count;
+    a.N = d->N; a.H = d->H; a.W = d->W; a.Cin = d->Cin; a.Cout = d->Cout;
+    a.R = d->R; a.S = d->S; a.stride = d->stride; a.pad = d->pad;
+    a.Ho = p.Ho; a.Wo = p.Wo; a.Hp = p.Hp; a.FR = p.FR;
+    hipStream_t hs = as_stream(stream);
+    if (p.path == PATH_DIRECT) {
+        const size_t total = (size_t)p.FR * p.Wo * d->Cout;
+        const int grid = (int)std::min<size_t>((total + 255) / 256, 256 * 64);
+        if (qx.n > 8) hipLaunchKernelGGL(conv_direct_kernel<int16_t>, dim3(grid), dim3(256), 0, hs, a);
+        else hipLaunchKernelGGL(conv_direct_kernel<int8_t>, dim3(grid), dim3(256), 0, hs, a);
+        return launch_status();
+    }
+    a.RH = p.RH; a.TW = p.TW; a.PW = p.PW; a.NPIXA = p.NPIXA;
+    a.tiles_c = p.tiles_c; a.tiles_n = p.tiles_n; a.CoutP = p.CoutP; a.nchunks = p.nchunks;
+    a.total_work = p.tiles_m * p.tiles_n;
+    a.per_xcd = (a.total_work + 7) / 8;
+    if (p.limbs == 2) return p.BN == 128 ? launch_mfma<2, 2>(a, p, hs) : launch_mfma<2, 1>(a, p, hs);
+    return p.BN == 128 ? launch_mfma<1, 2>(a, p, hs) : launch_mfma<1, 1>(a, p, hs);
+}
+
+static lp_status pack_weights(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, const void *w,
+                              void *packed, size_t packed_bytes, void *stream)
+{
+    Plan p;
+    lp_status st = make_plan(d, qx, qw, &p);
+    if (st != LP_OK) return st;
+    if (!w || !packed || !aligned16(w) || !aligned16(packed)) return LP_EINVAL;
+    if (packed_bytes < p.packed_bytes) return LP_EWORKSPACE;
+    hipStream_t hs = as_stream(stream);
+    const bool w16 = qw.n > 8;
+    const int RS = d->R * d->S;
+    if (p.path == PATH_DIRECT) {
+        const size_t total = (size_t)d->Cout * RS * d->Cin;
+        const int grid = (int)std::min<size_t>((total + 255) / 256, 65535);
+        if (w16) hipLaunchKernelGGL(widen_weights_kernel<int16_t>, dim3(grid), dim3(256), 0, hs,
+                                    (const int16_t *)w, (int16_t *)packed, total);
+        else hipLaunchKernelGGL(widen_weights_kernel<int8_t>, dim3(grid), dim3(256), 0, hs,
+                                (const int8_t *)w, (int16_t *)packed, total);
+        return launch_status();
+    }
+    const size_t total = (size_t)RS * p.nchunks * p.CoutP * CK;
+    const int grid = (int)std::min<size_t>((total + 255) / 256, 65535);
+    unsigned char *out = (unsigned char *)packed;
+    int64_t *corr = (int64_t *)(out + p.corr_offset);
+    const int cgrid = (p.CoutP + 63) / 64;
+#define LP_PACK(WT, L)                                                                              \
+    hipLaunchKernelGGL((pack_weights_kernel<WT, L>), dim3(grid), dim3(256), 0, hs, (const WT *)w, out, \
+                       d->Cout, d->Cin, RS, p.nchunks, p.CoutP, total);                                \
+    hipLaunchKernelGGL(weight_corr_kernel<WT>, dim3(cgrid), dim3(64), 0, hs, (const WT *)w, corr,      \
+                       d->Cout, p.CoutP, RS * d->Cin, L)
+    if (p.limbs == 2) {
+        if (w16) { LP_PACK(int16_t, 2); } else { LP_PACK(int8_t, 2); }
+    } else {
+        LP_PACK(int8_t, 1);
+    }
+#undef LP_PACK
+    return launch_status();
+}
+
+static lp_conv_desc fc_desc(int M, int K, int Nout)
+{
+    lp_conv_desc d = {M, 1, 1, K, Nout, 1, 1, 1, 0};
+    return d;
+}
+
+} // namespace lp
+
+using namespace lp;
+
+extern "C" lp_status lp_conv_packed_bytes(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw,
+                                          size_t *bytes_host)
+{
+    if (!bytes_host) return LP_EINVAL;
+    Plan p;
+    lp_status st = make_plan(d, qx, qw, &p);
+    if (st == LP_OK) *bytes_host = p.packed_bytes;
+    return st;
+}
+
+extern "C" lp_status lp_conv_pack_weights(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw,
+                                          const void *w_codes_dev, void *packed_dev,
+                                          size_t packed_bytes, void *stream)
+{
+    return pack_weights(d, qx, qw, w_codes_dev, packed_dev, packed_bytes, stream);
+}
+
+extern "C" lp_status lp_conv_plan_info(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw,
+                                       lp_plan_info *out_host)
+{
+    if (!out_host) return LP_EINVAL;
+    Plan p;
+    lp_status st = make_plan(d, qx, qw, &p);
+    if (st != LP_OK) return st;
+    lp_plan_info o = {};
+    o.path = p.path;
+    o.limbs = p.limbs;
+    if (p.path == PATH_MFMA) {
+        o.bn = p.BN; o.tile_rows = p.RH; o.tile_cols = p.TW; o.patch_rows = p.PRA; o.patch_cols = p.PW;
+        o.tiles_m = p.tiles_m; o.tiles_n = p.tiles_n; o.lds_bytes = (int32_t)p.lds_bytes;
+    }
+    *out_host = o;
+    return LP_OK;
+}
+
+extern "C" lp_status lp_conv_workspace_bytes(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw,
+                                             size_t *bytes_host)
+{
+    if (!bytes_host) return LP_EINVAL;
+    Plan p;
+    lp_status st = make_plan(d, qx, qw, &p);
+    if (st == LP_OK) *bytes_host = 0;
+    return st;
+}
+
+extern "C" lp_status lp_conv_fwd(const lp_conv_desc *d, const void *x_codes_dev, lp_qfmt qx,
+                                 const void *w_packed_dev, lp_qfmt qw, const void *bias_codes_dev,
+                                 lp_qfmt qb, int64_t *acc_out_dev, void *y_codes_dev, lp_qfmt qy,
+                                 int relu, lp_round r, uint64_t *zero_count_dev, void *workspace_dev,
+                                 size_t workspace_bytes, void *stream)
+{
+    (void)workspace_dev;
+    (void)workspace_bytes;
+    return conv_forward(d, x_codes_dev, qx, w_packed_dev, qw, bias_codes_dev, qb, acc_out_dev,
+                        y_codes_dev, qy, relu, r, zero_count_dev, stream);
+}
+
+extern "C" lp_status lp_fc_packed_bytes(int M, int K, int Nout, lp_qfmt qx, lp_qfmt qw,
+                                        size_t *bytes_host)
+{
+    const lp_conv_desc d = fc_desc(M, K, Nout);
+    return lp_conv_packed_bytes(&d, qx, qw, bytes_host);
+}
+
+extern "C" lp_status lp_fc_pack_weights(int M, int K, int Nout, lp_qfmt qx, lp_qfmt qw,
+                                        const void *w_codes_dev, void *packed_dev, size_t packed_bytes,
+                                        void *stream)
+{
+    const lp_conv_desc d = fc_desc(M, K, Nout);
+    return pack_weights(&d, qx, qw, w_codes_dev, packed_dev, packed_bytes, stream);
+}
+
+extern "C" lp_status lp_fc_workspace_bytes(int M, int K, int Nout, lp_qfmt qx, lp_qfmt qw,
+                                           size_t *bytes_host)
+{
+    const lp_conv_desc d = fc_desc(M, K, Nout);
+    return lp_conv_workspace_bytes(&d, qx, qw, bytes_host);
+}
+
+extern "C" lp_status lp_fc_fwd(int M, int K, int Nout, const void *x_codes_dev, lp_qfmt qx,
+                               const void *w_packed_dev, lp_qfmt qw, const void *bias_codes_dev,
+                               lp_qfmt qb, int64_t *acc_out_dev, void *y_codes_dev, lp_qfmt qy,
+                               int relu, lp_round r, uint64_t *zero_count_dev, void *workspace_dev,
+                               size_t workspace_bytes, void *stream)
+{
+    (void)workspace_dev;
+    (void)workspace_bytes;
+    const lp_conv_desc d = fc_desc(M, K, Nout);
+    return conv_forward(&d, x_codes_dev, qx, w_packed_dev, qw, bias_codes_dev, qb, acc_out_dev,
+                        y_codes_dev, qy, relu, r, zero_count_dev, stream);
+}

@@ -1,0 +1,492 @@
+// HBM-bound kernels of the low-precision forward pass: quantize, dynamic-range
+// histogram, standalone LPAct, 2x2 max-pool.  Each thread moves 16-byte vectors;
+// counters use the wave ballot (a v_cmp result) + popcount and one atomic per wave.
+#include "lp_device.h"
+
+namespace lp {
+
+constexpr int kThreads = 256;
+
+static int grid_for(size_t groups)
+{
+    // enough blocks to fill 256 CUs several times over, grid-stride beyond that
+    size_t blocks = (groups + kThreads - 1) / kThreads;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    return (int)blocks;
+}
+
+// ------------------------------------------------------------------ Philox4x32-10
+// Counter-based generator of Salmon, Moraes, Dror, Shaw (SC'11): ten rounds of two
+// 32x32->64 multiplies and xors, key bumped by the Weyl constants each round.
+__device__ __forceinline__ uint32_t philox4x32_10_word0(uint64_t ctr, uint64_t key)
+{
+    uint32_t c0 = (uint32_t)ctr, c1 = (uint32_t)(ctr >> 32), c2 = 0, c3 = 0;
+    uint32_t k0 = (uint32_t)key, k1 = (uint32_t)(key >> 32);
+#pragma unroll
+    for (int i = 0; i < 10; ++i) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return c0;
+}
+
+// ------------------------------------------------------------------------ quantize
+
+template <int MODE>
+__device__ __forceinline__ int quantize_one(float x, float scale, float lo, float hi, uint64_t index,
+                                            uint64_t seed, bool &sat)
+{
+    const float t = x * scale; // exact: scale is a power of two
+    float r;
+    if (MODE == LP_ROUND_NEAREST_AWAY) {
+        r = roundf(t);
+    } else if (MODE == LP_ROUND_NEAREST_EVEN) {
+        r = rintf(t);
+    } else {
+        const float fl = floorf(t);
+        const float frac = t - fl; // exact
+        const uint32_t w = philox4x32_10_word0(index, seed);
+        r = ((double)w < (double)frac * 4294967296.0) ? fl + 1.0f : fl;
+    }
+    if (t != t) r = 0.0f;
+    sat = (r < lo) || (r > hi);
+    r = fminf(fmaxf(r, lo), hi);
+    return (int)r;
+}
+
+template <typename OutT, int MODE, bool COUNT>
+__global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restrict__ x,
+                                                           OutT *__restrict__ y, size_t count,
+                                                           float scale, float lo, float hi,
+                                                           uint64_t seed,
+                                                           unsigned long long *zero_count,
+                                                           unsigned long long *sat_count)
+{
+    const size_t groups = count / 8;
+    unsigned zeros = 0, sats = 0; // wave-uniform running totals
+    // lane 0 of a wave has the smallest index, so it runs every iteration any lane of its
+    // wave runs and its running totals see every ballot
+    for (size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x; g < groups;
+         g += (size_t)gridDim.x * kThreads) {
+        int c[8];
+        bool z[8], s[8];
+        {
+            const v4f a = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(x) + 2 * g);
+            const v4f b = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(x) + 2 * g + 1);
+            const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                c[j] = quantize_one<MODE>(v[j], scale, lo, hi, 8 * g + j, seed, s[j]);
+                z[j] = (c[j] == 0);
+            }
+            if (sizeof(OutT) == 2) {
+                v4i o;
+                o.x = (c[0] & 0xffff) | (c[1] << 16);
+                o.y = (c[2] & 0xffff) | (c[3] << 16);
+                o.z = (c[4] & 0xffff) | (c[5] << 16);
+                o.w = (c[6] & 0xffff) | (c[7] << 16);
+                reinterpret_cast<v4i *>(y)[g] = o;
+            } else {
+                v2i o;
+                o.x = (c[0] & 0xff) | ((c[1] & 0xff) << 8) | ((c[2] & 0xff) << 16) | (c[3] << 24);
+                o.y = (c[4] & 0xff) | ((c[5] & 0xff) << 8) | ((c[6] & 0xff) << 16) | (c[7] << 24);
+                reinterpret_cast<v2i *>(y)[g] = o;
+            }
+        }
+        if (COUNT) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                zeros += wave_count(z[j]);
+                sats += wave_count(s[j]);
+            }
+        }
+    }
+    // ragged tail (fewer than 8 elements): first wave of block 0
+    if (blockIdx.x == 0 && threadIdx.x < 64) {
+        const size_t i = groups * 8 + threadIdx.x;
+        bool z = false, s = false;
+        if (threadIdx.x < 8 && i < count) {
+            const int c = quantize_one<MODE>(x[i], scale, lo, hi, i, seed, s);
+            y[i] = (OutT)c;
+            z = (c == 0);
+        }
+        if (COUNT) {
+            zeros += wave_count(z);
+            sats += wave_count(s);
+        }
+    }
+    if (COUNT && (threadIdx.x & 63) == 0) {
+        if (zero_count && zeros) atomicAdd(zero_count, (unsigned long long)zeros);
+        if (sat_count && sats) atomicAdd(sat_count, (unsigned long long)sats);
+    }
+}
+
+template <typename OutT, int MODE>
+static void launch_quantize(const float *x, void *y, size_t count, float scale, float lo, float hi,
+                            uint64_t seed, uint64_t *zc, uint64_t *sc, hipStream_t st)
+{
+    const int grid = grid_for(count / 8);
+    if (zc || sc)
+        hipLaunchKernelGGL((quantize_kernel<OutT, MODE, true>), dim3(grid), dim3(kThreads), 0, st, x,
+                           (OutT *)y, count, scale, lo, hi, seed, (unsigned long long *)zc,
+                           (unsigned long long *)sc);
+    else
+        hipLaunchKernelGGL((quantize_kernel<OutT, MODE, false>), dim3(grid), dim3(kThreads), 0, st, x,
+                           (OutT *)y, count, scale, lo, hi, seed, nullptr, nullptr);
+}
+
+// --------------------------------------------------------------------------- range
+// Bucket b of a value = the smallest m (integer bits incl. sign) for which it is not
+// lost, i.e. |v| < 2^(b-1); b in 1..17, 17 collecting everything that needs more than
+// 16.  Each thread owns one column of an LDS histogram, so there are no conflicts.
+
+constexpr int kBuckets = 18;
+
+__device__ __forceinline__ int bucket_f32(float v)
+{
+    const uint32_t bits = __float_as_uint(v) & 0x7fffffffu;
+    if (bits > 0x7f800000u) return 1; // NaN: never counted as lost
+    const int e = (int)(bits >> 23) - 127;
+    if (e < 0) return 1;
+    return e + 2 > 17 ? 17 : e + 2;
+}
+
+__device__ __forceinline__ int bucket_i64(int64_t a, int f_acc, int relu)
+{
+    if (relu && a < 0) a = 0;
+    const uint64_t mag = (uint64_t)(a < 0 ? -a : a);
+    if ((mag >> f_acc) == 0) return 1; // |v| < 1
+    const int top = 63 - __clzll((long long)mag); // floor(log2 mag)
+    const int b = top - f_acc + 2;
+    return b > 17 ? 17 : b;
+}
+
+__device__ __forceinline__ void flush_hist(unsigned *h, unsigned long long *hist_out)
+{
+    __syncthreads();
+    const int t = threadIdx.x;
+    if (t < (kBuckets - 1) * 8) {
+        const int b = 1 + t / 8, part = t % 8;
+        unsigned long long sum = 0;
+        for (int i = 0; i < kThreads / 8; ++i) sum += h[b * kThreads + part * (kThreads / 8) + i];
+        if (sum) atomicAdd(&hist_out[b], sum);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void range_f32_kernel(const float *__restrict__ x, size_t count,
+                                                            unsigned long long *hist_out)
+{
+    __shared__ unsigned h[kBuckets * kThreads];
+    for (int b = 0; b < kBuckets; ++b) h[b * kThreads + threadIdx.x] = 0;
+    // columns are private to a thread: no barrier needed before use
+    const size_t groups = count / 4;
+    for (size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x; g < groups;
+         g += (size_t)gridDim.x * kThreads) {
+        const v4f a = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(x) + g);
+        h[bucket_f32(a.x) * kThreads + threadIdx.x] += 1;
+        h[bucket_f32(a.y) * kThreads + threadIdx.x] += 1;
+        h[bucket_f32(a.z) * kThreads + threadIdx.x] += 1;
+        h[bucket_f32(a.w) * kThreads + threadIdx.x] += 1;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < 4) {
+        const size_t i = groups * 4 + threadIdx.x;
+        if (i < count) h[bucket_f32(x[i]) * kThreads + threadIdx.x] += 1;
+    }
+    flush_hist(h, hist_out);
+}
+
+__global__ __launch_bounds__(kThreads) void range_i64_kernel(const int64_t *__restrict__ acc,
+                                                            size_t count, int f_acc, int relu,
+                                                            unsigned long long *hist_out)
+{
+    __shared__ unsigned h[kBuckets * kThreads];
+    for (int b = 0; b < kBuckets; ++b) h[b * kThreads + threadIdx.x] = 0;
+    const size_t groups = count / 2;
+    for (size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x; g < groups;
+         g += (size_t)gridDim.x * kThreads) {
+        const v4i a = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(acc) + g);
+        const int64_t a0 = (int64_t)(((uint64_t)(uint32_t)a.y << 32) | (uint32_t)a.x);
+        const int64_t a1 = (int64_t)(((uint64_t)(uint32_t)a.w << 32) | (uint32_t)a.z);
+        h[bucket_i64(a0, f_acc, relu) * kThreads + threadIdx.x] += 1;
+        h[bucket_i64(a1, f_acc, relu) * kThreads + threadIdx.x] += 1;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0 && (count & 1))
+        h[bucket_i64(acc[count - 1], f_acc, relu) * kThreads] += 1;
+    flush_hist(h, hist_out);
+}
+
+__global__ void clear_words_kernel(unsigned long long *p, int words)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < words) p[i] = 0;
+}
+
+// Host side of the rule of Sec. 2.3: smallest m whose lost share is within the threshold.
+static void pick_format(const unsigned long long *hist, size_t count, int n, double threshold,
+                        lp_qfmt *out, uint64_t *lost_host)
+{
+    int chosen = n;
+    bool found = false;
+    for (int m = 1; m <= n; ++m) {
+        unsigned long long lost = 0;
+        for (int b = m + 1; b < kBuckets; ++b) lost += hist[b];
+        if (lost_host) lost_host[m] = lost;
+        if (!found && (double)lost <= threshold * (double)count) {
+            chosen = m;
+            found = true;
+        }
+    }
+    if (lost_host) lost_host[0] = 0;
+    out->n = n;
+    out->m = chosen;
+    out->f = n - chosen;
+}
+
+static lp_status finish_range(unsigned long long *hist_dev, size_t count, int n, double threshold,
+                              lp_qfmt *out, uint64_t *lost_host, hipStream_t st)
+{
+    if (hipGetLastError() != hipSuccess) return LP_EDEVICE;
+    unsigned long long hist[LP_RANGE_WORKSPACE_WORDS];
+    if (hipMemcpyAsync(hist, hist_dev, sizeof(hist), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return LP_EDEVICE;
+    if (hipStreamSynchronize(st) != hipSuccess) return LP_EDEVICE;
+    pick_format(hist, count, n, threshold, out, lost_host);
+    return LP_OK;
+}
+
+// ----------------------------------------------------------------------------- act
+
+template <typename OutT>
+__global__ __launch_bounds__(kThreads) void act_kernel(const int64_t *__restrict__ acc,
+                                                      OutT *__restrict__ y, size_t count,
+                                                      ActParams p, unsigned long long *zero_count)
+{
+    const size_t groups = count / 8;
+    unsigned zeros = 0;
+    for (size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x; g < groups;
+         g += (size_t)gridDim.x * kThreads) {
+        bool z[8];
+        {
+            int c[8];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const v4i a = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(acc) + 4 * g + j);
+                const int64_t a0 = (int64_t)(((uint64_t)(uint32_t)a.y << 32) | (uint32_t)a.x);
+                const int64_t a1 = (int64_t)(((uint64_t)(uint32_t)a.w << 32) | (uint32_t)a.z);
+                c[2 * j] = act_one(a0, p);
+                c[2 * j + 1] = act_one(a1, p);
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) z[j] = (c[j] == 0);
+            if (sizeof(OutT) == 2) {
+                v4i o;
+                o.x = (c[0] & 0xffff) | (c[1] << 16);
+                o.y = (c[2] & 0xffff) | (c[3] << 16);
+                o.z = (c[4] & 0xffff) | (c[5] << 16);
+                o.w = (c[6] & 0xffff) | (c[7] << 16);
+                reinterpret_cast<v4i *>(y)[g] = o;
+            } else {
+                v2i o;
+                o.x = (c[0] & 0xff) | ((c[1] & 0xff) << 8) | ((c[2] & 0xff) << 16) | (c[3] << 24);
+                o.y = (c[4] & 0xff) | ((c[5] & 0xff) << 8) | ((c[6] & 0xff) << 16) | (c[7] << 24);
+                reinterpret_cast<v2i *>(y)[g] = o;
+            }
+        }
+        if (zero_count) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) zeros += wave_count(z[j]);
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < 64) {
+        const size_t i = groups * 8 + threadIdx.x;
+        bool z = false;
+        if (threadIdx.x < 8 && i < count) {
+            const int c = act_one(acc[i], p);
+            y[i] = (OutT)c;
+            z = (c == 0);
+        }
+        if (zero_count) zeros += wave_count(z);
+    }
+    if (zero_count && (threadIdx.x & 63) == 0 && zeros)
+        atomicAdd(zero_count, (unsigned long long)zeros);
+}
+
+// ------------------------------------------------------------------------- maxpool
+
+// One thread: one output pixel x one 16-byte channel group (8 int16 or 16 int8).
+template <typename VecT>
+__global__ __launch_bounds__(kThreads) void maxpool_vec_kernel(const VecT *__restrict__ x,
+                                                              VecT *__restrict__ y, int Ho, int Wo,
+                                                              int Cv, size_t total)
+{
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total;
+         i += (size_t)gridDim.x * kThreads) {
+        const int c = (int)(i % Cv);
+        size_t t = i / Cv;
+        const int xo = (int)(t % Wo);
+        t /= Wo; // t = n*Ho + yo
+        const size_t W = (size_t)2 * Wo;
+        const size_t base = ((2 * t) * W + 2 * xo) * Cv + c;
+        const VecT a = x[base], b = x[base + Cv], d = x[base + W * Cv], e = x[base + W * Cv + Cv];
+        y[i] = __builtin_elementwise_max(__builtin_elementwise_max(a, b),
+                                         __builtin_elementwise_max(d, e));
+    }
+    (void)Ho;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void maxpool_scalar_kernel(const T *__restrict__ x,
+                                                                 T *__restrict__ y, int Wo, int C,
+                                                                 size_t total)
+{
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < total;
+         i += (size_t)gridDim.x * kThreads) {
+        const int c = (int)(i % C);
+        size_t t = i / C;
+        const int xo = (int)(t % Wo);
+        t /= Wo;
+        const size_t W = (size_t)2 * Wo;
+        const size_t base = ((2 * t) * W + 2 * xo) * C + c;
+        T m = x[base];
+        const T b = x[base + C], d = x[base + W * C], e = x[base + W * C + C];
+        m = b > m ? b : m;
+        m = d > m ? d : m;
+        m = e > m ? e : m;
+        y[i] = m;
+    }
+}
+
+} // namespace lp
+
+using namespace lp;
+
+extern "C" const char *lp_status_string(lp_status s)
+{
+    switch (s) {
+    case LP_OK: return "ok";
+    case LP_EINVAL: return "invalid argument";
+    case LP_EUNSUPPORTED: return "unsupported problem";
+    case LP_EWORKSPACE: return "workspace or packed buffer too small";
+    case LP_EDEVICE: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+extern "C" lp_status lp_range(const float *x_dev, size_t count, int n, double loss_threshold,
+                              lp_qfmt *out_host, uint64_t *lost_host, uint64_t *workspace_dev,
+                              void *stream)
+{
+    if (!out_host || !workspace_dev || n < 2 || n > 16 || !(loss_threshold >= 0.0)) return LP_EINVAL;
+    if (count && (!x_dev || !aligned16(x_dev))) return LP_EINVAL;
+    hipStream_t st = as_stream(stream);
+    unsigned long long *hist = (unsigned long long *)workspace_dev;
+    hipLaunchKernelGGL(clear_words_kernel, dim3(1), dim3(64), 0, st, hist, LP_RANGE_WORKSPACE_WORDS);
+    if (count)
+        hipLaunchKernelGGL(range_f32_kernel, dim3(grid_for(count / 4)), dim3(kThreads), 0, st, x_dev,
+                           count, hist);
+    return finish_range(hist, count, n, loss_threshold, out_host, lost_host, st);
+}
+
+extern "C" lp_status lp_range_acc(const int64_t *acc_dev, size_t count, int f_acc, int relu, int n,
+                                  double loss_threshold, lp_qfmt *out_host, uint64_t *lost_host,
+                                  uint64_t *workspace_dev, void *stream)
+{
+    if (!out_host || !workspace_dev || n < 2 || n > 16 || !(loss_threshold >= 0.0) || f_acc < 0 ||
+        f_acc > 40)
+        return LP_EINVAL;
+    if (count && (!acc_dev || !aligned16(acc_dev))) return LP_EINVAL;
+    hipStream_t st = as_stream(stream);
+    unsigned long long *hist = (unsigned long long *)workspace_dev;
+    hipLaunchKernelGGL(clear_words_kernel, dim3(1), dim3(64), 0, st, hist, LP_RANGE_WORKSPACE_WORDS);
+    if (count)
+        hipLaunchKernelGGL(range_i64_kernel, dim3(grid_for(count / 2)), dim3(kThreads), 0, st,
+                           acc_dev, count, f_acc, relu ? 1 : 0, hist);
+    return finish_range(hist, count, n, loss_threshold, out_host, lost_host, st);
+}
+
+extern "C" lp_status lp_quantize(const float *x_dev, void *codes_dev, size_t count, lp_qfmt q,
+                                 lp_round r, uint64_t seed, uint64_t *zero_count_dev,
+                                 uint64_t *sat_count_dev, void *stream)
+{
+    if (!fmt_ok(q) || (int)r < 0 || (int)r > 2) return LP_EINVAL;
+    if (count == 0) return LP_OK;
+    if (!x_dev || !codes_dev || !aligned16(x_dev) || !aligned16(codes_dev)) return LP_EINVAL;
+    hipStream_t st = as_stream(stream);
+    const float scale = (float)(1 << q.f);
+    const float lo = -(float)(1 << (q.n - 1)), hi = (float)((1 << (q.n - 1)) - 1);
+    const bool wide = q.n > 8;
+#define LP_Q(T, M) launch_quantize<T, M>(x_dev, codes_dev, count, scale, lo, hi, seed, zero_count_dev, sat_count_dev, st)
+    if (wide) {
+        if (r == LP_ROUND_NEAREST_AWAY) LP_Q(int16_t, 0);
+        else if (r == LP_ROUND_NEAREST_EVEN) LP_Q(int16_t, 1);
+        else LP_Q(int16_t, 2);
+    } else {
+        if (r == LP_ROUND_NEAREST_AWAY) LP_Q(int8_t, 0);
+        else if (r == LP_ROUND_NEAREST_EVEN) LP_Q(int8_t, 1);
+        else LP_Q(int8_t, 2);
+    }
+#undef LP_Q
+    return launch_status();
+}
+
+extern "C" lp_status lp_act(const int64_t *acc_dev, size_t count, int f_acc, lp_qfmt qy, int relu,
+                            lp_round r, void *y_codes_dev, uint64_t *zero_count_dev, void *stream)
+{
+    if (!fmt_ok(qy) || f_acc < 0 || (r != LP_ROUND_NEAREST_AWAY && r != LP_ROUND_NEAREST_EVEN))
+        return LP_EINVAL;
+    const int s = f_acc - qy.f;
+    if (s > 62 || s < -31) return LP_EINVAL;
+    if (count == 0) return LP_OK;
+    if (!acc_dev || !y_codes_dev || !aligned16(acc_dev) || !aligned16(y_codes_dev)) return LP_EINVAL;
+    hipStream_t st = as_stream(stream);
+    const ActParams p = make_act_params(f_acc, qy, relu, r);
+    const int grid = grid_for(count / 8);
+    if (qy.n > 8)
+        hipLaunchKernelGGL(act_kernel<int16_t>, dim3(grid), dim3(kThreads), 0, st, acc_dev,
+                           (int16_t *)y_codes_dev, count, p, (unsigned long long *)zero_count_dev);
+    else
+        hipLaunchKernelGGL(act_kernel<int8_t>, dim3(grid), dim3(kThreads), 0, st, acc_dev,
+                           (int8_t *)y_codes_dev, count, p, (unsigned long long *)zero_count_dev);
+    return launch_status();
+}
+
+extern "C" lp_status lp_maxpool2x2(const void *x_codes_dev, void *y_codes_dev, int N, int H, int W,
+                                   int C, int n_bits, void *stream)
+{
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || (H & 1) || (W & 1) || n_bits < 2 || n_bits > 16)
+        return LP_EINVAL;
+    if (!x_codes_dev || !y_codes_dev || !aligned16(x_codes_dev) || !aligned16(y_codes_dev))
+        return LP_EINVAL;
+    hipStream_t st = as_stream(stream);
+    const int Ho = H / 2, Wo = W / 2;
+    const int per_vec = n_bits > 8 ? 8 : 16;
+    typedef short s8v __attribute__((ext_vector_type(8)));
+    typedef signed char c16v __attribute__((ext_vector_type(16)));
+    if (C % per_vec == 0) {
+        const int Cv = C / per_vec;
+        const size_t total = (size_t)N * Ho * Wo * Cv;
+        if (n_bits > 8)
+            hipLaunchKernelGGL(maxpool_vec_kernel<s8v>, dim3(grid_for(total)), dim3(kThreads), 0, st,
+                               (const s8v *)x_codes_dev, (s8v *)y_codes_dev, Ho, Wo, Cv, total);
+        else
+            hipLaunchKernelGGL(maxpool_vec_kernel<c16v>, dim3(grid_for(total)), dim3(kThreads), 0, st,
+                               (const c16v *)x_codes_dev, (c16v *)y_codes_dev, Ho, Wo, Cv, total);
+    } else {
+        const size_t total = (size_t)N * Ho * Wo * C;
+        if (n_bits > 8)
+            hipLaunchKernelGGL(maxpool_scalar_kernel<int16_t>, dim3(grid_for(total)), dim3(kThreads), 0,
+                               st, (const int16_t *)x_codes_dev, (int16_t *)y_codes_dev, Wo, C, total);
+        else
+            hipLaunchKernelGGL(maxpool_scalar_kernel<int8_t>, dim3(grid_for(total)), dim3(kThreads), 0,
+                               st, (const int8_t *)x_codes_dev, (int8_t *)y_codes_dev, Wo, C, total);
+    }
+    return launch_status();
+}

@@ -1,0 +1,80 @@
+"""Marshalling helpers for the GPU parity tests: numpy (oracle layout: NCHW, int32 codes) <->
+torch CUDA tensors (library layout: NHWC, int8/int16 codes).  No arithmetic of the method."""
+import numpy as np
+import torch
+
+import paper_1711_04713_amd as lp
+
+
+def code_np_dtype(n):
+    return np.int16 if n > 8 else np.int8
+
+
+def code_torch_dtype(n):
+    return torch.int16 if n > 8 else torch.int8
+
+
+def to_dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def counter():
+    return torch.zeros(1, dtype=torch.int64, device="cuda")
+
+
+def quantize(x, q, r=lp.LP_ROUND_NEAREST_AWAY, seed=0, counters=True):
+    """x: numpy float32 (any shape) -> (codes int32 numpy same shape, zeros, sats)."""
+    xd = to_dev(np.asarray(x, np.float32).reshape(-1))
+    codes = torch.empty(xd.numel(), dtype=code_torch_dtype(q[0]), device="cuda")
+    z, s = (counter(), counter()) if counters else (None, None)
+    lp.lp_quantize(xd, codes, q, r, seed, z, s)
+    torch.cuda.synchronize()
+    out = codes.cpu().numpy().astype(np.int32).reshape(np.shape(x))
+    return out, (int(z.item()) if counters else None), (int(s.item()) if counters else None)
+
+
+def conv(x_codes, qx, w_codes, qw, qy=None, relu=True, r=lp.LP_ROUND_NEAREST_AWAY, bias=None, qb=None,
+         stride=1, pad=1, want_acc=True, want_y=True):
+    """x_codes [N,Cin,H,W], w_codes [Cout,Cin,R,S] (numpy ints, oracle layout).
+    Returns dict(acc=[N,Cout,Ho,Wo] int64 or None, y=int32 codes or None, zeros=int, info=plan)."""
+    N, Cin, H, W = x_codes.shape
+    Cout, _, R, S = w_codes.shape
+    d = lp.ConvDesc(N, H, W, Cin, Cout, R, S, stride, pad)
+    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    xd = to_dev(x_codes.transpose(0, 2, 3, 1).astype(code_np_dtype(qx[0])))
+    wd = to_dev(w_codes.transpose(0, 2, 3, 1).astype(code_np_dtype(qw[0])))
+    packed = torch.empty(lp.lp_conv_packed_bytes(d, qx, qw), dtype=torch.uint8, device="cuda")
+    lp.lp_conv_pack_weights(d, qx, qw, wd, packed)
+    bd = to_dev(np.asarray(bias).astype(code_np_dtype(qb[0]))) if bias is not None else None
+    acc = torch.empty((N, Ho, Wo, Cout), dtype=torch.int64, device="cuda") if want_acc else None
+    y = torch.empty((N, Ho, Wo, Cout), dtype=code_torch_dtype(qy[0]), device="cuda") if (want_y and qy) else None
+    z = counter()
+    lp.lp_conv_fwd(d, xd, qx, packed, qw, qy=qy, y_codes=y, acc_out=acc, relu=relu, r=r, bias_codes=bd, qb=qb,
+                   zero_count=z)
+    torch.cuda.synchronize()
+    return {
+        "acc": acc.cpu().numpy().transpose(0, 3, 1, 2) if acc is not None else None,
+        "y": y.cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2) if y is not None else None,
+        "zeros": int(z.item()),
+        "info": lp.lp_conv_plan_info(d, qx, qw),
+    }
+
+
+def fc(x_codes, qx, w_codes, qw, qy=None, relu=True, r=lp.LP_ROUND_NEAREST_AWAY, bias=None, qb=None,
+       want_acc=True):
+    M, K = x_codes.shape
+    Nout = w_codes.shape[0]
+    xd = to_dev(x_codes.astype(code_np_dtype(qx[0])))
+    wd = to_dev(w_codes.astype(code_np_dtype(qw[0])))
+    packed = torch.empty(lp.lp_fc_packed_bytes(M, K, Nout, qx, qw), dtype=torch.uint8, device="cuda")
+    lp.lp_fc_pack_weights(M, K, Nout, qx, qw, wd, packed)
+    bd = to_dev(np.asarray(bias).astype(code_np_dtype(qb[0]))) if bias is not None else None
+    acc = torch.empty((M, Nout), dtype=torch.int64, device="cuda") if want_acc else None
+    y = torch.empty((M, Nout), dtype=code_torch_dtype(qy[0]), device="cuda") if qy else None
+    z = counter()
+    ws = torch.empty(max(lp.lp_fc_workspace_bytes(M, K, Nout, qx, qw), 16), dtype=torch.uint8, device="cuda")
+    lp.lp_fc_fwd(M, K, Nout, xd, qx, packed, qw, qy=qy, y_codes=y, acc_out=acc, relu=relu, r=r, bias_codes=bd,
+                 qb=qb, zero_count=z, workspace=ws)
+    torch.cuda.synchronize()
+    return {"acc": acc.cpu().numpy() if acc is not None else None,
+            "y": y.cpu().numpy().astype(np.int32) if y is not None else None, "zeros": int(z.item())}

@@ -1,0 +1,171 @@
+"""GPU parity: lp_conv_fwd / lp_fc_fwd against the CPU oracle, bit for bit (int64 accumulators,
+requantized codes, zero counts), through the C ABI."""
+import numpy as np
+import pytest
+
+import lp_inputs
+import paper_1711_04713_amd as lp
+from gpu_helpers import conv, fc, quantize
+
+pytestmark = pytest.mark.gpu
+
+QX, QW, QY = (16, 4, 12), (16, 1, 15), (16, 5, 11)
+
+
+def _codes(rng, shape, n=16, zero_frac=0.0, full_range=True):
+    if full_range:
+        c = rng.integers(-(1 << (n - 1)), 1 << (n - 1), shape)
+    else:
+        c = np.clip(np.round(rng.standard_normal(shape) * (1 << (n - 3))), -(1 << (n - 1)), (1 << (n - 1)) - 1)
+    c = c.astype(np.int32)
+    if zero_frac:
+        c[rng.random(shape) < zero_frac] = 0
+    return c
+
+
+def _check(oracle, x, w, qx, qw, qy, relu=True, bias=None, qb=None, stride=1, pad=1, expect_path=None,
+           modes=("away",)):
+    f_acc = qx[2] + qw[2]
+    want_acc = oracle.conv(x, w, bias=bias, f_acc=f_acc, fb=qb[2] if qb else 0, stride=stride, pad=pad, threads=8)
+    for mode in modes:
+        r_gpu = lp.LP_ROUND_NEAREST_AWAY if mode == "away" else lp.LP_ROUND_NEAREST_EVEN
+        r_cpu = oracle.ROUND_AWAY if mode == "away" else oracle.ROUND_EVEN
+        got = conv(x, qx, w, qw, qy=qy, relu=relu, r=r_gpu, bias=bias, qb=qb, stride=stride, pad=pad)
+        if expect_path is not None:
+            assert got["info"]["path"] == expect_path
+        assert np.array_equal(got["acc"], want_acc)
+        want_y, want_z = oracle.act(want_acc, f_acc, qy[0], qy[1], qy[2], relu, r_cpu)
+        assert np.array_equal(got["y"], want_y)
+        assert got["zeros"] == want_z
+    return got
+
+
+def test_config1_single_layer(oracle):
+    """Batch 1, 16->16 channels, 16x16, 3x3 pad 1; w ~N(0, 0.1) in Q1.15, x = ReLU(N(0,1)) in Q8.8,
+    output Q8.8 with ReLU and zero count; seed 0."""
+    xf, wf = lp_inputs.config1(seed=0)
+    qx, qw, qy = (16, 8, 8), (16, 1, 15), (16, 8, 8)
+    x, _, _ = quantize(xf, qx)
+    w, _, _ = quantize(wf, qw)
+    assert np.array_equal(x, oracle.quantize(xf, *qx)[0]) and np.array_equal(w, oracle.quantize(wf, *qw)[0])
+    got = _check(oracle, x, w, qx, qw, qy, expect_path=1, modes=("away", "even"))
+    assert 0.3 < got["zeros"] / got["y"].size < 0.7
+
+
+@pytest.mark.parametrize("N,Cin,H,W,Cout,R,S,pad", [
+    (2, 64, 20, 24, 64, 3, 3, 1),      # several tiles, ragged right/bottom edges
+    (1, 64, 33, 17, 128, 3, 3, 1),     # BN = 128
+    (3, 32, 14, 14, 64, 3, 3, 1),      # row strips that straddle images; half-filled channel chunk
+    (2, 128, 9, 9, 192, 3, 3, 1),      # two chunks, Cout padded to 256 (BN = 128), ragged channels
+    (2, 192, 7, 7, 40, 3, 3, 1),       # three chunks, Cout < 64
+    (1, 16, 40, 40, 16, 3, 3, 1),
+    (5, 64, 2, 2, 64, 3, 3, 1),        # tiny images, many boundaries per tile
+    (2, 64, 12, 12, 64, 1, 1, 0),      # 1x1
+    (1, 32, 16, 16, 32, 5, 5, 2),      # Table 1 kernel sizes
+    (1, 16, 18, 18, 32, 7, 7, 3),
+    (2, 64, 10, 10, 64, 3, 3, 0),      # no padding
+    (1, 32, 9, 30, 32, 3, 5, 2),       # non-square kernel, padding wider than (R-1)/2 vertically
+])
+def test_conv_two_limb_shapes(oracle, N, Cin, H, W, Cout, R, S, pad):
+    rng = np.random.default_rng(N * 131 + Cin + H)
+    x = _codes(rng, (N, Cin, H, W), zero_frac=0.5)
+    w = _codes(rng, (Cout, Cin, R, S))
+    _check(oracle, x, w, QX, QW, (16, 12, 4), pad=pad, expect_path=1)
+
+
+def test_conv_realistic_values_and_bias(oracle):
+    rng = np.random.default_rng(5)
+    x = np.maximum(_codes(rng, (2, 64, 18, 18), full_range=False), 0)
+    w = _codes(rng, (64, 64, 3, 3), full_range=False)
+    bias = _codes(rng, (64,))
+    for relu in (True, False):
+        _check(oracle, x, w, QX, QW, (16, 9, 7), relu=relu, bias=bias, qb=(16, 3, 13), modes=("away", "even"))
+    _check(oracle, x, w, QX, QW, (16, 9, 7), bias=(bias >> 8), qb=(8, 2, 6))      # 8-bit bias codes
+
+
+def test_conv_extreme_codes(oracle):
+    """All-minimum and all-maximum codes: the largest limb sums and int64 results the path can see."""
+    for xv, wv in ((-32768, -32768), (32767, -32768), (-32768, 32767), (32767, 32767)):
+        x = np.full((1, 512, 6, 6), xv, np.int32)
+        w = np.full((64, 512, 3, 3), wv, np.int32)
+        got = _check(oracle, x, w, QX, QW, (16, 15, 1), relu=False)
+        assert abs(int(got["acc"][0, 0, 2, 2])) == 9 * 512 * abs(xv) * abs(wv)
+
+
+@pytest.mark.parametrize("N,Cin,H,W,Cout", [(2, 64, 14, 14, 64), (1, 128, 28, 28, 128), (3, 48, 10, 12, 80), (2, 256, 7, 7, 64)])
+def test_conv_int8_single_limb(oracle, N, Cin, H, W, Cout):
+    rng = np.random.default_rng(Cin + H)
+    x = np.maximum(_codes(rng, (N, Cin, H, W), n=8), 0)
+    w = _codes(rng, (Cout, Cin, 3, 3), n=8)
+    _check(oracle, x, w, (8, 3, 5), (8, 1, 7), (8, 4, 4), expect_path=1, modes=("away", "even"))
+    _check(oracle, -x - 1, w, (8, 3, 5), (8, 1, 7), (8, 6, 2), relu=False, expect_path=1)
+
+
+def test_conv_mixed_widths_and_direct_path(oracle):
+    rng = np.random.default_rng(9)
+    x16, x8 = _codes(rng, (2, 32, 9, 9)), _codes(rng, (2, 32, 9, 9), n=8)
+    w16, w8 = _codes(rng, (24, 32, 3, 3)), _codes(rng, (24, 32, 3, 3), n=8)
+    _check(oracle, x16, w8, QX, (8, 1, 7), (16, 10, 6), expect_path=1)       # 8-bit weights on the two-limb kernel
+    _check(oracle, x8, w16, (8, 3, 5), QW, (16, 10, 6), expect_path=0)       # direct kernel
+    _check(oracle, x16, w16, QX, QW, QY, stride=2, expect_path=0)
+    # three input channels (first VGG16 layer), output to 8-bit codes
+    x3, w3 = _codes(rng, (2, 3, 20, 20)), _codes(rng, (64, 3, 3, 3))
+    _check(oracle, x3, w3, QX, QW, (8, 7, 1), expect_path=0)
+
+
+def test_conv_only_codes_or_only_accumulators(oracle):
+    rng = np.random.default_rng(10)
+    x, w = _codes(rng, (1, 64, 8, 8)), _codes(rng, (64, 64, 3, 3))
+    acc = oracle.conv(x, w)
+    got = conv(x, QX, w, QW, qy=None, want_y=False)
+    assert got["y"] is None and np.array_equal(got["acc"], acc) and got["zeros"] == 0
+    got = conv(x, QX, w, QW, qy=QY, want_acc=False)
+    y, z = oracle.act(acc, 27, *QY, True, oracle.ROUND_AWAY)
+    assert got["acc"] is None and np.array_equal(got["y"], y) and got["zeros"] == z
+
+
+def test_conv1_2_shaped_layer_small_batch(oracle):
+    """The conv1_2-shaped workload (64->64, 3x3) on a 56x56 crop, formats from the dynamic range."""
+    xf, wf = lp_inputs.config2(seed=1, batch=2, hw=56)
+    mx, mw = oracle.range_float(xf, 16)[0], oracle.range_float(wf, 16)[0]
+    qx, qw = (16, mx, 16 - mx), (16, mw, 16 - mw)
+    x, w = oracle.quantize(xf, *qx)[0], oracle.quantize(wf, *qw)[0]
+    acc = oracle.conv(x, w, threads=8)
+    mo = oracle.range_acc(acc, qx[2] + qw[2], True, 16)[0]
+    _check(oracle, x, w, qx, qw, (16, mo, 16 - mo), expect_path=1)
+
+
+# ------------------------------------------------------------------------------------ fc
+
+@pytest.mark.parametrize("M,K,Nout", [(4, 64, 10), (130, 200, 70), (256, 1024, 1000), (3, 4096, 129), (1, 8, 1)])
+def test_fc_matches_oracle(oracle, M, K, Nout):
+    rng = np.random.default_rng(M + K)
+    x, w = _codes(rng, (M, K), zero_frac=0.5), _codes(rng, (Nout, K))
+    bias = _codes(rng, (Nout,))
+    want = oracle.fc(x, w, bias=bias, f_acc=27, fb=15, threads=8)
+    for relu in (True, False):
+        got = fc(x, QX, w, QW, qy=(16, 14, 2), relu=relu, bias=bias, qb=(16, 1, 15))
+        assert np.array_equal(got["acc"], want)
+        y, z = oracle.act(want, 27, 16, 14, 2, relu, oracle.ROUND_AWAY)
+        assert np.array_equal(got["y"], y) and got["zeros"] == z
+
+
+def test_fc_extreme_k(oracle):
+    """K = 25088 with every code at the minimum: 25088 * 2^30 per output, the widest sum of the FC path."""
+    K = 25088
+    x = np.full((2, K), -32768, np.int32)
+    w = np.full((64, K), -32768, np.int32)
+    w[1] = 32767
+    got = fc(x, QX, w, QW, qy=(16, 16, 0), relu=False)
+    assert np.array_equal(got["acc"], oracle.fc(x, w, threads=8))
+    assert got["acc"][0, 0] == K * (1 << 30)
+
+
+def test_fc_int8(oracle):
+    rng = np.random.default_rng(3)
+    x, w = _codes(rng, (40, 512), n=8), _codes(rng, (100, 512), n=8)
+    want = oracle.fc(x, w)
+    got = fc(x, (8, 3, 5), w, (8, 1, 7), qy=(8, 8, 0), relu=True)
+    assert np.array_equal(got["acc"], want)
+    y, z = oracle.act(want, 12, 8, 8, 0, True, oracle.ROUND_AWAY)
+    assert np.array_equal(got["y"], y) and got["zeros"] == z

@@ -1,0 +1,137 @@
+"""CPU-only checks of the GPU library's host side: the shared object loads and exports every
+symbol include/lp.h declares, argument validation refuses bad calls before any launch, and the
+tile geometry the planner hands to the MFMA kernel addresses exactly the pixels the
+convolution's definition names (simulated here with the kernel's index formulas).
+No GPU compute is called."""
+import os
+import re
+
+import pytest
+
+import paper_1711_04713_amd as lp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+Q16 = (16, 4, 12)
+W16 = (16, 1, 15)
+Q8 = (8, 3, 5)
+W8 = (8, 1, 7)
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "lp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lp_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    if not os.path.exists(lp.lib_path()):
+        pytest.skip("liblp.so not built in this checkout (run __graft_entry__.build())")
+    lib = lp.load()
+    names = _declared_functions()
+    assert len(names) >= 15
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(lp.exported_symbols()) == names
+
+
+def test_status_strings_and_validation_without_gpu():
+    assert lp.lp_status_string(0) == "ok"
+    d = lp.ConvDesc(1, 8, 8, 16, 16, 3, 3, 1, 1)
+    with pytest.raises(lp.LpError) as e:
+        lp.lp_conv_packed_bytes(d, (16, 8, 7), W16)          # n != m + f
+    assert e.value.status == 1
+    with pytest.raises(lp.LpError) as e:
+        lp.lp_conv_packed_bytes(lp.ConvDesc(1, 8, 8, 16, 16, 3, 3, 0, 1), Q16, W16)   # stride 0
+    assert e.value.status == 1
+    with pytest.raises(lp.LpError) as e:
+        lp.lp_conv_packed_bytes(lp.ConvDesc(1, 1, 1, 65536, 16, 1, 1, 1, 0), Q16, W16)  # int32 limb sums could overflow
+    assert e.value.status == 2
+    with pytest.raises(lp.LpError) as e:
+        lp.lp_conv_packed_bytes(lp.ConvDesc(4096, 512, 512, 64, 64, 3, 3, 1, 1), Q16, W16)  # >= 2^31 elements
+    assert e.value.status == 2
+    assert lp.lp_conv_packed_bytes(d, Q16, W16) > 0
+    assert lp.lp_fc_packed_bytes(4, 64, 10, Q16, W16) >= 64 * 64 * 2
+    assert lp.lp_conv_workspace_bytes(d, Q16, W16) == 0
+
+
+def test_path_selection():
+    info = lp.lp_conv_plan_info(lp.ConvDesc(2, 16, 16, 64, 64, 3, 3, 1, 1), Q16, W16)
+    assert info["path"] == 1 and info["limbs"] == 2 and info["bn"] == 64
+    info = lp.lp_conv_plan_info(lp.ConvDesc(2, 16, 16, 64, 128, 3, 3, 1, 1), Q8, W8)
+    assert info["path"] == 1 and info["limbs"] == 1 and info["bn"] == 128
+    # 16-bit activations with 8-bit weights ride the two-limb kernel; the reverse, Cin = 3,
+    # and stride 2 take the direct kernel
+    assert lp.lp_conv_plan_info(lp.ConvDesc(2, 16, 16, 64, 64, 3, 3, 1, 1), Q16, W8)["path"] == 1
+    assert lp.lp_conv_plan_info(lp.ConvDesc(2, 16, 16, 64, 64, 3, 3, 1, 1), Q8, W16)["path"] == 0
+    assert lp.lp_conv_plan_info(lp.ConvDesc(2, 16, 16, 3, 64, 3, 3, 1, 1), Q16, W16)["path"] == 0
+    assert lp.lp_conv_plan_info(lp.ConvDesc(2, 16, 16, 64, 64, 3, 3, 2, 1), Q16, W16)["path"] == 0
+
+
+SHAPES = [
+    # N, H, W, Cin, Cout, R, S, pad
+    (1, 16, 16, 16, 16, 3, 3, 1),
+    (2, 224, 224, 64, 64, 3, 3, 1),
+    (3, 112, 112, 64, 128, 3, 3, 1),
+    (5, 56, 56, 128, 256, 3, 3, 1),
+    (7, 28, 28, 256, 512, 3, 3, 1),
+    (32, 14, 14, 512, 512, 3, 3, 1),
+    (3, 13, 11, 32, 48, 3, 3, 1),
+    (2, 9, 20, 16, 200, 5, 5, 2),
+    (2, 18, 18, 64, 64, 7, 7, 3),
+    (4, 10, 10, 64, 64, 3, 3, 0),
+    (2, 12, 12, 64, 64, 1, 1, 0),
+    (2, 6, 40, 32, 32, 3, 5, 2),
+    (300, 1, 1, 4096, 1000, 1, 1, 0),      # FC as a 1x1 conv over a 1x1 image
+    (130, 2, 2, 64, 64, 3, 3, 1),          # many image boundaries inside one tile
+    (1, 3, 200, 16, 16, 3, 3, 1),
+]
+
+
+@pytest.mark.parametrize("N,H,W,Cin,Cout,R,S,pad", SHAPES)
+def test_tile_geometry_addresses_the_right_pixels(N, H, W, Cin, Cout, R, S, pad):
+    """Re-run the kernel's table construction for every tile: each output pixel is produced by
+    exactly one tile row, and tap (r, s) of that row reads input pixel (y+r-pad, x+s-pad) of the
+    same image, or the zero code outside the image; every staged index stays inside the patch."""
+    info = lp.lp_conv_plan_info(lp.ConvDesc(N, H, W, Cin, Cout, R, S, 1, pad), Q16, W16)
+    assert info["path"] == 1
+    RH, TW, PRA, PW = info["tile_rows"], info["tile_cols"], info["patch_rows"], info["patch_cols"]
+    Ho, Wo, Hp = H + 2 * pad - R + 1, W + 2 * pad - S + 1, H + 2 * pad
+    FR = N * Ho
+    assert RH * TW <= 128 and PW == TW + S - 1
+    tiles_r, tiles_c = -(-FR // RH), -(-Wo // TW)
+    assert info["tiles_m"] == tiles_r * tiles_c
+    assert info["lds_bytes"] <= 80 * 1024
+    NPIXA = PRA * PW
+    seen = set()
+    # every tile when there are few; otherwise the first, the last and a spread in between
+    rows = range(tiles_r) if tiles_r <= 64 else sorted(set([0, 1, tiles_r - 2, tiles_r - 1] + list(range(0, tiles_r, max(1, tiles_r // 50)))))
+    for tile_r in rows:
+        fr0 = tile_r * RH
+        vr0 = (fr0 // Ho) * Hp + fr0 % Ho
+        for tile_c in range(tiles_c):
+            x0 = tile_c * TW
+            tab = []
+            for p in range(NPIXA):
+                pr, pc = divmod(p, PW)
+                vr = vr0 + pr
+                n, iy, ix = vr // Hp, vr % Hp - pad, x0 - pad + pc
+                ok = n < N and 0 <= iy < H and 0 <= ix < W
+                tab.append((n * H + iy) * W + ix if ok else -1)
+            for m in range(128):
+                j, t = divmod(m, TW)
+                fr, xo = fr0 + j, x0 + t
+                if not (j < RH and fr < FR and xo < Wo):
+                    continue
+                n, yo = divmod(fr, Ho)
+                out = fr * Wo + xo
+                assert out not in seen
+                seen.add(out)
+                base = ((fr // Ho) * Hp + fr % Ho - vr0) * PW + t
+                assert 0 <= base and base + (R - 1) * PW + (S - 1) < NPIXA
+                for r in (0, R // 2, R - 1):
+                    for s in (0, S // 2, S - 1):
+                        iy, ix = yo + r - pad, xo + s - pad
+                        want = (n * H + iy) * W + ix if (0 <= iy < H and 0 <= ix < W) else -1
+                        assert tab[base + r * PW + s] == want
+    if tiles_r <= 64:
+        assert len(seen) == FR * Wo
