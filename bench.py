@@ -1,0 +1,155 @@
+#!/usr/bin/env python3
+"""Benchmark: VGG16 16-bit fixed-point conv-stack forward on one MI355X.
+
+A step = one pass of the whole hot path over one synthetic batch already resident in HBM:
+lp_quantize of the float input, 13 x lp_conv_fwd (int8-MFMA implicit GEMM, exact two-limb
+16-bit arithmetic, fused LPAct + ReLU + zero count) and the 5 max-pools.  Weights are
+quantized/packed and per-layer formats calibrated beforehand (untimed, as the paper does
+offline).  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+INT8_PEAK_TOPS = 5000.0     # MI355X dense int8 MFMA, published (5.0 POP/s)
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--calib", type=int, default=2, help="images used to fix the per-layer formats")
+    ap.add_argument("--cpu-images", type=int, default=2, help="images the CPU oracle is timed on (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards by batch, see DESIGN.md",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import lp_inputs
+    import paper_1711_04713_amd as lp
+    from paper_1711_04713_amd.stack import ConvStack
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    lp.load()        # raises if liblp.so is not built: there is no fallback
+    torch.cuda.set_device(0)
+    B = args.batch
+
+    x_np = lp_inputs.config3_input(seed=2, batch=B)                       # U(0,1) images, NCHW
+    w_np = lp_inputs.vgg16_conv_weights(seed=2)                           # He-normal
+    pools = [p for (_, _, _, _, p) in lp_inputs.VGG16_CONV]
+    x = torch.from_numpy(np.ascontiguousarray(x_np.transpose(0, 2, 3, 1))).cuda()
+    ws = [torch.from_numpy(np.ascontiguousarray(w.transpose(0, 2, 3, 1))).cuda() for w in w_np]
+
+    stack = ConvStack(ws, pools, n_act=16, n_w=16)
+    stack.calibrate(x[:args.calib])
+    stack.prepare(B, 224, 224)
+
+    for _ in range(args.warmup):
+        stack.forward(x)
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        stack.forward(x, events)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    # per-launch durations from the HIP events recorded on the launch stream
+    per = {}
+    for label, a, b in events:
+        per.setdefault(label, []).append(a.elapsed_time(b))
+    avg = {k: sum(v) / len(v) for k, v in per.items()}
+    zeros = stack.zero_counts.cpu().numpy()
+    layers = []
+    total_macs = 0
+    kern_ops, kern_ms = {}, {}
+    for i, L in enumerate(stack.layers):
+        name = lp_inputs.VGG16_CONV[i][0]
+        ms = avg["conv%d" % i]
+        macs = L["macs"]
+        total_macs += macs
+        info = L["info"]
+        kname = "conv_mfma_kernel<%d,%d>" % (info["limbs"], info["bn"] // 64) if info["path"] == 1 else "conv_direct_kernel"
+        kern_ops[kname] = kern_ops.get(kname, 0) + 8 * macs          # 4 int8 limb MACs = 8 int8 ops per 16-bit MAC
+        kern_ms[kname] = kern_ms.get(kname, 0.0) + ms
+        layers.append({
+            "layer": name, "ms": round(ms, 4), "format_in": repr(L["qx"]), "format_w": repr(L["qw"]),
+            "format_out": repr(L["qy"]), "sparsity": round(float(zeros[i]) / L["y"].numel(), 4),
+            "int8_tops": round(8 * macs / (ms * 1e-3) / 1e12, 1), "kernel": kname,
+            "tile": [info["tile_rows"], info["tile_cols"], info["bn"]],
+        })
+    dominant = max(kern_ms, key=kern_ms.get)
+    achieved = kern_ops[dominant] / (kern_ms[dominant] * 1e-3) / 1e12
+    images_per_s = B / (ms_per_step * 1e-3)
+    useful_tops = 2 * total_macs / (ms_per_step * 1e-3) / 1e12
+    int8_tops = 4 * useful_tops
+
+    out = {
+        "metric": "VGG16 16-bit fixed-point conv fwd images/s",
+        "value": round(images_per_s, 1),
+        "unit": "images/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int16 codes as 2x int8 limbs, int32/int64 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "VGG16 conv stack (13 conv 3x3 pad 1 + 5 max-pool), 16-bit weights and activations, "
+                               "per-layer Qm.f from dynamic range", "batch": B, "input": "3x224x224 U(0,1)",
+                   "calibration_images": args.calib},
+        "int_mac_tops_useful": round(useful_tops, 2),
+        "int8_mfma_tops": round(int8_tops, 1),
+        "pct_of_int8_mfma_peak": round(100.0 * int8_tops / INT8_PEAK_TOPS, 2),
+        "roofline": {
+            "bound": "mfma", "kernel": dominant, "achieved": round(achieved, 1), "peak": INT8_PEAK_TOPS,
+            "unit": "TOP/s", "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": None,
+            "launches_per_step": sum(1 for l in layers if l["kernel"] == dominant),
+            "ms_per_step_in_kernel": round(kern_ms[dominant], 4),
+        },
+        "other_kernels_ms": {k: round(v, 4) for k, v in avg.items() if not k.startswith("conv")},
+        "layers": layers,
+    }
+    in_bytes = x.numel() * 4 + stack.x_codes.numel() * 2
+    out["quantize_gbs"] = round(in_bytes / (avg["quantize"] * 1e-3) / 1e9, 1)
+
+    if args.cpu_images > 0:
+        import oracle
+        from oracle import vgg as ovgg
+
+        nimg = min(args.cpu_images, B)
+        threads = min(os.cpu_count() or 1, len(os.sched_getaffinity(0)), 16)
+        frozen = [{"mx": stack.qx.m, "mw": stack.qw[i].m, "mo": stack.qy[i].m} for i in range(len(pools))]
+        t0 = time.perf_counter()
+        ref = ovgg.conv_stack(x_np[:nimg], w_np, pools, n=16, threads=threads, formats=frozen, keep_codes=False)
+        cpu_s = time.perf_counter() - t0
+        got = stack.layers[-1]["pooled"][:nimg].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2)
+        out["cpu_baseline"] = {
+            "value": round(nimg / cpu_s, 4), "unit": "images/s", "cores": threads, "kind": "oracle",
+            "sample": "first %d image(s) of the same batch, whole 13-layer stack, frozen formats, gcc -O2 direct loops, "
+                      "OpenMP over (image, output channel); includes weight quantization" % nimg,
+            "seconds": round(cpu_s, 2),
+            "matches_gpu_final_codes": bool(np.array_equal(got, ref["final"])),
+        }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

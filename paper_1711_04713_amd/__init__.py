@@ -3,6 +3,7 @@ the C-ABI library liblp.so declared in include/lp.h.  All arithmetic runs in the
 kernels; this package only marshals arguments (torch is used for device memory and streams).
 """
 from .binding import (  # noqa: F401
+    LP_RANGE_WORKSPACE_WORDS,
     LP_ROUND_NEAREST_AWAY,
     LP_ROUND_NEAREST_EVEN,
     LP_ROUND_STOCHASTIC,

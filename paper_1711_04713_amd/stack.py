@@ -1,0 +1,127 @@
+"""Host-side sequencing of the C-ABI calls for a stack of low-precision layers (Sec. 2.1
+workflow: quantize -> [LPConvolution -> LPAct+ReLU -> optional 2x2 max-pool] x L).
+
+Only launches and buffer bookkeeping live here; every number is produced by the kernels
+behind include/lp.h.  Activations are NHWC torch tensors on the GPU.
+"""
+import torch
+
+from . import binding as lp
+
+
+class ConvStack:
+    """A chain of 3x3/stride-1/pad-1 low-precision conv layers with frozen per-layer formats.
+
+    weights: list of float32 CUDA tensors [Cout][R][S][Cin]; pool_after: list of bool.
+    n_act / n_w: total bits of activations / weights.  Formats are fixed by calibrate().
+    """
+
+    def __init__(self, weights, pool_after, n_act=16, n_w=16, loss_threshold=0.0, r=lp.LP_ROUND_NEAREST_AWAY,
+                 pad=1):
+        assert len(weights) == len(pool_after)
+        self.n_act, self.n_w, self.thr, self.r, self.pad = n_act, n_w, loss_threshold, r, pad
+        self.pool_after = list(pool_after)
+        self.w_float = weights
+        self.range_ws = torch.empty(lp.LP_RANGE_WORKSPACE_WORDS, dtype=torch.int64, device="cuda")
+        # weight formats and codes: Sec. 2.3 rule on the weights themselves (done once, offline)
+        self.qw, self.w_codes = [], []
+        for w in weights:
+            q, _ = lp.lp_range(w.reshape(-1), n_w, loss_threshold, self.range_ws)
+            codes = torch.empty(w.shape, dtype=torch.int16 if n_w > 8 else torch.int8, device="cuda")
+            lp.lp_quantize(w.reshape(-1), codes, q, r)
+            self.qw.append(q)
+            self.w_codes.append(codes)
+        self.qx = None        # input format
+        self.qy = []          # per-layer output formats
+        self.plans = None
+
+    def _desc(self, i, N, H, W):
+        cout, R, S, cin = self.w_float[i].shape
+        return lp.ConvDesc(N, H, W, cin, cout, R, S, 1, self.pad)
+
+    def calibrate(self, x_float):
+        """Fix the input format and every layer's output format from the dynamic range seen on
+        this (small) batch: raw int64 accumulators -> lp_range_acc -> lp_act -> pool -> next."""
+        N, H, W, _ = x_float.shape
+        dt = torch.int16 if self.n_act > 8 else torch.int8
+        self.qx, _ = lp.lp_range(x_float.reshape(-1), self.n_act, self.thr, self.range_ws)
+        cur = torch.empty(x_float.shape, dtype=dt, device="cuda")
+        lp.lp_quantize(x_float.reshape(-1), cur, self.qx, self.r)
+        q_in = self.qx
+        self.qy = []
+        for i, pool in enumerate(self.pool_after):
+            d = self._desc(i, N, H, W)
+            packed = torch.empty(lp.lp_conv_packed_bytes(d, q_in, self.qw[i]), dtype=torch.uint8, device="cuda")
+            lp.lp_conv_pack_weights(d, q_in, self.qw[i], self.w_codes[i], packed)
+            acc = torch.empty((N, H, W, d.Cout), dtype=torch.int64, device="cuda")
+            lp.lp_conv_fwd(d, cur, q_in, packed, self.qw[i], acc_out=acc, r=self.r)
+            f_acc = q_in.f + self.qw[i].f
+            qy, _ = lp.lp_range_acc(acc.reshape(-1), f_acc, True, self.n_act, self.thr, self.range_ws)
+            y = torch.empty((N, H, W, d.Cout), dtype=dt, device="cuda")
+            lp.lp_act(acc.reshape(-1), f_acc, qy, True, y, self.r)
+            if pool:
+                p = torch.empty((N, H // 2, W // 2, d.Cout), dtype=dt, device="cuda")
+                lp.lp_maxpool2x2(y, p, N, H, W, d.Cout, self.n_act)
+                y, H, W = p, H // 2, W // 2
+            self.qy.append(qy)
+            cur, q_in = y, qy
+        torch.cuda.synchronize()
+        return self.qx, self.qy
+
+    def set_formats(self, qx, qy):
+        self.qx, self.qy = lp.QFmt(*qx), [lp.QFmt(*q) for q in qy]
+
+    def prepare(self, N, H, W):
+        """Pack weights for the frozen formats and allocate every buffer of a forward pass."""
+        assert self.qx is not None, "calibrate() or set_formats() first"
+        dt = torch.int16 if self.n_act > 8 else torch.int8
+        self.in_shape = (N, H, W, self.w_float[0].shape[3])
+        self.x_codes = torch.empty(self.in_shape, dtype=dt, device="cuda")
+        self.zero_counts = torch.zeros(len(self.pool_after), dtype=torch.int64, device="cuda")
+        self.layers = []
+        q_in = self.qx
+        for i, pool in enumerate(self.pool_after):
+            d = self._desc(i, N, H, W)
+            packed = torch.empty(lp.lp_conv_packed_bytes(d, q_in, self.qw[i]), dtype=torch.uint8, device="cuda")
+            lp.lp_conv_pack_weights(d, q_in, self.qw[i], self.w_codes[i], packed)
+            y = torch.empty((N, H, W, d.Cout), dtype=dt, device="cuda")
+            p = None
+            if pool:
+                p = torch.empty((N, H // 2, W // 2, d.Cout), dtype=dt, device="cuda")
+            self.layers.append({"desc": d, "packed": packed, "qx": q_in, "qw": self.qw[i], "qy": self.qy[i], "y": y,
+                                "pooled": p, "H": H, "W": W, "macs": N * H * W * d.Cout * d.R * d.S * d.Cin,
+                                "info": lp.lp_conv_plan_info(d, q_in, self.qw[i])})
+            if pool:
+                H, W = H // 2, W // 2
+            q_in = self.qy[i]
+        torch.cuda.synchronize()
+
+    def forward(self, x_float, events=None):
+        """One pass over the batch: input quantize + every conv (+fused LPAct/ReLU/zero count) +
+        pools.  events (optional): list to which (label, start_event, end_event) are appended."""
+        assert tuple(x_float.shape) == self.in_shape
+        self.zero_counts.zero_()
+
+        def timed(label, fn):
+            if events is None:
+                fn()
+                return
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            events.append((label, a, b))
+
+        timed("quantize", lambda: lp.lp_quantize(x_float.reshape(-1), self.x_codes, self.qx, self.r))
+        cur = self.x_codes
+        for i, L in enumerate(self.layers):
+            timed("conv%d" % i, lambda L=L, cur=cur, i=i: lp.lp_conv_fwd(
+                L["desc"], cur, L["qx"], L["packed"], L["qw"], qy=L["qy"], y_codes=L["y"], relu=True, r=self.r,
+                zero_count=self.zero_counts[i:i + 1]))
+            cur = L["y"]
+            if L["pooled"] is not None:
+                d = L["desc"]
+                timed("pool%d" % i, lambda L=L, d=d: lp.lp_maxpool2x2(L["y"], L["pooled"], d.N, L["H"], L["W"], d.Cout,
+                                                                       self.n_act))
+                cur = L["pooled"]
+        return cur
