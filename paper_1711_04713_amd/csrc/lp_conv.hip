@@ -13,7 +13,10 @@
 // pixels are RH consecutive rows (of the N*Ho stacked output rows) x TW columns; the
 // input patch they need, (rows + R-1) x (TW + S-1) pixels x 64 channels, is staged in LDS
 // once per 64-channel chunk and every tap reads it at a shifted offset (implicit GEMM with
-// halo reuse).  Weights stream through LDS one (tap, chunk) slab at a time.
+// halo reuse).  Weights stream through LDS one (tap, chunk) slab at a time, double
+// buffered: the next slab's global loads are in flight while the current one feeds the MFMAs.
+// Layers with very few input channels (the first VGG16 layer, Cin = 3) use the "flat"
+// variant: the whole R*S*Cin window is one K <= 64 slab gathered per output pixel.
 #include <algorithm>
 #include <mutex>
 #include <utility>
@@ -33,6 +36,8 @@ enum { PATH_DIRECT = 0, PATH_MFMA = 1 };
 struct Plan {
     int path;
     int limbs;   // 1: int8 x int8, 2: 16-bit x 16-bit
+    int flat;    // whole window gathered as one K <= 64 slab (tiny Cin)
+    int taps, ksteps; // slabs per chunk, K=32 MFMA steps per slab
     int Ho, Wo, Hp, FR;
     int nchunks, CoutP, BN;
     int RH, TW, PW, PRA, NPIXA;
@@ -50,11 +55,15 @@ static bool desc_ok(const lp_conv_desc *d)
            d->W + 2 * d->pad >= d->S;
 }
 
-static size_t mfma_lds_bytes(int limbs, int npixa, int bn)
+// LDS: tables (2*ntab + 2*BM ints), staged patch (arows pixels per limb plane), two weight slabs
+static size_t mfma_lds_bytes(int limbs, int npixa, int bn, int flat)
 {
-    size_t tables = round_up((size_t)(2 * npixa + 2 * BM) * 4, 16);
-    return tables + (size_t)limbs * npixa * PS + (size_t)limbs * bn * PS;
+    const int ntab = std::max(npixa, BM);
+    const int arows = flat ? BM : npixa;
+    size_t tables = round_up((size_t)(2 * ntab + 2 * BM) * 4, 16);
+    return tables + (size_t)limbs * arows * PS + (size_t)2 * limbs * bn * PS;
 }
+constexpr size_t kLdsBudget = 80000; // two workgroups per CU within the 160 KB of LDS
 
 // virtual row (in the stack of zero-padded images, Hp rows each) of stacked output row fr
 static inline int vrow(int fr, int Ho, int Hp) { return (fr / Ho) * Hp + fr % Ho; }
@@ -117,7 +126,9 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
     p.limbs = x16 ? 2 : 1;
     p.path = PATH_DIRECT;
     const int cvec = x16 ? 8 : 16; // codes per 16-byte load
-    if (d->stride == 1 && (x16 || !w16) && d->Cin % cvec == 0 && d->Cin >= 16) {
+    const bool chunked = d->Cin % cvec == 0 && d->Cin >= 16;
+    p.flat = (!chunked && x16 && K <= 64) ? 1 : 0;
+    if (d->stride == 1 && (x16 || !w16) && (chunked || p.flat)) {
         // tile search: RH x TW <= 128 output pixels, minimise wasted MFMA rows, then patch size
         const int RS = d->R * d->S;
         double best = 1e300;
@@ -130,7 +141,7 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
                 const int cross = (p.Ho % rh == 0) ? 0 : std::min((rh - 1 + p.Ho - 1) / p.Ho, d->N - 1);
                 const int pra = rh + d->R - 1 + cross * (d->R - 1);
                 const int npixa = pra * pw;
-                if (mfma_lds_bytes(p.limbs, npixa, 128) > 72 * 1024) continue;
+                if (mfma_lds_bytes(p.limbs, npixa, 128, p.flat) > kLdsBudget) continue;
                 const double cost = (double)tiles_c * tiles_r * ((double)BM * RS + 0.5 * npixa);
                 if (cost < best) {
                     best = cost;
@@ -141,13 +152,17 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
         if (best < 1e300) p.path = PATH_MFMA;
     }
     if (p.path == PATH_MFMA) {
-        p.nchunks = (d->Cin + CK - 1) / CK;
+        p.nchunks = p.flat ? 1 : (d->Cin + CK - 1) / CK;
+        p.taps = p.flat ? 1 : d->R * d->S;
+        p.ksteps = p.flat ? (int)((K + 31) / 32) : 2;
         p.CoutP = (int)round_up(d->Cout, 64);
-        p.BN = (p.CoutP % 128 == 0) ? 128 : 64;
         p.tiles_m = p.tiles_r * p.tiles_c;
+        // 128-wide channel tiles halve the patch re-reads, but a grid with fewer workgroups than
+        // the chip has slots (256 CUs x 2) is better cut finer
+        p.BN = (p.CoutP % 128 == 0 && (long long)p.tiles_m * (p.CoutP / 128) >= 512) ? 128 : 64;
         p.tiles_n = p.CoutP / p.BN;
-        p.lds_bytes = mfma_lds_bytes(p.limbs, p.NPIXA, p.BN);
-        p.corr_offset = round_up((size_t)d->R * d->S * p.nchunks * p.limbs * p.CoutP * CK, 256);
+        p.lds_bytes = mfma_lds_bytes(p.limbs, p.NPIXA, p.BN, p.flat);
+        p.corr_offset = round_up((size_t)p.taps * p.nchunks * p.limbs * p.CoutP * CK, 256);
         p.packed_bytes = p.corr_offset + (size_t)p.CoutP * sizeof(int64_t);
     } else {
         // direct path keeps a plain int16 copy of the weights
@@ -177,7 +192,7 @@ __global__ void pack_weights_kernel(const WT *__restrict__ w, unsigned char *__r
         int hi = 0, lo = 0;
         if (co < Cout && ci < Cin) {
             const int code = (int)w[((size_t)co * RS + tap) * Cin + ci];
-            if (LIMBS == 2) {
+            if constexpr (LIMBS == 2) {
                 hi = code >> 8;
                 lo = (code & 255) - 128;
             } else {
@@ -186,8 +201,26 @@ __global__ void pack_weights_kernel(const WT *__restrict__ w, unsigned char *__r
         }
         const size_t base = (((size_t)tap * nchunks + chunk) * LIMBS) * CoutP;
         out[(base + co) * CK + kk] = (unsigned char)hi;
-        if (LIMBS == 2) out[(base + CoutP + co) * CK + kk] = (unsigned char)lo;
+        if constexpr (LIMBS == 2) out[(base + CoutP + co) * CK + kk] = (unsigned char)lo;
     }
+}
+
+// Flat layout: one slab [limb][CoutP][64], byte k of a row = weight k of the (r, s, ci) window.
+template <typename WT>
+__global__ void pack_weights_flat_kernel(const WT *__restrict__ w, unsigned char *__restrict__ out,
+                                         int Cout, int K, int CoutP)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= CoutP * CK) return;
+    const int kk = i % CK, co = i / CK;
+    int hi = 0, lo = 0;
+    if (co < Cout && kk < K) {
+        const int code = (int)w[(size_t)co * K + kk];
+        hi = code >> 8;
+        lo = (code & 255) - 128;
+    }
+    out[(size_t)co * CK + kk] = (unsigned char)hi;
+    out[((size_t)CoutP + co) * CK + kk] = (unsigned char)lo;
 }
 
 // corr[co] = 128 * sum_k w[co][k] - 16384 * K for the two-limb path, 0 otherwise.
@@ -228,9 +261,10 @@ struct ConvArgs {
     unsigned long long *zero_count;
     int N, H, W, Cin, Cout, R, S, stride, pad;
     int Ho, Wo, Hp, FR;
-    int RH, TW, PW, NPIXA;
-    int tiles_c, tiles_n, CoutP, nchunks;
+    int RH, TW, PW, NPIXA, NTAB, AROWS;
+    int tiles_c, tiles_n, CoutP, nchunks, taps, ksteps, Kflat;
     int total_work, per_xcd;
+    int fast; // 32-bit requantization is exact for this call (see epilogue)
     ActParams act;
 };
 
@@ -295,13 +329,35 @@ __device__ __forceinline__ v16i mfma_i8(v4i a, v4i b, v16i c)
     return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
 }
 
+// Requantization of v = 65536*hi + lo16 (hi = floor(v / 65536), 0 <= lo16 < 65536) to
+// clamp(floor((v + 2^(s-1)) / 2^s), 0, cmax) in 32-bit arithmetic, 1 <= s <= 31.  Negative v
+// give 0 (ReLU).  S16: 0 for s >= 17 (lo16 cannot matter), 1 for s == 16, 2 for s <= 15.
+template <int S16>
+__device__ __forceinline__ int requant_relu32(int hi, int lo16, int s, int cmax)
+{
+    int q;
+    if (S16 == 0) {
+        q = (hi + (1 << (s - 17))) >> (s - 16);
+    } else if (S16 == 1) {
+        q = hi + (lo16 >> 15);
+    } else {
+        const int h = hi < 32768 ? hi : 32768; // beyond this the result saturates anyway
+        q = (h << (16 - s)) + ((lo16 + (1 << (s - 1))) >> s);
+    }
+    return min(max(q, 0), cmax); // compiles to v_med3_i32
+}
+
 // LIMBS: 1 (int8 codes) or 2 (16-bit codes as two int8 limbs).  NB: 32-column blocks per
 // wave; the workgroup covers BN = 64*NB output channels with 2x2 waves of 64 x 32*NB each.
-template <int LIMBS, int NB>
+// FLAT: the window is gathered as one slab per output pixel instead of staging a patch.
+template <int LIMBS, int NB, bool FLAT>
 __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvArgs a)
 {
     constexpr int BN = 64 * NB;
     constexpr int NACC = (LIMBS == 2) ? 3 : 1;
+    constexpr int BPL = BN * PS;              // bytes per limb plane of a weight slab
+    constexpr int BSLAB = LIMBS * BPL;        // bytes per weight slab buffer
+    constexpr int BITEMS = LIMBS * BN * 4 / kConvThreads; // 16-byte pieces of a slab per thread
     extern __shared__ __align__(16) unsigned char smem[];
 
     // XCD-aware work order: consecutive workgroup ids land on the 8 XCDs round-robin, so
@@ -317,21 +373,23 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
 
     const int NPIXA = a.NPIXA;
     int *tab = (int *)smem;          // staged pixel -> input pixel index, -1 outside the image
-    int *psum = tab + NPIXA;         // per staged pixel: sum of its codes over all channels
-    int *outoff = psum + NPIXA;      // tile row -> output pixel index, -1 if not an output
+    int *psum = tab + a.NTAB;        // per staged pixel (FLAT: per tile row): sum of its codes
+    int *outoff = psum + a.NTAB;     // tile row -> output pixel index, -1 if not an output
     int *abase_s = outoff + BM;      // tile row -> staged pixel of its (r=0, s=0) tap
-    unsigned char *Asm = smem + (((size_t)(2 * NPIXA + 2 * BM) * 4 + 15) & ~(size_t)15);
-    unsigned char *Bsm = Asm + (size_t)LIMBS * NPIXA * PS;
-    const int APL = NPIXA * PS;      // bytes per limb plane of the patch
-    constexpr int BPL = BN * PS;
+    unsigned char *Asm = smem + (((size_t)(2 * a.NTAB + 2 * BM) * 4 + 15) & ~(size_t)15);
+    const int APL = a.AROWS * PS;    // bytes per limb plane of the staged activations
+    unsigned char *Bsm = Asm + (size_t)LIMBS * APL;
 
     const int tid = threadIdx.x;
-    for (int p = tid; p < NPIXA; p += kConvThreads) {
-        const int pr = p / a.PW, pc = p % a.PW;
-        const int vr = vr0 + pr;
-        const int n = vr / a.Hp, iy = vr % a.Hp - a.pad, ix = x0 - a.pad + pc;
-        const bool ok = n < a.N && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
-        tab[p] = ok ? (n * a.H + iy) * a.W + ix : -1;
+    for (int p = tid; p < a.NTAB; p += kConvThreads) {
+        int g = -1;
+        if (p < NPIXA) {
+            const int pr = p / a.PW, pc = p % a.PW;
+            const int vr = vr0 + pr;
+            const int n = vr / a.Hp, iy = vr % a.Hp - a.pad, ix = x0 - a.pad + pc;
+            if (n < a.N && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) g = (n * a.H + iy) * a.W + ix;
+        }
+        tab[p] = g;
         psum[p] = 0;
     }
     for (int m = tid; m < BM; m += kConvThreads) {
@@ -341,6 +399,30 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
         outoff[m] = ok ? fr * a.Wo + xo : -1;
         abase_s[m] = ok ? ((fr / a.Ho) * a.Hp + fr % a.Ho - vr0) * a.PW + t : 0;
     }
+
+    // weight slabs: slab t = chunk * taps + tap lives at [tap][chunk][limb][CoutP][64]
+    const int nslabs = a.nchunks * a.taps;
+    v4i breg[BITEMS];
+    auto load_slab = [&](int t) {
+        const int cc = t / a.taps, tap = t - cc * a.taps;
+        const unsigned char *src =
+            a.wp + (((size_t)tap * a.nchunks + cc) * LIMBS * a.CoutP + (size_t)ntile * BN) * CK;
+#pragma unroll
+        for (int j = 0; j < BITEMS; ++j) {
+            const int i = tid + j * kConvThreads;
+            const int lb = i / (BN * 4), rem = i - lb * (BN * 4);
+            breg[j] = *(const v4i *)(src + ((size_t)lb * a.CoutP + (rem >> 2)) * CK + (rem & 3) * 16);
+        }
+    };
+    auto store_slab = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < BITEMS; ++j) {
+            const int i = tid + j * kConvThreads;
+            const int lb = i / (BN * 4), rem = i - lb * (BN * 4);
+            *(v4i *)(Bsm + buf * BSLAB + lb * BPL + (rem >> 2) * PS + (rem & 3) * 16) = breg[j];
+        }
+    };
+    load_slab(0);
     __syncthreads();
 
     const int lane = tid & 63, wave = tid >> 6;
@@ -348,7 +430,10 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
     const int l32 = lane & 31, kg = lane >> 5;
     int aoff[2], boff[NB];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb) aoff[mb] = abase_s[wm * 64 + mb * 32 + l32] * PS + kg * 16;
+    for (int mb = 0; mb < 2; ++mb) {
+        const int row = wm * 64 + mb * 32 + l32;
+        aoff[mb] = (FLAT ? row : abase_s[row]) * PS + kg * 16;
+    }
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) boff[nb] = (wn * (NB * 32) + nb * 32 + l32) * PS + kg * 16;
 
@@ -362,11 +447,42 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[mb][nb][q][v] = 0;
 
-    const int RS = a.R * a.S;
+    int t = 0;
     for (int cc = 0; cc < a.nchunks; ++cc) {
-        __syncthreads(); // all reads of the previous chunk's patch and weights are done
-        // ---- stage the input patch for channels [cc*64, cc*64+64)
-        if (LIMBS == 2) {
+        if (cc) __syncthreads(); // all reads of the previous chunk's activations are done
+        // ---- stage activations
+        if constexpr (FLAT) {
+            // one 16-byte piece per limb = 16 consecutive k of one tile row's window
+            const int16_t *x = (const int16_t *)a.x;
+            const int SC = a.S * a.Cin;
+            for (int i = tid; i < BM * 4; i += kConvThreads) {
+                const int row = i >> 2, k0 = (i & 3) * 16;
+                const int base = abase_s[row];
+                int r = k0 / SC, rem = k0 - r * SC;
+                int s = rem / a.Cin, ci = rem - s * a.Cin;
+                unsigned hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
+                int sum = 0;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    if (k0 + j < a.Kflat) {
+                        const int g = tab[base + r * a.PW + s];
+                        const int val = g >= 0 ? (int)x[(size_t)g * a.Cin + ci] : 0;
+                        sum += val;
+                        hi[j >> 2] |= (unsigned)((val >> 8) & 255) << (8 * (j & 3));
+                        lo[j >> 2] |= (unsigned)((val & 255) ^ 128) << (8 * (j & 3));
+                        if (++ci == a.Cin) {
+                            ci = 0;
+                            if (++s == a.S) { s = 0; ++r; }
+                        }
+                    }
+                }
+                if (sum) atomicAdd(&psum[row], sum);
+                const v4i vh = {(int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+                const v4i vl = {(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3]};
+                *(v4i *)(Asm + row * PS + k0) = vh;
+                *(v4i *)(Asm + APL + row * PS + k0) = vl;
+            }
+        } else if constexpr (LIMBS == 2) {
             const int16_t *x = (const int16_t *)a.x;
             for (int i = tid; i < NPIXA * 8; i += kConvThreads) {
                 const int p = i >> 3, c8 = i & 7, ch = cc * CK + c8 * 8;
@@ -399,69 +515,68 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
                 *(v4i *)(Asm + p * PS + c4 * 16) = v;
             }
         }
-        for (int tap = 0; tap < RS; ++tap) {
-            if (tap) __syncthreads(); // previous tap's weight reads are done
-            // ---- stage the weight slab of (tap, chunk): LIMBS x BN rows x 64 bytes
-            {
-                const unsigned char *src =
-                    a.wp + (((size_t)tap * a.nchunks + cc) * LIMBS * a.CoutP + (size_t)ntile * BN) * CK;
-#pragma unroll
-                for (int lb = 0; lb < LIMBS; ++lb)
-#pragma unroll
-                    for (int i = tid; i < BN * 4; i += kConvThreads) {
-                        const int row = i >> 2, q = i & 3;
-                        const v4i v = *(const v4i *)(src + ((size_t)lb * a.CoutP + row) * CK + q * 16);
-                        *(v4i *)(Bsm + lb * BPL + row * PS + q * 16) = v;
-                    }
-            }
+        for (int tap = 0; tap < a.taps; ++tap, ++t) {
+            // slab t sits in registers: park it in buffer t&1 (last read two slabs ago, and every
+            // wave has passed a barrier since), then start fetching slab t+1
+            store_slab(t & 1);
+            if (t + 1 < nslabs) load_slab(t + 1);
             __syncthreads();
-            // ---- 64 channels of this tap: two K=32 MFMA steps
-            const int r = tap / a.S, s = tap - r * a.S;
-            const int tapoff = (r * a.PW + s) * PS;
+            const unsigned char *Bcur = Bsm + (t & 1) * BSLAB;
+            int tapoff = 0;
+            if constexpr (!FLAT) {
+                const int r = tap / a.S, s = tap - r * a.S;
+                tapoff = (r * a.PW + s) * PS;
+            }
 #pragma unroll
             for (int k32 = 0; k32 < 2; ++k32) {
-                v4i ah[2], al[2], bh[NB], bl[NB];
+                if (k32 < a.ksteps) {
+                    v4i ah[2], al[2], bh[NB], bl[NB];
 #pragma unroll
-                for (int mb = 0; mb < 2; ++mb) {
-                    ah[mb] = *(const v4i *)(Asm + aoff[mb] + tapoff + k32 * 32);
-                    if (LIMBS == 2) al[mb] = *(const v4i *)(Asm + APL + aoff[mb] + tapoff + k32 * 32);
-                }
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    bh[nb] = *(const v4i *)(Bsm + boff[nb] + k32 * 32);
-                    if (LIMBS == 2) bl[nb] = *(const v4i *)(Bsm + BPL + boff[nb] + k32 * 32);
-                }
-#pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
+                    for (int mb = 0; mb < 2; ++mb) {
+                        ah[mb] = *(const v4i *)(Asm + aoff[mb] + tapoff + k32 * 32);
+                        if constexpr (LIMBS == 2) al[mb] = *(const v4i *)(Asm + APL + aoff[mb] + tapoff + k32 * 32);
+                    }
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
-                        acc[mb][nb][0] = mfma_i8(ah[mb], bh[nb], acc[mb][nb][0]);
-                        if (LIMBS == 2) {
-                            acc[mb][nb][1] = mfma_i8(ah[mb], bl[nb], acc[mb][nb][1]);
-                            acc[mb][nb][2] = mfma_i8(al[mb], bl[nb], acc[mb][nb][2]);
-                        }
+                        bh[nb] = *(const v4i *)(Bcur + boff[nb] + k32 * 32);
+                        if constexpr (LIMBS == 2) bl[nb] = *(const v4i *)(Bcur + BPL + boff[nb] + k32 * 32);
                     }
-                if (LIMBS == 2) {
 #pragma unroll
                     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                        for (int nb = 0; nb < NB; ++nb)
-                            acc[mb][nb][1] = mfma_i8(al[mb], bh[nb], acc[mb][nb][1]);
+                        for (int nb = 0; nb < NB; ++nb) {
+                            acc[mb][nb][0] = mfma_i8(ah[mb], bh[nb], acc[mb][nb][0]);
+                            if constexpr (LIMBS == 2) {
+                                acc[mb][nb][1] = mfma_i8(ah[mb], bl[nb], acc[mb][nb][1]);
+                                acc[mb][nb][2] = mfma_i8(al[mb], bl[nb], acc[mb][nb][2]);
+                            }
+                        }
+                    if constexpr (LIMBS == 2) {
+#pragma unroll
+                        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                            for (int nb = 0; nb < NB; ++nb)
+                                acc[mb][nb][1] = mfma_i8(al[mb], bh[nb], acc[mb][nb][1]);
+                    }
                 }
             }
         }
     }
 
-    // ---- per-row correction 128 * sum(a) over the window, from the staged channel sums
+    // ---- per-row sum of the window's codes (two-limb correction term 128 * sum(a))
     __syncthreads();
-    int64_t *rowterm = (int64_t *)Asm; // the patch is no longer needed
-    if (LIMBS == 2) {
+    int *rowsum = (int *)Asm; // the staged activations are no longer needed
+    if constexpr (LIMBS == 2) {
         for (int m = tid; m < BM; m += kConvThreads) {
-            const int base = abase_s[m];
             int sum = 0;
-            for (int r = 0; r < a.R; ++r)
-                for (int s = 0; s < a.S; ++s) sum += psum[base + r * a.PW + s];
-            rowterm[m] = (int64_t)sum * 128;
+            if constexpr (FLAT) {
+                sum = psum[m];
+            } else {
+                const int base = abase_s[m];
+                for (int r = 0; r < a.R; ++r)
+                    for (int s = 0; s < a.S; ++s) sum += psum[base + r * a.PW + s];
+            }
+            rowsum[m] = sum;
         }
         __syncthreads();
     }
@@ -477,50 +592,101 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
         colterm[nb] = 0;
         if (colg[nb] < a.Cout) colterm[nb] = a.corr[colg[nb]] + bias_term(a, colg[nb]);
     }
+    if (a.fast) {
+        // v = 2^16*A + 2^8*B + C with every piece in int32: the column constant is split the same
+        // way, 128*rowsum = 2^8*(rowsum >> 1) + 128*(rowsum & 1); then carries are pushed upward.
+        const int s = a.act.s, cmax = a.act.hi;
+        int cA[NB], cB[NB], cC[NB];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+        for (int nb = 0; nb < NB; ++nb) {
+            cA[nb] = (int)(colterm[nb] >> 16);
+            cB[nb] = (int)((colterm[nb] >> 8) & 255);
+            cC[nb] = (int)(colterm[nb] & 255);
+        }
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = wm * 64 + mb * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-            const int oo = outoff[row];
-            const int64_t rt = (LIMBS == 2) ? rowterm[row] : 0;
+        for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                int64_t val;
-                if (LIMBS == 2)
-                    val = ((int64_t)acc[mb][nb][0][v] << 16) + ((int64_t)acc[mb][nb][1][v] << 8) +
-                          (int64_t)acc[mb][nb][2][v] + rt + colterm[nb];
-                else
-                    val = (int64_t)acc[mb][nb][0][v] + colterm[nb];
-                const bool ok = oo >= 0 && colg[nb] < a.Cout;
-                bool z = false;
-                if (ok) {
-                    const size_t idx = (size_t)oo * a.Cout + colg[nb];
-                    if (a.acc_out) a.acc_out[idx] = val;
-                    if (a.y) {
-                        const int c = act_one(val, a.act);
+            for (int v = 0; v < 16; ++v) {
+                const int row = wm * 64 + mb * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+                const int oo = outoff[row];
+                int rB = 0, rC = 0;
+                if constexpr (LIMBS == 2) {
+                    const int rs = rowsum[row];
+                    rB = rs >> 1;
+                    rC = (rs & 1) << 7;
+                }
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    int hi, lo16;
+                    if constexpr (LIMBS == 2) {
+                        const int C = acc[mb][nb][2][v] + cC[nb] + rC;
+                        const int B = acc[mb][nb][1][v] + cB[nb] + rB + (C >> 8);
+                        hi = acc[mb][nb][0][v] + cA[nb] + (B >> 8);
+                        lo16 = ((B & 255) << 8) | (C & 255);
+                    } else {
+                        const int C = acc[mb][nb][0][v] + (int)colterm[nb];
+                        hi = C >> 16;
+                        lo16 = C & 65535;
+                    }
+                    int c;
+                    if (s >= 17) c = requant_relu32<0>(hi, lo16, s, cmax);
+                    else if (s == 16) c = requant_relu32<1>(hi, lo16, s, cmax);
+                    else c = requant_relu32<2>(hi, lo16, s, cmax);
+                    const bool ok = oo >= 0 && colg[nb] < a.Cout;
+                    if (ok) {
+                        const size_t idx = (size_t)oo * a.Cout + colg[nb];
                         if (a.y16) ((int16_t *)a.y)[idx] = (int16_t)c;
                         else ((int8_t *)a.y)[idx] = (int8_t)c;
-                        z = (c == 0);
                     }
+                    zeros += wave_count(ok && c == 0);
                 }
-                zeros += wave_count(z);
             }
-        }
+    } else {
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = wm * 64 + mb * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+                const int oo = outoff[row];
+                const int64_t rt = (LIMBS == 2) ? (int64_t)rowsum[row] * 128 : 0;
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    int64_t val;
+                    if constexpr (LIMBS == 2)
+                        val = ((int64_t)acc[mb][nb][0][v] << 16) + ((int64_t)acc[mb][nb][1][v] << 8) +
+                              (int64_t)acc[mb][nb][2][v] + rt + colterm[nb];
+                    else
+                        val = (int64_t)acc[mb][nb][0][v] + colterm[nb];
+                    const bool ok = oo >= 0 && colg[nb] < a.Cout;
+                    bool z = false;
+                    if (ok) {
+                        const size_t idx = (size_t)oo * a.Cout + colg[nb];
+                        if (a.acc_out) a.acc_out[idx] = val;
+                        if (a.y) {
+                            const int c = act_one(val, a.act);
+                            if (a.y16) ((int16_t *)a.y)[idx] = (int16_t)c;
+                            else ((int8_t *)a.y)[idx] = (int8_t)c;
+                            z = (c == 0);
+                        }
+                    }
+                    zeros += wave_count(z);
+                }
+            }
+    }
     if (a.zero_count && a.y && lane == 0 && zeros) atomicAdd(a.zero_count, (unsigned long long)zeros);
 }
 
-template <int LIMBS, int NB>
+template <int LIMBS, int NB, bool FLAT>
 static lp_status launch_mfma(const ConvArgs &a, const Plan &p, hipStream_t st)
 {
     static bool attr_set = false; // raise the dynamic LDS limit once per kernel instance
     if (!attr_set) {
-        if (hipFuncSetAttribute((const void *)conv_mfma_kernel<LIMBS, NB>,
+        if (hipFuncSetAttribute((const void *)conv_mfma_kernel<LIMBS, NB, FLAT>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
             return LP_EDEVICE;
         attr_set = true;
     }
-    hipLaunchKernelGGL((conv_mfma_kernel<LIMBS, NB>), dim3(a.per_xcd * 8), dim3(kConvThreads),
+    hipLaunchKernelGGL((conv_mfma_kernel<LIMBS, NB, FLAT>), dim3(a.per_xcd * 8), dim3(kConvThreads),
                        p.lds_bytes, st, a);
     return launch_status();
 }
@@ -566,11 +732,22 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
         return launch_status();
     }
     a.RH = p.RH; a.TW = p.TW; a.PW = p.PW; a.NPIXA = p.NPIXA;
+    a.NTAB = std::max(p.NPIXA, BM);
+    a.AROWS = p.flat ? BM : p.NPIXA;
     a.tiles_c = p.tiles_c; a.tiles_n = p.tiles_n; a.CoutP = p.CoutP; a.nchunks = p.nchunks;
+    a.taps = p.taps; a.ksteps = p.ksteps; a.Kflat = d->R * d->S * d->Cin;
     a.total_work = p.tiles_m * p.tiles_n;
     a.per_xcd = (a.total_work + 7) / 8;
-    if (p.limbs == 2) return p.BN == 128 ? launch_mfma<2, 2>(a, p, hs) : launch_mfma<2, 1>(a, p, hs);
-    return p.BN == 128 ? launch_mfma<1, 2>(a, p, hs) : launch_mfma<1, 1>(a, p, hs);
+    // The 32-bit epilogue is exact when only codes are wanted, with ReLU, round-half-away,
+    // a right shift of 1..31 bits, and sums small enough that no int32 piece can overflow
+    // (K <= 8192 keeps |HH|, |HL+LH| and the folded constants below 2^29).
+    const long long K = (long long)d->R * d->S * d->Cin;
+    a.fast = (y && !acc_out && relu && r == LP_ROUND_NEAREST_AWAY && a.act.s >= 1 && a.act.s <= 31 &&
+              K <= 8192 && (!bias || a.bias_shift <= 24)) ? 1 : 0;
+    if (p.flat) return p.BN == 128 ? launch_mfma<2, 2, true>(a, p, hs) : launch_mfma<2, 1, true>(a, p, hs);
+    if (p.limbs == 2)
+        return p.BN == 128 ? launch_mfma<2, 2, false>(a, p, hs) : launch_mfma<2, 1, false>(a, p, hs);
+    return p.BN == 128 ? launch_mfma<1, 2, false>(a, p, hs) : launch_mfma<1, 1, false>(a, p, hs);
 }
 
 static lp_status pack_weights(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, const void *w,
@@ -598,6 +775,21 @@ static lp_status pack_weights(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, con
     unsigned char *out = (unsigned char *)packed;
     int64_t *corr = (int64_t *)(out + p.corr_offset);
     const int cgrid = (p.CoutP + 63) / 64;
+    if (p.flat) {
+        const int K = RS * d->Cin, fgrid = (p.CoutP * CK + 255) / 256;
+        if (w16) {
+            hipLaunchKernelGGL(pack_weights_flat_kernel<int16_t>, dim3(fgrid), dim3(256), 0, hs,
+                               (const int16_t *)w, out, d->Cout, K, p.CoutP);
+            hipLaunchKernelGGL(weight_corr_kernel<int16_t>, dim3(cgrid), dim3(64), 0, hs,
+                               (const int16_t *)w, corr, d->Cout, p.CoutP, K, 2);
+        } else {
+            hipLaunchKernelGGL(pack_weights_flat_kernel<int8_t>, dim3(fgrid), dim3(256), 0, hs,
+                               (const int8_t *)w, out, d->Cout, K, p.CoutP);
+            hipLaunchKernelGGL(weight_corr_kernel<int8_t>, dim3(cgrid), dim3(64), 0, hs,
+                               (const int8_t *)w, corr, d->Cout, p.CoutP, K, 2);
+        }
+        return launch_status();
+    }
 #define LP_PACK(WT, L)                                                                              \
     hipLaunchKernelGGL((pack_weights_kernel<WT, L>), dim3(grid), dim3(256), 0, hs, (const WT *)w, out, \
                        d->Cout, d->Cin, RS, p.nchunks, p.CoutP, total);                                \

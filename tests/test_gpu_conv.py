@@ -54,9 +54,10 @@ def test_config1_single_layer(oracle):
 
 @pytest.mark.parametrize("N,Cin,H,W,Cout,R,S,pad", [
     (2, 64, 20, 24, 64, 3, 3, 1),      # several tiles, ragged right/bottom edges
-    (1, 64, 33, 17, 128, 3, 3, 1),     # BN = 128
+    (1, 64, 33, 17, 128, 3, 3, 1),
+    (70, 64, 32, 32, 128, 3, 3, 1),    # grid large enough for 128-wide channel tiles (BN = 128)
     (3, 32, 14, 14, 64, 3, 3, 1),      # row strips that straddle images; half-filled channel chunk
-    (2, 128, 9, 9, 192, 3, 3, 1),      # two chunks, Cout padded to 256 (BN = 128), ragged channels
+    (2, 128, 9, 9, 192, 3, 3, 1),      # two chunks, ragged channel tiles
     (2, 192, 7, 7, 40, 3, 3, 1),       # three chunks, Cout < 64
     (1, 16, 40, 40, 16, 3, 3, 1),
     (5, 64, 2, 2, 64, 3, 3, 1),        # tiny images, many boundaries per tile
@@ -108,9 +109,59 @@ def test_conv_mixed_widths_and_direct_path(oracle):
     _check(oracle, x16, w8, QX, (8, 1, 7), (16, 10, 6), expect_path=1)       # 8-bit weights on the two-limb kernel
     _check(oracle, x8, w16, (8, 3, 5), QW, (16, 10, 6), expect_path=0)       # direct kernel
     _check(oracle, x16, w16, QX, QW, QY, stride=2, expect_path=0)
-    # three input channels (first VGG16 layer), output to 8-bit codes
-    x3, w3 = _codes(rng, (2, 3, 20, 20)), _codes(rng, (64, 3, 3, 3))
-    _check(oracle, x3, w3, QX, QW, (8, 7, 1), expect_path=0)
+    x12, w12 = _codes(rng, (1, 12, 8, 8)), _codes(rng, (16, 12, 3, 3))      # neither chunkable nor tiny
+    _check(oracle, x12, w12, QX, QW, QY, expect_path=0)
+    x3, w3 = _codes(rng, (2, 3, 10, 10), n=8), _codes(rng, (8, 3, 3, 3), n=8)
+    _check(oracle, x3, w3, (8, 3, 5), (8, 1, 7), (8, 7, 1), expect_path=0)
+
+
+@pytest.mark.parametrize("N,Cin,H,W,Cout,R,S,pad,qy", [
+    (2, 3, 20, 20, 64, 3, 3, 1, (8, 7, 1)),       # first VGG16 layer shape, 8-bit output codes
+    (1, 3, 37, 29, 64, 3, 3, 1, (16, 12, 4)),
+    (2, 1, 18, 18, 16, 7, 7, 3, (16, 12, 4)),     # K = 49: two K=32 steps
+    (3, 4, 9, 9, 40, 3, 3, 1, (16, 12, 4)),       # K = 36
+    (2, 5, 6, 6, 130, 1, 1, 0, (16, 12, 4)),      # K = 5
+    (2, 7, 8, 8, 64, 3, 3, 0, (16, 12, 4)),       # K = 63
+    (9, 3, 2, 2, 64, 3, 3, 1, (16, 12, 4)),       # tiles straddling many images
+])
+def test_conv_flat_window(oracle, N, Cin, H, W, Cout, R, S, pad, qy):
+    """Tiny input-channel counts: the whole window is gathered as one slab (K <= 64)."""
+    rng = np.random.default_rng(N + Cin * 10 + H)
+    x, w = _codes(rng, (N, Cin, H, W), zero_frac=0.3), _codes(rng, (Cout, Cin, R, S))
+    _check(oracle, x, w, QX, QW, qy, pad=pad, expect_path=1, modes=("away", "even"))
+    _check(oracle, x, w, QX, QW, qy, relu=False, pad=pad, expect_path=1)
+
+
+@pytest.mark.parametrize("fo", [15, 14, 11, 10, 3, 0])
+def test_conv_requantization_shift_sweep(oracle, fo):
+    """Output formats that put the right shift f_acc - fo at 12, 13, 16, 17, 24 and 27 bits, with
+    values scaled so that results spread over zero, mid-range and saturated codes."""
+    rng = np.random.default_rng(40 + fo)
+    f_acc = 27
+    s = f_acc - fo
+    x = np.maximum(_codes(rng, (2, 64, 12, 12), full_range=False), 0)
+    w = (_codes(rng, (64, 64, 3, 3), full_range=False).astype(np.float64) * 2.0 ** min(0, s - 24)).astype(np.int32)
+    bias = _codes(rng, (64,), n=12)
+    for q16 in ((16, 16 - fo, fo), (8, 8 - fo, fo) if fo <= 7 else None):
+        if q16 is None:
+            continue
+        _check(oracle, x, w, QX, QW, q16, bias=bias, qb=(16, 4, 12), expect_path=1)
+        got = conv(x, QX, w, QW, qy=q16, bias=bias, qb=(16, 4, 12), want_acc=False)       # 32-bit epilogue
+        acc = oracle.conv(x, w, bias=bias, f_acc=f_acc, fb=12)
+        y, z = oracle.act(acc, f_acc, *q16, True, oracle.ROUND_AWAY)
+        assert np.array_equal(got["y"], y) and got["zeros"] == z
+        assert 0 < z < y.size
+
+
+def test_conv_int8_wide_tiles(oracle):
+    rng = np.random.default_rng(12)
+    x = np.maximum(_codes(rng, (66, 64, 32, 32), n=8), 0)
+    w = _codes(rng, (128, 64, 3, 3), n=8)
+    got = conv(x, (8, 3, 5), w, (8, 1, 7), qy=(8, 5, 3), want_acc=False)
+    assert got["info"]["bn"] == 128 and got["info"]["limbs"] == 1
+    acc = oracle.conv(x, w, threads=16)
+    y, z = oracle.act(acc, 12, 8, 5, 3, True, oracle.ROUND_AWAY)
+    assert np.array_equal(got["y"], y) and got["zeros"] == z
 
 
 def test_conv_only_codes_or_only_accumulators(oracle):

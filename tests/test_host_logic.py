@@ -58,12 +58,17 @@ def test_path_selection():
     info = lp.lp_conv_plan_info(lp.ConvDesc(2, 16, 16, 64, 64, 3, 3, 1, 1), Q16, W16)
     assert info["path"] == 1 and info["limbs"] == 2 and info["bn"] == 64
     info = lp.lp_conv_plan_info(lp.ConvDesc(2, 16, 16, 64, 128, 3, 3, 1, 1), Q8, W8)
+    assert info["path"] == 1 and info["limbs"] == 1 and info["bn"] == 64      # small grid: finer channel tiles
+    info = lp.lp_conv_plan_info(lp.ConvDesc(64, 56, 56, 128, 256, 3, 3, 1, 1), Q8, W8)
     assert info["path"] == 1 and info["limbs"] == 1 and info["bn"] == 128
-    # 16-bit activations with 8-bit weights ride the two-limb kernel; the reverse, Cin = 3,
-    # and stride 2 take the direct kernel
+    # 16-bit activations with 8-bit weights ride the two-limb kernel, and so does a 16-bit layer
+    # with a tiny window (Cin = 3: the whole 27-long window is one slab); 8-bit activations with
+    # 16-bit weights, windows that are neither chunkable nor tiny, and stride 2 take the direct kernel
     assert lp.lp_conv_plan_info(lp.ConvDesc(2, 16, 16, 64, 64, 3, 3, 1, 1), Q16, W8)["path"] == 1
+    assert lp.lp_conv_plan_info(lp.ConvDesc(2, 16, 16, 3, 64, 3, 3, 1, 1), Q16, W16)["path"] == 1
     assert lp.lp_conv_plan_info(lp.ConvDesc(2, 16, 16, 64, 64, 3, 3, 1, 1), Q8, W16)["path"] == 0
-    assert lp.lp_conv_plan_info(lp.ConvDesc(2, 16, 16, 3, 64, 3, 3, 1, 1), Q16, W16)["path"] == 0
+    assert lp.lp_conv_plan_info(lp.ConvDesc(2, 16, 16, 3, 64, 3, 3, 1, 1), Q8, W8)["path"] == 0
+    assert lp.lp_conv_plan_info(lp.ConvDesc(2, 16, 16, 12, 64, 3, 3, 1, 1), Q16, W16)["path"] == 0
     assert lp.lp_conv_plan_info(lp.ConvDesc(2, 16, 16, 64, 64, 3, 3, 2, 1), Q16, W16)["path"] == 0
 
 
@@ -84,6 +89,8 @@ SHAPES = [
     (300, 1, 1, 4096, 1000, 1, 1, 0),      # FC as a 1x1 conv over a 1x1 image
     (130, 2, 2, 64, 64, 3, 3, 1),          # many image boundaries inside one tile
     (1, 3, 200, 16, 16, 3, 3, 1),
+    (2, 224, 224, 3, 64, 3, 3, 1),         # first VGG16 layer: flat-window variant
+    (3, 20, 20, 1, 16, 7, 7, 3),
 ]
 
 
