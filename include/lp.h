@@ -138,7 +138,8 @@ typedef struct {
 } lp_plan_info;
 lp_status lp_conv_plan_info(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, lp_plan_info *out_host);
 
-/* Bytes of device workspace lp_conv_fwd needs for this problem (may be 0). */
+/* Bytes of device workspace lp_conv_fwd needs for this problem when zero_count_dev is
+ * given (per-workgroup partial counts; may be 0).  Without zero_count_dev none is needed. */
 lp_status lp_conv_workspace_bytes(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, size_t *bytes_host);
 
 /*
@@ -152,7 +153,8 @@ lp_status lp_conv_workspace_bytes(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw,
  *   bias_codes_dev nullable; Cout codes in format qb (int8/int16 by qb.n), qb.f <= f_acc
  *   acc_out_dev   nullable; receives the raw int64 accumulators, N x Ho x Wo x Cout
  *   y_codes_dev   nullable; receives lp_act(acc) in format qy (see lp_act), same shape
- *   zero_count_dev nullable; += zeros among the y codes written
+ *   zero_count_dev nullable; += zeros among the y codes written; needs workspace_dev of
+ *                 lp_conv_workspace_bytes (16-byte aligned), else LP_EWORKSPACE
  * At least one of acc_out_dev / y_codes_dev must be given.
  * LP_EUNSUPPORTED: R*S*Cin >= 65536 with 16-bit operands (int32 limb sums
  * could overflow), tensors with 2^31 or more elements.

@@ -142,6 +142,7 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
                 const int pra = rh + d->R - 1 + cross * (d->R - 1);
                 const int npixa = pra * pw;
                 if (mfma_lds_bytes(p.limbs, npixa, 128, p.flat) > kLdsBudget) continue;
+                if (p.flat && (size_t)npixa * d->Cin * 2 > (size_t)2 * 64 * PS) continue; // raw patch parks in a weight buffer
                 const double cost = (double)tiles_c * tiles_r * ((double)BM * RS + 0.5 * npixa);
                 if (cost < best) {
                     best = cost;
@@ -160,6 +161,9 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
         // 128-wide channel tiles halve the patch re-reads, but a grid with fewer workgroups than
         // the chip has slots (256 CUs x 2) is better cut finer
         p.BN = (p.CoutP % 128 == 0 && (long long)p.tiles_m * (p.CoutP / 128) >= 512) ? 128 : 64;
+        // the two-limb kernel holds three accumulator sets; at 128 channels they leave too few
+        // registers for the prefetch pipeline, so it always runs 64-wide
+        if (p.limbs == 2) p.BN = 64;
         p.tiles_n = p.CoutP / p.BN;
         p.lds_bytes = mfma_lds_bytes(p.limbs, p.NPIXA, p.BN, p.flat);
         p.corr_offset = round_up((size_t)p.taps * p.nchunks * p.limbs * p.CoutP * CK, 256);
@@ -259,6 +263,7 @@ struct ConvArgs {
     void *y;
     int y16;
     unsigned long long *zero_count;
+    unsigned *zero_partial; // one count per workgroup (MFMA path), summed by a second kernel
     int N, H, W, Cin, Cout, R, S, stride, pad;
     int Ho, Wo, Hp, FR;
     int RH, TW, PW, NPIXA, NTAB, AROWS;
@@ -400,10 +405,13 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
         abase_s[m] = ok ? ((fr / a.Ho) * a.Hp + fr % a.Ho - vr0) * a.PW + t : 0;
     }
 
-    // weight slabs: slab t = chunk * taps + tap lives at [tap][chunk][limb][CoutP][64]
+    // weight slabs: slab t = chunk * taps + tap lives at [tap][chunk][limb][CoutP][64].  A slab
+    // travels global -> registers -> LDS; DEPTH slabs are in flight in registers so that the
+    // L2 latency is covered by the MFMAs of the slabs before it.
+    constexpr int DEPTH = (BITEMS <= 2) ? 2 : 1;
     const int nslabs = a.nchunks * a.taps;
-    v4i breg[BITEMS];
-    auto load_slab = [&](int t) {
+    v4i breg0[BITEMS], breg1[DEPTH == 2 ? BITEMS : 1];
+    auto load_slab = [&](int t, v4i *reg) {
         const int cc = t / a.taps, tap = t - cc * a.taps;
         const unsigned char *src =
             a.wp + (((size_t)tap * a.nchunks + cc) * LIMBS * a.CoutP + (size_t)ntile * BN) * CK;
@@ -411,18 +419,19 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
         for (int j = 0; j < BITEMS; ++j) {
             const int i = tid + j * kConvThreads;
             const int lb = i / (BN * 4), rem = i - lb * (BN * 4);
-            breg[j] = *(const v4i *)(src + ((size_t)lb * a.CoutP + (rem >> 2)) * CK + (rem & 3) * 16);
+            reg[j] = *(const v4i *)(src + ((size_t)lb * a.CoutP + (rem >> 2)) * CK + (rem & 3) * 16);
         }
     };
-    auto store_slab = [&](int buf) {
+    auto store_slab = [&](int buf, const v4i *reg) {
 #pragma unroll
         for (int j = 0; j < BITEMS; ++j) {
             const int i = tid + j * kConvThreads;
             const int lb = i / (BN * 4), rem = i - lb * (BN * 4);
-            *(v4i *)(Bsm + buf * BSLAB + lb * BPL + (rem >> 2) * PS + (rem & 3) * 16) = breg[j];
+            *(v4i *)(Bsm + buf * BSLAB + lb * BPL + (rem >> 2) * PS + (rem & 3) * 16) = reg[j];
         }
     };
-    load_slab(0);
+    load_slab(0, breg0);
+    if (DEPTH == 2 && nslabs > 1) load_slab(1, breg1);
     __syncthreads();
 
     const int lane = tid & 63, wave = tid >> 6;
@@ -447,50 +456,43 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[mb][nb][q][v] = 0;
 
-    int t = 0;
-    for (int cc = 0; cc < a.nchunks; ++cc) {
-        if (cc) __syncthreads(); // all reads of the previous chunk's activations are done
-        // ---- stage activations
-        if constexpr (FLAT) {
-            // one 16-byte piece per limb = 16 consecutive k of one tile row's window
-            const int16_t *x = (const int16_t *)a.x;
-            const int SC = a.S * a.Cin;
-            for (int i = tid; i < BM * 4; i += kConvThreads) {
-                const int row = i >> 2, k0 = (i & 3) * 16;
-                const int base = abase_s[row];
-                int r = k0 / SC, rem = k0 - r * SC;
-                int s = rem / a.Cin, ci = rem - s * a.Cin;
-                unsigned hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
-                int sum = 0;
+    // Activations travel global -> registers -> LDS in batches of APF 16-byte pieces per thread,
+    // so that a batch's loads are all in flight together.  PIECES: 16-byte pieces per staged
+    // pixel and chunk (8 x 8 int16 codes, or 4 x 16 int8 codes).
+    constexpr int APF = (NB == 2 && LIMBS == 2) ? 4 : 8;
+    constexpr int PIECES = (LIMBS == 2) ? 8 : 4;
+    v4i areg[APF];
+    auto load_act = [&](int cc, int first) {
 #pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    if (k0 + j < a.Kflat) {
-                        const int g = tab[base + r * a.PW + s];
-                        const int val = g >= 0 ? (int)x[(size_t)g * a.Cin + ci] : 0;
-                        sum += val;
-                        hi[j >> 2] |= (unsigned)((val >> 8) & 255) << (8 * (j & 3));
-                        lo[j >> 2] |= (unsigned)((val & 255) ^ 128) << (8 * (j & 3));
-                        if (++ci == a.Cin) {
-                            ci = 0;
-                            if (++s == a.S) { s = 0; ++r; }
-                        }
-                    }
-                }
-                if (sum) atomicAdd(&psum[row], sum);
-                const v4i vh = {(int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
-                const v4i vl = {(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3]};
-                *(v4i *)(Asm + row * PS + k0) = vh;
-                *(v4i *)(Asm + APL + row * PS + k0) = vl;
-            }
-        } else if constexpr (LIMBS == 2) {
-            const int16_t *x = (const int16_t *)a.x;
-            for (int i = tid; i < NPIXA * 8; i += kConvThreads) {
-                const int p = i >> 3, c8 = i & 7, ch = cc * CK + c8 * 8;
+        for (int j = 0; j < APF; ++j) {
+            const int i = first + tid + j * kConvThreads;
+            v4i v = {0, 0, 0, 0};
+            if (i < NPIXA * PIECES) {
+                const int p = i / PIECES, c = i % PIECES;
+                const int ch = cc * CK + c * (CK / PIECES);
                 const int g = tab[p];
-                v2i hi = {0, 0}, lo = {0, 0};
-                if (ch < a.Cin) {
-                    if (g >= 0) {
-                        const v4i v = *(const v4i *)(x + (size_t)g * a.Cin + ch);
+                if (ch < a.Cin && g >= 0) {
+                    if constexpr (LIMBS == 2)
+                        v = *(const v4i *)((const int16_t *)a.x + (size_t)g * a.Cin + ch);
+                    else
+                        v = *(const v4i *)((const int8_t *)a.x + (size_t)g * a.Cin + ch);
+                }
+            }
+            areg[j] = v;
+        }
+    };
+    auto store_act = [&](int cc, int first) {
+#pragma unroll
+        for (int j = 0; j < APF; ++j) {
+            const int i = first + tid + j * kConvThreads;
+            if (i < NPIXA * PIECES) {
+                const int p = i / PIECES, c = i % PIECES;
+                const v4i v = areg[j];
+                if constexpr (LIMBS == 2) {
+                    const int ch = cc * CK + c * 8;
+                    v2i hi = {0, 0}, lo = {0, 0};
+                    if (ch < a.Cin) {
+                        // codes outside the image were loaded as 0 = limbs (0, -128)
                         hi.x = (int)__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x07050301u);
                         hi.y = (int)__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x07050301u);
                         lo.x = (int)(__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x06040200u) ^ 0x80808080u);
@@ -498,69 +500,134 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
                         const int sum = ((v.x << 16) >> 16) + (v.x >> 16) + ((v.y << 16) >> 16) + (v.y >> 16) +
                                         ((v.z << 16) >> 16) + (v.z >> 16) + ((v.w << 16) >> 16) + (v.w >> 16);
                         if (sum) atomicAdd(&psum[p], sum);
-                    } else {
-                        lo.x = lo.y = (int)0x80808080u; // the code 0 outside the image
                     }
+                    *(v2i *)(Asm + p * PS + c * 8) = hi;
+                    *(v2i *)(Asm + APL + p * PS + c * 8) = lo;
+                } else {
+                    *(v4i *)(Asm + p * PS + c * 16) = v;
                 }
-                *(v2i *)(Asm + p * PS + c8 * 8) = hi;
-                *(v2i *)(Asm + APL + p * PS + c8 * 8) = lo;
-            }
-        } else {
-            const int8_t *x = (const int8_t *)a.x;
-            for (int i = tid; i < NPIXA * 4; i += kConvThreads) {
-                const int p = i >> 2, c4 = i & 3, ch = cc * CK + c4 * 16;
-                const int g = tab[p];
-                v4i v = {0, 0, 0, 0};
-                if (ch < a.Cin && g >= 0) v = *(const v4i *)(x + (size_t)g * a.Cin + ch);
-                *(v4i *)(Asm + p * PS + c4 * 16) = v;
             }
         }
-        for (int tap = 0; tap < a.taps; ++tap, ++t) {
-            // slab t sits in registers: park it in buffer t&1 (last read two slabs ago, and every
-            // wave has passed a barrier since), then start fetching slab t+1
-            store_slab(t & 1);
-            if (t + 1 < nslabs) load_slab(t + 1);
-            __syncthreads();
-            const unsigned char *Bcur = Bsm + (t & 1) * BSLAB;
-            int tapoff = 0;
-            if constexpr (!FLAT) {
-                const int r = tap / a.S, s = tap - r * a.S;
-                tapoff = (r * a.PW + s) * PS;
-            }
+    };
+    // FLAT: the raw patch (all Cin channels, int16) is parked in the unused second weight
+    // buffer, then each tile row's window is gathered from there, 16 consecutive k per piece.
+    auto stage_flat = [&]() {
+        const int16_t *x = (const int16_t *)a.x;
+        int16_t *raw = (int16_t *)(Bsm + BSLAB);
+        const int nraw = NPIXA * a.Cin;
+        for (int i = tid; i < nraw; i += kConvThreads) {
+            const int p = i / a.Cin, ci = i - p * a.Cin;
+            const int g = tab[p];
+            raw[i] = g >= 0 ? x[(size_t)g * a.Cin + ci] : (int16_t)0;
+        }
+        __syncthreads();
+        const int SC = a.S * a.Cin;
+        for (int i = tid; i < BM * 4; i += kConvThreads) {
+            const int row = i >> 2, k0 = (i & 3) * 16;
+            const int base = abase_s[row];
+            int r = k0 / SC, rem = k0 - r * SC;
+            int s = rem / a.Cin, ci = rem - s * a.Cin;
+            unsigned hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
+            int sum = 0;
 #pragma unroll
-            for (int k32 = 0; k32 < 2; ++k32) {
-                if (k32 < a.ksteps) {
-                    v4i ah[2], al[2], bh[NB], bl[NB];
-#pragma unroll
-                    for (int mb = 0; mb < 2; ++mb) {
-                        ah[mb] = *(const v4i *)(Asm + aoff[mb] + tapoff + k32 * 32);
-                        if constexpr (LIMBS == 2) al[mb] = *(const v4i *)(Asm + APL + aoff[mb] + tapoff + k32 * 32);
+            for (int j = 0; j < 16; ++j) {
+                if (k0 + j < a.Kflat) {
+                    const int val = (int)raw[(base + r * a.PW + s) * a.Cin + ci];
+                    sum += val;
+                    hi[j >> 2] |= (unsigned)((val >> 8) & 255) << (8 * (j & 3));
+                    lo[j >> 2] |= (unsigned)((val & 255) ^ 128) << (8 * (j & 3));
+                    if (++ci == a.Cin) {
+                        ci = 0;
+                        if (++s == a.S) { s = 0; ++r; }
                     }
+                }
+            }
+            if (sum) atomicAdd(&psum[row], sum);
+            const v4i vh = {(int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+            const v4i vl = {(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3]};
+            *(v4i *)(Asm + row * PS + k0) = vh;
+            *(v4i *)(Asm + APL + row * PS + k0) = vl;
+        }
+    };
+    // With few live registers (NB == 1) the first batch of the next chunk is fetched a few slabs
+    // early and waits in registers; otherwise it is fetched at the chunk boundary.
+    constexpr bool EARLY = (NB == 1) && !FLAT;
+    const int early_tap = a.taps >= 4 ? a.taps - 3 : 0;
+    auto stage_activations = [&](int cc, bool have_first) {
+        if constexpr (FLAT) {
+            stage_flat();
+        } else {
+            const int total = NPIXA * PIECES;
+            for (int first = 0; first < total; first += APF * kConvThreads) {
+                if (!(have_first && first == 0)) load_act(cc, first);
+                store_act(cc, first);
+            }
+        }
+    };
+    auto compute_slab = [&](int tap, int t) {
+        const unsigned char *Bcur = Bsm + (t & 1) * BSLAB;
+        int tapoff = 0;
+        if constexpr (!FLAT) {
+            const int r = tap / a.S, s = tap - r * a.S;
+            tapoff = (r * a.PW + s) * PS;
+        }
+#pragma unroll
+        for (int k32 = 0; k32 < 2; ++k32) {
+            if (k32 < a.ksteps) {
+                v4i ah[2], al[2], bh[NB], bl[NB];
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb) {
+                    ah[mb] = *(const v4i *)(Asm + aoff[mb] + tapoff + k32 * 32);
+                    if constexpr (LIMBS == 2) al[mb] = *(const v4i *)(Asm + APL + aoff[mb] + tapoff + k32 * 32);
+                }
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    bh[nb] = *(const v4i *)(Bcur + boff[nb] + k32 * 32);
+                    if constexpr (LIMBS == 2) bl[nb] = *(const v4i *)(Bcur + BPL + boff[nb] + k32 * 32);
+                }
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
-                        bh[nb] = *(const v4i *)(Bcur + boff[nb] + k32 * 32);
-                        if constexpr (LIMBS == 2) bl[nb] = *(const v4i *)(Bcur + BPL + boff[nb] + k32 * 32);
+                        acc[mb][nb][0] = mfma_i8(ah[mb], bh[nb], acc[mb][nb][0]);
+                        if constexpr (LIMBS == 2) {
+                            acc[mb][nb][1] = mfma_i8(ah[mb], bl[nb], acc[mb][nb][1]);
+                            acc[mb][nb][2] = mfma_i8(al[mb], bl[nb], acc[mb][nb][2]);
+                        }
                     }
+                if constexpr (LIMBS == 2) {
 #pragma unroll
                     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                        for (int nb = 0; nb < NB; ++nb) {
-                            acc[mb][nb][0] = mfma_i8(ah[mb], bh[nb], acc[mb][nb][0]);
-                            if constexpr (LIMBS == 2) {
-                                acc[mb][nb][1] = mfma_i8(ah[mb], bl[nb], acc[mb][nb][1]);
-                                acc[mb][nb][2] = mfma_i8(al[mb], bl[nb], acc[mb][nb][2]);
-                            }
-                        }
-                    if constexpr (LIMBS == 2) {
-#pragma unroll
-                        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                            for (int nb = 0; nb < NB; ++nb)
-                                acc[mb][nb][1] = mfma_i8(al[mb], bh[nb], acc[mb][nb][1]);
-                    }
+                        for (int nb = 0; nb < NB; ++nb)
+                            acc[mb][nb][1] = mfma_i8(al[mb], bh[nb], acc[mb][nb][1]);
                 }
             }
         }
+    };
+
+    int cc = 0, tap = 0;
+    if (EARLY) load_act(0, 0);
+    auto step = [&](int t, v4i *reg) {
+        if (tap == 0) {
+            if (t) __syncthreads(); // all reads of the previous chunk's activations are done
+            stage_activations(cc, EARLY);
+        }
+        // slab t has arrived in registers: park it in buffer t&1 (last read two slabs ago, and
+        // every wave has passed a barrier since), then start fetching slab t+DEPTH
+        store_slab(t & 1, reg);
+        if (t + DEPTH < nslabs) load_slab(t + DEPTH, reg);
+        __syncthreads();
+        if (EARLY && tap == early_tap && cc + 1 < a.nchunks) load_act(cc + 1, 0);
+        compute_slab(tap, t);
+        if (++tap == a.taps) {
+            tap = 0;
+            ++cc;
+        }
+    };
+    for (int t = 0; t < nslabs; t += 2) {
+        step(t, breg0);
+        if (t + 1 < nslabs) step(t + 1, DEPTH == 2 ? breg1 : breg0);
     }
 
     // ---- per-row sum of the window's codes (two-limb correction term 128 * sum(a))
@@ -673,7 +740,28 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
                 }
             }
     }
-    if (a.zero_count && a.y && lane == 0 && zeros) atomicAdd(a.zero_count, (unsigned long long)zeros);
+    // one count per workgroup, no atomics: thousands of same-address atomics would serialise
+    if (a.zero_partial) {
+        if (lane == 0) psum[wave] = (int)zeros;
+        __syncthreads();
+        if (tid == 0) a.zero_partial[wi] = (unsigned)(psum[0] + psum[1] + psum[2] + psum[3]);
+    }
+}
+
+__global__ __launch_bounds__(256) void sum_partials_kernel(const unsigned *__restrict__ partial, int n,
+                                                          unsigned long long *out)
+{
+    __shared__ unsigned long long part[4];
+    unsigned long long s = 0;
+    for (int i = threadIdx.x; i < n; i += 256) s += partial[i];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) s += __shfl_down(s, off, 64);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned long long t = part[0] + part[1] + part[2] + part[3];
+        if (t) atomicAdd(out, t);
+    }
 }
 
 template <int LIMBS, int NB, bool FLAT>
@@ -691,9 +779,15 @@ static lp_status launch_mfma(const ConvArgs &a, const Plan &p, hipStream_t st)
     return launch_status();
 }
 
+static size_t workspace_bytes_for(const Plan &p)
+{
+    return p.path == PATH_MFMA ? round_up((size_t)p.tiles_m * p.tiles_n * sizeof(unsigned), 256) : 0;
+}
+
 static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, const void *wp,
                               lp_qfmt qw, const void *bias, lp_qfmt qb, int64_t *acc_out, void *y,
-                              lp_qfmt qy, int relu, lp_round r, uint64_t *zero_count, void *stream)
+                              lp_qfmt qy, int relu, lp_round r, uint64_t *zero_count, void *workspace,
+                              size_t workspace_bytes, void *stream)
 {
     Plan p;
     lp_status st = make_plan(d, qx, qw, &p);
@@ -738,16 +832,25 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     a.taps = p.taps; a.ksteps = p.ksteps; a.Kflat = d->R * d->S * d->Cin;
     a.total_work = p.tiles_m * p.tiles_n;
     a.per_xcd = (a.total_work + 7) / 8;
+    const bool counting = zero_count && y;
+    if (counting) {
+        if (!workspace || workspace_bytes < workspace_bytes_for(p) || !aligned16(workspace)) return LP_EWORKSPACE;
+        a.zero_partial = (unsigned *)workspace;
+    }
     // The 32-bit epilogue is exact when only codes are wanted, with ReLU, round-half-away,
     // a right shift of 1..31 bits, and sums small enough that no int32 piece can overflow
     // (K <= 8192 keeps |HH|, |HL+LH| and the folded constants below 2^29).
     const long long K = (long long)d->R * d->S * d->Cin;
     a.fast = (y && !acc_out && relu && r == LP_ROUND_NEAREST_AWAY && a.act.s >= 1 && a.act.s <= 31 &&
               K <= 8192 && (!bias || a.bias_shift <= 24)) ? 1 : 0;
-    if (p.flat) return p.BN == 128 ? launch_mfma<2, 2, true>(a, p, hs) : launch_mfma<2, 1, true>(a, p, hs);
-    if (p.limbs == 2)
-        return p.BN == 128 ? launch_mfma<2, 2, false>(a, p, hs) : launch_mfma<2, 1, false>(a, p, hs);
-    return p.BN == 128 ? launch_mfma<1, 2, false>(a, p, hs) : launch_mfma<1, 1, false>(a, p, hs);
+    lp_status st2;
+    if (p.flat) st2 = launch_mfma<2, 1, true>(a, p, hs);
+    else if (p.limbs == 2) st2 = launch_mfma<2, 1, false>(a, p, hs);
+    else st2 = p.BN == 128 ? launch_mfma<1, 2, false>(a, p, hs) : launch_mfma<1, 1, false>(a, p, hs);
+    if (st2 != LP_OK || !counting) return st2;
+    hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(256), 0, hs, a.zero_partial, a.total_work,
+                       (unsigned long long *)zero_count);
+    return launch_status();
 }
 
 static lp_status pack_weights(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, const void *w,
@@ -855,7 +958,7 @@ extern "C" lp_status lp_conv_workspace_bytes(const lp_conv_desc *d, lp_qfmt qx, 
     if (!bytes_host) return LP_EINVAL;
     Plan p;
     lp_status st = make_plan(d, qx, qw, &p);
-    if (st == LP_OK) *bytes_host = 0;
+    if (st == LP_OK) *bytes_host = workspace_bytes_for(p);
     return st;
 }
 
@@ -865,10 +968,8 @@ extern "C" lp_status lp_conv_fwd(const lp_conv_desc *d, const void *x_codes_dev,
                                  int relu, lp_round r, uint64_t *zero_count_dev, void *workspace_dev,
                                  size_t workspace_bytes, void *stream)
 {
-    (void)workspace_dev;
-    (void)workspace_bytes;
     return conv_forward(d, x_codes_dev, qx, w_packed_dev, qw, bias_codes_dev, qb, acc_out_dev,
-                        y_codes_dev, qy, relu, r, zero_count_dev, stream);
+                        y_codes_dev, qy, relu, r, zero_count_dev, workspace_dev, workspace_bytes, stream);
 }
 
 extern "C" lp_status lp_fc_packed_bytes(int M, int K, int Nout, lp_qfmt qx, lp_qfmt qw,
@@ -899,9 +1000,7 @@ extern "C" lp_status lp_fc_fwd(int M, int K, int Nout, const void *x_codes_dev, 
                                int relu, lp_round r, uint64_t *zero_count_dev, void *workspace_dev,
                                size_t workspace_bytes, void *stream)
 {
-    (void)workspace_dev;
-    (void)workspace_bytes;
     const lp_conv_desc d = fc_desc(M, K, Nout);
     return conv_forward(&d, x_codes_dev, qx, w_packed_dev, qw, bias_codes_dev, qb, acc_out_dev,
-                        y_codes_dev, qy, relu, r, zero_count_dev, stream);
+                        y_codes_dev, qy, relu, r, zero_count_dev, workspace_dev, workspace_bytes, stream);
 }

@@ -88,7 +88,8 @@ class ConvStack:
             p = None
             if pool:
                 p = torch.empty((N, H // 2, W // 2, d.Cout), dtype=dt, device="cuda")
-            self.layers.append({"desc": d, "packed": packed, "qx": q_in, "qw": self.qw[i], "qy": self.qy[i], "y": y,
+            ws = torch.empty(max(lp.lp_conv_workspace_bytes(d, q_in, self.qw[i]), 16), dtype=torch.uint8, device="cuda")
+            self.layers.append({"desc": d, "packed": packed, "ws": ws, "qx": q_in, "qw": self.qw[i], "qy": self.qy[i], "y": y,
                                 "pooled": p, "H": H, "W": W, "macs": N * H * W * d.Cout * d.R * d.S * d.Cin,
                                 "info": lp.lp_conv_plan_info(d, q_in, self.qw[i])})
             if pool:
@@ -117,7 +118,7 @@ class ConvStack:
         for i, L in enumerate(self.layers):
             timed("conv%d" % i, lambda L=L, cur=cur, i=i: lp.lp_conv_fwd(
                 L["desc"], cur, L["qx"], L["packed"], L["qw"], qy=L["qy"], y_codes=L["y"], relu=True, r=self.r,
-                zero_count=self.zero_counts[i:i + 1]))
+                zero_count=self.zero_counts[i:i + 1], workspace=L["ws"]))
             cur = L["y"]
             if L["pooled"] is not None:
                 d = L["desc"]

@@ -49,8 +49,9 @@ def conv(x_codes, qx, w_codes, qw, qy=None, relu=True, r=lp.LP_ROUND_NEAREST_AWA
     acc = torch.empty((N, Ho, Wo, Cout), dtype=torch.int64, device="cuda") if want_acc else None
     y = torch.empty((N, Ho, Wo, Cout), dtype=code_torch_dtype(qy[0]), device="cuda") if (want_y and qy) else None
     z = counter()
+    ws = torch.empty(max(lp.lp_conv_workspace_bytes(d, qx, qw), 16), dtype=torch.uint8, device="cuda")
     lp.lp_conv_fwd(d, xd, qx, packed, qw, qy=qy, y_codes=y, acc_out=acc, relu=relu, r=r, bias_codes=bd, qb=qb,
-                   zero_count=z)
+                   zero_count=z, workspace=ws)
     torch.cuda.synchronize()
     return {
         "acc": acc.cpu().numpy().transpose(0, 3, 1, 2) if acc is not None else None,

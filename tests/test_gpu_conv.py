@@ -220,3 +220,27 @@ def test_fc_int8(oracle):
     assert np.array_equal(got["acc"], want)
     y, z = oracle.act(want, 12, 8, 8, 0, True, oracle.ROUND_AWAY)
     assert np.array_equal(got["y"], y) and got["zeros"] == z
+
+
+def test_zero_count_needs_workspace_and_accumulates(oracle):
+    import torch
+    from gpu_helpers import to_dev
+
+    rng = np.random.default_rng(11)
+    x, w = _codes(rng, (1, 64, 8, 8), zero_frac=0.5), _codes(rng, (64, 64, 3, 3))
+    d = lp.ConvDesc(1, 8, 8, 64, 64, 3, 3, 1, 1)
+    xd = to_dev(x.transpose(0, 2, 3, 1).astype(np.int16))
+    wd = to_dev(w.transpose(0, 2, 3, 1).astype(np.int16))
+    packed = torch.empty(lp.lp_conv_packed_bytes(d, QX, QW), dtype=torch.uint8, device="cuda")
+    lp.lp_conv_pack_weights(d, QX, QW, wd, packed)
+    y = torch.empty((1, 8, 8, 64), dtype=torch.int16, device="cuda")
+    z = torch.full((1,), 1000, dtype=torch.int64, device="cuda")
+    with pytest.raises(lp.LpError) as e:
+        lp.lp_conv_fwd(d, xd, QX, packed, QW, qy=QY, y_codes=y, zero_count=z)      # no workspace
+    assert e.value.status == 3
+    ws = torch.empty(lp.lp_conv_workspace_bytes(d, QX, QW), dtype=torch.uint8, device="cuda")
+    for _ in range(2):                                                             # counters are added to
+        lp.lp_conv_fwd(d, xd, QX, packed, QW, qy=QY, y_codes=y, zero_count=z, workspace=ws)
+    torch.cuda.synchronize()
+    _, want = oracle.act(oracle.conv(x, w), 27, *QY, True, oracle.ROUND_AWAY)
+    assert int(z.item()) == 1000 + 2 * want
