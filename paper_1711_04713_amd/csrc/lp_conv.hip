@@ -41,6 +41,7 @@ struct Plan {
     int Ho, Wo, Hp, FR;
     int nchunks, CoutP, BN;
     int RH, TW, PW, PRA, NPIXA;
+    int PITCH;   // LDS bytes between staged patch rows
     int tiles_r, tiles_c, tiles_m, tiles_n;
     size_t lds_bytes;
     size_t packed_bytes, corr_offset;
@@ -55,13 +56,24 @@ static bool desc_ok(const lp_conv_desc *d)
            d->W + 2 * d->pad >= d->S;
 }
 
-// LDS: tables (2*ntab + 2*BM ints), staged patch (arows pixels per limb plane), two weight slabs
-static size_t mfma_lds_bytes(int limbs, int npixa, int bn, int flat)
+// Staged patch rows are PITCH bytes apart.  A 16-byte fragment read is served 16 lanes at a
+// time from 64 four-byte banks; with pixels 80 bytes = 5 slots apart, 16 consecutive pixels hit
+// 16 distinct slots.  Lanes walk the tile row-major (TW pixels, then the next patch row), so a
+// pitch of 5*TW slots (mod 16) makes every 16-lane group look like 16 consecutive pixels.
+static int patch_pitch(int pw, int tw)
 {
-    const int ntab = std::max(npixa, BM);
-    const int arows = flat ? BM : npixa;
-    size_t tables = round_up((size_t)(2 * ntab + 2 * BM) * 4, 16);
-    return tables + (size_t)limbs * arows * PS + (size_t)2 * limbs * bn * PS;
+    int slots = 5 * pw;
+    while ((slots - 5 * tw) % 16 != 0) ++slots;
+    return slots * 16;
+}
+
+// LDS: tables (3*ntab + 2*BM ints), staged patch (one plane per limb), two weight slabs
+static size_t mfma_lds_bytes(int limbs, int pra, int pw, int tw, int bn, int flat)
+{
+    const int ntab = std::max(pra * pw, BM);
+    const size_t plane = flat ? (size_t)BM * PS : (size_t)pra * patch_pitch(pw, tw);
+    size_t tables = round_up((size_t)(3 * ntab + 2 * BM) * 4, 16);
+    return tables + (size_t)limbs * plane + (size_t)2 * limbs * bn * PS;
 }
 constexpr size_t kLdsBudget = 80000; // two workgroups per CU within the 160 KB of LDS
 
@@ -141,7 +153,7 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
                 const int cross = (p.Ho % rh == 0) ? 0 : std::min((rh - 1 + p.Ho - 1) / p.Ho, d->N - 1);
                 const int pra = rh + d->R - 1 + cross * (d->R - 1);
                 const int npixa = pra * pw;
-                if (mfma_lds_bytes(p.limbs, npixa, 128, p.flat) > kLdsBudget) continue;
+                if (mfma_lds_bytes(p.limbs, pra, pw, tw, p.limbs == 2 ? 64 : 128, p.flat) > kLdsBudget) continue;
                 if (p.flat && (size_t)npixa * d->Cin * 2 > (size_t)2 * 64 * PS) continue; // raw patch parks in a weight buffer
                 const double cost = (double)tiles_c * tiles_r * ((double)BM * RS + 0.5 * npixa);
                 if (cost < best) {
@@ -165,7 +177,8 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
         // registers for the prefetch pipeline, so it always runs 64-wide
         if (p.limbs == 2) p.BN = 64;
         p.tiles_n = p.CoutP / p.BN;
-        p.lds_bytes = mfma_lds_bytes(p.limbs, p.NPIXA, p.BN, p.flat);
+        p.PITCH = patch_pitch(p.PW, p.TW);
+        p.lds_bytes = mfma_lds_bytes(p.limbs, p.PRA, p.PW, p.TW, p.BN, p.flat);
         p.corr_offset = round_up((size_t)p.taps * p.nchunks * p.limbs * p.CoutP * CK, 256);
         p.packed_bytes = p.corr_offset + (size_t)p.CoutP * sizeof(int64_t);
     } else {
@@ -179,7 +192,7 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
 
 // --------------------------------------------------------------------- weight packing
 
-// MFMA layout: [tap][chunk][limb][CoutP][64] int8.
+// MFMA layout: [chunk][tap][limb][CoutP][64] int8, i.e. slabs in the order the kernel streams them.
 template <typename WT, int LIMBS>
 __global__ void pack_weights_kernel(const WT *__restrict__ w, unsigned char *__restrict__ out, int Cout,
                                     int Cin, int RS, int nchunks, int CoutP, size_t total)
@@ -203,7 +216,7 @@ __global__ void pack_weights_kernel(const WT *__restrict__ w, unsigned char *__r
                 hi = code;
             }
         }
-        const size_t base = (((size_t)tap * nchunks + chunk) * LIMBS) * CoutP;
+        const size_t base = (((size_t)chunk * RS + tap) * LIMBS) * CoutP;
         out[(base + co) * CK + kk] = (unsigned char)hi;
         if constexpr (LIMBS == 2) out[(base + CoutP + co) * CK + kk] = (unsigned char)lo;
     }
@@ -266,7 +279,7 @@ struct ConvArgs {
     unsigned *zero_partial; // one count per workgroup (MFMA path), summed by a second kernel
     int N, H, W, Cin, Cout, R, S, stride, pad;
     int Ho, Wo, Hp, FR;
-    int RH, TW, PW, NPIXA, NTAB, AROWS;
+    int RH, TW, PW, NPIXA, NTAB, APLANE, PITCH;
     int tiles_c, tiles_n, CoutP, nchunks, taps, ksteps, Kflat;
     int total_work, per_xcd;
     int fast; // 32-bit requantization is exact for this call (see epilogue)
@@ -356,7 +369,7 @@ __device__ __forceinline__ int requant_relu32(int hi, int lo16, int s, int cmax)
 // wave; the workgroup covers BN = 64*NB output channels with 2x2 waves of 64 x 32*NB each.
 // FLAT: the window is gathered as one slab per output pixel instead of staging a patch.
 template <int LIMBS, int NB, bool FLAT>
-__global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvArgs a)
+__global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void conv_mfma_kernel(const ConvArgs a)
 {
     constexpr int BN = 64 * NB;
     constexpr int NACC = (LIMBS == 2) ? 3 : 1;
@@ -379,10 +392,11 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
     const int NPIXA = a.NPIXA;
     int *tab = (int *)smem;          // staged pixel -> input pixel index, -1 outside the image
     int *psum = tab + a.NTAB;        // per staged pixel (FLAT: per tile row): sum of its codes
-    int *outoff = psum + a.NTAB;     // tile row -> output pixel index, -1 if not an output
+    int *apos = psum + a.NTAB;       // staged pixel -> byte offset inside a limb plane
+    int *outoff = apos + a.NTAB;     // tile row -> output pixel index, -1 if not an output
     int *abase_s = outoff + BM;      // tile row -> staged pixel of its (r=0, s=0) tap
-    unsigned char *Asm = smem + (((size_t)(2 * a.NTAB + 2 * BM) * 4 + 15) & ~(size_t)15);
-    const int APL = a.AROWS * PS;    // bytes per limb plane of the staged activations
+    unsigned char *Asm = smem + (((size_t)(3 * a.NTAB + 2 * BM) * 4 + 15) & ~(size_t)15);
+    const int APL = a.APLANE;        // bytes per limb plane of the staged activations
     unsigned char *Bsm = Asm + (size_t)LIMBS * APL;
 
     const int tid = threadIdx.x;
@@ -390,6 +404,7 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
         int g = -1;
         if (p < NPIXA) {
             const int pr = p / a.PW, pc = p % a.PW;
+            apos[p] = pr * a.PITCH + pc * PS;
             const int vr = vr0 + pr;
             const int n = vr / a.Hp, iy = vr % a.Hp - a.pad, ix = x0 - a.pad + pc;
             if (n < a.N && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) g = (n * a.H + iy) * a.W + ix;
@@ -411,18 +426,31 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
     constexpr int DEPTH = (BITEMS <= 2) ? 2 : 1;
     const int nslabs = a.nchunks * a.taps;
     v4i breg0[BITEMS], breg1[DEPTH == 2 ? BITEMS : 1];
-    auto load_slab = [&](int t, v4i *reg) {
-        const int cc = t / a.taps, tap = t - cc * a.taps;
-        const unsigned char *src =
-            a.wp + (((size_t)tap * a.nchunks + cc) * LIMBS * a.CoutP + (size_t)ntile * BN) * CK;
+    // Slabs are consecutive in memory in the order they are consumed, so fetching the next one is
+    // a pointer bump.  The fetch is issued on every step, also past the last slab (where it
+    // re-reads the last one): an unconditional load keeps the number of loads in flight the same
+    // on every path, so the wait before a slab is parked in LDS covers that slab only.
+    const size_t slab_bytes = (size_t)LIMBS * a.CoutP * CK;
+    const unsigned char *bsrc;
+    {
+        const int lb0 = tid / (BN * 4), rem0 = tid - lb0 * (BN * 4);
+        bsrc = a.wp + ((size_t)ntile * BN + (size_t)lb0 * a.CoutP + (rem0 >> 2)) * CK + (rem0 & 3) * 16;
+    }
+    // piece j of a thread is piece tid + j*256 of the slab: limb plane (j*256) / (BN*4), and
+    // ((j*256) % (BN*4)) / 4 rows below the thread's first piece
+    int pf = 0; // index of the next slab to fetch
+    auto load_slab = [&](v4i *reg) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < BITEMS; ++j) {
-            const int i = tid + j * kConvThreads;
-            const int lb = i / (BN * 4), rem = i - lb * (BN * 4);
-            reg[j] = *(const v4i *)(src + ((size_t)lb * a.CoutP + (rem >> 2)) * CK + (rem & 3) * 16);
+            const int lbj = (j * kConvThreads) / (BN * 4), rowj = ((j * kConvThreads) % (BN * 4)) / 4;
+            reg[j] = *(const v4i *)(bsrc + ((size_t)lbj * a.CoutP + rowj) * CK);
+        }
+        if (pf + 1 < nslabs) {
+            ++pf;
+            bsrc += slab_bytes;
         }
     };
-    auto store_slab = [&](int buf, const v4i *reg) {
+    auto store_slab = [&](int buf, const v4i *reg) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < BITEMS; ++j) {
             const int i = tid + j * kConvThreads;
@@ -430,8 +458,8 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
             *(v4i *)(Bsm + buf * BSLAB + lb * BPL + (rem >> 2) * PS + (rem & 3) * 16) = reg[j];
         }
     };
-    load_slab(0, breg0);
-    if (DEPTH == 2 && nslabs > 1) load_slab(1, breg1);
+    load_slab(breg0);
+    if (DEPTH == 2) load_slab(breg1);
     __syncthreads();
 
     const int lane = tid & 63, wave = tid >> 6;
@@ -441,7 +469,7 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb) {
         const int row = wm * 64 + mb * 32 + l32;
-        aoff[mb] = (FLAT ? row : abase_s[row]) * PS + kg * 16;
+        aoff[mb] = (FLAT ? row * PS : apos[abase_s[row]]) + kg * 16;
     }
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) boff[nb] = (wn * (NB * 32) + nb * 32 + l32) * PS + kg * 16;
@@ -462,56 +490,68 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
     constexpr int APF = (NB == 2 && LIMBS == 2) ? 4 : 8;
     constexpr int PIECES = (LIMBS == 2) ? 8 : 4;
     v4i areg[APF];
-    auto load_act = [&](int cc, int first) {
+    // Loads are unconditional (indices clamped into the patch, pixels outside the image read
+    // pixel 0 and are zeroed afterwards), so the whole batch is straight-line code: all table
+    // reads first, then all global loads back to back.
+    unsigned act_ok = 0; // bit j: piece j of the batch lies inside the image
+    auto load_act = [&](int cc, int first) __attribute__((always_inline)) {
+        int g[APF];
 #pragma unroll
         for (int j = 0; j < APF; ++j) {
-            const int i = first + tid + j * kConvThreads;
-            v4i v = {0, 0, 0, 0};
-            if (i < NPIXA * PIECES) {
-                const int p = i / PIECES, c = i % PIECES;
-                const int ch = cc * CK + c * (CK / PIECES);
-                const int g = tab[p];
-                if (ch < a.Cin && g >= 0) {
-                    if constexpr (LIMBS == 2)
-                        v = *(const v4i *)((const int16_t *)a.x + (size_t)g * a.Cin + ch);
-                    else
-                        v = *(const v4i *)((const int8_t *)a.x + (size_t)g * a.Cin + ch);
-                }
-            }
-            areg[j] = v;
+            const int i = min(first + tid + j * kConvThreads, NPIXA * PIECES - 1);
+            g[j] = tab[i / PIECES];
+        }
+        act_ok = 0;
+#pragma unroll
+        for (int j = 0; j < APF; ++j) {
+            const int i = min(first + tid + j * kConvThreads, NPIXA * PIECES - 1);
+            const int c = i % PIECES;
+            const int ch = min(cc * CK + c * (CK / PIECES), a.Cin - CK / PIECES);
+            act_ok |= (g[j] >= 0 ? 1u : 0u) << j;
+            const unsigned off = (unsigned)(max(g[j], 0) * a.Cin + ch) * (unsigned)(LIMBS == 2 ? 2 : 1);
+            areg[j] = *(const v4i *)((const unsigned char *)a.x + off);
         }
     };
-    auto store_act = [&](int cc, int first) {
+    auto store_act = [&](int cc, int first) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < APF; ++j) {
             const int i = first + tid + j * kConvThreads;
-            if (i < NPIXA * PIECES) {
-                const int p = i / PIECES, c = i % PIECES;
-                const v4i v = areg[j];
-                if constexpr (LIMBS == 2) {
-                    const int ch = cc * CK + c * 8;
-                    v2i hi = {0, 0}, lo = {0, 0};
-                    if (ch < a.Cin) {
-                        // codes outside the image were loaded as 0 = limbs (0, -128)
-                        hi.x = (int)__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x07050301u);
-                        hi.y = (int)__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x07050301u);
-                        lo.x = (int)(__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x06040200u) ^ 0x80808080u);
-                        lo.y = (int)(__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x06040200u) ^ 0x80808080u);
-                        const int sum = ((v.x << 16) >> 16) + (v.x >> 16) + ((v.y << 16) >> 16) + (v.y >> 16) +
-                                        ((v.z << 16) >> 16) + (v.z >> 16) + ((v.w << 16) >> 16) + (v.w >> 16);
-                        if (sum) atomicAdd(&psum[p], sum);
-                    }
-                    *(v2i *)(Asm + p * PS + c * 8) = hi;
-                    *(v2i *)(Asm + APL + p * PS + c * 8) = lo;
-                } else {
-                    *(v4i *)(Asm + p * PS + c * 16) = v;
+            const bool live = i < NPIXA * PIECES;
+            const int p = i / PIECES, c = i % PIECES;
+            const int ch = cc * CK + c * (CK / PIECES);
+            v4i v = areg[j];
+            if (!((act_ok >> j) & 1)) v = (v4i){0, 0, 0, 0}; // outside the image: the code 0
+            if constexpr (LIMBS == 2) {
+                v2i hi = {0, 0}, lo = {0, 0};
+                int sum = 0;
+                if (live && ch < a.Cin) {
+                    hi.x = (int)__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x07050301u);
+                    hi.y = (int)__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x07050301u);
+                    lo.x = (int)(__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x06040200u) ^ 0x80808080u);
+                    lo.y = (int)(__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x06040200u) ^ 0x80808080u);
+                    sum = ((v.x << 16) >> 16) + (v.x >> 16) + ((v.y << 16) >> 16) + (v.y >> 16) +
+                          ((v.z << 16) >> 16) + (v.z >> 16) + ((v.w << 16) >> 16) + (v.w >> 16);
                 }
+                // the 8 pieces of a pixel sit in 8 adjacent lanes: add them up with DPP lane
+                // exchanges (xor 1, xor 2 inside quads, then mirror inside the half row)
+                sum += __builtin_amdgcn_mov_dpp(sum, 0xB1, 0xF, 0xF, true);
+                sum += __builtin_amdgcn_mov_dpp(sum, 0x4E, 0xF, 0xF, true);
+                sum += __builtin_amdgcn_mov_dpp(sum, 0x141, 0xF, 0xF, true);
+                if (live) {
+                    if (c == 0 && sum) atomicAdd(&psum[p], sum); // single owner; no value returned
+                    const int pos = apos[p];
+                    *(v2i *)(Asm + pos + c * 8) = hi;
+                    *(v2i *)(Asm + APL + pos + c * 8) = lo;
+                }
+            } else {
+                if (ch >= a.Cin) v = (v4i){0, 0, 0, 0};
+                if (live) *(v4i *)(Asm + apos[p] + c * 16) = v;
             }
         }
     };
     // FLAT: the raw patch (all Cin channels, int16) is parked in the unused second weight
     // buffer, then each tile row's window is gathered from there, 16 consecutive k per piece.
-    auto stage_flat = [&]() {
+    auto stage_flat = [&]() __attribute__((always_inline)) {
         const int16_t *x = (const int16_t *)a.x;
         int16_t *raw = (int16_t *)(Bsm + BSLAB);
         const int nraw = NPIXA * a.Cin;
@@ -549,11 +589,7 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
             *(v4i *)(Asm + APL + row * PS + k0) = vl;
         }
     };
-    // With few live registers (NB == 1) the first batch of the next chunk is fetched a few slabs
-    // early and waits in registers; otherwise it is fetched at the chunk boundary.
-    constexpr bool EARLY = (NB == 1) && !FLAT;
-    const int early_tap = a.taps >= 4 ? a.taps - 3 : 0;
-    auto stage_activations = [&](int cc, bool have_first) {
+    auto stage_activations = [&](int cc, bool have_first) __attribute__((always_inline)) {
         if constexpr (FLAT) {
             stage_flat();
         } else {
@@ -564,13 +600,9 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
             }
         }
     };
-    auto compute_slab = [&](int tap, int t) {
+    int tap_s = 0, tapoff = 0, taprow = 0; // patch offset of the current tap, kept incrementally
+    auto compute_slab = [&](int t) __attribute__((always_inline)) {
         const unsigned char *Bcur = Bsm + (t & 1) * BSLAB;
-        int tapoff = 0;
-        if constexpr (!FLAT) {
-            const int r = tap / a.S, s = tap - r * a.S;
-            tapoff = (r * a.PW + s) * PS;
-        }
 #pragma unroll
         for (int k32 = 0; k32 < 2; ++k32) {
             if (k32 < a.ksteps) {
@@ -606,29 +638,44 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
         }
     };
 
+    // Pipeline: slab t+1 is parked in the other LDS buffer and slab t+1+DEPTH is requested while
+    // the MFMAs of slab t run, so one barrier per slab suffices and neither the LDS write nor
+    // the global latency sits between a barrier and the first fragment read.
     int cc = 0, tap = 0;
-    if (EARLY) load_act(0, 0);
-    auto step = [&](int t, v4i *reg) {
-        if (tap == 0) {
-            if (t) __syncthreads(); // all reads of the previous chunk's activations are done
-            stage_activations(cc, EARLY);
+    stage_activations(0, false);
+    store_slab(0, breg0);
+    load_slab(breg0);
+    auto step = [&](int t, v4i *next) __attribute__((always_inline)) {
+        if (tap == 0 && t) {
+            __syncthreads(); // all reads of the previous chunk's activations are done
+            stage_activations(cc, false);
         }
-        // slab t has arrived in registers: park it in buffer t&1 (last read two slabs ago, and
-        // every wave has passed a barrier since), then start fetching slab t+DEPTH
-        store_slab(t & 1, reg);
-        if (t + DEPTH < nslabs) load_slab(t + DEPTH, reg);
-        __syncthreads();
-        if (EARLY && tap == early_tap && cc + 1 < a.nchunks) load_act(cc + 1, 0);
-        compute_slab(tap, t);
+        __syncthreads(); // slab t (and a freshly staged patch) visible; slab t-1 fully consumed
+        store_slab((t + 1) & 1, next);
+        load_slab(next);
+        compute_slab(t);
         if (++tap == a.taps) {
             tap = 0;
             ++cc;
+            tap_s = 0;
+            tapoff = taprow = 0;
+        } else if (!FLAT) {
+            tapoff += PS;
+            if (++tap_s == a.S) {
+                tap_s = 0;
+                taprow += a.PITCH;
+                tapoff = taprow;
+            }
         }
     };
-    for (int t = 0; t < nslabs; t += 2) {
-        step(t, breg0);
-        if (t + 1 < nslabs) step(t + 1, DEPTH == 2 ? breg1 : breg0);
+    // both halves unconditional inside the loop (a skipped half would make the in-flight load
+    // count path dependent); an odd last slab is handled after it
+    int t = 0;
+    for (; t + 1 < nslabs; t += 2) {
+        step(t, DEPTH == 2 ? breg1 : breg0);
+        step(t + 1, breg0);
     }
+    if (t < nslabs) step(t, DEPTH == 2 ? breg1 : breg0);
 
     // ---- per-row sum of the window's codes (two-limb correction term 128 * sum(a))
     __syncthreads();
@@ -663,6 +710,9 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
         // v = 2^16*A + 2^8*B + C with every piece in int32: the column constant is split the same
         // way, 128*rowsum = 2^8*(rowsum >> 1) + 128*(rowsum & 1); then carries are pushed upward.
         const int s = a.act.s, cmax = a.act.hi;
+        const int esz = a.y16 ? 2 : 1;
+        const int ostride = BN * esz + 16;             // padded: 4 rows apart != 0 mod 256 bytes
+        unsigned char *otile = Asm + BM * 4;           // behind rowsum[]; patch and slabs are dead
         int cA[NB], cB[NB], cC[NB];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
@@ -700,14 +750,34 @@ __global__ __launch_bounds__(kConvThreads, 2) void conv_mfma_kernel(const ConvAr
                     else if (s == 16) c = requant_relu32<1>(hi, lo16, s, cmax);
                     else c = requant_relu32<2>(hi, lo16, s, cmax);
                     const bool ok = oo >= 0 && colg[nb] < a.Cout;
-                    if (ok) {
-                        const size_t idx = (size_t)oo * a.Cout + colg[nb];
-                        if (a.y16) ((int16_t *)a.y)[idx] = (int16_t)c;
-                        else ((int8_t *)a.y)[idx] = (int8_t)c;
-                    }
+                    const int colw = wn * (NB * 32) + nb * 32 + l32;
+                    if (a.y16) *(int16_t *)(otile + row * ostride + colw * 2) = (int16_t)c;
+                    else *(int8_t *)(otile + row * ostride + colw) = (int8_t)c;
                     zeros += wave_count(ok && c == 0);
                 }
             }
+        // the tile now sits in LDS row-major: write it out 16 bytes (8 or 16 channels) per lane,
+        // a pixel's channels contiguous, instead of one 2-byte store per value
+        __syncthreads();
+        constexpr int LOGP = (BN == 64) ? 2 : 3;       // log2(BN / 16)
+        const int lsh = LOGP + esz - 1;                // log2(16-byte pieces per tile row)
+        const int epp = 16 / esz;                      // codes per piece
+        const bool vec_ok = (a.Cout % epp) == 0;       // rows of the output tensor 16-byte aligned
+        for (int i = tid; i < (BM << lsh); i += kConvThreads) {
+            const int row = i >> lsh, c = i - (row << lsh);
+            const int oo = outoff[row];
+            const int col0 = ntile * BN + c * epp;
+            if (oo >= 0 && col0 < a.Cout) {
+                const unsigned char *src = otile + row * ostride + c * 16;
+                unsigned char *dst = (unsigned char *)a.y + ((size_t)oo * a.Cout + col0) * esz;
+                if (vec_ok && col0 + epp <= a.Cout) {
+                    *(v4i *)dst = *(const v4i *)src;
+                } else { // ragged channel tail, or rows not 16-byte aligned
+                    const int nbytes = min(epp, a.Cout - col0) * esz;
+                    for (int e = 0; e < nbytes; ++e) dst[e] = src[e];
+                }
+            }
+        }
     } else {
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
@@ -827,7 +897,8 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     }
     a.RH = p.RH; a.TW = p.TW; a.PW = p.PW; a.NPIXA = p.NPIXA;
     a.NTAB = std::max(p.NPIXA, BM);
-    a.AROWS = p.flat ? BM : p.NPIXA;
+    a.PITCH = p.PITCH;
+    a.APLANE = p.flat ? BM * PS : p.PRA * p.PITCH;
     a.tiles_c = p.tiles_c; a.tiles_n = p.tiles_n; a.CoutP = p.CoutP; a.nchunks = p.nchunks;
     a.taps = p.taps; a.ksteps = p.ksteps; a.Kflat = d->R * d->S * d->Cin;
     a.total_work = p.tiles_m * p.tiles_n;
@@ -947,6 +1018,7 @@ extern "C" lp_status lp_conv_plan_info(const lp_conv_desc *d, lp_qfmt qx, lp_qfm
     if (p.path == PATH_MFMA) {
         o.bn = p.BN; o.tile_rows = p.RH; o.tile_cols = p.TW; o.patch_rows = p.PRA; o.patch_cols = p.PW;
         o.tiles_m = p.tiles_m; o.tiles_n = p.tiles_n; o.lds_bytes = (int32_t)p.lds_bytes;
+        o.patch_pitch = p.PITCH;
     }
     *out_host = o;
     return LP_OK;

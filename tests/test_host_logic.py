@@ -110,6 +110,15 @@ def test_tile_geometry_addresses_the_right_pixels(N, H, W, Cin, Cout, R, S, pad)
     assert info["tiles_m"] == tiles_r * tiles_c
     assert info["lds_bytes"] <= 80 * 1024
     NPIXA = PRA * PW
+    pitch = info["patch_pitch"]
+    assert pitch >= PW * 80 and pitch % 16 == 0
+    if Cin >= 16:
+        # fragment reads: 16 lanes = 16 consecutive tile rows m read 16 bytes each at
+        # patch_row * pitch + patch_col * 80 (+ the same tap offset); served conflict-free when
+        # the 16-byte slots are distinct modulo the 256 bytes of the 64 LDS banks
+        for m0 in range(0, (RH * TW) // 16 * 16, 16):
+            slots = {(((m // TW) * pitch + (m % TW) * 80) // 16) % 16 for m in range(m0, m0 + 16)}
+            assert len(slots) == 16
     seen = set()
     # every tile when there are few; otherwise the first, the last and a spread in between
     rows = range(tiles_r) if tiles_r <= 64 else sorted(set([0, 1, tiles_r - 2, tiles_r - 1] + list(range(0, tiles_r, max(1, tiles_r // 50)))))
