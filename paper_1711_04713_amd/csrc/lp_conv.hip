@@ -19,6 +19,7 @@
 // variant: the whole R*S*Cin window is one K <= 64 slab gathered per output pixel.
 #include <algorithm>
 #include <mutex>
+#include <type_traits>
 #include <utility>
 #include <vector>
 
@@ -513,6 +514,10 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2,
         }
     };
     auto store_act = [&](int cc, int first) __attribute__((always_inline)) {
+        int pos_r[APF]; // LDS positions first, all reads in flight together (see the epilogue note)
+#pragma unroll
+        for (int j = 0; j < APF; ++j)
+            pos_r[j] = apos[min(first + tid + j * kConvThreads, NPIXA * PIECES - 1) / PIECES];
 #pragma unroll
         for (int j = 0; j < APF; ++j) {
             const int i = first + tid + j * kConvThreads;
@@ -539,13 +544,13 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2,
                 sum += __builtin_amdgcn_mov_dpp(sum, 0x141, 0xF, 0xF, true);
                 if (live) {
                     if (c == 0 && sum) atomicAdd(&psum[p], sum); // single owner; no value returned
-                    const int pos = apos[p];
+                    const int pos = pos_r[j];
                     *(v2i *)(Asm + pos + c * 8) = hi;
                     *(v2i *)(Asm + APL + pos + c * 8) = lo;
                 }
             } else {
                 if (ch >= a.Cin) v = (v4i){0, 0, 0, 0};
-                if (live) *(v4i *)(Asm + apos[p] + c * 16) = v;
+                if (live) *(v4i *)(Asm + pos_r[j] + c * 16) = v;
             }
         }
     };
@@ -709,74 +714,117 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2,
     if (a.fast) {
         // v = 2^16*A + 2^8*B + C with every piece in int32: the column constant is split the same
         // way, 128*rowsum = 2^8*(rowsum >> 1) + 128*(rowsum & 1); then carries are pushed upward.
+        // The codes go to an LDS tile first and leave as 16-byte row pieces.  Shift class and
+        // code width are compile-time here: the per-value work is about ten VALU operations.
         const int s = a.act.s, cmax = a.act.hi;
-        const int esz = a.y16 ? 2 : 1;
-        const int ostride = BN * esz + 16;             // padded: 4 rows apart != 0 mod 256 bytes
-        unsigned char *otile = Asm + BM * 4;           // behind rowsum[]; patch and slabs are dead
-        int cA[NB], cB[NB], cC[NB];
+        unsigned char *otile = Asm + BM * 4; // behind rowsum[]; patch and slabs are dead
+        auto requant_tile = [&](auto s16c, auto y16c) __attribute__((always_inline)) {
+            constexpr int S16 = decltype(s16c)::value;
+            constexpr bool Y16 = decltype(y16c)::value;
+            constexpr int ESZ = Y16 ? 2 : 1;
+            constexpr int OSTRIDE = BN * ESZ + 16; // padded: 4 rows apart != 0 mod 256 bytes
+            int cA[NB], cB[NB], cC[NB];
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            cA[nb] = (int)(colterm[nb] >> 16);
-            cB[nb] = (int)((colterm[nb] >> 8) & 255);
-            cC[nb] = (int)(colterm[nb] & 255);
-        }
+            for (int nb = 0; nb < NB; ++nb) {
+                cA[nb] = (int)(colterm[nb] >> 16);
+                cB[nb] = (int)((colterm[nb] >> 8) & 255);
+                cC[nb] = (int)(colterm[nb] & 255);
+            }
+            int rs_r[2][16]; // row sums first, all LDS reads in flight together
+            if constexpr (LIMBS == 2) {
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+                for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = wm * 64 + mb * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-                const int oo = outoff[row];
-                int rB = 0, rC = 0;
-                if constexpr (LIMBS == 2) {
-                    const int rs = rowsum[row];
-                    rB = rs >> 1;
-                    rC = (rs & 1) << 7;
-                }
+                    for (int v = 0; v < 16; ++v)
+                        rs_r[mb][v] = rowsum[wm * 64 + mb * 32 + 8 * (v >> 2) + 4 * kg + (v & 3)];
+            }
+            unsigned char *obase = otile + (wn * (NB * 32) + l32) * ESZ;
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    int hi, lo16;
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = wm * 64 + mb * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+                    int rB = 0, rC = 0;
                     if constexpr (LIMBS == 2) {
-                        const int C = acc[mb][nb][2][v] + cC[nb] + rC;
-                        const int B = acc[mb][nb][1][v] + cB[nb] + rB + (C >> 8);
-                        hi = acc[mb][nb][0][v] + cA[nb] + (B >> 8);
-                        lo16 = ((B & 255) << 8) | (C & 255);
-                    } else {
-                        const int C = acc[mb][nb][0][v] + (int)colterm[nb];
-                        hi = C >> 16;
-                        lo16 = C & 65535;
+                        rB = rs_r[mb][v] >> 1;
+                        rC = (rs_r[mb][v] & 1) << 7;
                     }
-                    int c;
-                    if (s >= 17) c = requant_relu32<0>(hi, lo16, s, cmax);
-                    else if (s == 16) c = requant_relu32<1>(hi, lo16, s, cmax);
-                    else c = requant_relu32<2>(hi, lo16, s, cmax);
-                    const bool ok = oo >= 0 && colg[nb] < a.Cout;
-                    const int colw = wn * (NB * 32) + nb * 32 + l32;
-                    if (a.y16) *(int16_t *)(otile + row * ostride + colw * 2) = (int16_t)c;
-                    else *(int8_t *)(otile + row * ostride + colw) = (int8_t)c;
-                    zeros += wave_count(ok && c == 0);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        int hi, lo16 = 0;
+                        if constexpr (LIMBS == 2) {
+                            const int C = acc[mb][nb][2][v] + cC[nb] + rC;
+                            const int B = acc[mb][nb][1][v] + cB[nb] + rB + (C >> 8);
+                            hi = acc[mb][nb][0][v] + cA[nb] + (B >> 8);
+                            if constexpr (S16 != 0) lo16 = ((B & 255) << 8) | (C & 255);
+                        } else {
+                            const int C = acc[mb][nb][0][v] + (int)colterm[nb];
+                            hi = C >> 16;
+                            lo16 = C & 65535;
+                        }
+                        const int c = requant_relu32<S16>(hi, lo16, s, cmax);
+                        unsigned char *o = obase + row * OSTRIDE + nb * 32 * ESZ;
+                        if constexpr (Y16) *(int16_t *)o = (int16_t)c;
+                        else *(int8_t *)o = (int8_t)c;
+                    }
+                }
+            // the tile now sits in LDS row-major: write it out 16 bytes (8 or 16 channels) per
+            // lane, a pixel's channels contiguous, and count the zero codes among the bytes written
+            __syncthreads();
+            constexpr int LSH = ((BN == 64) ? 2 : 3) + ESZ - 1; // log2(16-byte pieces per tile row)
+            constexpr int EPP = 16 / ESZ;                       // codes per piece
+            const bool vec_ok = (a.Cout % EPP) == 0;            // output rows 16-byte aligned
+            unsigned nz = 0;
+#pragma unroll
+            for (int k = 0; k < (BM << LSH) / kConvThreads; ++k) {
+                const int i = tid + k * kConvThreads;
+                const int row = i >> LSH, c = i - (row << LSH);
+                const int oo = outoff[row];
+                const int col0 = ntile * BN + c * EPP;
+                if (oo >= 0 && col0 < a.Cout) {
+                    const unsigned char *src = otile + row * OSTRIDE + c * 16;
+                    unsigned char *dst = (unsigned char *)a.y + ((size_t)oo * a.Cout + col0) * ESZ;
+                    if (vec_ok && col0 + EPP <= a.Cout) {
+                        const v4i q = *(const v4i *)src;
+                        *(v4i *)dst = q;
+                        // exact per-lane zero test: the top bit of a 16-bit (8-bit) lane survives
+                        // only when every bit of that lane is clear; no carry crosses lanes
+                        constexpr unsigned LOW = Y16 ? 0x7fff7fffu : 0x7f7f7f7fu;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const unsigned x = (unsigned)q[e];
+                            nz += __popc(~(((x & LOW) + LOW) | x | LOW));
+                        }
+                    } else { // ragged channel tail, or rows not 16-byte aligned
+                        const int ncodes = min(EPP, a.Cout - col0);
+                        for (int e = 0; e < ncodes; ++e) {
+                            if constexpr (Y16) {
+                                const int16_t q = ((const int16_t *)src)[e];
+                                ((int16_t *)dst)[e] = q;
+                                nz += (q == 0);
+                            } else {
+                                const int8_t q = ((const int8_t *)src)[e];
+                                ((int8_t *)dst)[e] = q;
+                                nz += (q == 0);
+                            }
+                        }
+                    }
                 }
             }
-        // the tile now sits in LDS row-major: write it out 16 bytes (8 or 16 channels) per lane,
-        // a pixel's channels contiguous, instead of one 2-byte store per value
-        __syncthreads();
-        constexpr int LOGP = (BN == 64) ? 2 : 3;       // log2(BN / 16)
-        const int lsh = LOGP + esz - 1;                // log2(16-byte pieces per tile row)
-        const int epp = 16 / esz;                      // codes per piece
-        const bool vec_ok = (a.Cout % epp) == 0;       // rows of the output tensor 16-byte aligned
-        for (int i = tid; i < (BM << lsh); i += kConvThreads) {
-            const int row = i >> lsh, c = i - (row << lsh);
-            const int oo = outoff[row];
-            const int col0 = ntile * BN + c * epp;
-            if (oo >= 0 && col0 < a.Cout) {
-                const unsigned char *src = otile + row * ostride + c * 16;
-                unsigned char *dst = (unsigned char *)a.y + ((size_t)oo * a.Cout + col0) * esz;
-                if (vec_ok && col0 + epp <= a.Cout) {
-                    *(v4i *)dst = *(const v4i *)src;
-                } else { // ragged channel tail, or rows not 16-byte aligned
-                    const int nbytes = min(epp, a.Cout - col0) * esz;
-                    for (int e = 0; e < nbytes; ++e) dst[e] = src[e];
-                }
-            }
+            // wave total of the per-lane counts, bit plane by bit plane: ballot + popcount
+            // (a lane counts at most 4 pieces x 16 codes = 64 zeros: 7 bits)
+#pragma unroll
+            for (int b = 0; b < 7; ++b) zeros += wave_count((nz >> b) & 1) << b;
+        };
+        using std::integral_constant;
+        if (a.y16) {
+            if (s >= 17) requant_tile(integral_constant<int, 0>{}, integral_constant<bool, true>{});
+            else if (s == 16) requant_tile(integral_constant<int, 1>{}, integral_constant<bool, true>{});
+            else requant_tile(integral_constant<int, 2>{}, integral_constant<bool, true>{});
+        } else {
+            if (s >= 17) requant_tile(integral_constant<int, 0>{}, integral_constant<bool, false>{});
+            else if (s == 16) requant_tile(integral_constant<int, 1>{}, integral_constant<bool, false>{});
+            else requant_tile(integral_constant<int, 2>{}, integral_constant<bool, false>{});
         }
     } else {
 #pragma unroll
