@@ -19,6 +19,23 @@ sys.path.insert(0, ROOT)
 INT8_PEAK_TOPS = 5000.0     # MI355X dense int8 MFMA, published (5.0 POP/s)
 HBM_PEAK_GBS = 8000.0
 
+# HBM traffic of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
+# profiles/): average bytes per launch over the 13 launches of one step, already scaled by the
+# copy-kernel factor.  Valid only for the kernel source it was measured on (sha256 of lp_conv.hip);
+# reported as null for any other source.
+TRAFFIC_RECORD = {"lp_conv_sha256": None, "bytes_per_launch": None}
+
+
+def _traffic_for_current_source():
+    import hashlib
+
+    path = os.path.join(ROOT, "paper_1711_04713_amd", "csrc", "lp_conv.hip")
+    try:
+        sha = hashlib.sha256(open(path, "rb").read()).hexdigest()
+    except OSError:
+        return None
+    return TRAFFIC_RECORD["bytes_per_launch"] if sha == TRAFFIC_RECORD["lp_conv_sha256"] else None
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -28,6 +45,8 @@ def main():
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--calib", type=int, default=2, help="images used to fix the per-layer formats")
     ap.add_argument("--cpu-images", type=int, default=2, help="images the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy (calibrates FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards by batch, see DESIGN.md",
@@ -68,6 +87,15 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
+
+    if args.copy_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        src.zero_()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # per-launch durations from the HIP events recorded on the launch stream
     per = {}
@@ -120,7 +148,7 @@ def main():
         "pct_of_int8_mfma_peak": round(100.0 * int8_tops / INT8_PEAK_TOPS, 2),
         "roofline": {
             "bound": "mfma", "kernel": dominant, "achieved": round(achieved, 1), "peak": INT8_PEAK_TOPS,
-            "unit": "TOP/s", "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": None,
+            "unit": "TOP/s", "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": _traffic_for_current_source(),
             "launches_per_step": sum(1 for l in layers if l["kernel"] == dominant),
             "ms_per_step_in_kernel": round(kern_ms[dominant], 4),
         },
