@@ -499,14 +499,14 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2,
         int g[APF];
 #pragma unroll
         for (int j = 0; j < APF; ++j) {
-            const int i = min(first + tid + j * kConvThreads, NPIXA * PIECES - 1);
+            const unsigned i = (unsigned)min(first + tid + j * kConvThreads, NPIXA * PIECES - 1);
             g[j] = tab[i / PIECES];
         }
         act_ok = 0;
 #pragma unroll
         for (int j = 0; j < APF; ++j) {
-            const int i = min(first + tid + j * kConvThreads, NPIXA * PIECES - 1);
-            const int c = i % PIECES;
+            const unsigned i = (unsigned)min(first + tid + j * kConvThreads, NPIXA * PIECES - 1);
+            const int c = (int)(i % PIECES);
             const int ch = min(cc * CK + c * (CK / PIECES), a.Cin - CK / PIECES);
             act_ok |= (g[j] >= 0 ? 1u : 0u) << j;
             const unsigned off = (unsigned)(max(g[j], 0) * a.Cin + ch) * (unsigned)(LIMBS == 2 ? 2 : 1);
@@ -517,12 +517,12 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2,
         int pos_r[APF]; // LDS positions first, all reads in flight together (see the epilogue note)
 #pragma unroll
         for (int j = 0; j < APF; ++j)
-            pos_r[j] = apos[min(first + tid + j * kConvThreads, NPIXA * PIECES - 1) / PIECES];
+            pos_r[j] = apos[(unsigned)min(first + tid + j * kConvThreads, NPIXA * PIECES - 1) / PIECES];
 #pragma unroll
         for (int j = 0; j < APF; ++j) {
             const int i = first + tid + j * kConvThreads;
             const bool live = i < NPIXA * PIECES;
-            const int p = i / PIECES, c = i % PIECES;
+            const int p = (int)((unsigned)i / PIECES), c = (int)((unsigned)i % PIECES);
             const int ch = cc * CK + c * (CK / PIECES);
             v4i v = areg[j];
             if (!((act_ok >> j) & 1)) v = (v4i){0, 0, 0, 0}; // outside the image: the code 0
@@ -594,6 +594,8 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2,
             *(v4i *)(Asm + APL + row * PS + k0) = vl;
         }
     };
+    constexpr bool EARLY = (NB == 1) && !FLAT; // registers to spare only with 64-wide channel tiles
+    const int early_tap = a.taps - 1;
     auto stage_activations = [&](int cc, bool have_first) __attribute__((always_inline)) {
         if constexpr (FLAT) {
             stage_flat();
@@ -653,11 +655,15 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2,
     auto step = [&](int t, v4i *next) __attribute__((always_inline)) {
         if (tap == 0 && t) {
             __syncthreads(); // all reads of the previous chunk's activations are done
-            stage_activations(cc, false);
+            stage_activations(cc, EARLY);
         }
         __syncthreads(); // slab t (and a freshly staged patch) visible; slab t-1 fully consumed
         store_slab((t + 1) & 1, next);
         load_slab(next);
+        // the next chunk's first batch of activations is requested before the chunk's last slab
+        // is multiplied and waits in registers; issued after the slab fetch, so that no slab
+        // wait in between forces it to complete early (loads return in order)
+        if (EARLY && tap == early_tap && cc + 1 < a.nchunks) load_act(cc + 1, 0);
         compute_slab(t);
         if (++tap == a.taps) {
             tap = 0;
