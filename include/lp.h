@@ -130,12 +130,14 @@ lp_status lp_conv_pack_weights(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, co
  * implicit GEMM.  For path 1: limbs (1 = int8 codes, 2 = 16-bit codes as two int8
  * limbs), the workgroup tile (128 output pixels = tile_rows consecutive rows of the
  * N*Ho stacked output rows x tile_cols columns, times bn output channels), the staged
- * input patch (patch_rows x patch_cols pixels, 80 bytes per pixel and limb, rows
- * patch_pitch bytes apart), tile counts and LDS bytes per workgroup.
+ * input patch (patch_rows x patch_cols pixels, 64 bytes per pixel and limb, rows
+ * patch_pitch bytes apart; the 16-byte slots of a pixel are stored in the order
+ * slot ^ (((patch_col >> 2) + swizzle_kmul * patch_row) & 3)), tile counts and LDS bytes per
+ * workgroup.
  */
 typedef struct {
     int32_t path, limbs, bn, tile_rows, tile_cols, patch_rows, patch_cols, tiles_m, tiles_n;
-    int32_t lds_bytes, patch_pitch;
+    int32_t lds_bytes, patch_pitch, swizzle_kmul;
 } lp_plan_info;
 lp_status lp_conv_plan_info(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, lp_plan_info *out_host);
 

@@ -29,7 +29,7 @@ namespace lp {
 
 constexpr int BM = 128;      // output pixels per workgroup
 constexpr int CK = 64;       // channels (bytes per limb) per staged chunk
-constexpr int PS = 80;       // LDS bytes per staged pixel / weight row (64 + 16 pad)
+constexpr int PS = 64;       // LDS bytes per staged pixel / weight row and limb (swizzled, see swz)
 constexpr int kConvThreads = 256;
 
 enum { PATH_DIRECT = 0, PATH_MFMA = 1 };
@@ -43,6 +43,7 @@ struct Plan {
     int nchunks, CoutP, BN;
     int RH, TW, PW, PRA, NPIXA;
     int PITCH;   // LDS bytes between staged patch rows
+    int KMUL;    // row multiplier of the patch swizzle key (4: one-dimensional key)
     int tiles_r, tiles_c, tiles_m, tiles_n;
     size_t lds_bytes;
     size_t packed_bytes, corr_offset;
@@ -57,26 +58,61 @@ static bool desc_ok(const lp_conv_desc *d)
            d->W + 2 * d->pad >= d->S;
 }
 
-// Staged patch rows are PITCH bytes apart.  A 16-byte fragment read is served 16 lanes at a
-// time from 64 four-byte banks; with pixels 80 bytes = 5 slots apart, 16 consecutive pixels hit
-// 16 distinct slots.  Lanes walk the tile row-major (TW pixels, then the next patch row), so a
-// pitch of 5*TW slots (mod 16) makes every 16-lane group look like 16 consecutive pixels.
-static int patch_pitch(int pw, int tw)
+// LDS layout of staged pixels and weight rows: 64 bytes each, no padding; the four 16-byte
+// slots of an item are stored in the order slot ^ key.  A 16-byte fragment read is served 16
+// lanes at a time from 64 four-byte banks (256 bytes): an item's number modulo 4 picks its
+// 64-byte quarter, and the key must differ among the (up to four) items of a group that share
+// a quarter.  Weight rows and flat-window rows are numbered consecutively per lane group, so
+// key = (number >> 2) & 3 does it.  Patch pixels are visited tile-row-major (TW pixels, then the
+// next patch row), so their key is ((patch_col >> 2) + kmul * patch_row) & 3 with the rows
+// pitch pixels apart, or, for kmul == 4, the one-dimensional (pixel number >> 2) & 3 (best when
+// PW == TW, e.g. 1x1 kernels and the FC layers); pitch (PW..PW+3) and kmul (0..4) are chosen
+// per plan by counting the conflicts of every 16-lane group at every tap.
+static int swizzle_conflicts(int pw, int tw, int rh, int R, int S, int pitch_px, int kmul)
 {
-    int slots = 5 * pw;
-    while ((slots - 5 * tw) % 16 != 0) ++slots;
-    return slots * 16;
+    int cost = 0;
+    const int rows = rh * tw;
+    for (int r = 0; r < R; ++r)
+        for (int s = 0; s < S; ++s)
+            for (int m0 = 0; m0 < rows; m0 += 16) {
+                int seen[16] = {0};
+                int worst = 0;
+                for (int m = m0; m < std::min(m0 + 16, rows); ++m) {
+                    const int prow = m / tw + r, pcol = m % tw + s;
+                    const int key = (kmul == 4 ? (prow * pitch_px + pcol) >> 2 : (pcol >> 2) + kmul * prow) & 3;
+                    const int group = (4 * (prow * pitch_px + pcol) + key) & 15; // slot 0; others permute
+                    worst = std::max(worst, ++seen[group]);
+                }
+                cost += worst - 1;
+            }
+    (void)pw;
+    return cost;
+}
+
+static void choose_swizzle(int pw, int tw, int rh, int R, int S, int *pitch_px, int *kmul)
+{
+    int best = 1 << 30;
+    for (int px = pw; px < (S == 1 ? pw + 1 : pw + 4); ++px) // without horizontal taps the 1-D key is exact
+        for (int k = 0; k < 5; ++k) {
+            const int c = swizzle_conflicts(pw, tw, rh, R, S, px, k) * 64 + (px - pw); // ties: less padding
+            if (c < best) {
+                best = c;
+                *pitch_px = px;
+                *kmul = k;
+            }
+        }
 }
 
 // LDS: tables (3*ntab + 2*BM ints), staged patch (one plane per limb), two weight slabs
-static size_t mfma_lds_bytes(int limbs, int pra, int pw, int tw, int bn, int flat)
+static size_t mfma_lds_bytes(int limbs, int pra, int pw, int pitch_px, int bn, int flat)
 {
     const int ntab = std::max(pra * pw, BM);
-    const size_t plane = flat ? (size_t)BM * PS : (size_t)pra * patch_pitch(pw, tw);
+    const size_t plane = flat ? (size_t)BM * PS : (size_t)pra * pitch_px * PS;
     size_t tables = round_up((size_t)(3 * ntab + 2 * BM) * 4, 16);
     return tables + (size_t)limbs * plane + (size_t)2 * limbs * bn * PS;
 }
-constexpr size_t kLdsBudget = 80000; // two workgroups per CU within the 160 KB of LDS
+// LDS budgets tried in turn: three workgroups per CU (160 KB / 3), else two
+constexpr size_t kLdsBudgets[2] = {54400, 80000};
 
 // virtual row (in the stack of zero-padded images, Hp rows each) of stacked output row fr
 static inline int vrow(int fr, int Ho, int Hp) { return (fr / Ho) * Hp + fr % Ho; }
@@ -145,6 +181,7 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
         // tile search: RH x TW <= 128 output pixels, minimise wasted MFMA rows, then patch size
         const int RS = d->R * d->S;
         double best = 1e300;
+        for (int pass = 0; pass < 2 && best == 1e300; ++pass)
         for (int tw = 1; tw <= std::min(p.Wo, BM); ++tw)
             for (int rh = std::min(BM / tw, p.FR); rh >= 1; --rh) {
                 const int tiles_c = (p.Wo + tw - 1) / tw, tiles_r = (p.FR + rh - 1) / rh;
@@ -154,7 +191,7 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
                 const int cross = (p.Ho % rh == 0) ? 0 : std::min((rh - 1 + p.Ho - 1) / p.Ho, d->N - 1);
                 const int pra = rh + d->R - 1 + cross * (d->R - 1);
                 const int npixa = pra * pw;
-                if (mfma_lds_bytes(p.limbs, pra, pw, tw, p.limbs == 2 ? 64 : 128, p.flat) > kLdsBudget) continue;
+                if (mfma_lds_bytes(p.limbs, pra, pw, d->S == 1 ? pw : pw + 3, p.limbs == 2 ? 64 : 128, p.flat) > kLdsBudgets[pass]) continue;
                 if (p.flat && (size_t)npixa * d->Cin * 2 > (size_t)2 * 64 * PS) continue; // raw patch parks in a weight buffer
                 const double cost = (double)tiles_c * tiles_r * ((double)BM * RS + 0.5 * npixa);
                 if (cost < best) {
@@ -178,8 +215,13 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
         // registers for the prefetch pipeline, so it always runs 64-wide
         if (p.limbs == 2) p.BN = 64;
         p.tiles_n = p.CoutP / p.BN;
-        p.PITCH = patch_pitch(p.PW, p.TW);
-        p.lds_bytes = mfma_lds_bytes(p.limbs, p.PRA, p.PW, p.TW, p.BN, p.flat);
+        {
+            int px = p.PW, k = 0;
+            if (!p.flat) choose_swizzle(p.PW, p.TW, p.RH, d->R, d->S, &px, &k);
+            p.PITCH = px * PS;
+            p.KMUL = k;
+        }
+        p.lds_bytes = mfma_lds_bytes(p.limbs, p.PRA, p.PW, p.PITCH / PS, p.BN, p.flat);
         p.corr_offset = round_up((size_t)p.taps * p.nchunks * p.limbs * p.CoutP * CK, 256);
         p.packed_bytes = p.corr_offset + (size_t)p.CoutP * sizeof(int64_t);
     } else {
@@ -280,7 +322,7 @@ struct ConvArgs {
     unsigned *zero_partial; // one count per workgroup (MFMA path), summed by a second kernel
     int N, H, W, Cin, Cout, R, S, stride, pad;
     int Ho, Wo, Hp, FR;
-    int RH, TW, PW, NPIXA, NTAB, APLANE, PITCH;
+    int RH, TW, PW, NPIXA, NTAB, APLANE, PITCH, KMUL;
     int tiles_c, tiles_n, CoutP, nchunks, taps, ksteps, Kflat;
     int total_work, per_xcd;
     int fast; // 32-bit requantization is exact for this call (see epilogue)
@@ -343,6 +385,12 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(const ConvArgs a)
 
 // -------------------------------------------------------------------------- MFMA path
 
+// byte offset of 16-byte slot q of the pixel / weight row that starts at byte offset pix (a
+// multiple of 64) in the swizzled layout
+__device__ __forceinline__ int swz(int pix, int q) { return pix + (((q ^ (pix >> 8)) & 3) << 4); }
+// the same with an explicit key (patch pixels: key from patch row and column)
+__device__ __forceinline__ int swzk(int pix, int q, int key) { return pix + (((q ^ key) & 3) << 4); }
+
 __device__ __forceinline__ v16i mfma_i8(v4i a, v4i b, v16i c)
 {
     return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
@@ -370,7 +418,7 @@ __device__ __forceinline__ int requant_relu32(int hi, int lo16, int s, int cmax)
 // wave; the workgroup covers BN = 64*NB output channels with 2x2 waves of 64 x 32*NB each.
 // FLAT: the window is gathered as one slab per output pixel instead of staging a patch.
 template <int LIMBS, int NB, bool FLAT>
-__global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void conv_mfma_kernel(const ConvArgs a)
+__global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void conv_mfma_kernel(const ConvArgs a)
 {
     constexpr int BN = 64 * NB;
     constexpr int NACC = (LIMBS == 2) ? 3 : 1;
@@ -405,7 +453,8 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2,
         int g = -1;
         if (p < NPIXA) {
             const int pr = p / a.PW, pc = p % a.PW;
-            apos[p] = pr * a.PITCH + pc * PS;
+            const int off = pr * a.PITCH + pc * PS;
+            apos[p] = off | ((a.KMUL == 4 ? off >> 8 : (pc >> 2) + a.KMUL * pr) & 3); // offset | swizzle key
             const int vr = vr0 + pr;
             const int n = vr / a.Hp, iy = vr % a.Hp - a.pad, ix = x0 - a.pad + pc;
             if (n < a.N && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) g = (n * a.H + iy) * a.W + ix;
@@ -424,7 +473,7 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2,
     // weight slabs: slab t = chunk * taps + tap lives at [tap][chunk][limb][CoutP][64].  A slab
     // travels global -> registers -> LDS; DEPTH slabs are in flight in registers so that the
     // L2 latency is covered by the MFMAs of the slabs before it.
-    constexpr int DEPTH = (BITEMS <= 2) ? 2 : 1;
+    constexpr int DEPTH = 1;
     const int nslabs = a.nchunks * a.taps;
     v4i breg0[BITEMS], breg1[DEPTH == 2 ? BITEMS : 1];
     // Slabs are consecutive in memory in the order they are consumed, so fetching the next one is
@@ -456,7 +505,7 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2,
         for (int j = 0; j < BITEMS; ++j) {
             const int i = tid + j * kConvThreads;
             const int lb = i / (BN * 4), rem = i - lb * (BN * 4);
-            *(v4i *)(Bsm + buf * BSLAB + lb * BPL + (rem >> 2) * PS + (rem & 3) * 16) = reg[j];
+            *(v4i *)(Bsm + buf * BSLAB + lb * BPL + swz((rem >> 2) * PS, rem & 3)) = reg[j];
         }
     };
     load_slab(breg0);
@@ -466,14 +515,16 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2,
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave & 1, wn = wave >> 1;
     const int l32 = lane & 31, kg = lane >> 5;
-    int aoff[2], boff[NB];
+    int aoff[2], apr[2], apc[2], boff[NB];
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb) {
         const int row = wm * 64 + mb * 32 + l32;
-        aoff[mb] = (FLAT ? row * PS : apos[abase_s[row]]) + kg * 16;
+        aoff[mb] = FLAT ? row * PS : (apos[abase_s[row]] & ~3); // start of the row's (r=0, s=0) pixel
+        apr[mb] = FLAT ? 0 : abase_s[row] / a.PW;               // its patch row and column
+        apc[mb] = FLAT ? 0 : abase_s[row] % a.PW;
     }
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) boff[nb] = (wn * (NB * 32) + nb * 32 + l32) * PS + kg * 16;
+    for (int nb = 0; nb < NB; ++nb) boff[nb] = swz((wn * (NB * 32) + nb * 32 + l32) * PS, kg);
 
     v16i acc[2][NB][NACC];
 #pragma unroll
@@ -488,7 +539,7 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2,
     // Activations travel global -> registers -> LDS in batches of APF 16-byte pieces per thread,
     // so that a batch's loads are all in flight together.  PIECES: 16-byte pieces per staged
     // pixel and chunk (8 x 8 int16 codes, or 4 x 16 int8 codes).
-    constexpr int APF = (NB == 2 && LIMBS == 2) ? 4 : 8;
+    constexpr int APF = 4;
     constexpr int PIECES = (LIMBS == 2) ? 8 : 4;
     v4i areg[APF];
     // Loads are unconditional (indices clamped into the patch, pixels outside the image read
@@ -545,12 +596,13 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2,
                 if (live) {
                     if (c == 0 && sum) atomicAdd(&psum[p], sum); // single owner; no value returned
                     const int pos = pos_r[j];
-                    *(v2i *)(Asm + pos + c * 8) = hi;
-                    *(v2i *)(Asm + APL + pos + c * 8) = lo;
+                    const int at = swzk(pos & ~3, c >> 1, pos) + (c & 1) * 8;
+                    *(v2i *)(Asm + at) = hi;
+                    *(v2i *)(Asm + APL + at) = lo;
                 }
             } else {
                 if (ch >= a.Cin) v = (v4i){0, 0, 0, 0};
-                if (live) *(v4i *)(Asm + pos_r[j] + c * 16) = v;
+                if (live) *(v4i *)(Asm + swzk(pos_r[j] & ~3, c, pos_r[j])) = v;
             }
         }
     };
@@ -590,11 +642,11 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2,
             if (sum) atomicAdd(&psum[row], sum);
             const v4i vh = {(int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
             const v4i vl = {(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3]};
-            *(v4i *)(Asm + row * PS + k0) = vh;
-            *(v4i *)(Asm + APL + row * PS + k0) = vl;
+            *(v4i *)(Asm + swz(row * PS, k0 >> 4)) = vh;
+            *(v4i *)(Asm + APL + swz(row * PS, k0 >> 4)) = vl;
         }
     };
-    constexpr bool EARLY = (NB == 1) && !FLAT; // registers to spare only with 64-wide channel tiles
+    constexpr bool EARLY = false;
     const int early_tap = a.taps - 1;
     auto stage_activations = [&](int cc, bool have_first) __attribute__((always_inline)) {
         if constexpr (FLAT) {
@@ -607,22 +659,32 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2,
             }
         }
     };
-    int tap_s = 0, tapoff = 0, taprow = 0; // patch offset of the current tap, kept incrementally
+    int tap_s = 0, tap_r = 0, tapoff = 0, taprow = 0; // patch offset of the current tap, kept incrementally
     auto compute_slab = [&](int t) __attribute__((always_inline)) {
         const unsigned char *Bcur = Bsm + (t & 1) * BSLAB;
+        int afrag[2]; // this tap's pixel per row block, slot kg; the second K=32 step is slot kg+2
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            if constexpr (FLAT) afrag[mb] = swz(aoff[mb], kg);
+            else {
+                const int pix = aoff[mb] + tapoff;
+                const int key = a.KMUL == 4 ? pix >> 8 : ((apc[mb] + tap_s) >> 2) + a.KMUL * (apr[mb] + tap_r);
+                afrag[mb] = swzk(pix, kg, key);
+            }
+        }
 #pragma unroll
         for (int k32 = 0; k32 < 2; ++k32) {
             if (k32 < a.ksteps) {
                 v4i ah[2], al[2], bh[NB], bl[NB];
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb) {
-                    ah[mb] = *(const v4i *)(Asm + aoff[mb] + tapoff + k32 * 32);
-                    if constexpr (LIMBS == 2) al[mb] = *(const v4i *)(Asm + APL + aoff[mb] + tapoff + k32 * 32);
+                    ah[mb] = *(const v4i *)(Asm + (afrag[mb] ^ (k32 * 32)));
+                    if constexpr (LIMBS == 2) al[mb] = *(const v4i *)(Asm + APL + (afrag[mb] ^ (k32 * 32)));
                 }
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    bh[nb] = *(const v4i *)(Bcur + boff[nb] + k32 * 32);
-                    if constexpr (LIMBS == 2) bl[nb] = *(const v4i *)(Bcur + BPL + boff[nb] + k32 * 32);
+                    bh[nb] = *(const v4i *)(Bcur + (boff[nb] ^ (k32 * 32)));
+                    if constexpr (LIMBS == 2) bl[nb] = *(const v4i *)(Bcur + BPL + (boff[nb] ^ (k32 * 32)));
                 }
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb)
@@ -642,6 +704,9 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2,
                             acc[mb][nb][1] = mfma_i8(al[mb], bh[nb], acc[mb][nb][1]);
                 }
             }
+            // keep the second half's fragment loads behind the first half's MFMAs: both sets
+            // live at once would cost 24 more registers than three waves per SIMD leave
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
@@ -668,12 +733,13 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(2,
         if (++tap == a.taps) {
             tap = 0;
             ++cc;
-            tap_s = 0;
+            tap_s = tap_r = 0;
             tapoff = taprow = 0;
         } else if (!FLAT) {
             tapoff += PS;
             if (++tap_s == a.S) {
                 tap_s = 0;
+                ++tap_r;
                 taprow += a.PITCH;
                 tapoff = taprow;
             }
@@ -952,6 +1018,7 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     a.RH = p.RH; a.TW = p.TW; a.PW = p.PW; a.NPIXA = p.NPIXA;
     a.NTAB = std::max(p.NPIXA, BM);
     a.PITCH = p.PITCH;
+    a.KMUL = p.KMUL;
     a.APLANE = p.flat ? BM * PS : p.PRA * p.PITCH;
     a.tiles_c = p.tiles_c; a.tiles_n = p.tiles_n; a.CoutP = p.CoutP; a.nchunks = p.nchunks;
     a.taps = p.taps; a.ksteps = p.ksteps; a.Kflat = d->R * d->S * d->Cin;
@@ -1073,6 +1140,7 @@ extern "C" lp_status lp_conv_plan_info(const lp_conv_desc *d, lp_qfmt qx, lp_qfm
         o.bn = p.BN; o.tile_rows = p.RH; o.tile_cols = p.TW; o.patch_rows = p.PRA; o.patch_cols = p.PW;
         o.tiles_m = p.tiles_m; o.tiles_n = p.tiles_n; o.lds_bytes = (int32_t)p.lds_bytes;
         o.patch_pitch = p.PITCH;
+        o.swizzle_kmul = p.KMUL;
     }
     *out_host = o;
     return LP_OK;
