@@ -1,0 +1,153 @@
+"""GPU parity at the full sizes of the workload configurations, in the launch configuration
+bench.py times (fused LPAct + ReLU + zero count, codes only).  Where the whole tensor is out of
+the oracle's reach, sampled outputs are recomputed one by one by the oracle and size-independent
+properties are checked (zero count equals the zeros among the written codes, ReLU range)."""
+import numpy as np
+import pytest
+import torch
+
+import lp_inputs
+import paper_1711_04713_amd as lp
+from gpu_helpers import to_dev
+from oracle import vgg as ovgg
+from paper_1711_04713_amd.stack import ConvStack
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_layer(x_codes_nchw, w_codes, qx, qw, qy, relu=True):
+    """One fused conv launch on NCHW int codes; returns (y torch NHWC tensor, zero count)."""
+    N, Cin, H, W = x_codes_nchw.shape
+    Cout = w_codes.shape[0]
+    d = lp.ConvDesc(N, H, W, Cin, Cout, 3, 3, 1, 1)
+    dt = np.int16 if qx[0] > 8 else np.int8
+    xd = to_dev(np.ascontiguousarray(x_codes_nchw.transpose(0, 2, 3, 1)).astype(dt))
+    wd = to_dev(np.ascontiguousarray(w_codes.transpose(0, 2, 3, 1)).astype(np.int16 if qw[0] > 8 else np.int8))
+    packed = torch.empty(lp.lp_conv_packed_bytes(d, qx, qw), dtype=torch.uint8, device="cuda")
+    lp.lp_conv_pack_weights(d, qx, qw, wd, packed)
+    y = torch.empty((N, H, W, Cout), dtype=torch.int16 if qy[0] > 8 else torch.int8, device="cuda")
+    z = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ws = torch.empty(max(lp.lp_conv_workspace_bytes(d, qx, qw), 16), dtype=torch.uint8, device="cuda")
+    lp.lp_conv_fwd(d, xd, qx, packed, qw, qy=qy, y_codes=y, relu=relu, zero_count=z, workspace=ws)
+    torch.cuda.synchronize()
+    return y, int(z.item()), lp.lp_conv_plan_info(d, qx, qw)
+
+
+def _check_sampled(oracle, x, w, y, zeros, qx, qw, qy, samples, seed):
+    N, Cout, H, W = x.shape[0], w.shape[0], x.shape[2], x.shape[3]
+    rng = np.random.default_rng(seed)
+    total = N * Cout * H * W
+    idx = rng.integers(0, total, samples)
+    # always include the image corners and the last element (padding and ragged-tile paths)
+    idx[:4] = [0, W - 1, (H - 1) * W, total - 1]
+    acc = oracle.conv_sampled(x, w, idx)
+    want, _ = oracle.act(acc, qx[2] + qw[2], *qy, True, oracle.ROUND_AWAY)
+    xo = idx % W
+    yo = (idx // W) % H
+    co = (idx // (W * H)) % Cout
+    n = idx // (W * H * Cout)
+    got = y[torch.from_numpy(n).cuda(), torch.from_numpy(yo).cuda(), torch.from_numpy(xo).cuda(),
+            torch.from_numpy(co).cuda()].cpu().numpy().astype(np.int32)
+    assert np.array_equal(got, want)
+    assert zeros == int((y == 0).sum().item())          # the counter matches the codes it counted
+    assert int(y.min().item()) >= 0                      # ReLU
+
+
+def test_config2_conv1_2_layer_full_size(oracle):
+    """Batch 8, 64->64 channels, 224x224: formats from the dynamic range of the float tensors
+    (both sides), output format from a calibration on the first image (both sides)."""
+    xf, wf = lp_inputs.config2(seed=1, batch=8, hw=224)
+    ws_dev = torch.empty(lp.LP_RANGE_WORKSPACE_WORDS, dtype=torch.int64, device="cuda")
+    qx_gpu, _ = lp.lp_range(to_dev(xf.reshape(-1)), 16, 0.0, ws_dev)
+    qw_gpu, _ = lp.lp_range(to_dev(wf.reshape(-1)), 16, 0.0, ws_dev)
+    mx, mw = oracle.range_float(xf, 16)[0], oracle.range_float(wf, 16)[0]
+    assert (qx_gpu.m, qw_gpu.m) == (mx, mw)
+    qx, qw = (16, mx, 16 - mx), (16, mw, 16 - mw)
+    x, w = oracle.quantize(xf, *qx)[0], oracle.quantize(wf, *qw)[0]
+    acc0 = oracle.conv(x[:1], w, threads=16)
+    mo = oracle.range_acc(acc0, qx[2] + qw[2], True, 16)[0]
+    qy = (16, mo, 16 - mo)
+    y, zeros, info = _run_layer(x, w, qx, qw, qy)
+    assert info["path"] == 1
+    want0, _ = oracle.act(acc0, qx[2] + qw[2], *qy, True, oracle.ROUND_AWAY)       # first image in full
+    assert np.array_equal(y[:1].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2), want0)
+    _check_sampled(oracle, x, w, y, zeros, qx, qw, qy, 4000, 2)
+    assert 0.3 < zeros / y.numel() < 0.8
+
+
+def test_config3_vgg16_stack_batch32(oracle):
+    """The benchmark's own configuration: 13 conv + 5 pools at batch 32, formats calibrated on the
+    first image; the first image's codes of every layer are compared with the oracle chain, the
+    rest of the batch through the counters."""
+    B = 32
+    x = lp_inputs.config3_input(seed=2, batch=B)
+    ws = lp_inputs.vgg16_conv_weights(seed=2)
+    pools = [p for (*_, p) in lp_inputs.VGG16_CONV]
+    cal = ovgg.conv_stack(x[:1], ws, pools, n=16, threads=16)
+    st = ConvStack([to_dev(np.ascontiguousarray(w.transpose(0, 2, 3, 1))) for w in ws], pools)
+    xd = to_dev(np.ascontiguousarray(x.transpose(0, 2, 3, 1)))
+    st.calibrate(xd[:1])
+    assert st.qx.m == cal["mx"]
+    st.prepare(B, 224, 224)
+    out = st.forward(xd)
+    torch.cuda.synchronize()
+    for i, (L, G) in enumerate(zip(cal["layers"], st.layers)):
+        assert (st.qw[i].m, st.qy[i].m) == (L["mw"], L["mo"]), "layer %d formats" % i
+        got = G["y"][:1].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2)
+        assert np.array_equal(got, L["codes"]), "layer %d codes of image 0" % i
+        assert int(st.zero_counts[i].item()) == int((G["y"] == 0).sum().item()), "layer %d zero count" % i
+        assert 0.3 < int(st.zero_counts[i].item()) / G["y"].numel() < 0.8
+    assert np.array_equal(out[:1].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2), cal["final"])
+
+
+@pytest.mark.parametrize("index", [0, 1, 3, 4, 6, 8])
+def test_config4_int8_layers_batch64(oracle, index):
+    """conv3_1 .. conv5_3 at their true shapes, batch 64, 8-bit weights and activations."""
+    name, xf, wf = lp_inputs.config4_layer(index, seed=3, batch=64)
+    mx, mw = oracle.range_float(xf, 8)[0], oracle.range_float(wf, 8)[0]
+    assert mw == 1                                              # Q1.7 weights
+    qx, qw = (8, mx, 8 - mx), (8, mw, 8 - mw)
+    x, w = oracle.quantize(xf, *qx)[0], oracle.quantize(wf, *qw)[0]
+    idx = np.random.default_rng(index).integers(0, x.shape[2] * x.shape[3] * w.shape[0], 3000)
+    acc = oracle.conv_sampled(x[:1], w, idx)
+    mo = oracle.range_acc(acc, qx[2] + qw[2], True, 8)[0]       # output format from a sample of image 0
+    qy = (8, mo, 8 - mo)
+    y, zeros, info = _run_layer(x, w, qx, qw, qy)
+    assert info["path"] == 1 and info["limbs"] == 1
+    _check_sampled(oracle, x, w, y, zeros, qx, qw, qy, 3000, 5 + index)
+
+
+def test_config5_fc_classifier_batch256(oracle):
+    """fc6 25088->4096, fc7 4096->4096, fc8 4096->1000 at batch 256, 16-bit; each layer is fed the
+    oracle's input codes and compared on 8 full rows plus sampled entries; fc8 has no ReLU."""
+    M = 256
+    x = lp_inputs.config5_input(seed=4, batch=M)
+    ws = lp_inputs.config5_weights(seed=4)
+    mx = oracle.range_float(x, 16)[0]
+    cur, q_in = oracle.quantize(x, 16, mx, 16 - mx)[0], (16, mx, 16 - mx)
+    rows = np.array([0, 1, 63, 64, 127, 128, 200, 255])
+    for (name, K, Nout, relu), wf in zip(lp_inputs.VGG16_FC, ws):
+        mw = oracle.range_float(wf, 16)[0]
+        qw = (16, mw, 16 - mw)
+        w = oracle.quantize(wf, *qw)[0]
+        f_acc = q_in[2] + qw[2]
+        acc_rows = oracle.fc(cur[rows], w, threads=16)
+        mo = oracle.range_acc(acc_rows, f_acc, relu, 16)[0]
+        qy = (16, mo, 16 - mo)
+        want_rows, _ = oracle.act(acc_rows, f_acc, *qy, relu, oracle.ROUND_AWAY)
+        xd, wd = to_dev(cur.astype(np.int16)), to_dev(w.astype(np.int16))
+        packed = torch.empty(lp.lp_fc_packed_bytes(M, K, Nout, q_in, qw), dtype=torch.uint8, device="cuda")
+        lp.lp_fc_pack_weights(M, K, Nout, q_in, qw, wd, packed)
+        y = torch.empty((M, Nout), dtype=torch.int16, device="cuda")
+        z = torch.zeros(1, dtype=torch.int64, device="cuda")
+        wsb = torch.empty(max(lp.lp_fc_workspace_bytes(M, K, Nout, q_in, qw), 16), dtype=torch.uint8, device="cuda")
+        lp.lp_fc_fwd(M, K, Nout, xd, q_in, packed, qw, qy=qy, y_codes=y, relu=relu, zero_count=z, workspace=wsb)
+        torch.cuda.synchronize()
+        got = y.cpu().numpy().astype(np.int32)
+        assert np.array_equal(got[rows], want_rows), name
+        assert int(z.item()) == int((got == 0).sum()), name
+        # next layer's input: the oracle's own codes for the whole batch
+        acc_all = oracle.fc(cur, w, threads=16)
+        nxt, _ = oracle.act(acc_all, f_acc, *qy, relu, oracle.ROUND_AWAY)
+        assert np.array_equal(got, nxt), name
+        cur, q_in = nxt, qy
