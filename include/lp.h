@@ -133,16 +133,22 @@ lp_status lp_conv_pack_weights(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, co
  * input patch (patch_rows x patch_cols pixels, 64 bytes per pixel and limb, rows
  * patch_pitch bytes apart; the 16-byte slots of a pixel are stored in the order
  * slot ^ (((patch_col >> 2) + swizzle_kmul * patch_row) & 3)), tile counts and LDS bytes per
- * workgroup.
+ * workgroup; the launch: workgroups in the grid, and split = parts into which each tile of the
+ * last, partly filled round of workgroup slots is cut along the reduction (1 = none; used
+ * only when a workspace is passed).
  */
 typedef struct {
     int32_t path, limbs, bn, tile_rows, tile_cols, patch_rows, patch_cols, tiles_m, tiles_n;
-    int32_t lds_bytes, patch_pitch, swizzle_kmul;
+    int32_t lds_bytes, patch_pitch, swizzle_kmul, workgroups, split;
 } lp_plan_info;
 lp_status lp_conv_plan_info(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, lp_plan_info *out_host);
 
-/* Bytes of device workspace lp_conv_fwd needs for this problem when zero_count_dev is
- * given (per-workgroup partial counts; may be 0).  Without zero_count_dev none is needed. */
+/* Bytes of device workspace lp_conv_fwd uses for this problem (may be 0): per-workgroup
+ * partial zero counts, and room for the partial sums of tiles whose reduction is shared
+ * between workgroups.  The workspace is required when zero_count_dev is given; otherwise it
+ * is optional, and without it every tile is reduced by a single workgroup (same results,
+ * idle CUs in the last round).  Its contents need no initialisation and carry nothing from
+ * call to call; calls that share one workspace must not overlap in time. */
 lp_status lp_conv_workspace_bytes(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, size_t *bytes_host);
 
 /*
@@ -156,8 +162,9 @@ lp_status lp_conv_workspace_bytes(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw,
  *   bias_codes_dev nullable; Cout codes in format qb (int8/int16 by qb.n), qb.f <= f_acc
  *   acc_out_dev   nullable; receives the raw int64 accumulators, N x Ho x Wo x Cout
  *   y_codes_dev   nullable; receives lp_act(acc) in format qy (see lp_act), same shape
- *   zero_count_dev nullable; += zeros among the y codes written; needs workspace_dev of
- *                 lp_conv_workspace_bytes (16-byte aligned), else LP_EWORKSPACE
+ *   zero_count_dev nullable; += zeros among the y codes written; needs workspace_dev
+ *   workspace_dev nullable unless zero_count_dev is given; 16-byte aligned and at least
+ *                 lp_conv_workspace_bytes long, else LP_EWORKSPACE
  * At least one of acc_out_dev / y_codes_dev must be given.
  * LP_EUNSUPPORTED: R*S*Cin >= 65536 with 16-bit operands (int32 limb sums
  * could overflow), tensors with 2^31 or more elements.

@@ -31,6 +31,8 @@ constexpr int BM = 128;      // output pixels per workgroup
 constexpr int CK = 64;       // channels (bytes per limb) per staged chunk
 constexpr int PS = 64;       // LDS bytes per staged pixel / weight row and limb (swizzled, see swz)
 constexpr int kConvThreads = 256;
+constexpr int kCUs = 256;    // compute units of the chip the launch geometry is tuned for
+constexpr int kXCDs = 8;     // consecutive workgroup ids go round-robin to this many dies
 
 enum { PATH_DIRECT = 0, PATH_MFMA = 1 };
 
@@ -45,8 +47,20 @@ struct Plan {
     int PITCH;   // LDS bytes between staged patch rows
     int KMUL;    // row multiplier of the patch swizzle key (4: one-dimensional key)
     int tiles_r, tiles_c, tiles_m, tiles_n;
+    // Launch geometry.  Every die gets per_xcd consecutive tiles.  The first full_per_xcd of
+    // them (a whole number of rounds of the die's workgroup slots) are computed by one workgroup
+    // each; each of the remaining tail tiles is cut along the reduction into `split` parts, so
+    // that the last, partly filled round keeps every CU busy (see the kernel's merge step).
+    int per_xcd, full_per_xcd, split, grid;
+    size_t part_bytes;   // bytes of one part's accumulators and row sums in the workspace
     size_t lds_bytes;
     size_t packed_bytes, corr_offset;
+};
+
+// Workspace layout: one zero count per workgroup, then the tail tiles' partial accumulators
+// [die][tail tile][part].
+struct WorkspaceLayout {
+    size_t partials, total;
 };
 
 static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -113,6 +127,29 @@ static size_t mfma_lds_bytes(int limbs, int pra, int pw, int pitch_px, int bn, i
 }
 // LDS budgets tried in turn: three workgroups per CU (160 KB / 3), else two
 constexpr size_t kLdsBudgets[2] = {54400, 80000};
+
+// Parts per tail tile.  Durations are estimated in units of one weight slab's MFMA work, with
+// constants fitted to measurements on 3x3 layers: a workgroup pays a fixed cost of about 10
+// slabs (tables, first patch, epilogue or partial store) on top of its share of the slabs, the
+// tail takes as many rounds as its parts need slots, the finishing kernel costs about 6, and
+// every part adds traffic (its accumulators are written once and read once).  A split must
+// promise a clear gain over the plain launch to be taken.
+static int choose_split(int tail_tiles, int slots, int nslabs, size_t part_bytes)
+{
+    const double fixed = 10.0, finish = 6.0, per_part = 0.03 * (double)part_bytes / 98816.0;
+    const double whole = nslabs + fixed;
+    int best = 1;
+    double best_t = 0.8 * whole;
+    for (int s = 2; s <= std::min(nslabs, 8); ++s) {
+        const int rounds = (tail_tiles * s + slots - 1) / slots;
+        const double t = rounds * ((double)nslabs / s + fixed) + finish + per_part * kXCDs * tail_tiles * s;
+        if (t < best_t) {
+            best_t = t;
+            best = s;
+        }
+    }
+    return best;
+}
 
 // virtual row (in the stack of zero-padded images, Hp rows each) of stacked output row fr
 static inline int vrow(int fr, int Ho, int Hp) { return (fr / Ho) * Hp + fr % Ho; }
@@ -222,6 +259,20 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
             p.KMUL = k;
         }
         p.lds_bytes = mfma_lds_bytes(p.limbs, p.PRA, p.PW, p.PITCH / PS, p.BN, p.flat);
+        {
+            // workgroup slots per die: three waves per SIMD by registers, and what the LDS holds
+            const int total = p.tiles_m * p.tiles_n, nslabs = p.nchunks * p.taps;
+            const int wg_per_cu = (int)std::max<size_t>(1, std::min<size_t>(3, (160 * 1024) / p.lds_bytes));
+            const int slots = wg_per_cu * (kCUs / kXCDs);
+            p.per_xcd = (total + kXCDs - 1) / kXCDs;
+            p.full_per_xcd = p.per_xcd / slots * slots;
+            p.part_bytes = (size_t)BM * p.BN * (p.limbs == 2 ? 3 : 1) * 4 + (size_t)BM * 4;
+            p.split = 1;
+            if (p.per_xcd > p.full_per_xcd && nslabs > 1)
+                p.split = choose_split(p.per_xcd - p.full_per_xcd, slots, nslabs, p.part_bytes);
+            if (p.split == 1) p.full_per_xcd = p.per_xcd;
+            p.grid = kXCDs * (p.full_per_xcd + (p.per_xcd - p.full_per_xcd) * p.split);
+        }
         p.corr_offset = round_up((size_t)p.taps * p.nchunks * p.limbs * p.CoutP * CK, 256);
         p.packed_bytes = p.corr_offset + (size_t)p.CoutP * sizeof(int64_t);
     } else {
@@ -324,7 +375,9 @@ struct ConvArgs {
     int Ho, Wo, Hp, FR;
     int RH, TW, PW, NPIXA, NTAB, APLANE, PITCH, KMUL;
     int tiles_c, tiles_n, CoutP, nchunks, taps, ksteps, Kflat;
-    int total_work, per_xcd;
+    int total_work, per_xcd, full_per_xcd, split;
+    unsigned char *partials; // tail tiles' partial accumulators, part_bytes per (tile, part)
+    int part_bytes;
     int fast; // 32-bit requantization is exact for this call (see epilogue)
     ActParams act;
 };
@@ -414,366 +467,21 @@ __device__ __forceinline__ int requant_relu32(int hi, int lo16, int s, int cmax)
     return min(max(q, 0), cmax); // compiles to v_med3_i32
 }
 
-// LIMBS: 1 (int8 codes) or 2 (16-bit codes as two int8 limbs).  NB: 32-column blocks per
-// wave; the workgroup covers BN = 64*NB output channels with 2x2 waves of 64 x 32*NB each.
-// FLAT: the window is gathered as one slab per output pixel instead of staging a patch.
-template <int LIMBS, int NB, bool FLAT>
-__global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void conv_mfma_kernel(const ConvArgs a)
+// Epilogue of one 128 x BN tile: combine limbs exactly, add corrections and bias, LPAct (or raw
+// accumulators), count zeros.  acc is the calling thread's share in the MFMA 32x32 result layout:
+// lane holds column (lane & 31), rows 8*(v/4) + 4*(lane/32) + v%4.  rowsum (LDS, BM ints, two-limb
+// only) and outoff (LDS, BM ints) are complete and visible; otile is LDS scratch for the tile of
+// codes.  Returns the wave's count of zero codes (the same value in every lane).
+template <int LIMBS, int NB, int MB, int THREADS>
+__device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)[MB][NB][LIMBS == 2 ? 3 : 1],
+                                                  const int *rowsum, const int *outoff, unsigned char *otile,
+                                                  int ntile)
 {
     constexpr int BN = 64 * NB;
-    constexpr int NACC = (LIMBS == 2) ? 3 : 1;
-    constexpr int BPL = BN * PS;              // bytes per limb plane of a weight slab
-    constexpr int BSLAB = LIMBS * BPL;        // bytes per weight slab buffer
-    constexpr int BITEMS = LIMBS * BN * 4 / kConvThreads; // 16-byte pieces of a slab per thread
-    extern __shared__ __align__(16) unsigned char smem[];
-
-    // XCD-aware work order: consecutive workgroup ids land on the 8 XCDs round-robin, so
-    // each XCD is handed one contiguous range of (pixel tile, channel tile) work items and
-    // the tiles sharing an input patch or a halo meet in the same L2.
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int wi = xcd * a.per_xcd + slot;
-    if (slot >= a.per_xcd || wi >= a.total_work) return;
-    const int mtile = wi / a.tiles_n, ntile = wi % a.tiles_n;
-    const int tile_r = mtile / a.tiles_c, tile_c = mtile % a.tiles_c;
-    const int fr0 = tile_r * a.RH, x0 = tile_c * a.TW;
-    const int vr0 = (fr0 / a.Ho) * a.Hp + fr0 % a.Ho;
-
-    const int NPIXA = a.NPIXA;
-    int *tab = (int *)smem;          // staged pixel -> input pixel index, -1 outside the image
-    int *psum = tab + a.NTAB;        // per staged pixel (FLAT: per tile row): sum of its codes
-    int *apos = psum + a.NTAB;       // staged pixel -> byte offset inside a limb plane
-    int *outoff = apos + a.NTAB;     // tile row -> output pixel index, -1 if not an output
-    int *abase_s = outoff + BM;      // tile row -> staged pixel of its (r=0, s=0) tap
-    unsigned char *Asm = smem + (((size_t)(3 * a.NTAB + 2 * BM) * 4 + 15) & ~(size_t)15);
-    const int APL = a.APLANE;        // bytes per limb plane of the staged activations
-    unsigned char *Bsm = Asm + (size_t)LIMBS * APL;
-
-    const int tid = threadIdx.x;
-    for (int p = tid; p < a.NTAB; p += kConvThreads) {
-        int g = -1;
-        if (p < NPIXA) {
-            const int pr = p / a.PW, pc = p % a.PW;
-            const int off = pr * a.PITCH + pc * PS;
-            apos[p] = off | ((a.KMUL == 4 ? off >> 8 : (pc >> 2) + a.KMUL * pr) & 3); // offset | swizzle key
-            const int vr = vr0 + pr;
-            const int n = vr / a.Hp, iy = vr % a.Hp - a.pad, ix = x0 - a.pad + pc;
-            if (n < a.N && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) g = (n * a.H + iy) * a.W + ix;
-        }
-        tab[p] = g;
-        psum[p] = 0;
-    }
-    for (int m = tid; m < BM; m += kConvThreads) {
-        const int j = m / a.TW, t = m % a.TW;
-        const int fr = fr0 + j, xo = x0 + t;
-        const bool ok = j < a.RH && fr < a.FR && xo < a.Wo;
-        outoff[m] = ok ? fr * a.Wo + xo : -1;
-        abase_s[m] = ok ? ((fr / a.Ho) * a.Hp + fr % a.Ho - vr0) * a.PW + t : 0;
-    }
-
-    // weight slabs: slab t = chunk * taps + tap lives at [tap][chunk][limb][CoutP][64].  A slab
-    // travels global -> registers -> LDS; DEPTH slabs are in flight in registers so that the
-    // L2 latency is covered by the MFMAs of the slabs before it.
-    constexpr int DEPTH = 1;
-    const int nslabs = a.nchunks * a.taps;
-    v4i breg0[BITEMS], breg1[DEPTH == 2 ? BITEMS : 1];
-    // Slabs are consecutive in memory in the order they are consumed, so fetching the next one is
-    // a pointer bump.  The fetch is issued on every step, also past the last slab (where it
-    // re-reads the last one): an unconditional load keeps the number of loads in flight the same
-    // on every path, so the wait before a slab is parked in LDS covers that slab only.
-    const size_t slab_bytes = (size_t)LIMBS * a.CoutP * CK;
-    const unsigned char *bsrc;
-    {
-        const int lb0 = tid / (BN * 4), rem0 = tid - lb0 * (BN * 4);
-        bsrc = a.wp + ((size_t)ntile * BN + (size_t)lb0 * a.CoutP + (rem0 >> 2)) * CK + (rem0 & 3) * 16;
-    }
-    // piece j of a thread is piece tid + j*256 of the slab: limb plane (j*256) / (BN*4), and
-    // ((j*256) % (BN*4)) / 4 rows below the thread's first piece
-    int pf = 0; // index of the next slab to fetch
-    auto load_slab = [&](v4i *reg) __attribute__((always_inline)) {
-#pragma unroll
-        for (int j = 0; j < BITEMS; ++j) {
-            const int lbj = (j * kConvThreads) / (BN * 4), rowj = ((j * kConvThreads) % (BN * 4)) / 4;
-            reg[j] = *(const v4i *)(bsrc + ((size_t)lbj * a.CoutP + rowj) * CK);
-        }
-        if (pf + 1 < nslabs) {
-            ++pf;
-            bsrc += slab_bytes;
-        }
-    };
-    auto store_slab = [&](int buf, const v4i *reg) __attribute__((always_inline)) {
-#pragma unroll
-        for (int j = 0; j < BITEMS; ++j) {
-            const int i = tid + j * kConvThreads;
-            const int lb = i / (BN * 4), rem = i - lb * (BN * 4);
-            *(v4i *)(Bsm + buf * BSLAB + lb * BPL + swz((rem >> 2) * PS, rem & 3)) = reg[j];
-        }
-    };
-    load_slab(breg0);
-    if (DEPTH == 2) load_slab(breg1);
-    __syncthreads();
-
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave & 1, wn = wave >> 1;
+    constexpr int WMC = BM / (32 * MB), WROWS = 32 * MB;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WMC, wn = wave / WMC;
     const int l32 = lane & 31, kg = lane >> 5;
-    int aoff[2], apr[2], apc[2], boff[NB];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-        const int row = wm * 64 + mb * 32 + l32;
-        aoff[mb] = FLAT ? row * PS : (apos[abase_s[row]] & ~3); // start of the row's (r=0, s=0) pixel
-        apr[mb] = FLAT ? 0 : abase_s[row] / a.PW;               // its patch row and column
-        apc[mb] = FLAT ? 0 : abase_s[row] % a.PW;
-    }
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) boff[nb] = swz((wn * (NB * 32) + nb * 32 + l32) * PS, kg);
-
-    v16i acc[2][NB][NACC];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int q = 0; q < NACC; ++q)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[mb][nb][q][v] = 0;
-
-    // Activations travel global -> registers -> LDS in batches of APF 16-byte pieces per thread,
-    // so that a batch's loads are all in flight together.  PIECES: 16-byte pieces per staged
-    // pixel and chunk (8 x 8 int16 codes, or 4 x 16 int8 codes).
-    constexpr int APF = 4;
-    constexpr int PIECES = (LIMBS == 2) ? 8 : 4;
-    v4i areg[APF];
-    // Loads are unconditional (indices clamped into the patch, pixels outside the image read
-    // pixel 0 and are zeroed afterwards), so the whole batch is straight-line code: all table
-    // reads first, then all global loads back to back.
-    unsigned act_ok = 0; // bit j: piece j of the batch lies inside the image
-    auto load_act = [&](int cc, int first) __attribute__((always_inline)) {
-        int g[APF];
-#pragma unroll
-        for (int j = 0; j < APF; ++j) {
-            const unsigned i = (unsigned)min(first + tid + j * kConvThreads, NPIXA * PIECES - 1);
-            g[j] = tab[i / PIECES];
-        }
-        act_ok = 0;
-#pragma unroll
-        for (int j = 0; j < APF; ++j) {
-            const unsigned i = (unsigned)min(first + tid + j * kConvThreads, NPIXA * PIECES - 1);
-            const int c = (int)(i % PIECES);
-            const int ch = min(cc * CK + c * (CK / PIECES), a.Cin - CK / PIECES);
-            act_ok |= (g[j] >= 0 ? 1u : 0u) << j;
-            const unsigned off = (unsigned)(max(g[j], 0) * a.Cin + ch) * (unsigned)(LIMBS == 2 ? 2 : 1);
-            areg[j] = *(const v4i *)((const unsigned char *)a.x + off);
-        }
-    };
-    auto store_act = [&](int cc, int first) __attribute__((always_inline)) {
-        int pos_r[APF]; // LDS positions first, all reads in flight together (see the epilogue note)
-#pragma unroll
-        for (int j = 0; j < APF; ++j)
-            pos_r[j] = apos[(unsigned)min(first + tid + j * kConvThreads, NPIXA * PIECES - 1) / PIECES];
-#pragma unroll
-        for (int j = 0; j < APF; ++j) {
-            const int i = first + tid + j * kConvThreads;
-            const bool live = i < NPIXA * PIECES;
-            const int p = (int)((unsigned)i / PIECES), c = (int)((unsigned)i % PIECES);
-            const int ch = cc * CK + c * (CK / PIECES);
-            v4i v = areg[j];
-            if (!((act_ok >> j) & 1)) v = (v4i){0, 0, 0, 0}; // outside the image: the code 0
-            if constexpr (LIMBS == 2) {
-                v2i hi = {0, 0}, lo = {0, 0};
-                int sum = 0;
-                if (live && ch < a.Cin) {
-                    hi.x = (int)__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x07050301u);
-                    hi.y = (int)__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x07050301u);
-                    lo.x = (int)(__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x06040200u) ^ 0x80808080u);
-                    lo.y = (int)(__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x06040200u) ^ 0x80808080u);
-                    sum = ((v.x << 16) >> 16) + (v.x >> 16) + ((v.y << 16) >> 16) + (v.y >> 16) +
-                          ((v.z << 16) >> 16) + (v.z >> 16) + ((v.w << 16) >> 16) + (v.w >> 16);
-                }
-                // the 8 pieces of a pixel sit in 8 adjacent lanes: add them up with DPP lane
-                // exchanges (xor 1, xor 2 inside quads, then mirror inside the half row)
-                sum += __builtin_amdgcn_mov_dpp(sum, 0xB1, 0xF, 0xF, true);
-                sum += __builtin_amdgcn_mov_dpp(sum, 0x4E, 0xF, 0xF, true);
-                sum += __builtin_amdgcn_mov_dpp(sum, 0x141, 0xF, 0xF, true);
-                if (live) {
-                    if (c == 0 && sum) atomicAdd(&psum[p], sum); // single owner; no value returned
-                    const int pos = pos_r[j];
-                    const int at = swzk(pos & ~3, c >> 1, pos) + (c & 1) * 8;
-                    *(v2i *)(Asm + at) = hi;
-                    *(v2i *)(Asm + APL + at) = lo;
-                }
-            } else {
-                if (ch >= a.Cin) v = (v4i){0, 0, 0, 0};
-                if (live) *(v4i *)(Asm + swzk(pos_r[j] & ~3, c, pos_r[j])) = v;
-            }
-        }
-    };
-    // FLAT: the raw patch (all Cin channels, int16) is parked in the unused second weight
-    // buffer, then each tile row's window is gathered from there, 16 consecutive k per piece.
-    auto stage_flat = [&]() __attribute__((always_inline)) {
-        const int16_t *x = (const int16_t *)a.x;
-        int16_t *raw = (int16_t *)(Bsm + BSLAB);
-        const int nraw = NPIXA * a.Cin;
-        for (int i = tid; i < nraw; i += kConvThreads) {
-            const int p = i / a.Cin, ci = i - p * a.Cin;
-            const int g = tab[p];
-            raw[i] = g >= 0 ? x[(size_t)g * a.Cin + ci] : (int16_t)0;
-        }
-        __syncthreads();
-        const int SC = a.S * a.Cin;
-        for (int i = tid; i < BM * 4; i += kConvThreads) {
-            const int row = i >> 2, k0 = (i & 3) * 16;
-            const int base = abase_s[row];
-            int r = k0 / SC, rem = k0 - r * SC;
-            int s = rem / a.Cin, ci = rem - s * a.Cin;
-            unsigned hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
-            int sum = 0;
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                if (k0 + j < a.Kflat) {
-                    const int val = (int)raw[(base + r * a.PW + s) * a.Cin + ci];
-                    sum += val;
-                    hi[j >> 2] |= (unsigned)((val >> 8) & 255) << (8 * (j & 3));
-                    lo[j >> 2] |= (unsigned)((val & 255) ^ 128) << (8 * (j & 3));
-                    if (++ci == a.Cin) {
-                        ci = 0;
-                        if (++s == a.S) { s = 0; ++r; }
-                    }
-                }
-            }
-            if (sum) atomicAdd(&psum[row], sum);
-            const v4i vh = {(int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
-            const v4i vl = {(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3]};
-            *(v4i *)(Asm + swz(row * PS, k0 >> 4)) = vh;
-            *(v4i *)(Asm + APL + swz(row * PS, k0 >> 4)) = vl;
-        }
-    };
-    constexpr bool EARLY = false;
-    const int early_tap = a.taps - 1;
-    auto stage_activations = [&](int cc, bool have_first) __attribute__((always_inline)) {
-        if constexpr (FLAT) {
-            stage_flat();
-        } else {
-            const int total = NPIXA * PIECES;
-            for (int first = 0; first < total; first += APF * kConvThreads) {
-                if (!(have_first && first == 0)) load_act(cc, first);
-                store_act(cc, first);
-            }
-        }
-    };
-    int tap_s = 0, tap_r = 0, tapoff = 0, taprow = 0; // patch offset of the current tap, kept incrementally
-    auto compute_slab = [&](int t) __attribute__((always_inline)) {
-        const unsigned char *Bcur = Bsm + (t & 1) * BSLAB;
-        int afrag[2]; // this tap's pixel per row block, slot kg; the second K=32 step is slot kg+2
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-            if constexpr (FLAT) afrag[mb] = swz(aoff[mb], kg);
-            else {
-                const int pix = aoff[mb] + tapoff;
-                const int key = a.KMUL == 4 ? pix >> 8 : ((apc[mb] + tap_s) >> 2) + a.KMUL * (apr[mb] + tap_r);
-                afrag[mb] = swzk(pix, kg, key);
-            }
-        }
-#pragma unroll
-        for (int k32 = 0; k32 < 2; ++k32) {
-            if (k32 < a.ksteps) {
-                v4i ah[2], al[2], bh[NB], bl[NB];
-#pragma unroll
-                for (int mb = 0; mb < 2; ++mb) {
-                    ah[mb] = *(const v4i *)(Asm + (afrag[mb] ^ (k32 * 32)));
-                    if constexpr (LIMBS == 2) al[mb] = *(const v4i *)(Asm + APL + (afrag[mb] ^ (k32 * 32)));
-                }
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    bh[nb] = *(const v4i *)(Bcur + (boff[nb] ^ (k32 * 32)));
-                    if constexpr (LIMBS == 2) bl[nb] = *(const v4i *)(Bcur + BPL + (boff[nb] ^ (k32 * 32)));
-                }
-#pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        acc[mb][nb][0] = mfma_i8(ah[mb], bh[nb], acc[mb][nb][0]);
-                        if constexpr (LIMBS == 2) {
-                            acc[mb][nb][1] = mfma_i8(ah[mb], bl[nb], acc[mb][nb][1]);
-                            acc[mb][nb][2] = mfma_i8(al[mb], bl[nb], acc[mb][nb][2]);
-                        }
-                    }
-                if constexpr (LIMBS == 2) {
-#pragma unroll
-                    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                        for (int nb = 0; nb < NB; ++nb)
-                            acc[mb][nb][1] = mfma_i8(al[mb], bh[nb], acc[mb][nb][1]);
-                }
-            }
-            // keep the second half's fragment loads behind the first half's MFMAs: both sets
-            // live at once would cost 24 more registers than three waves per SIMD leave
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-
-    // Pipeline: slab t+1 is parked in the other LDS buffer and slab t+1+DEPTH is requested while
-    // the MFMAs of slab t run, so one barrier per slab suffices and neither the LDS write nor
-    // the global latency sits between a barrier and the first fragment read.
-    int cc = 0, tap = 0;
-    stage_activations(0, false);
-    store_slab(0, breg0);
-    load_slab(breg0);
-    auto step = [&](int t, v4i *next) __attribute__((always_inline)) {
-        if (tap == 0 && t) {
-            __syncthreads(); // all reads of the previous chunk's activations are done
-            stage_activations(cc, EARLY);
-        }
-        __syncthreads(); // slab t (and a freshly staged patch) visible; slab t-1 fully consumed
-        store_slab((t + 1) & 1, next);
-        load_slab(next);
-        // the next chunk's first batch of activations is requested before the chunk's last slab
-        // is multiplied and waits in registers; issued after the slab fetch, so that no slab
-        // wait in between forces it to complete early (loads return in order)
-        if (EARLY && tap == early_tap && cc + 1 < a.nchunks) load_act(cc + 1, 0);
-        compute_slab(t);
-        if (++tap == a.taps) {
-            tap = 0;
-            ++cc;
-            tap_s = tap_r = 0;
-            tapoff = taprow = 0;
-        } else if (!FLAT) {
-            tapoff += PS;
-            if (++tap_s == a.S) {
-                tap_s = 0;
-                ++tap_r;
-                taprow += a.PITCH;
-                tapoff = taprow;
-            }
-        }
-    };
-    // both halves unconditional inside the loop (a skipped half would make the in-flight load
-    // count path dependent); an odd last slab is handled after it
-    int t = 0;
-    for (; t + 1 < nslabs; t += 2) {
-        step(t, DEPTH == 2 ? breg1 : breg0);
-        step(t + 1, breg0);
-    }
-    if (t < nslabs) step(t, DEPTH == 2 ? breg1 : breg0);
-
-    // ---- per-row sum of the window's codes (two-limb correction term 128 * sum(a))
-    __syncthreads();
-    int *rowsum = (int *)Asm; // the staged activations are no longer needed
-    if constexpr (LIMBS == 2) {
-        for (int m = tid; m < BM; m += kConvThreads) {
-            int sum = 0;
-            if constexpr (FLAT) {
-                sum = psum[m];
-            } else {
-                const int base = abase_s[m];
-                for (int r = 0; r < a.R; ++r)
-                    for (int s = 0; s < a.S; ++s) sum += psum[base + r * a.PW + s];
-            }
-            rowsum[m] = sum;
-        }
-        __syncthreads();
-    }
-
-    // ---- epilogue: combine limbs exactly, add corrections and bias, LPAct, count zeros.
-    // MFMA 32x32 result layout: lane holds column (lane & 31), rows 8*(v/4) + 4*(lane/32) + v%4.
     unsigned zeros = 0;
     int64_t colterm[NB];
     int colg[NB];
@@ -789,7 +497,6 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(3,
         // The codes go to an LDS tile first and leave as 16-byte row pieces.  Shift class and
         // code width are compile-time here: the per-value work is about ten VALU operations.
         const int s = a.act.s, cmax = a.act.hi;
-        unsigned char *otile = Asm + BM * 4; // behind rowsum[]; patch and slabs are dead
         auto requant_tile = [&](auto s16c, auto y16c) __attribute__((always_inline)) {
             constexpr int S16 = decltype(s16c)::value;
             constexpr bool Y16 = decltype(y16c)::value;
@@ -802,20 +509,20 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(3,
                 cB[nb] = (int)((colterm[nb] >> 8) & 255);
                 cC[nb] = (int)(colterm[nb] & 255);
             }
-            int rs_r[2][16]; // row sums first, all LDS reads in flight together
+            int rs_r[MB][16]; // row sums first, all LDS reads in flight together
             if constexpr (LIMBS == 2) {
 #pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
+                for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                     for (int v = 0; v < 16; ++v)
-                        rs_r[mb][v] = rowsum[wm * 64 + mb * 32 + 8 * (v >> 2) + 4 * kg + (v & 3)];
+                        rs_r[mb][v] = rowsum[wm * WROWS + mb * 32 + 8 * (v >> 2) + 4 * kg + (v & 3)];
             }
             unsigned char *obase = otile + (wn * (NB * 32) + l32) * ESZ;
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
+            for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int row = wm * 64 + mb * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+                    const int row = wm * WROWS + mb * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
                     int rB = 0, rC = 0;
                     if constexpr (LIMBS == 2) {
                         rB = rs_r[mb][v] >> 1;
@@ -848,8 +555,8 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(3,
             const bool vec_ok = (a.Cout % EPP) == 0;            // output rows 16-byte aligned
             unsigned nz = 0;
 #pragma unroll
-            for (int k = 0; k < (BM << LSH) / kConvThreads; ++k) {
-                const int i = tid + k * kConvThreads;
+            for (int k = 0; k < (BM << LSH) / THREADS; ++k) {
+                const int i = tid + k * THREADS;
                 const int row = i >> LSH, c = i - (row << LSH);
                 const int oo = outoff[row];
                 const int col0 = ntile * BN + c * EPP;
@@ -900,10 +607,10 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(3,
         }
     } else {
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+        for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int row = wm * 64 + mb * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+                const int row = wm * WROWS + mb * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
                 const int oo = outoff[row];
                 const int64_t rt = (LIMBS == 2) ? (int64_t)rowsum[row] * 128 : 0;
 #pragma unroll
@@ -930,12 +637,512 @@ __global__ __launch_bounds__(kConvThreads) __attribute__((amdgpu_waves_per_eu(3,
                 }
             }
     }
+    return zeros;
+}
+
+// LIMBS: 1 (int8 codes) or 2 (16-bit codes as two int8 limbs).  NB: 32-column blocks per
+// wave; the workgroup covers BN = 64*NB output channels with 2x2 waves of 64 x 32*NB each.
+// FLAT: the window is gathered as one slab per output pixel instead of staging a patch.
+template <int LIMBS, int NB, bool FLAT, int MB>
+__global__ __launch_bounds__(MB == 2 ? 256 : 512)
+    __attribute__((amdgpu_waves_per_eu(MB == 2 ? 3 : 4, MB == 2 ? 3 : 4))) void conv_mfma_kernel(const ConvArgs a)
+{
+    // MB: 32-row blocks per wave.  MB = 2: 4 waves (2 x 2) of 64 rows; MB = 1: 8 waves (4 x 2) of
+    // 32 rows, half the accumulators per wave, so a fourth wave fits on each SIMD and every
+    // per-thread phase (staging, epilogue) is half as long.
+    constexpr int THREADS = (MB == 2) ? 256 : 512;
+    constexpr int WMC = BM / (32 * MB);       // waves along the pixel dimension
+    constexpr int WROWS = 32 * MB;            // tile rows per wave
+    constexpr int BN = 64 * NB;
+    constexpr int NACC = (LIMBS == 2) ? 3 : 1;
+    constexpr int BPL = BN * PS;              // bytes per limb plane of a weight slab
+    constexpr int BSLAB = LIMBS * BPL;        // bytes per weight slab buffer
+    constexpr int BITEMS = LIMBS * BN * 4 / THREADS; // 16-byte pieces of a slab per thread
+    static_assert(BITEMS >= 1, "a weight slab must give every thread at least one piece");
+    extern __shared__ __align__(16) unsigned char smem[];
+
+    // XCD-aware work order: consecutive workgroup ids land on the 8 XCDs round-robin, so
+    // each XCD is handed one contiguous range of (pixel tile, channel tile) work items and
+    // the tiles sharing an input patch or a halo meet in the same L2.
+    // A die's first full_per_xcd work items are whole tiles; each later one is cut along the
+    // reduction into a.split parts (consecutive slots), dispatched after all whole tiles.
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    int tl = slot, part = 0, nparts = 1;
+    if (slot >= a.full_per_xcd) {
+        const int u = slot - a.full_per_xcd;
+        tl = a.full_per_xcd + u / a.split;
+        part = u % a.split;
+        nparts = a.split;
+    }
+    const int wi = xcd * a.per_xcd + tl;
+    if (tl >= a.per_xcd || wi >= a.total_work) {
+        if (a.zero_partial && threadIdx.x == 0) a.zero_partial[blockIdx.x] = 0;
+        return;
+    }
+    const int mtile = wi / a.tiles_n, ntile = wi % a.tiles_n;
+    const int tile_r = mtile / a.tiles_c, tile_c = mtile % a.tiles_c;
+    const int fr0 = tile_r * a.RH, x0 = tile_c * a.TW;
+    const int vr0 = (fr0 / a.Ho) * a.Hp + fr0 % a.Ho;
+
+    const int NPIXA = a.NPIXA;
+    int *tab = (int *)smem;          // staged pixel -> input pixel index, -1 outside the image
+    int *psum = tab + a.NTAB;        // per staged pixel (FLAT: per tile row): sum of its codes
+    int *apos = psum + a.NTAB;       // staged pixel -> byte offset inside a limb plane
+    int *outoff = apos + a.NTAB;     // tile row -> output pixel index, -1 if not an output
+    int *abase_s = outoff + BM;      // tile row -> staged pixel of its (r=0, s=0) tap
+    unsigned char *Asm = smem + (((size_t)(3 * a.NTAB + 2 * BM) * 4 + 15) & ~(size_t)15);
+    const int APL = a.APLANE;        // bytes per limb plane of the staged activations
+    unsigned char *Bsm = Asm + (size_t)LIMBS * APL;
+
+    const int tid = threadIdx.x;
+    for (int p = tid; p < a.NTAB; p += THREADS) {
+        int g = -1;
+        if (p < NPIXA) {
+            const int pr = p / a.PW, pc = p % a.PW;
+            const int off = pr * a.PITCH + pc * PS;
+            apos[p] = off | ((a.KMUL == 4 ? off >> 8 : (pc >> 2) + a.KMUL * pr) & 3); // offset | swizzle key
+            const int vr = vr0 + pr;
+            const int n = vr / a.Hp, iy = vr % a.Hp - a.pad, ix = x0 - a.pad + pc;
+            if (n < a.N && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) g = (n * a.H + iy) * a.W + ix;
+        }
+        tab[p] = g;
+        psum[p] = 0;
+    }
+    for (int m = tid; m < BM; m += THREADS) {
+        const int j = m / a.TW, t = m % a.TW;
+        const int fr = fr0 + j, xo = x0 + t;
+        const bool ok = j < a.RH && fr < a.FR && xo < a.Wo;
+        outoff[m] = ok ? fr * a.Wo + xo : -1;
+        abase_s[m] = ok ? ((fr / a.Ho) * a.Hp + fr % a.Ho - vr0) * a.PW + t : 0;
+    }
+
+    // weight slabs: slab t = chunk * taps + tap lives at [tap][chunk][limb][CoutP][64].  A slab
+    // travels global -> registers -> LDS; DEPTH slabs are in flight in registers so that the
+    // L2 latency is covered by the MFMAs of the slabs before it.
+    constexpr int DEPTH = 1;
+    const int nslabs = a.nchunks * a.taps;
+    const int s0 = part * nslabs / nparts, s1 = (part + 1) * nslabs / nparts; // this workgroup's slabs
+    v4i breg0[BITEMS], breg1[DEPTH == 2 ? BITEMS : 1];
+    // Slabs are consecutive in memory in the order they are consumed, so fetching the next one is
+    // a pointer bump.  The fetch is issued on every step, also past the last slab (where it
+    // re-reads the last one): an unconditional load keeps the number of loads in flight the same
+    // on every path, so the wait before a slab is parked in LDS covers that slab only.
+    const size_t slab_bytes = (size_t)LIMBS * a.CoutP * CK;
+    const unsigned char *bsrc;
+    {
+        const int lb0 = tid / (BN * 4), rem0 = tid - lb0 * (BN * 4);
+        bsrc = a.wp + ((size_t)ntile * BN + (size_t)lb0 * a.CoutP + (rem0 >> 2)) * CK + (rem0 & 3) * 16;
+        bsrc += (size_t)s0 * slab_bytes;
+    }
+    // piece j of a thread is piece tid + j*256 of the slab: limb plane (j*256) / (BN*4), and
+    // ((j*256) % (BN*4)) / 4 rows below the thread's first piece
+    int pf = s0; // index of the next slab to fetch
+    auto load_slab = [&](v4i *reg) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < BITEMS; ++j) {
+            const int lbj = (j * THREADS) / (BN * 4), rowj = ((j * THREADS) % (BN * 4)) / 4;
+            reg[j] = *(const v4i *)(bsrc + ((size_t)lbj * a.CoutP + rowj) * CK);
+        }
+        if (pf + 1 < s1) {
+            ++pf;
+            bsrc += slab_bytes;
+        }
+    };
+    auto store_slab = [&](int buf, const v4i *reg) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < BITEMS; ++j) {
+            const int i = tid + j * THREADS;
+            const int lb = i / (BN * 4), rem = i - lb * (BN * 4);
+            *(v4i *)(Bsm + buf * BSLAB + lb * BPL + swz((rem >> 2) * PS, rem & 3)) = reg[j];
+        }
+    };
+    load_slab(breg0);
+    if (DEPTH == 2) load_slab(breg1);
+    __syncthreads();
+
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WMC, wn = wave / WMC;
+    const int l32 = lane & 31, kg = lane >> 5;
+    int aoff[MB], apr[MB], apc[MB], boff[NB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        const int row = wm * WROWS + mb * 32 + l32;
+        aoff[mb] = FLAT ? row * PS : (apos[abase_s[row]] & ~3); // start of the row's (r=0, s=0) pixel
+        apr[mb] = FLAT ? 0 : abase_s[row] / a.PW;               // its patch row and column
+        apc[mb] = FLAT ? 0 : abase_s[row] % a.PW;
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) boff[nb] = swz((wn * (NB * 32) + nb * 32 + l32) * PS, kg);
+
+    v16i acc[MB][NB][NACC];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int q = 0; q < NACC; ++q)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mb][nb][q][v] = 0;
+
+    // Activations travel global -> registers -> LDS in batches of APF 16-byte pieces per thread,
+    // so that a batch's loads are all in flight together.  PIECES: 16-byte pieces per staged
+    // pixel and chunk (8 x 8 int16 codes, or 4 x 16 int8 codes).
+    constexpr int APF = 4;
+    constexpr int PIECES = (LIMBS == 2) ? 8 : 4;
+    v4i areg[APF];
+    // Loads are unconditional (indices clamped into the patch, pixels outside the image read
+    // pixel 0 and are zeroed afterwards), so the whole batch is straight-line code: all table
+    // reads first, then all global loads back to back.
+    unsigned act_ok = 0; // bit j: piece j of the batch lies inside the image
+    // A chunk's channel sums are collected by the part that holds the chunk's first tap, so that
+    // parts which share a chunk do not count it twice.
+    bool own_sums = (s0 % a.taps) == 0;
+    auto load_act = [&](int cc, int first) __attribute__((always_inline)) {
+        int g[APF];
+#pragma unroll
+        for (int j = 0; j < APF; ++j) {
+            const unsigned i = (unsigned)min(first + tid + j * THREADS, NPIXA * PIECES - 1);
+            g[j] = tab[i / PIECES];
+        }
+        act_ok = 0;
+#pragma unroll
+        for (int j = 0; j < APF; ++j) {
+            const unsigned i = (unsigned)min(first + tid + j * THREADS, NPIXA * PIECES - 1);
+            const int c = (int)(i % PIECES);
+            const int ch = min(cc * CK + c * (CK / PIECES), a.Cin - CK / PIECES);
+            act_ok |= (g[j] >= 0 ? 1u : 0u) << j;
+            const unsigned off = (unsigned)(max(g[j], 0) * a.Cin + ch) * (unsigned)(LIMBS == 2 ? 2 : 1);
+            areg[j] = *(const v4i *)((const unsigned char *)a.x + off);
+        }
+    };
+    auto store_act = [&](int cc, int first) __attribute__((always_inline)) {
+        int pos_r[APF]; // LDS positions first, all reads in flight together (see the epilogue note)
+#pragma unroll
+        for (int j = 0; j < APF; ++j)
+            pos_r[j] = apos[(unsigned)min(first + tid + j * THREADS, NPIXA * PIECES - 1) / PIECES];
+#pragma unroll
+        for (int j = 0; j < APF; ++j) {
+            const int i = first + tid + j * THREADS;
+            const bool live = i < NPIXA * PIECES;
+            const int p = (int)((unsigned)i / PIECES), c = (int)((unsigned)i % PIECES);
+            const int ch = cc * CK + c * (CK / PIECES);
+            v4i v = areg[j];
+            if (!((act_ok >> j) & 1)) v = (v4i){0, 0, 0, 0}; // outside the image: the code 0
+            if constexpr (LIMBS == 2) {
+                v2i hi = {0, 0}, lo = {0, 0};
+                int sum = 0;
+                if (live && ch < a.Cin) {
+                    hi.x = (int)__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x07050301u);
+                    hi.y = (int)__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x07050301u);
+                    lo.x = (int)(__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x06040200u) ^ 0x80808080u);
+                    lo.y = (int)(__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x06040200u) ^ 0x80808080u);
+                    sum = ((v.x << 16) >> 16) + (v.x >> 16) + ((v.y << 16) >> 16) + (v.y >> 16) +
+                          ((v.z << 16) >> 16) + (v.z >> 16) + ((v.w << 16) >> 16) + (v.w >> 16);
+                }
+                // the 8 pieces of a pixel sit in 8 adjacent lanes: add them up with DPP lane
+                // exchanges (xor 1, xor 2 inside quads, then mirror inside the half row)
+                sum += __builtin_amdgcn_mov_dpp(sum, 0xB1, 0xF, 0xF, true);
+                sum += __builtin_amdgcn_mov_dpp(sum, 0x4E, 0xF, 0xF, true);
+                sum += __builtin_amdgcn_mov_dpp(sum, 0x141, 0xF, 0xF, true);
+                if (live) {
+                    if (c == 0 && sum && own_sums) atomicAdd(&psum[p], sum); // single owner; no value returned
+                    const int pos = pos_r[j];
+                    const int at = swzk(pos & ~3, c >> 1, pos) + (c & 1) * 8;
+                    *(v2i *)(Asm + at) = hi;
+                    *(v2i *)(Asm + APL + at) = lo;
+                }
+            } else {
+                if (ch >= a.Cin) v = (v4i){0, 0, 0, 0};
+                if (live) *(v4i *)(Asm + swzk(pos_r[j] & ~3, c, pos_r[j])) = v;
+            }
+        }
+    };
+    // FLAT: the raw patch (all Cin channels, int16) is parked in the unused second weight
+    // buffer, then each tile row's window is gathered from there, 16 consecutive k per piece.
+    auto stage_flat = [&]() __attribute__((always_inline)) {
+        const int16_t *x = (const int16_t *)a.x;
+        int16_t *raw = (int16_t *)(Bsm + BSLAB);
+        const int nraw = NPIXA * a.Cin;
+        for (int i = tid; i < nraw; i += THREADS) {
+            const int p = i / a.Cin, ci = i - p * a.Cin;
+            const int g = tab[p];
+            raw[i] = g >= 0 ? x[(size_t)g * a.Cin + ci] : (int16_t)0;
+        }
+        __syncthreads();
+        const int SC = a.S * a.Cin;
+        for (int i = tid; i < BM * 4; i += THREADS) {
+            const int row = i >> 2, k0 = (i & 3) * 16;
+            const int base = abase_s[row];
+            int r = k0 / SC, rem = k0 - r * SC;
+            int s = rem / a.Cin, ci = rem - s * a.Cin;
+            unsigned hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
+            int sum = 0;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                if (k0 + j < a.Kflat) {
+                    const int val = (int)raw[(base + r * a.PW + s) * a.Cin + ci];
+                    sum += val;
+                    hi[j >> 2] |= (unsigned)((val >> 8) & 255) << (8 * (j & 3));
+                    lo[j >> 2] |= (unsigned)((val & 255) ^ 128) << (8 * (j & 3));
+                    if (++ci == a.Cin) {
+                        ci = 0;
+                        if (++s == a.S) { s = 0; ++r; }
+                    }
+                }
+            }
+            if (sum) atomicAdd(&psum[row], sum);
+            const v4i vh = {(int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+            const v4i vl = {(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3]};
+            *(v4i *)(Asm + swz(row * PS, k0 >> 4)) = vh;
+            *(v4i *)(Asm + APL + swz(row * PS, k0 >> 4)) = vl;
+        }
+    };
+    constexpr bool EARLY = false;
+    const int early_tap = a.taps - 1;
+    auto stage_activations = [&](int cc, bool have_first) __attribute__((always_inline)) {
+        if constexpr (FLAT) {
+            stage_flat();
+        } else {
+            const int total = NPIXA * PIECES;
+            for (int first = 0; first < total; first += APF * THREADS) {
+                if (!(have_first && first == 0)) load_act(cc, first);
+                store_act(cc, first);
+            }
+        }
+    };
+    // chunk and tap of the current slab, and the tap's patch offset, kept incrementally
+    int cc = s0 / a.taps, tap = s0 % a.taps;
+    int tap_r = FLAT ? 0 : tap / a.S, tap_s = FLAT ? 0 : tap % a.S;
+    int taprow = tap_r * a.PITCH, tapoff = taprow + tap_s * PS;
+    auto compute_slab = [&](int t) __attribute__((always_inline)) {
+        const unsigned char *Bcur = Bsm + (t & 1) * BSLAB;
+        int afrag[MB]; // this tap's pixel per row block, slot kg; the second K=32 step is slot kg+2
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            if constexpr (FLAT) afrag[mb] = swz(aoff[mb], kg);
+            else {
+                const int pix = aoff[mb] + tapoff;
+                const int key = a.KMUL == 4 ? pix >> 8 : ((apc[mb] + tap_s) >> 2) + a.KMUL * (apr[mb] + tap_r);
+                afrag[mb] = swzk(pix, kg, key);
+            }
+        }
+#pragma unroll
+        for (int k32 = 0; k32 < 2; ++k32) {
+            if (k32 < a.ksteps) {
+                v4i ah[MB], al[MB], bh[NB], bl[NB];
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    ah[mb] = *(const v4i *)(Asm + (afrag[mb] ^ (k32 * 32)));
+                    if constexpr (LIMBS == 2) al[mb] = *(const v4i *)(Asm + APL + (afrag[mb] ^ (k32 * 32)));
+                }
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    bh[nb] = *(const v4i *)(Bcur + (boff[nb] ^ (k32 * 32)));
+                    if constexpr (LIMBS == 2) bl[nb] = *(const v4i *)(Bcur + BPL + (boff[nb] ^ (k32 * 32)));
+                }
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        acc[mb][nb][0] = mfma_i8(ah[mb], bh[nb], acc[mb][nb][0]);
+                        if constexpr (LIMBS == 2) {
+                            acc[mb][nb][1] = mfma_i8(ah[mb], bl[nb], acc[mb][nb][1]);
+                            acc[mb][nb][2] = mfma_i8(al[mb], bl[nb], acc[mb][nb][2]);
+                        }
+                    }
+                if constexpr (LIMBS == 2) {
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            acc[mb][nb][1] = mfma_i8(al[mb], bh[nb], acc[mb][nb][1]);
+                }
+            }
+            // keep the second half's fragment loads behind the first half's MFMAs: both sets
+            // live at once would cost 24 more registers than three waves per SIMD leave
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // Pipeline: slab t+1 is parked in the other LDS buffer and slab t+1+DEPTH is requested while
+    // the MFMAs of slab t run, so one barrier per slab suffices and neither the LDS write nor
+    // the global latency sits between a barrier and the first fragment read.
+    stage_activations(cc, false);
+    own_sums = true; // every later chunk starts at its first tap
+    store_slab(s0 & 1, breg0);
+    load_slab(breg0);
+    auto step = [&](int t, v4i *next) __attribute__((always_inline)) {
+        if (tap == 0 && t != s0) {
+            __syncthreads(); // all reads of the previous chunk's activations are done
+            stage_activations(cc, EARLY);
+        }
+        __syncthreads(); // slab t (and a freshly staged patch) visible; slab t-1 fully consumed
+        store_slab((t + 1) & 1, next);
+        load_slab(next);
+        // the next chunk's first batch of activations is requested before the chunk's last slab
+        // is multiplied and waits in registers; issued after the slab fetch, so that no slab
+        // wait in between forces it to complete early (loads return in order)
+        if (EARLY && tap == early_tap && cc + 1 < a.nchunks) load_act(cc + 1, 0);
+        compute_slab(t);
+        if (++tap == a.taps) {
+            tap = 0;
+            ++cc;
+            tap_s = tap_r = 0;
+            tapoff = taprow = 0;
+        } else if (!FLAT) {
+            tapoff += PS;
+            if (++tap_s == a.S) {
+                tap_s = 0;
+                ++tap_r;
+                taprow += a.PITCH;
+                tapoff = taprow;
+            }
+        }
+    };
+    // both halves unconditional inside the loop (a skipped half would make the in-flight load
+    // count path dependent); an odd last slab is handled after it
+    int t = s0;
+    for (; t + 1 < s1; t += 2) {
+        step(t, DEPTH == 2 ? breg1 : breg0);
+        step(t + 1, breg0);
+    }
+    if (t < s1) step(t, DEPTH == 2 ? breg1 : breg0);
+
+    // ---- per-row sum of the window's codes (two-limb correction term 128 * sum(a))
+    __syncthreads();
+    int *rowsum = (int *)Asm; // the staged activations are no longer needed
+    if constexpr (LIMBS == 2) {
+        for (int m = tid; m < BM; m += THREADS) {
+            int sum = 0;
+            if constexpr (FLAT) {
+                sum = psum[m];
+            } else {
+                const int base = abase_s[m];
+                for (int r = 0; r < a.R; ++r)
+                    for (int s = 0; s < a.S; ++s) sum += psum[base + r * a.PW + s];
+            }
+            rowsum[m] = sum;
+        }
+        __syncthreads();
+    }
+
+    // ---- tail tiles: a part stores its accumulators and row sums and is done; the finishing
+    // kernel adds the parts up (integer sums: the order cannot matter) and runs the epilogue.
+    if (nparts > 1) {
+        const int tail_tile = xcd * (a.per_xcd - a.full_per_xcd) + (tl - a.full_per_xcd);
+        v4i *mine = (v4i *)(a.partials + ((size_t)tail_tile * nparts + part) * a.part_bytes);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int q = 0; q < NACC; ++q)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const v16i &c = acc[mb][nb][q];
+                        mine[(((mb * NB + nb) * NACC + q) * 4 + g) * THREADS + tid] =
+                            (v4i){c[4 * g], c[4 * g + 1], c[4 * g + 2], c[4 * g + 3]};
+                    }
+        if constexpr (LIMBS == 2) {
+            int *rs = (int *)(mine + MB * NB * NACC * 4 * THREADS);
+            for (int m = tid; m < BM; m += THREADS) rs[m] = rowsum[m];
+        }
+        if (a.zero_partial && tid == 0) a.zero_partial[blockIdx.x] = 0;
+        return;
+    }
+
+    unsigned zeros = tile_epilogue<LIMBS, NB, MB, THREADS>(a, acc, rowsum, outoff, Asm + BM * 4, ntile);
     // one count per workgroup, no atomics: thousands of same-address atomics would serialise
     if (a.zero_partial) {
         if (lane == 0) psum[wave] = (int)zeros;
         __syncthreads();
-        if (tid == 0) a.zero_partial[wi] = (unsigned)(psum[0] + psum[1] + psum[2] + psum[3]);
+        if (tid == 0) {
+            unsigned total = 0;
+            for (int w = 0; w < THREADS / 64; ++w) total += (unsigned)psum[w];
+            a.zero_partial[blockIdx.x] = total;
+        }
     }
+}
+
+
+// Finishes the tail tiles: one workgroup per tile adds up the parts' accumulators and row sums
+// and runs the epilogue; its zero count goes straight to the total (few workgroups).  Workgroup 0
+// also adds the per-workgroup counts of the main kernel.
+template <int LIMBS, int NB, int MB>
+__global__ __launch_bounds__(256) void conv_finish_kernel(const ConvArgs a, int main_grid)
+{
+    constexpr int THREADS = 256;
+    constexpr int BN = 64 * NB;
+    constexpr int NACC = (LIMBS == 2) ? 3 : 1;
+    __shared__ int outoff[BM];
+    __shared__ int rowsum[BM];
+    __shared__ __align__(16) unsigned char otile[BM * (BN * 2 + 16)];
+    __shared__ unsigned wave_zeros[THREADS / 64];
+    const int tid = threadIdx.x;
+    const int tails = a.per_xcd - a.full_per_xcd;
+    const int xcd = blockIdx.x / tails, tl = a.full_per_xcd + blockIdx.x % tails;
+    const int wi = xcd * a.per_xcd + tl;
+    unsigned long long total = 0;
+    if (wi < a.total_work) {
+        const int mtile = wi / a.tiles_n, ntile = wi % a.tiles_n;
+        const int tile_r = mtile / a.tiles_c, tile_c = mtile % a.tiles_c;
+        const int fr0 = tile_r * a.RH, x0 = tile_c * a.TW;
+        for (int m = tid; m < BM; m += THREADS) {
+            const int j = m / a.TW, t = m % a.TW;
+            const int fr = fr0 + j, xo = x0 + t;
+            outoff[m] = (j < a.RH && fr < a.FR && xo < a.Wo) ? fr * a.Wo + xo : -1;
+            rowsum[m] = 0;
+        }
+        v16i acc[MB][NB][NACC];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int q = 0; q < NACC; ++q)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[mb][nb][q][v] = 0;
+        for (int o = 0; o < a.split; ++o) {
+            const v4i *theirs = (const v4i *)(a.partials + ((size_t)blockIdx.x * a.split + o) * a.part_bytes);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int q = 0; q < NACC; ++q)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            const v4i v = theirs[(((mb * NB + nb) * NACC + q) * 4 + g) * THREADS + tid];
+                            acc[mb][nb][q][4 * g] += v.x;
+                            acc[mb][nb][q][4 * g + 1] += v.y;
+                            acc[mb][nb][q][4 * g + 2] += v.z;
+                            acc[mb][nb][q][4 * g + 3] += v.w;
+                        }
+            if constexpr (LIMBS == 2) {
+                const int *rs = (const int *)(theirs + MB * NB * NACC * 4 * THREADS);
+                if (tid < BM) rowsum[tid] += rs[tid]; // each row has one owner: no race
+            }
+        }
+        __syncthreads();
+        const unsigned zeros = tile_epilogue<LIMBS, NB, MB, THREADS>(a, acc, rowsum, outoff, otile, ntile);
+        if ((tid & 63) == 0) wave_zeros[tid >> 6] = zeros;
+        __syncthreads();
+        if (tid == 0)
+            for (int w = 0; w < THREADS / 64; ++w) total += wave_zeros[w];
+    }
+    if (!a.zero_partial) return;
+    if (blockIdx.x == 0) {
+        unsigned long long sum = 0;
+        for (int i = tid; i < main_grid; i += THREADS) sum += a.zero_partial[i];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) sum += __shfl_down(sum, off, 64);
+        __syncthreads(); // wave_zeros[] has been read
+        if ((tid & 63) == 0) wave_zeros[tid >> 6] = (unsigned)sum; // a launch has fewer than 2^32 outputs
+        __syncthreads();
+        if (tid == 0)
+            for (int w = 0; w < THREADS / 64; ++w) total += wave_zeros[w];
+    }
+    if (tid == 0 && total) atomicAdd(a.zero_count, total);
 }
 
 __global__ __launch_bounds__(256) void sum_partials_kernel(const unsigned *__restrict__ partial, int n,
@@ -954,24 +1161,31 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(const unsigned *__res
     }
 }
 
-template <int LIMBS, int NB, bool FLAT>
-static lp_status launch_mfma(const ConvArgs &a, const Plan &p, hipStream_t st)
+template <int LIMBS, int NB, bool FLAT, int MB>
+static lp_status launch_mfma(const ConvArgs &a, const Plan &p, int grid, int tails, hipStream_t st)
 {
     static bool attr_set = false; // raise the dynamic LDS limit once per kernel instance
     if (!attr_set) {
-        if (hipFuncSetAttribute((const void *)conv_mfma_kernel<LIMBS, NB, FLAT>,
+        if (hipFuncSetAttribute((const void *)conv_mfma_kernel<LIMBS, NB, FLAT, MB>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
             return LP_EDEVICE;
         attr_set = true;
     }
-    hipLaunchKernelGGL((conv_mfma_kernel<LIMBS, NB, FLAT>), dim3(a.per_xcd * 8), dim3(kConvThreads),
+    hipLaunchKernelGGL((conv_mfma_kernel<LIMBS, NB, FLAT, MB>), dim3(grid), dim3(MB == 2 ? 256 : 512),
                        p.lds_bytes, st, a);
+    if (tails) // the split tail tiles are merged and written by a second, small kernel
+        hipLaunchKernelGGL((conv_finish_kernel<LIMBS, NB, MB>), dim3(tails), dim3(256), 0, st, a, grid);
     return launch_status();
 }
 
-static size_t workspace_bytes_for(const Plan &p)
+static WorkspaceLayout workspace_layout(const Plan &p)
 {
-    return p.path == PATH_MFMA ? round_up((size_t)p.tiles_m * p.tiles_n * sizeof(unsigned), 256) : 0;
+    WorkspaceLayout w = {0, 0};
+    if (p.path != PATH_MFMA) return w;
+    const size_t tails = (size_t)kXCDs * (p.per_xcd - p.full_per_xcd);
+    w.partials = round_up((size_t)p.grid * sizeof(unsigned), 256);
+    w.total = w.partials + tails * p.split * p.part_bytes;
+    return w;
 }
 
 static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, const void *wp,
@@ -1023,11 +1237,23 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     a.tiles_c = p.tiles_c; a.tiles_n = p.tiles_n; a.CoutP = p.CoutP; a.nchunks = p.nchunks;
     a.taps = p.taps; a.ksteps = p.ksteps; a.Kflat = d->R * d->S * d->Cin;
     a.total_work = p.tiles_m * p.tiles_n;
-    a.per_xcd = (a.total_work + 7) / 8;
+    a.per_xcd = p.per_xcd;
+    a.full_per_xcd = p.full_per_xcd;
+    a.split = p.split;
+    int grid = p.grid;
     const bool counting = zero_count && y;
-    if (counting) {
-        if (!workspace || workspace_bytes < workspace_bytes_for(p) || !aligned16(workspace)) return LP_EWORKSPACE;
-        a.zero_partial = (unsigned *)workspace;
+    const WorkspaceLayout wl = workspace_layout(p);
+    if (workspace) {
+        if (workspace_bytes < wl.total || !aligned16(workspace)) return LP_EWORKSPACE;
+        if (counting) a.zero_partial = (unsigned *)workspace;
+        a.partials = (unsigned char *)workspace + wl.partials;
+        a.part_bytes = (int)p.part_bytes;
+    } else {
+        if (counting) return LP_EWORKSPACE;
+        // nowhere to merge partial sums: every tile is computed by one workgroup
+        a.full_per_xcd = p.per_xcd;
+        a.split = 1;
+        grid = kXCDs * p.per_xcd;
     }
     // The 32-bit epilogue is exact when only codes are wanted, with ReLU, round-half-away,
     // a right shift of 1..31 bits, and sums small enough that no int32 piece can overflow
@@ -1036,11 +1262,12 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     a.fast = (y && !acc_out && relu && r == LP_ROUND_NEAREST_AWAY && a.act.s >= 1 && a.act.s <= 31 &&
               K <= 8192 && (!bias || a.bias_shift <= 24)) ? 1 : 0;
     lp_status st2;
-    if (p.flat) st2 = launch_mfma<2, 1, true>(a, p, hs);
-    else if (p.limbs == 2) st2 = launch_mfma<2, 1, false>(a, p, hs);
-    else st2 = p.BN == 128 ? launch_mfma<1, 2, false>(a, p, hs) : launch_mfma<1, 1, false>(a, p, hs);
-    if (st2 != LP_OK || !counting) return st2;
-    hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(256), 0, hs, a.zero_partial, a.total_work,
+    const int tails = a.split > 1 ? kXCDs * (p.per_xcd - p.full_per_xcd) : 0; // finishing workgroups
+    if (p.flat) st2 = launch_mfma<2, 1, true, 2>(a, p, grid, tails, hs);
+    else if (p.limbs == 2) st2 = launch_mfma<2, 1, false, 2>(a, p, grid, tails, hs);
+    else st2 = p.BN == 128 ? launch_mfma<1, 2, false, 2>(a, p, grid, tails, hs) : launch_mfma<1, 1, false, 2>(a, p, grid, tails, hs);
+    if (st2 != LP_OK || tails || !counting) return st2;
+    hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(256), 0, hs, a.zero_partial, grid,
                        (unsigned long long *)zero_count);
     return launch_status();
 }
@@ -1141,6 +1368,8 @@ extern "C" lp_status lp_conv_plan_info(const lp_conv_desc *d, lp_qfmt qx, lp_qfm
         o.tiles_m = p.tiles_m; o.tiles_n = p.tiles_n; o.lds_bytes = (int32_t)p.lds_bytes;
         o.patch_pitch = p.PITCH;
         o.swizzle_kmul = p.KMUL;
+        o.workgroups = p.grid;
+        o.split = p.split;
     }
     *out_host = o;
     return LP_OK;
@@ -1152,7 +1381,7 @@ extern "C" lp_status lp_conv_workspace_bytes(const lp_conv_desc *d, lp_qfmt qx, 
     if (!bytes_host) return LP_EINVAL;
     Plan p;
     lp_status st = make_plan(d, qx, qw, &p);
-    if (st == LP_OK) *bytes_host = workspace_bytes_for(p);
+    if (st == LP_OK) *bytes_host = workspace_layout(p).total;
     return st;
 }
 

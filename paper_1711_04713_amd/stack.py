@@ -69,7 +69,8 @@ class ConvStack:
         return self.qx, self.qy
 
     def set_formats(self, qx, qy):
-        self.qx, self.qy = lp.QFmt(*qx), [lp.QFmt(*q) for q in qy]
+        as_fmt = lambda q: lp.QFmt(*(q.astuple() if isinstance(q, lp.QFmt) else q))
+        self.qx, self.qy = as_fmt(qx), [as_fmt(q) for q in qy]
 
     def prepare(self, N, H, W):
         """Pack weights for the frozen formats and allocate every buffer of a forward pass."""

@@ -49,7 +49,8 @@ def conv(x_codes, qx, w_codes, qw, qy=None, relu=True, r=lp.LP_ROUND_NEAREST_AWA
     acc = torch.empty((N, Ho, Wo, Cout), dtype=torch.int64, device="cuda") if want_acc else None
     y = torch.empty((N, Ho, Wo, Cout), dtype=code_torch_dtype(qy[0]), device="cuda") if (want_y and qy) else None
     z = counter()
-    ws = torch.empty(max(lp.lp_conv_workspace_bytes(d, qx, qw), 16), dtype=torch.uint8, device="cuda")
+    # filled with junk: the library must not rely on the workspace's previous contents
+    ws = torch.full((max(lp.lp_conv_workspace_bytes(d, qx, qw), 16),), 0xA5, dtype=torch.uint8, device="cuda")
     lp.lp_conv_fwd(d, xd, qx, packed, qw, qy=qy, y_codes=y, acc_out=acc, relu=relu, r=r, bias_codes=bd, qb=qb,
                    zero_count=z, workspace=ws)
     torch.cuda.synchronize()
@@ -73,7 +74,7 @@ def fc(x_codes, qx, w_codes, qw, qy=None, relu=True, r=lp.LP_ROUND_NEAREST_AWAY,
     acc = torch.empty((M, Nout), dtype=torch.int64, device="cuda") if want_acc else None
     y = torch.empty((M, Nout), dtype=code_torch_dtype(qy[0]), device="cuda") if qy else None
     z = counter()
-    ws = torch.empty(max(lp.lp_fc_workspace_bytes(M, K, Nout, qx, qw), 16), dtype=torch.uint8, device="cuda")
+    ws = torch.full((max(lp.lp_fc_workspace_bytes(M, K, Nout, qx, qw), 16),), 0xA5, dtype=torch.uint8, device="cuda")
     lp.lp_fc_fwd(M, K, Nout, xd, qx, packed, qw, qy=qy, y_codes=y, acc_out=acc, relu=relu, r=r, bias_codes=bd,
                  qb=qb, zero_count=z, workspace=ws)
     torch.cuda.synchronize()
