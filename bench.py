@@ -80,10 +80,12 @@ def main():
     for _ in range(args.warmup):
         stack.forward(x)
     torch.cuda.synchronize()
+    # HIP events bracket every launch on one step in four of the timed region (recording them on
+    # every step would itself cost about 5 % of the step time)
     events = []
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        stack.forward(x, events)
+    for k in range(args.steps):
+        stack.forward(x, events if k % 4 == 0 else None)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
@@ -112,14 +114,17 @@ def main():
         macs = L["macs"]
         total_macs += macs
         info = L["info"]
-        kname = "conv_mfma_kernel<%d,%d>" % (info["limbs"], info["bn"] // 64) if info["path"] == 1 else "conv_direct_kernel"
+        flat = info["path"] == 1 and L["desc"].Cin < 16          # whole window as one slab (first layer)
+        kname = ("conv_mfma_kernel<%d,%d,%s>" % (info["limbs"], info["bn"] // 64, "flat" if flat else "patch")
+                 if info["path"] == 1 else "conv_direct_kernel")
         kern_ops[kname] = kern_ops.get(kname, 0) + 8 * macs          # 4 int8 limb MACs = 8 int8 ops per 16-bit MAC
         kern_ms[kname] = kern_ms.get(kname, 0.0) + ms
         layers.append({
             "layer": name, "ms": round(ms, 4), "format_in": repr(L["qx"]), "format_w": repr(L["qw"]),
             "format_out": repr(L["qy"]), "sparsity": round(float(zeros[i]) / L["y"].numel(), 4),
             "int8_tops": round(8 * macs / (ms * 1e-3) / 1e12, 1), "kernel": kname,
-            "tile": [info["tile_rows"], info["tile_cols"], info["bn"]],
+            "tile": [info["tile_rows"], info["tile_cols"], info["bn"]], "workgroups": info["workgroups"],
+            "split": info["split"],
         })
     dominant = max(kern_ms, key=kern_ms.get)
     achieved = kern_ops[dominant] / (kern_ms[dominant] * 1e-3) / 1e12

@@ -117,12 +117,13 @@ static void choose_swizzle(int pw, int tw, int rh, int R, int S, int *pitch_px, 
         }
 }
 
-// LDS: tables (3*ntab + 2*BM ints), staged patch (one plane per limb), two weight slabs
+// LDS: tables (3*ntab + 2*BM ints, 3*bn ints of channel constants), staged patch (one plane per
+// limb), two weight slabs
 static size_t mfma_lds_bytes(int limbs, int pra, int pw, int pitch_px, int bn, int flat)
 {
     const int ntab = std::max(pra * pw, BM);
     const size_t plane = flat ? (size_t)BM * PS : (size_t)pra * pitch_px * PS;
-    size_t tables = round_up((size_t)(3 * ntab + 2 * BM) * 4, 16);
+    size_t tables = round_up((size_t)(3 * ntab + 2 * BM) * 4, 16) + (size_t)3 * bn * 4;
     return tables + (size_t)limbs * plane + (size_t)2 * limbs * bn * PS;
 }
 // LDS budgets tried in turn: three workgroups per CU (160 KB / 3), else two
@@ -467,133 +468,118 @@ __device__ __forceinline__ int requant_relu32(int hi, int lo16, int s, int cmax)
     return min(max(q, 0), cmax); // compiles to v_med3_i32
 }
 
+// Per-channel constants of a tile (weight correction + bias) into LDS, in the form the epilogue
+// wants: three int32 planes (bits 16.., 8..15, 0..7) for the 32-bit epilogue, else int64.
+template <int BN, int THREADS>
+__device__ __forceinline__ void build_colterms(const ConvArgs &a, int ntile, int *ctab)
+{
+    for (int c = threadIdx.x; c < BN; c += THREADS) {
+        const int colg = ntile * BN + c;
+        const int64_t t = colg < a.Cout ? a.corr[colg] + bias_term(a, colg) : 0;
+        if (a.fast) {
+            ctab[c] = (int)(t >> 16);
+            ctab[BN + c] = (int)((t >> 8) & 255);
+            ctab[2 * BN + c] = (int)(t & 255);
+        } else {
+            ((int64_t *)ctab)[c] = t;
+        }
+    }
+}
+
 // Epilogue of one 128 x BN tile: combine limbs exactly, add corrections and bias, LPAct (or raw
-// accumulators), count zeros.  acc is the calling thread's share in the MFMA 32x32 result layout:
-// lane holds column (lane & 31), rows 8*(v/4) + 4*(lane/32) + v%4.  rowsum (LDS, BM ints, two-limb
-// only) and outoff (LDS, BM ints) are complete and visible; otile is LDS scratch for the tile of
-// codes.  Returns the wave's count of zero codes (the same value in every lane).
-template <int LIMBS, int NB, int MB, int THREADS>
+// accumulators), count zeros.  The MFMAs are issued with the weights as the row operand, so in
+// the 32x32 result layout a lane holds one output pixel (tile row wm*WROWS + mb*32 + (lane & 31))
+// and, in register v, channel 8*(v/4) + 4*(lane/32) + v%4 of its 32-channel block: four
+// consecutive channels per group of four registers, which leave as one 8-byte (4-byte) store.
+// row_sum(m): sum of the codes under tile row m's window (two-limb only); outoff and ctab (see
+// build_colterms) are LDS tables, complete and visible.  Returns the wave's count of zero codes
+// (the same value in every lane).
+template <int LIMBS, int NB, int MB, int THREADS, typename RowSum>
 __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)[MB][NB][LIMBS == 2 ? 3 : 1],
-                                                  const int *rowsum, const int *outoff, unsigned char *otile,
-                                                  int ntile)
+                                                  RowSum row_sum, const int *outoff, const int *ctab, int ntile)
 {
     constexpr int BN = 64 * NB;
     constexpr int WMC = BM / (32 * MB), WROWS = 32 * MB;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WMC, wn = wave / WMC;
     const int l32 = lane & 31, kg = lane >> 5;
-    unsigned zeros = 0;
-    int64_t colterm[NB];
-    int colg[NB];
+    unsigned nz = 0; // zero codes written by this lane (at most 16 * MB * NB <= 64)
+    int oo[MB], rs[MB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        colg[nb] = ntile * BN + wn * (NB * 32) + nb * 32 + l32;
-        colterm[nb] = 0;
-        if (colg[nb] < a.Cout) colterm[nb] = a.corr[colg[nb]] + bias_term(a, colg[nb]);
+    for (int mb = 0; mb < MB; ++mb) {
+        const int m = wm * WROWS + mb * 32 + l32;
+        oo[mb] = outoff[m];
+        rs[mb] = (LIMBS == 2) ? row_sum(m) : 0;
     }
     if (a.fast) {
-        // v = 2^16*A + 2^8*B + C with every piece in int32: the column constant is split the same
+        // v = 2^16*A + 2^8*B + C with every piece in int32: the channel constant is split the same
         // way, 128*rowsum = 2^8*(rowsum >> 1) + 128*(rowsum & 1); then carries are pushed upward.
-        // The codes go to an LDS tile first and leave as 16-byte row pieces.  Shift class and
-        // code width are compile-time here: the per-value work is about ten VALU operations.
+        // Shift class and code width are compile-time: about ten VALU operations per value.
         const int s = a.act.s, cmax = a.act.hi;
         auto requant_tile = [&](auto s16c, auto y16c) __attribute__((always_inline)) {
             constexpr int S16 = decltype(s16c)::value;
             constexpr bool Y16 = decltype(y16c)::value;
             constexpr int ESZ = Y16 ? 2 : 1;
-            constexpr int OSTRIDE = BN * ESZ + 16; // padded: 4 rows apart != 0 mod 256 bytes
-            int cA[NB], cB[NB], cC[NB];
+            const bool vec_ok = (a.Cout & 3) == 0; // every group of four channels is aligned
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                cA[nb] = (int)(colterm[nb] >> 16);
-                cB[nb] = (int)((colterm[nb] >> 8) & 255);
-                cC[nb] = (int)(colterm[nb] & 255);
-            }
-            int rs_r[MB][16]; // row sums first, all LDS reads in flight together
-            if constexpr (LIMBS == 2) {
+            for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
+                for (int g = 0; g < 4; ++g) {
+                    const int cl = wn * (NB * 32) + nb * 32 + 8 * g + 4 * kg; // channel within the tile
+                    const int col0 = ntile * BN + cl;
+                    const v4i cA = *(const v4i *)(ctab + cl);
+                    const v4i cB = *(const v4i *)(ctab + BN + cl);
+                    const v4i cC = *(const v4i *)(ctab + 2 * BN + cl);
 #pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        rs_r[mb][v] = rowsum[wm * WROWS + mb * 32 + 8 * (v >> 2) + 4 * kg + (v & 3)];
-            }
-            unsigned char *obase = otile + (wn * (NB * 32) + l32) * ESZ;
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = wm * WROWS + mb * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-                    int rB = 0, rC = 0;
-                    if constexpr (LIMBS == 2) {
-                        rB = rs_r[mb][v] >> 1;
-                        rC = (rs_r[mb][v] & 1) << 7;
-                    }
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        int hi, lo16 = 0;
-                        if constexpr (LIMBS == 2) {
-                            const int C = acc[mb][nb][2][v] + cC[nb] + rC;
-                            const int B = acc[mb][nb][1][v] + cB[nb] + rB + (C >> 8);
-                            hi = acc[mb][nb][0][v] + cA[nb] + (B >> 8);
-                            if constexpr (S16 != 0) lo16 = ((B & 255) << 8) | (C & 255);
-                        } else {
-                            const int C = acc[mb][nb][0][v] + (int)colterm[nb];
-                            hi = C >> 16;
-                            lo16 = C & 65535;
-                        }
-                        const int c = requant_relu32<S16>(hi, lo16, s, cmax);
-                        unsigned char *o = obase + row * OSTRIDE + nb * 32 * ESZ;
-                        if constexpr (Y16) *(int16_t *)o = (int16_t)c;
-                        else *(int8_t *)o = (int8_t)c;
-                    }
-                }
-            // the tile now sits in LDS row-major: write it out 16 bytes (8 or 16 channels) per
-            // lane, a pixel's channels contiguous, and count the zero codes among the bytes written
-            __syncthreads();
-            constexpr int LSH = ((BN == 64) ? 2 : 3) + ESZ - 1; // log2(16-byte pieces per tile row)
-            constexpr int EPP = 16 / ESZ;                       // codes per piece
-            const bool vec_ok = (a.Cout % EPP) == 0;            // output rows 16-byte aligned
-            unsigned nz = 0;
-#pragma unroll
-            for (int k = 0; k < (BM << LSH) / THREADS; ++k) {
-                const int i = tid + k * THREADS;
-                const int row = i >> LSH, c = i - (row << LSH);
-                const int oo = outoff[row];
-                const int col0 = ntile * BN + c * EPP;
-                if (oo >= 0 && col0 < a.Cout) {
-                    const unsigned char *src = otile + row * OSTRIDE + c * 16;
-                    unsigned char *dst = (unsigned char *)a.y + ((size_t)oo * a.Cout + col0) * ESZ;
-                    if (vec_ok && col0 + EPP <= a.Cout) {
-                        const v4i q = *(const v4i *)src;
-                        *(v4i *)dst = q;
-                        // exact per-lane zero test: the top bit of a 16-bit (8-bit) lane survives
-                        // only when every bit of that lane is clear; no carry crosses lanes
-                        constexpr unsigned LOW = Y16 ? 0x7fff7fffu : 0x7f7f7f7fu;
+                    for (int mb = 0; mb < MB; ++mb) {
+                        int q[4];
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            const unsigned x = (unsigned)q[e];
-                            nz += __popc(~(((x & LOW) + LOW) | x | LOW));
-                        }
-                    } else { // ragged channel tail, or rows not 16-byte aligned
-                        const int ncodes = min(EPP, a.Cout - col0);
-                        for (int e = 0; e < ncodes; ++e) {
-                            if constexpr (Y16) {
-                                const int16_t q = ((const int16_t *)src)[e];
-                                ((int16_t *)dst)[e] = q;
-                                nz += (q == 0);
+                            const int v = 4 * g + e;
+                            int hi, lo16 = 0;
+                            if constexpr (LIMBS == 2) {
+                                const int C = acc[mb][nb][2][v] + cC[e] + ((rs[mb] & 1) << 7);
+                                const int B = acc[mb][nb][1][v] + cB[e] + (rs[mb] >> 1) + (C >> 8);
+                                hi = acc[mb][nb][0][v] + cA[e] + (B >> 8);
+                                if constexpr (S16 != 0) lo16 = ((B & 255) << 8) | (C & 255);
                             } else {
-                                const int8_t q = ((const int8_t *)src)[e];
-                                ((int8_t *)dst)[e] = q;
-                                nz += (q == 0);
+                                // one limb: the plane split is 2^16*cA + (2^8*cB + cC)
+                                const int C = acc[mb][nb][0][v] + (cB[e] << 8) + cC[e];
+                                hi = cA[e] + (C >> 16);
+                                lo16 = C & 65535;
+                            }
+                            q[e] = requant_relu32<S16>(hi, lo16, s, cmax);
+                        }
+                        if (oo[mb] >= 0 && col0 < a.Cout) {
+                            unsigned char *dst = (unsigned char *)a.y + ((size_t)oo[mb] * a.Cout + col0) * ESZ;
+                            if (vec_ok) {
+                                // codes are in [0, cmax]: packing needs no masks.  Exact per-field
+                                // zero test: the top bit of a 16-bit (8-bit) field survives only
+                                // when every bit of the field is clear; no carry crosses fields
+                                if constexpr (Y16) {
+                                    const unsigned w0 = (unsigned)q[0] | ((unsigned)q[1] << 16);
+                                    const unsigned w1 = (unsigned)q[2] | ((unsigned)q[3] << 16);
+                                    *(v2i *)dst = (v2i){(int)w0, (int)w1};
+                                    constexpr unsigned LOW = 0x7fff7fffu;
+                                    nz += __popc(~(((w0 & LOW) + LOW) | w0 | LOW)) + __popc(~(((w1 & LOW) + LOW) | w1 | LOW));
+                                } else {
+                                    const unsigned w0 = (unsigned)q[0] | ((unsigned)q[1] << 8) | ((unsigned)q[2] << 16) |
+                                                        ((unsigned)q[3] << 24);
+                                    *(unsigned *)dst = w0;
+                                    constexpr unsigned LOW = 0x7f7f7f7fu;
+                                    nz += __popc(~(((w0 & LOW) + LOW) | w0 | LOW));
+                                }
+                            } else { // ragged channel tail, or rows not aligned
+                                const int ncodes = min(4, a.Cout - col0);
+                                for (int e = 0; e < ncodes; ++e) {
+                                    if constexpr (Y16) ((int16_t *)dst)[e] = (int16_t)q[e];
+                                    else ((int8_t *)dst)[e] = (int8_t)q[e];
+                                    nz += (q[e] == 0);
+                                }
                             }
                         }
                     }
                 }
-            }
-            // wave total of the per-lane counts, bit plane by bit plane: ballot + popcount
-            // (a lane counts at most 4 pieces x 16 codes = 64 zeros: 7 bits)
-#pragma unroll
-            for (int b = 0; b < 7; ++b) zeros += wave_count((nz >> b) & 1) << b;
         };
         using std::integral_constant;
         if (a.y16) {
@@ -606,37 +592,43 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
             else requant_tile(integral_constant<int, 2>{}, integral_constant<bool, false>{});
         }
     } else {
+        const int64_t *ct64 = (const int64_t *)ctab;
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = wm * WROWS + mb * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-                const int oo = outoff[row];
-                const int64_t rt = (LIMBS == 2) ? (int64_t)rowsum[row] * 128 : 0;
+            for (int g = 0; g < 4; ++g) {
+                const int cl = wn * (NB * 32) + nb * 32 + 8 * g + 4 * kg;
+                const int col0 = ntile * BN + cl;
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    int64_t val;
-                    if constexpr (LIMBS == 2)
-                        val = ((int64_t)acc[mb][nb][0][v] << 16) + ((int64_t)acc[mb][nb][1][v] << 8) +
-                              (int64_t)acc[mb][nb][2][v] + rt + colterm[nb];
-                    else
-                        val = (int64_t)acc[mb][nb][0][v] + colterm[nb];
-                    const bool ok = oo >= 0 && colg[nb] < a.Cout;
-                    bool z = false;
-                    if (ok) {
-                        const size_t idx = (size_t)oo * a.Cout + colg[nb];
-                        if (a.acc_out) a.acc_out[idx] = val;
-                        if (a.y) {
-                            const int c = act_one(val, a.act);
-                            if (a.y16) ((int16_t *)a.y)[idx] = (int16_t)c;
-                            else ((int8_t *)a.y)[idx] = (int8_t)c;
-                            z = (c == 0);
+                for (int mb = 0; mb < MB; ++mb) {
+                    const int64_t rt = (LIMBS == 2) ? (int64_t)rs[mb] * 128 : 0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int v = 4 * g + e;
+                        int64_t val;
+                        if constexpr (LIMBS == 2)
+                            val = ((int64_t)acc[mb][nb][0][v] << 16) + ((int64_t)acc[mb][nb][1][v] << 8) +
+                                  (int64_t)acc[mb][nb][2][v] + rt + ct64[cl + e];
+                        else
+                            val = (int64_t)acc[mb][nb][0][v] + ct64[cl + e];
+                        if (oo[mb] >= 0 && col0 + e < a.Cout) {
+                            const size_t idx = (size_t)oo[mb] * a.Cout + col0 + e;
+                            if (a.acc_out) a.acc_out[idx] = val;
+                            if (a.y) {
+                                const int c = act_one(val, a.act);
+                                if (a.y16) ((int16_t *)a.y)[idx] = (int16_t)c;
+                                else ((int8_t *)a.y)[idx] = (int8_t)c;
+                                nz += (c == 0);
+                            }
                         }
                     }
-                    zeros += wave_count(z);
                 }
             }
     }
+    // wave total of the per-lane counts, bit plane by bit plane: ballot + popcount
+    unsigned zeros = 0;
+#pragma unroll
+    for (int b = 0; b < 7; ++b) zeros += wave_count((nz >> b) & 1) << b;
     return zeros;
 }
 
@@ -690,7 +682,8 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     int *apos = psum + a.NTAB;       // staged pixel -> byte offset inside a limb plane
     int *outoff = apos + a.NTAB;     // tile row -> output pixel index, -1 if not an output
     int *abase_s = outoff + BM;      // tile row -> staged pixel of its (r=0, s=0) tap
-    unsigned char *Asm = smem + (((size_t)(3 * a.NTAB + 2 * BM) * 4 + 15) & ~(size_t)15);
+    int *ctab = (int *)(smem + (((size_t)(3 * a.NTAB + 2 * BM) * 4 + 15) & ~(size_t)15)); // channel constants
+    unsigned char *Asm = (unsigned char *)(ctab + 3 * BN);
     const int APL = a.APLANE;        // bytes per limb plane of the staged activations
     unsigned char *Bsm = Asm + (size_t)LIMBS * APL;
 
@@ -715,6 +708,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         outoff[m] = ok ? fr * a.Wo + xo : -1;
         abase_s[m] = ok ? ((fr / a.Ho) * a.Hp + fr % a.Ho - vr0) * a.PW + t : 0;
     }
+    build_colterms<BN, THREADS>(a, ntile, ctab);
 
     // weight slabs: slab t = chunk * taps + tap lives at [tap][chunk][limb][CoutP][64].  A slab
     // travels global -> registers -> LDS; DEPTH slabs are in flight in registers so that the
@@ -944,10 +938,11 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
                 for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
-                        acc[mb][nb][0] = mfma_i8(ah[mb], bh[nb], acc[mb][nb][0]);
+                        // weights are the row operand: a lane ends up with one pixel's channels
+                        acc[mb][nb][0] = mfma_i8(bh[nb], ah[mb], acc[mb][nb][0]);
                         if constexpr (LIMBS == 2) {
-                            acc[mb][nb][1] = mfma_i8(ah[mb], bl[nb], acc[mb][nb][1]);
-                            acc[mb][nb][2] = mfma_i8(al[mb], bl[nb], acc[mb][nb][2]);
+                            acc[mb][nb][1] = mfma_i8(bl[nb], ah[mb], acc[mb][nb][1]);
+                            acc[mb][nb][2] = mfma_i8(bl[nb], al[mb], acc[mb][nb][2]);
                         }
                     }
                 if constexpr (LIMBS == 2) {
@@ -955,7 +950,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
                     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                         for (int nb = 0; nb < NB; ++nb)
-                            acc[mb][nb][1] = mfma_i8(al[mb], bh[nb], acc[mb][nb][1]);
+                            acc[mb][nb][1] = mfma_i8(bh[nb], al[mb], acc[mb][nb][1]);
                 }
             }
             // keep the second half's fragment loads behind the first half's MFMAs: both sets
@@ -1008,23 +1003,16 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     }
     if (t < s1) step(t, DEPTH == 2 ? breg1 : breg0);
 
-    // ---- per-row sum of the window's codes (two-limb correction term 128 * sum(a))
-    __syncthreads();
-    int *rowsum = (int *)Asm; // the staged activations are no longer needed
-    if constexpr (LIMBS == 2) {
-        for (int m = tid; m < BM; m += THREADS) {
-            int sum = 0;
-            if constexpr (FLAT) {
-                sum = psum[m];
-            } else {
-                const int base = abase_s[m];
-                for (int r = 0; r < a.R; ++r)
-                    for (int s = 0; s < a.S; ++s) sum += psum[base + r * a.PW + s];
-            }
-            rowsum[m] = sum;
-        }
-        __syncthreads();
-    }
+    // ---- sum of the codes under a tile row's window (two-limb correction term 128 * sum(a)):
+    // the channel sums of its R x S patch pixels, complete since the last chunk was staged
+    auto row_sum = [&](int m) __attribute__((always_inline)) {
+        if constexpr (FLAT) return psum[m];
+        const int base = abase_s[m];
+        int sum = 0;
+        for (int r = 0; r < a.R; ++r)
+            for (int s = 0; s < a.S; ++s) sum += psum[base + r * a.PW + s];
+        return sum;
+    };
 
     // ---- tail tiles: a part stores its accumulators and row sums and is done; the finishing
     // kernel adds the parts up (integer sums: the order cannot matter) and runs the epilogue.
@@ -1045,20 +1033,20 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
                     }
         if constexpr (LIMBS == 2) {
             int *rs = (int *)(mine + MB * NB * NACC * 4 * THREADS);
-            for (int m = tid; m < BM; m += THREADS) rs[m] = rowsum[m];
+            for (int m = tid; m < BM; m += THREADS) rs[m] = row_sum(m);
         }
         if (a.zero_partial && tid == 0) a.zero_partial[blockIdx.x] = 0;
         return;
     }
 
-    unsigned zeros = tile_epilogue<LIMBS, NB, MB, THREADS>(a, acc, rowsum, outoff, Asm + BM * 4, ntile);
+    unsigned zeros = tile_epilogue<LIMBS, NB, MB, THREADS>(a, acc, row_sum, outoff, ctab, ntile);
     // one count per workgroup, no atomics: thousands of same-address atomics would serialise
     if (a.zero_partial) {
-        if (lane == 0) psum[wave] = (int)zeros;
+        if (lane == 0) tab[wave] = (int)zeros; // tab[] was last read while staging
         __syncthreads();
         if (tid == 0) {
             unsigned total = 0;
-            for (int w = 0; w < THREADS / 64; ++w) total += (unsigned)psum[w];
+            for (int w = 0; w < THREADS / 64; ++w) total += (unsigned)tab[w];
             a.zero_partial[blockIdx.x] = total;
         }
     }
@@ -1076,7 +1064,7 @@ __global__ __launch_bounds__(256) void conv_finish_kernel(const ConvArgs a, int 
     constexpr int NACC = (LIMBS == 2) ? 3 : 1;
     __shared__ int outoff[BM];
     __shared__ int rowsum[BM];
-    __shared__ __align__(16) unsigned char otile[BM * (BN * 2 + 16)];
+    __shared__ __align__(16) int ctab[3 * BN];
     __shared__ unsigned wave_zeros[THREADS / 64];
     const int tid = threadIdx.x;
     const int tails = a.per_xcd - a.full_per_xcd;
@@ -1093,6 +1081,7 @@ __global__ __launch_bounds__(256) void conv_finish_kernel(const ConvArgs a, int 
             outoff[m] = (j < a.RH && fr < a.FR && xo < a.Wo) ? fr * a.Wo + xo : -1;
             rowsum[m] = 0;
         }
+        build_colterms<BN, THREADS>(a, ntile, ctab);
         v16i acc[MB][NB][NACC];
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
@@ -1124,7 +1113,8 @@ __global__ __launch_bounds__(256) void conv_finish_kernel(const ConvArgs a, int 
             }
         }
         __syncthreads();
-        const unsigned zeros = tile_epilogue<LIMBS, NB, MB, THREADS>(a, acc, rowsum, outoff, otile, ntile);
+        const unsigned zeros = tile_epilogue<LIMBS, NB, MB, THREADS>(
+            a, acc, [&](int m) { return rowsum[m]; }, outoff, ctab, ntile);
         if ((tid & 63) == 0) wave_zeros[tid >> 6] = zeros;
         __syncthreads();
         if (tid == 0)

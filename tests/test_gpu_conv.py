@@ -244,3 +244,36 @@ def test_zero_count_needs_workspace_and_accumulates(oracle):
     torch.cuda.synchronize()
     _, want = oracle.act(oracle.conv(x, w), 27, *QY, True, oracle.ROUND_AWAY)
     assert int(z.item()) == 1000 + 2 * want
+
+
+@pytest.mark.parametrize("shape", [(2, 12, 12, 256, 64), (1, 20, 16, 128, 192), (3, 8, 8, 192, 64)])
+def test_split_reduction_matches_single_workgroup_tiles(oracle, shape):
+    """With a workspace the tail tiles are cut along the reduction and merged by the finishing
+    kernel; without one every tile is reduced by a single workgroup.  Both must give the
+    oracle's codes, zero count (where counted) and raw accumulators."""
+    import torch
+    from gpu_helpers import to_dev
+
+    N, H, W, Cin, Cout = shape
+    rng = np.random.default_rng(17)
+    x, w = _codes(rng, (N, Cin, H, W), zero_frac=0.4), _codes(rng, (Cout, Cin, 3, 3))
+    d = lp.ConvDesc(N, H, W, Cin, Cout, 3, 3, 1, 1)
+    assert lp.lp_conv_plan_info(d, QX, QW)["split"] > 1
+    xd = to_dev(x.transpose(0, 2, 3, 1).astype(np.int16))
+    wd = to_dev(w.transpose(0, 2, 3, 1).astype(np.int16))
+    packed = torch.empty(lp.lp_conv_packed_bytes(d, QX, QW), dtype=torch.uint8, device="cuda")
+    lp.lp_conv_pack_weights(d, QX, QW, wd, packed)
+    want_acc = oracle.conv(x, w)
+    want_y, want_z = oracle.act(want_acc, 27, *QY, True, oracle.ROUND_AWAY)
+    for use_ws in (False, True):
+        ws = torch.full((lp.lp_conv_workspace_bytes(d, QX, QW),), 0x5A, dtype=torch.uint8, device="cuda") if use_ws else None
+        y = torch.full((N, H, W, Cout), -7, dtype=torch.int16, device="cuda")
+        acc = torch.full((N, H, W, Cout), -7, dtype=torch.int64, device="cuda")
+        z = torch.zeros(1, dtype=torch.int64, device="cuda") if use_ws else None
+        lp.lp_conv_fwd(d, xd, QX, packed, QW, qy=QY, y_codes=y, zero_count=z, workspace=ws)         # fast epilogue
+        lp.lp_conv_fwd(d, xd, QX, packed, QW, acc_out=acc, workspace=ws)                            # raw accumulators
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy().transpose(0, 3, 1, 2), want_y)
+        assert np.array_equal(acc.cpu().numpy().transpose(0, 3, 1, 2), want_acc)
+        if use_ws:
+            assert int(z.item()) == want_z

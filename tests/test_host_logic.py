@@ -165,3 +165,44 @@ def test_tile_geometry_addresses_the_right_pixels(N, H, W, Cin, Cout, R, S, pad)
                         assert tab[base + r * PW + s] == want
     if tiles_r <= 64:
         assert len(seen) == FR * Wo
+
+
+@pytest.mark.parametrize("N,H,W,Cin,Cout,R,S,pad", SHAPES + [(32, 56, 56, 256, 256, 3, 3, 1), (32, 28, 28, 512, 512, 3, 3, 1)])
+def test_launch_geometry_covers_every_tile_and_slab_once(N, H, W, Cin, Cout, R, S, pad):
+    """Re-run the kernel's decoding of a workgroup id into (tile, part): every tile is computed
+    either by one whole workgroup or by `split` parts whose slab ranges partition the reduction."""
+    info = lp.lp_conv_plan_info(lp.ConvDesc(N, H, W, Cin, Cout, R, S, 1, pad), Q16, W16)
+    total = info["tiles_m"] * info["tiles_n"]
+    split, grid = info["split"], info["workgroups"]
+    flat = Cin < 16
+    nslabs = 1 if flat else -(-Cin // 64) * R * S
+    per_xcd = -(-total // 8)
+    assert grid % 8 == 0 and 1 <= split <= max(1, min(nslabs, 8))
+    if split == 1:
+        full = per_xcd
+        assert grid == 8 * per_xcd
+    else:
+        assert (per_xcd * split - grid // 8) % (split - 1) == 0
+        full = (per_xcd * split - grid // 8) // (split - 1)
+        assert 0 <= full < per_xcd
+    covered = {}
+    for b in range(grid):
+        xcd, slot = b & 7, b >> 3
+        tl, part, nparts = slot, 0, 1
+        if slot >= full:
+            u = slot - full
+            tl, part, nparts = full + u // split, u % split, split
+        wi = xcd * per_xcd + tl
+        if tl >= per_xcd or wi >= total:
+            continue
+        s0, s1 = part * nslabs // nparts, (part + 1) * nslabs // nparts
+        assert s0 < s1
+        covered.setdefault(wi, []).append((s0, s1))
+    assert sorted(covered) == list(range(total))
+    for wi, ranges in covered.items():
+        ranges.sort()
+        assert ranges[0][0] == 0 and ranges[-1][1] == nslabs
+        assert all(a[1] == b[0] for a, b in zip(ranges, ranges[1:]))
+    ws = lp.lp_conv_workspace_bytes(lp.ConvDesc(N, H, W, Cin, Cout, R, S, 1, pad), Q16, W16)
+    tails = 8 * (per_xcd - full)
+    assert ws >= grid * 4 + (tails * split * (128 * info["bn"] * 3 * 4 + 512) if split > 1 else 0)
