@@ -779,75 +779,66 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
                 for (int v = 0; v < 16; ++v) acc[mb][nb][q][v] = 0;
 
     // Activations travel global -> registers -> LDS in batches of APF 16-byte pieces per thread,
-    // so that a batch's loads are all in flight together.  PIECES: 16-byte pieces per staged
-    // pixel and chunk (8 x 8 int16 codes, or 4 x 16 int8 codes).
-    constexpr int APF = 4;
-    constexpr int PIECES = (LIMBS == 2) ? 8 : 4;
-    v4i areg[APF];
-    // Loads are unconditional (indices clamped into the patch, pixels outside the image read
-    // pixel 0 and are zeroed afterwards), so the whole batch is straight-line code: all table
-    // reads first, then all global loads back to back.
-    unsigned act_ok = 0; // bit j: piece j of the batch lies inside the image
+    // two batches in flight: while one is unpacked and parked, the next is on its way.  PIECES:
+    // 16-byte pieces per staged pixel and chunk (8 x 8 int16 codes, or 4 x 16 int8 codes); since
+    // THREADS is a multiple of PIECES, a thread always handles the same piece of its pixels.
     // A chunk's channel sums are collected by the part that holds the chunk's first tap, so that
     // parts which share a chunk do not count it twice.
     bool own_sums = (s0 % a.taps) == 0;
-    auto load_act = [&](int cc, int first) __attribute__((always_inline)) {
-        int g[APF];
+    constexpr int APF = 2;
+    constexpr int PIECES = (LIMBS == 2) ? 8 : 4;
+    constexpr int ESZ_X = (LIMBS == 2) ? 2 : 1;
+    v4i aregA[APF], aregB[APF];
+    const int apiece = tid & (PIECES - 1), apix0 = tid / PIECES;
+    // Loads go through a buffer descriptor that covers exactly the input tensor: a piece outside
+    // the image or past the last channel is given an offset beyond it and reads as zeros, the
+    // code 0, with no branch and no select on the data.
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void *>(a.x), 0, (int)((unsigned)(a.N * a.H * a.W) * (unsigned)a.Cin * ESZ_X), 0x00020000);
+    auto load_act = [&](int cc, int first, v4i *reg) __attribute__((always_inline)) {
+        const int ch = cc * CK + apiece * (CK / PIECES);
 #pragma unroll
         for (int j = 0; j < APF; ++j) {
-            const unsigned i = (unsigned)min(first + tid + j * THREADS, NPIXA * PIECES - 1);
-            g[j] = tab[i / PIECES];
-        }
-        act_ok = 0;
-#pragma unroll
-        for (int j = 0; j < APF; ++j) {
-            const unsigned i = (unsigned)min(first + tid + j * THREADS, NPIXA * PIECES - 1);
-            const int c = (int)(i % PIECES);
-            const int ch = min(cc * CK + c * (CK / PIECES), a.Cin - CK / PIECES);
-            act_ok |= (g[j] >= 0 ? 1u : 0u) << j;
-            const unsigned off = (unsigned)(max(g[j], 0) * a.Cin + ch) * (unsigned)(LIMBS == 2 ? 2 : 1);
-            areg[j] = *(const v4i *)((const unsigned char *)a.x + off);
+            const int p = min(apix0 + (first + j * THREADS) / PIECES, NPIXA - 1);
+            const int g = tab[p];
+            const unsigned off = (g >= 0 && ch < a.Cin) ? (unsigned)(g * a.Cin + ch) * ESZ_X : 0xffffffffu;
+            const auto v = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)off, 0, 0);
+            reg[j] = (v4i){(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
         }
     };
-    auto store_act = [&](int cc, int first) __attribute__((always_inline)) {
-        int pos_r[APF]; // LDS positions first, all reads in flight together (see the epilogue note)
-#pragma unroll
-        for (int j = 0; j < APF; ++j)
-            pos_r[j] = apos[(unsigned)min(first + tid + j * THREADS, NPIXA * PIECES - 1) / PIECES];
+    auto store_act = [&](int first, const v4i *reg) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < APF; ++j) {
-            const int i = first + tid + j * THREADS;
-            const bool live = i < NPIXA * PIECES;
-            const int p = (int)((unsigned)i / PIECES), c = (int)((unsigned)i % PIECES);
-            const int ch = cc * CK + c * (CK / PIECES);
-            v4i v = areg[j];
-            if (!((act_ok >> j) & 1)) v = (v4i){0, 0, 0, 0}; // outside the image: the code 0
+            const int p = apix0 + (first + j * THREADS) / PIECES;
+            const bool live = p < NPIXA;
+            const int pos = apos[min(p, NPIXA - 1)];
+            const v4i v = reg[j];
             if constexpr (LIMBS == 2) {
-                v2i hi = {0, 0}, lo = {0, 0};
-                int sum = 0;
-                if (live && ch < a.Cin) {
-                    hi.x = (int)__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x07050301u);
-                    hi.y = (int)__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x07050301u);
-                    lo.x = (int)(__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x06040200u) ^ 0x80808080u);
-                    lo.y = (int)(__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x06040200u) ^ 0x80808080u);
-                    sum = ((v.x << 16) >> 16) + (v.x >> 16) + ((v.y << 16) >> 16) + (v.y >> 16) +
-                          ((v.z << 16) >> 16) + (v.z >> 16) + ((v.w << 16) >> 16) + (v.w >> 16);
-                }
+                v2i hi, lo;
+                hi.x = (int)__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x07050301u);
+                hi.y = (int)__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x07050301u);
+                lo.x = (int)(__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x06040200u) ^ 0x80808080u);
+                lo.y = (int)(__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x06040200u) ^ 0x80808080u);
+                // sum of the eight codes: four two-element dot products with (1, 1)
+                const v2s ones = {1, 1};
+                const int w0 = v.x, w1 = v.y, w2 = v.z, w3 = v.w;
+                int sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, w0), ones, 0, false);
+                sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, w1), ones, sum, false);
+                sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, w2), ones, sum, false);
+                sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, w3), ones, sum, false);
                 // the 8 pieces of a pixel sit in 8 adjacent lanes: add them up with DPP lane
                 // exchanges (xor 1, xor 2 inside quads, then mirror inside the half row)
                 sum += __builtin_amdgcn_mov_dpp(sum, 0xB1, 0xF, 0xF, true);
                 sum += __builtin_amdgcn_mov_dpp(sum, 0x4E, 0xF, 0xF, true);
                 sum += __builtin_amdgcn_mov_dpp(sum, 0x141, 0xF, 0xF, true);
                 if (live) {
-                    if (c == 0 && sum && own_sums) atomicAdd(&psum[p], sum); // single owner; no value returned
-                    const int pos = pos_r[j];
-                    const int at = swzk(pos & ~3, c >> 1, pos) + (c & 1) * 8;
+                    if (apiece == 0 && sum && own_sums) atomicAdd(&psum[p], sum); // single owner; no value returned
+                    const int at = swzk(pos & ~3, apiece >> 1, pos) + (apiece & 1) * 8;
                     *(v2i *)(Asm + at) = hi;
                     *(v2i *)(Asm + APL + at) = lo;
                 }
             } else {
-                if (ch >= a.Cin) v = (v4i){0, 0, 0, 0};
-                if (live) *(v4i *)(Asm + swzk(pos_r[j] & ~3, c, pos_r[j])) = v;
+                if (live) *(v4i *)(Asm + swzk(pos & ~3, apiece, pos)) = v;
             }
         }
     };
@@ -897,10 +888,16 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         if constexpr (FLAT) {
             stage_flat();
         } else {
+            // every load is issued, also the one past the end (it reads the last pixel again):
+            // the number of loads in flight is then the same on every path, and each wait
+            // covers exactly the batch about to be parked
             const int total = NPIXA * PIECES;
-            for (int first = 0; first < total; first += APF * THREADS) {
-                if (!(have_first && first == 0)) load_act(cc, first);
-                store_act(cc, first);
+            if (!have_first) load_act(cc, 0, aregA);
+            for (int first = 0; first < total; first += 2 * APF * THREADS) {
+                load_act(cc, first + APF * THREADS, aregB);
+                store_act(first, aregA);
+                load_act(cc, first + 2 * APF * THREADS, aregA);
+                store_act(first + APF * THREADS, aregB);
             }
         }
     };
@@ -977,7 +974,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         // the next chunk's first batch of activations is requested before the chunk's last slab
         // is multiplied and waits in registers; issued after the slab fetch, so that no slab
         // wait in between forces it to complete early (loads return in order)
-        if (EARLY && tap == early_tap && cc + 1 < a.nchunks) load_act(cc + 1, 0);
+        if (EARLY && tap == early_tap && cc + 1 < a.nchunks) load_act(cc + 1, 0, aregA);
         compute_slab(t);
         if (++tap == a.taps) {
             tap = 0;
