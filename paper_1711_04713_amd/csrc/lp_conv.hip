@@ -710,49 +710,51 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     }
     build_colterms<BN, THREADS>(a, ntile, ctab);
 
-    // weight slabs: slab t = chunk * taps + tap lives at [tap][chunk][limb][CoutP][64].  A slab
-    // travels global -> registers -> LDS; DEPTH slabs are in flight in registers so that the
-    // L2 latency is covered by the MFMAs of the slabs before it.
-    constexpr int DEPTH = 1;
+    // weight slabs: slab t = chunk * taps + tap lives at [chunk][tap][limb][CoutP][64], i.e.
+    // consecutive in memory in the order they are consumed.  A slab goes from global memory
+    // straight into LDS (no registers in between): lane l of a wave fills the 16 bytes at the
+    // wave's destination + 16*l.  A wave owns BITEMS consecutive 1 KB blocks of the buffer (one
+    // destination register, the blocks told apart by the instruction's immediate offset), so its
+    // piece j lands at byte 16 * (wave*BITEMS*64 + j*64 + lane).  The swizzle is applied on the
+    // source side: the thread that fills physical slot q' of a row fetches the row's logical slot
+    // q' ^ key.  The request is issued right after the barrier that frees the target buffer and
+    // is waited for just before the next barrier, one slab of MFMAs later.
     const int nslabs = a.nchunks * a.taps;
     const int s0 = part * nslabs / nparts, s1 = (part + 1) * nslabs / nparts; // this workgroup's slabs
-    v4i breg0[BITEMS], breg1[DEPTH == 2 ? BITEMS : 1];
-    // Slabs are consecutive in memory in the order they are consumed, so fetching the next one is
-    // a pointer bump.  The fetch is issued on every step, also past the last slab (where it
-    // re-reads the last one): an unconditional load keeps the number of loads in flight the same
-    // on every path, so the wait before a slab is parked in LDS covers that slab only.
     const size_t slab_bytes = (size_t)LIMBS * a.CoutP * CK;
     const unsigned char *bsrc;
     {
-        const int lb0 = tid / (BN * 4), rem0 = tid - lb0 * (BN * 4);
-        bsrc = a.wp + ((size_t)ntile * BN + (size_t)lb0 * a.CoutP + (rem0 >> 2)) * CK + (rem0 & 3) * 16;
+        // a wave's blocks lie in one limb plane, 16 rows (same key, 1 KB of source) apart
+        static_assert((BN * 4) % (BITEMS * 64) == 0, "a wave's blocks must not straddle limb planes");
+        const int i0 = (tid >> 6) * (BITEMS * 64) + (tid & 63);
+        const int lb0 = i0 / (BN * 4), rem0 = i0 - lb0 * (BN * 4);
+        const int slot = (rem0 ^ (rem0 >> 4)) & 3; // physical slot rem0 & 3, key (row >> 2) & 3
+        bsrc = a.wp + ((size_t)ntile * BN + (size_t)lb0 * a.CoutP + (rem0 >> 2)) * CK + slot * 16;
         bsrc += (size_t)s0 * slab_bytes;
     }
-    // piece j of a thread is piece tid + j*256 of the slab: limb plane (j*256) / (BN*4), and
-    // ((j*256) % (BN*4)) / 4 rows below the thread's first piece
     int pf = s0; // index of the next slab to fetch
-    auto load_slab = [&](v4i *reg) __attribute__((always_inline)) {
-#pragma unroll
-        for (int j = 0; j < BITEMS; ++j) {
-            const int lbj = (j * THREADS) / (BN * 4), rowj = ((j * THREADS) % (BN * 4)) / 4;
-            reg[j] = *(const v4i *)(bsrc + ((size_t)lbj * a.CoutP + rowj) * CK);
-        }
+    const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // The fetch is issued on every step, also past the last slab (where it re-reads the last one
+    // into the buffer nobody reads any more): the number of requests in flight is then the same
+    // on every path.
+    auto fetch_slab = [&](int buf) __attribute__((always_inline)) {
+        static_assert(BITEMS == 1 || BITEMS == 2, "one or two 1 KB blocks per wave");
+        auto *dst = (__attribute__((address_space(3))) void *)(Bsm + buf * BSLAB + wave_u * (BITEMS * 1024));
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)bsrc, dst, 16, 0, 0);
+        if constexpr (BITEMS == 2) // the immediate offset moves the source and the destination alike
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)bsrc, dst, 16, 1024, 0);
         if (pf + 1 < s1) {
             ++pf;
             bsrc += slab_bytes;
         }
     };
-    auto store_slab = [&](int buf, const v4i *reg) __attribute__((always_inline)) {
-#pragma unroll
-        for (int j = 0; j < BITEMS; ++j) {
-            const int i = tid + j * THREADS;
-            const int lb = i / (BN * 4), rem = i - lb * (BN * 4);
-            *(v4i *)(Bsm + buf * BSLAB + lb * BPL + swz((rem >> 2) * PS, rem & 3)) = reg[j];
-        }
+    // every outstanding request (the slab about to be read) has landed, then the barrier
+    auto slab_barrier = [&]() __attribute__((always_inline)) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
     };
-    load_slab(breg0);
-    if (DEPTH == 2) load_slab(breg1);
-    __syncthreads();
+    fetch_slab(s0 & 1);
+    __syncthreads(); // the tables are complete
 
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WMC, wn = wave / WMC;
@@ -956,21 +958,17 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         }
     };
 
-    // Pipeline: slab t+1 is parked in the other LDS buffer and slab t+1+DEPTH is requested while
-    // the MFMAs of slab t run, so one barrier per slab suffices and neither the LDS write nor
-    // the global latency sits between a barrier and the first fragment read.
+    // Pipeline: slab t+1 is requested into the other LDS buffer while the MFMAs of slab t run,
+    // so one barrier per slab suffices.
     stage_activations(cc, false);
     own_sums = true; // every later chunk starts at its first tap
-    store_slab(s0 & 1, breg0);
-    load_slab(breg0);
-    auto step = [&](int t, v4i *next) __attribute__((always_inline)) {
+    auto step = [&](int t) __attribute__((always_inline)) {
         if (tap == 0 && t != s0) {
             __syncthreads(); // all reads of the previous chunk's activations are done
             stage_activations(cc, EARLY);
         }
-        __syncthreads(); // slab t (and a freshly staged patch) visible; slab t-1 fully consumed
-        store_slab((t + 1) & 1, next);
-        load_slab(next);
+        slab_barrier(); // slab t (and a freshly staged patch) visible; slab t-1 fully consumed
+        fetch_slab((t + 1) & 1);
         // the next chunk's first batch of activations is requested before the chunk's last slab
         // is multiplied and waits in registers; issued after the slab fetch, so that no slab
         // wait in between forces it to complete early (loads return in order)
@@ -995,10 +993,10 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     // count path dependent); an odd last slab is handled after it
     int t = s0;
     for (; t + 1 < s1; t += 2) {
-        step(t, DEPTH == 2 ? breg1 : breg0);
-        step(t + 1, breg0);
+        step(t);
+        step(t + 1);
     }
-    if (t < s1) step(t, DEPTH == 2 ? breg1 : breg0);
+    if (t < s1) step(t);
 
     // ---- sum of the codes under a tile row's window (two-limb correction term 128 * sum(a)):
     // the channel sums of its R x S patch pixels, complete since the last chunk was staged
