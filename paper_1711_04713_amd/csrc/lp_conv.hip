@@ -770,15 +770,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) boff[nb] = swz((wn * (NB * 32) + nb * 32 + l32) * PS, kg);
 
-    v16i acc[MB][NB][NACC];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int q = 0; q < NACC; ++q)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[mb][nb][q][v] = 0;
+    v16i acc[MB][NB][NACC]; // zeroed after the first patch is staged: until then its registers are free
 
     // Activations travel global -> registers -> LDS in batches of APF 16-byte pieces per thread,
     // two batches in flight: while one is unpacked and parked, the next is on its way.  PIECES:
@@ -797,24 +789,21 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     // code 0, with no branch and no select on the data.
     const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<void *>(a.x), 0, (int)((unsigned)(a.N * a.H * a.W) * (unsigned)a.Cin * ESZ_X), 0x00020000);
-    auto load_act = [&](int cc, int first, v4i *reg) __attribute__((always_inline)) {
+    // piece number `first + tid` of chunk cc: request it / unpack it and park it in LDS
+    auto load_piece = [&](int cc, int first, v4i &reg) __attribute__((always_inline)) {
         const int ch = cc * CK + apiece * (CK / PIECES);
-#pragma unroll
-        for (int j = 0; j < APF; ++j) {
-            const int p = min(apix0 + (first + j * THREADS) / PIECES, NPIXA - 1);
-            const int g = tab[p];
-            const unsigned off = (g >= 0 && ch < a.Cin) ? (unsigned)(g * a.Cin + ch) * ESZ_X : 0xffffffffu;
-            const auto v = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)off, 0, 0);
-            reg[j] = (v4i){(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
-        }
+        const int p = min(apix0 + first / PIECES, NPIXA - 1);
+        const int g = tab[p];
+        const unsigned off = (g >= 0 && ch < a.Cin) ? (unsigned)(g * a.Cin + ch) * ESZ_X : 0xffffffffu;
+        const auto v = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)off, 0, 0);
+        reg = (v4i){(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
     };
-    auto store_act = [&](int first, const v4i *reg) __attribute__((always_inline)) {
-#pragma unroll
-        for (int j = 0; j < APF; ++j) {
-            const int p = apix0 + (first + j * THREADS) / PIECES;
+    auto store_piece = [&](int first, const v4i &reg) __attribute__((always_inline)) {
+        {
+            const int p = apix0 + first / PIECES;
             const bool live = p < NPIXA;
             const int pos = apos[min(p, NPIXA - 1)];
-            const v4i v = reg[j];
+            const v4i v = reg;
             if constexpr (LIMBS == 2) {
                 v2i hi, lo;
                 hi.x = (int)__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x07050301u);
@@ -843,6 +832,14 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
                 if (live) *(v4i *)(Asm + swzk(pos & ~3, apiece, pos)) = v;
             }
         }
+    };
+    auto load_act = [&](int cc, int first, v4i *reg) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < APF; ++j) load_piece(cc, first + j * THREADS, reg[j]);
+    };
+    auto store_act = [&](int first, const v4i *reg) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < APF; ++j) store_piece(first + j * THREADS, reg[j]);
     };
     // FLAT: the raw patch (all Cin channels, int16) is parked in the unused second weight
     // buffer, then each tile row's window is gathered from there, 16 consecutive k per piece.
@@ -886,7 +883,8 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     };
     constexpr bool EARLY = false;
     const int early_tap = a.taps - 1;
-    auto stage_activations = [&](int cc, bool have_first) __attribute__((always_inline)) {
+    constexpr int DEEP = 8;
+    auto stage_activations = [&](int cc, bool have_first, bool deep) __attribute__((always_inline)) {
         if constexpr (FLAT) {
             stage_flat();
         } else {
@@ -894,8 +892,20 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             // the number of loads in flight is then the same on every path, and each wait
             // covers exactly the batch about to be parked
             const int total = NPIXA * PIECES;
-            if (!have_first) load_act(cc, 0, aregA);
-            for (int first = 0; first < total; first += 2 * APF * THREADS) {
+            int first = 0;
+            if (deep) {
+                // the accumulators are not live yet: request the first DEEP pieces of every
+                // thread at once and pay the memory latency a single time
+                v4i d[DEEP];
+#pragma unroll
+                for (int j = 0; j < DEEP; ++j) load_piece(cc, j * THREADS, d[j]);
+#pragma unroll
+                for (int j = 0; j < DEEP; ++j) store_piece(j * THREADS, d[j]);
+                first = DEEP * THREADS;
+                if (first >= total) return;
+            }
+            if (!have_first) load_act(cc, first, aregA);
+            for (; first < total; first += 2 * APF * THREADS) {
                 load_act(cc, first + APF * THREADS, aregB);
                 store_act(first, aregA);
                 load_act(cc, first + 2 * APF * THREADS, aregA);
@@ -960,12 +970,20 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
 
     // Pipeline: slab t+1 is requested into the other LDS buffer while the MFMAs of slab t run,
     // so one barrier per slab suffices.
-    stage_activations(cc, false);
+    stage_activations(cc, false, true);
     own_sums = true; // every later chunk starts at its first tap
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int q = 0; q < NACC; ++q)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mb][nb][q][v] = 0;
     auto step = [&](int t) __attribute__((always_inline)) {
         if (tap == 0 && t != s0) {
             __syncthreads(); // all reads of the previous chunk's activations are done
-            stage_activations(cc, EARLY);
+            stage_activations(cc, EARLY, false);
         }
         slab_barrier(); // slab t (and a freshly staged patch) visible; slab t-1 fully consumed
         fetch_slab((t + 1) & 1);
