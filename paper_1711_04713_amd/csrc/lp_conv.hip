@@ -650,6 +650,10 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     constexpr int BPL = BN * PS;              // bytes per limb plane of a weight slab
     constexpr int BSLAB = LIMBS * BPL;        // bytes per weight slab buffer
     constexpr int BITEMS = LIMBS * BN * 4 / THREADS; // 16-byte pieces of a slab per thread
+    // Weight fragments: through LDS (one slab per barrier, FLAT only) or straight from global
+    // memory / L2 into the MFMA operand registers, one K=32 half ahead of its use.  Without the
+    // per-slab barrier the waves of a workgroup meet only when a new patch is staged.
+    constexpr bool BDIRECT = !FLAT;
     static_assert(BITEMS >= 1, "a weight slab must give every thread at least one piece");
     extern __shared__ __align__(16) unsigned char smem[];
 
@@ -753,7 +757,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     };
-    fetch_slab(s0 & 1);
+    if constexpr (!BDIRECT) fetch_slab(s0 & 1);
     __syncthreads(); // the tables are complete
 
     const int lane = tid & 63, wave = tid >> 6;
@@ -968,8 +972,68 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         }
     };
 
-    // Pipeline: slab t+1 is requested into the other LDS buffer while the MFMAs of slab t run,
-    // so one barrier per slab suffices.
+    // Direct variant: a lane's B operand for (slab, K half, limb, column block) is the 16 bytes at
+    // row (column block + lane % 32), byte 32*half + 16*(lane / 32) of the packed slab.  Two
+    // register sets alternate: X feeds the first half of a slab while Y (second half) is on its
+    // way, then Y feeds the second half while X is refilled from the next slab.
+    v4i bxh[NB], bxl[NB], byh[NB], byl[NB];
+    const unsigned char *bp = a.wp + (size_t)s0 * slab_bytes +
+                              ((size_t)ntile * BN + wn * (NB * 32) + l32) * CK + kg * 16;
+    int bt = s0; // slab bp points into
+    auto bload = [&](const unsigned char *src, v4i *h, v4i *l) __attribute__((always_inline)) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            h[nb] = *(const v4i *)(src + nb * 32 * CK);
+            if constexpr (LIMBS == 2) l[nb] = *(const v4i *)(src + nb * 32 * CK + (size_t)a.CoutP * CK);
+        }
+    };
+    auto mfma_half = [&](int k32, const int *afrag, const v4i *bh, const v4i *bl) __attribute__((always_inline)) {
+        v4i ah[MB], al[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            ah[mb] = *(const v4i *)(Asm + (afrag[mb] ^ (k32 * 32)));
+            if constexpr (LIMBS == 2) al[mb] = *(const v4i *)(Asm + APL + (afrag[mb] ^ (k32 * 32)));
+        }
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                acc[mb][nb][0] = mfma_i8(bh[nb], ah[mb], acc[mb][nb][0]);
+                if constexpr (LIMBS == 2) {
+                    acc[mb][nb][1] = mfma_i8(bl[nb], ah[mb], acc[mb][nb][1]);
+                    acc[mb][nb][2] = mfma_i8(bl[nb], al[mb], acc[mb][nb][2]);
+                }
+            }
+        if constexpr (LIMBS == 2) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) acc[mb][nb][1] = mfma_i8(bh[nb], al[mb], acc[mb][nb][1]);
+        }
+    };
+    auto compute_slab_direct = [&]() __attribute__((always_inline)) {
+        int afrag[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const int pix = aoff[mb] + tapoff;
+            const int key = a.KMUL == 4 ? pix >> 8 : ((apc[mb] + tap_s) >> 2) + a.KMUL * (apr[mb] + tap_r);
+            afrag[mb] = swzk(pix, kg, key);
+        }
+        bload(bp + 32, byh, byl);
+        mfma_half(0, afrag, bxh, bxl);
+        __builtin_amdgcn_sched_barrier(0);
+        if (bt + 1 < s1) { // past the last slab the last one is read again (and never used)
+            ++bt;
+            bp += slab_bytes;
+        }
+        bload(bp, bxh, bxl);
+        mfma_half(1, afrag, byh, byl);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    if constexpr (BDIRECT) bload(bp, bxh, bxl);
+
+    // Pipeline (LDS variant): slab t+1 is requested into the other LDS buffer while the MFMAs of
+    // slab t run, so one barrier per slab suffices.
     stage_activations(cc, false, true);
     own_sums = true; // every later chunk starts at its first tap
 #pragma unroll
@@ -985,13 +1049,18 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             __syncthreads(); // all reads of the previous chunk's activations are done
             stage_activations(cc, EARLY, false);
         }
-        slab_barrier(); // slab t (and a freshly staged patch) visible; slab t-1 fully consumed
-        fetch_slab((t + 1) & 1);
+        if constexpr (BDIRECT) {
+            if (tap == 0 || t == s0) __syncthreads(); // the freshly staged patch is visible
+        } else {
+            slab_barrier(); // slab t (and a freshly staged patch) visible; slab t-1 fully consumed
+            fetch_slab((t + 1) & 1);
+        }
         // the next chunk's first batch of activations is requested before the chunk's last slab
         // is multiplied and waits in registers; issued after the slab fetch, so that no slab
         // wait in between forces it to complete early (loads return in order)
         if (EARLY && tap == early_tap && cc + 1 < a.nchunks) load_act(cc + 1, 0, aregA);
-        compute_slab(t);
+        if constexpr (BDIRECT) compute_slab_direct();
+        else compute_slab(t);
         if (++tap == a.taps) {
             tap = 0;
             ++cc;
