@@ -13,8 +13,8 @@
 // pixels are RH consecutive rows (of the N*Ho stacked output rows) x TW columns; the
 // input patch they need, (rows + R-1) x (TW + S-1) pixels x 64 channels, is staged in LDS
 // once per 64-channel chunk and every tap reads it at a shifted offset (implicit GEMM with
-// halo reuse).  Weights stream through LDS one (tap, chunk) slab at a time, double
-// buffered: the next slab's global loads are in flight while the current one feeds the MFMAs.
+// halo reuse).  Weights are packed one (chunk, tap) slab after the other and are read from
+// global memory / L2 straight into MFMA operand registers, half a slab ahead of their use.
 // Layers with very few input channels (the first VGG16 layer, Cin = 3) use the "flat"
 // variant: the whole R*S*Cin window is one K <= 64 slab gathered per output pixel.
 #include <algorithm>
@@ -118,13 +118,13 @@ static void choose_swizzle(int pw, int tw, int rh, int R, int S, int *pitch_px, 
 }
 
 // LDS: tables (3*ntab + 2*BM ints, 3*bn ints of channel constants), staged patch (one plane per
-// limb), two weight slabs
+// limb); the flat variant also parks the raw patch (at most 8 KB)
 static size_t mfma_lds_bytes(int limbs, int pra, int pw, int pitch_px, int bn, int flat)
 {
     const int ntab = std::max(pra * pw, BM);
     const size_t plane = flat ? (size_t)BM * PS : (size_t)pra * pitch_px * PS;
     size_t tables = round_up((size_t)(3 * ntab + 2 * BM) * 4, 16) + (size_t)3 * bn * 4;
-    return tables + (size_t)limbs * plane + (size_t)2 * limbs * bn * PS;
+    return tables + (size_t)limbs * plane + (flat ? (size_t)2 * 64 * PS : 0); // flat: the raw patch
 }
 // LDS budgets tried in turn: three workgroups per CU (160 KB / 3), else two
 constexpr size_t kLdsBudgets[2] = {54400, 80000};
@@ -647,14 +647,6 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     constexpr int WROWS = 32 * MB;            // tile rows per wave
     constexpr int BN = 64 * NB;
     constexpr int NACC = (LIMBS == 2) ? 3 : 1;
-    constexpr int BPL = BN * PS;              // bytes per limb plane of a weight slab
-    constexpr int BSLAB = LIMBS * BPL;        // bytes per weight slab buffer
-    constexpr int BITEMS = LIMBS * BN * 4 / THREADS; // 16-byte pieces of a slab per thread
-    // Weight fragments: through LDS (one slab per barrier, FLAT only) or straight from global
-    // memory / L2 into the MFMA operand registers, one K=32 half ahead of its use.  Without the
-    // per-slab barrier the waves of a workgroup meet only when a new patch is staged.
-    constexpr bool BDIRECT = !FLAT;
-    static_assert(BITEMS >= 1, "a weight slab must give every thread at least one piece");
     extern __shared__ __align__(16) unsigned char smem[];
 
     // XCD-aware work order: consecutive workgroup ids land on the 8 XCDs round-robin, so
@@ -714,56 +706,18 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     }
     build_colterms<BN, THREADS>(a, ntile, ctab);
 
-    // weight slabs: slab t = chunk * taps + tap lives at [chunk][tap][limb][CoutP][64], i.e.
-    // consecutive in memory in the order they are consumed.  A slab goes from global memory
-    // straight into LDS (no registers in between): lane l of a wave fills the 16 bytes at the
-    // wave's destination + 16*l.  A wave owns BITEMS consecutive 1 KB blocks of the buffer (one
-    // destination register, the blocks told apart by the instruction's immediate offset), so its
-    // piece j lands at byte 16 * (wave*BITEMS*64 + j*64 + lane).  The swizzle is applied on the
-    // source side: the thread that fills physical slot q' of a row fetches the row's logical slot
-    // q' ^ key.  The request is issued right after the barrier that frees the target buffer and
-    // is waited for just before the next barrier, one slab of MFMAs later.
+    // Weight slabs: slab t = chunk * taps + tap lives at [chunk][tap][limb][CoutP][64], i.e.
+    // consecutive in memory in the order they are consumed; they never pass through LDS (see
+    // the operand loads below).
     const int nslabs = a.nchunks * a.taps;
     const int s0 = part * nslabs / nparts, s1 = (part + 1) * nslabs / nparts; // this workgroup's slabs
     const size_t slab_bytes = (size_t)LIMBS * a.CoutP * CK;
-    const unsigned char *bsrc;
-    {
-        // a wave's blocks lie in one limb plane, 16 rows (same key, 1 KB of source) apart
-        static_assert((BN * 4) % (BITEMS * 64) == 0, "a wave's blocks must not straddle limb planes");
-        const int i0 = (tid >> 6) * (BITEMS * 64) + (tid & 63);
-        const int lb0 = i0 / (BN * 4), rem0 = i0 - lb0 * (BN * 4);
-        const int slot = (rem0 ^ (rem0 >> 4)) & 3; // physical slot rem0 & 3, key (row >> 2) & 3
-        bsrc = a.wp + ((size_t)ntile * BN + (size_t)lb0 * a.CoutP + (rem0 >> 2)) * CK + slot * 16;
-        bsrc += (size_t)s0 * slab_bytes;
-    }
-    int pf = s0; // index of the next slab to fetch
-    const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);
-    // The fetch is issued on every step, also past the last slab (where it re-reads the last one
-    // into the buffer nobody reads any more): the number of requests in flight is then the same
-    // on every path.
-    auto fetch_slab = [&](int buf) __attribute__((always_inline)) {
-        static_assert(BITEMS == 1 || BITEMS == 2, "one or two 1 KB blocks per wave");
-        auto *dst = (__attribute__((address_space(3))) void *)(Bsm + buf * BSLAB + wave_u * (BITEMS * 1024));
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)bsrc, dst, 16, 0, 0);
-        if constexpr (BITEMS == 2) // the immediate offset moves the source and the destination alike
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)bsrc, dst, 16, 1024, 0);
-        if (pf + 1 < s1) {
-            ++pf;
-            bsrc += slab_bytes;
-        }
-    };
-    // every outstanding request (the slab about to be read) has landed, then the barrier
-    auto slab_barrier = [&]() __attribute__((always_inline)) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-    };
-    if constexpr (!BDIRECT) fetch_slab(s0 & 1);
     __syncthreads(); // the tables are complete
 
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WMC, wn = wave / WMC;
     const int l32 = lane & 31, kg = lane >> 5;
-    int aoff[MB], apr[MB], apc[MB], boff[NB];
+    int aoff[MB], apr[MB], apc[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         const int row = wm * WROWS + mb * 32 + l32;
@@ -771,9 +725,6 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         apr[mb] = FLAT ? 0 : abase_s[row] / a.PW;               // its patch row and column
         apc[mb] = FLAT ? 0 : abase_s[row] % a.PW;
     }
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) boff[nb] = swz((wn * (NB * 32) + nb * 32 + l32) * PS, kg);
-
     v16i acc[MB][NB][NACC]; // zeroed after the first patch is staged: until then its registers are free
 
     // Activations travel global -> registers -> LDS in batches of APF 16-byte pieces per thread,
@@ -849,7 +800,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     // buffer, then each tile row's window is gathered from there, 16 consecutive k per piece.
     auto stage_flat = [&]() __attribute__((always_inline)) {
         const int16_t *x = (const int16_t *)a.x;
-        int16_t *raw = (int16_t *)(Bsm + BSLAB);
+        int16_t *raw = (int16_t *)Bsm; // own LDS region behind the gathered windows
         const int nraw = NPIXA * a.Cin;
         for (int i = tid; i < nraw; i += THREADS) {
             const int p = i / a.Cin, ci = i - p * a.Cin;
@@ -885,10 +836,8 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             *(v4i *)(Asm + APL + swz(row * PS, k0 >> 4)) = vl;
         }
     };
-    constexpr bool EARLY = false;
-    const int early_tap = a.taps - 1;
     constexpr int DEEP = 8;
-    auto stage_activations = [&](int cc, bool have_first, bool deep) __attribute__((always_inline)) {
+    auto stage_activations = [&](int cc, bool deep) __attribute__((always_inline)) {
         if constexpr (FLAT) {
             stage_flat();
         } else {
@@ -908,7 +857,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
                 first = DEEP * THREADS;
                 if (first >= total) return;
             }
-            if (!have_first) load_act(cc, first, aregA);
+            load_act(cc, first, aregA);
             for (; first < total; first += 2 * APF * THREADS) {
                 load_act(cc, first + APF * THREADS, aregB);
                 store_act(first, aregA);
@@ -921,58 +870,9 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     int cc = s0 / a.taps, tap = s0 % a.taps;
     int tap_r = FLAT ? 0 : tap / a.S, tap_s = FLAT ? 0 : tap % a.S;
     int taprow = tap_r * a.PITCH, tapoff = taprow + tap_s * PS;
-    auto compute_slab = [&](int t) __attribute__((always_inline)) {
-        const unsigned char *Bcur = Bsm + (t & 1) * BSLAB;
-        int afrag[MB]; // this tap's pixel per row block, slot kg; the second K=32 step is slot kg+2
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            if constexpr (FLAT) afrag[mb] = swz(aoff[mb], kg);
-            else {
-                const int pix = aoff[mb] + tapoff;
-                const int key = a.KMUL == 4 ? pix >> 8 : ((apc[mb] + tap_s) >> 2) + a.KMUL * (apr[mb] + tap_r);
-                afrag[mb] = swzk(pix, kg, key);
-            }
-        }
-#pragma unroll
-        for (int k32 = 0; k32 < 2; ++k32) {
-            if (k32 < a.ksteps) {
-                v4i ah[MB], al[MB], bh[NB], bl[NB];
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    ah[mb] = *(const v4i *)(Asm + (afrag[mb] ^ (k32 * 32)));
-                    if constexpr (LIMBS == 2) al[mb] = *(const v4i *)(Asm + APL + (afrag[mb] ^ (k32 * 32)));
-                }
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    bh[nb] = *(const v4i *)(Bcur + (boff[nb] ^ (k32 * 32)));
-                    if constexpr (LIMBS == 2) bl[nb] = *(const v4i *)(Bcur + BPL + (boff[nb] ^ (k32 * 32)));
-                }
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        // weights are the row operand: a lane ends up with one pixel's channels
-                        acc[mb][nb][0] = mfma_i8(bh[nb], ah[mb], acc[mb][nb][0]);
-                        if constexpr (LIMBS == 2) {
-                            acc[mb][nb][1] = mfma_i8(bl[nb], ah[mb], acc[mb][nb][1]);
-                            acc[mb][nb][2] = mfma_i8(bl[nb], al[mb], acc[mb][nb][2]);
-                        }
-                    }
-                if constexpr (LIMBS == 2) {
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                        for (int nb = 0; nb < NB; ++nb)
-                            acc[mb][nb][1] = mfma_i8(bh[nb], al[mb], acc[mb][nb][1]);
-                }
-            }
-            // keep the second half's fragment loads behind the first half's MFMAs: both sets
-            // live at once would cost 24 more registers than three waves per SIMD leave
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-
-    // Direct variant: a lane's B operand for (slab, K half, limb, column block) is the 16 bytes at
+    // Weights go straight from global memory / L2 into the MFMA operand registers, one K=32 half
+    // ahead of their use; with no slab to publish, the waves of a workgroup meet only when a new
+    // patch is staged.  A lane's B operand for (slab, K half, limb, column block) is the 16 bytes at
     // row (column block + lane % 32), byte 32*half + 16*(lane / 32) of the packed slab.  Two
     // register sets alternate: X feeds the first half of a slab while Y (second half) is on its
     // way, then Y feeds the second half while X is refilled from the next slab.
@@ -1011,30 +911,33 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
                 for (int nb = 0; nb < NB; ++nb) acc[mb][nb][1] = mfma_i8(bh[nb], al[mb], acc[mb][nb][1]);
         }
     };
-    auto compute_slab_direct = [&]() __attribute__((always_inline)) {
-        int afrag[MB];
+    auto compute_slab = [&]() __attribute__((always_inline)) {
+        int afrag[MB]; // this tap's pixel per row block, slot kg; the second K=32 half is slot kg+2
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            const int pix = aoff[mb] + tapoff;
-            const int key = a.KMUL == 4 ? pix >> 8 : ((apc[mb] + tap_s) >> 2) + a.KMUL * (apr[mb] + tap_r);
-            afrag[mb] = swzk(pix, kg, key);
+            if constexpr (FLAT) afrag[mb] = swz(aoff[mb], kg);
+            else {
+                const int pix = aoff[mb] + tapoff;
+                const int key = a.KMUL == 4 ? pix >> 8 : ((apc[mb] + tap_s) >> 2) + a.KMUL * (apr[mb] + tap_r);
+                afrag[mb] = swzk(pix, kg, key);
+            }
         }
         bload(bp + 32, byh, byl);
         mfma_half(0, afrag, bxh, bxl);
+        // keep the second half's fragment loads behind the first half's MFMAs: both sets live
+        // at once would cost more registers than three waves per SIMD leave
         __builtin_amdgcn_sched_barrier(0);
         if (bt + 1 < s1) { // past the last slab the last one is read again (and never used)
             ++bt;
             bp += slab_bytes;
         }
         bload(bp, bxh, bxl);
-        mfma_half(1, afrag, byh, byl);
+        if (a.ksteps > 1) mfma_half(1, afrag, byh, byl); // a flat window of K <= 32 has one half
         __builtin_amdgcn_sched_barrier(0);
     };
-    if constexpr (BDIRECT) bload(bp, bxh, bxl);
+    bload(bp, bxh, bxl);
 
-    // Pipeline (LDS variant): slab t+1 is requested into the other LDS buffer while the MFMAs of
-    // slab t run, so one barrier per slab suffices.
-    stage_activations(cc, false, true);
+    stage_activations(cc, true);
     own_sums = true; // every later chunk starts at its first tap
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
@@ -1047,20 +950,10 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     auto step = [&](int t) __attribute__((always_inline)) {
         if (tap == 0 && t != s0) {
             __syncthreads(); // all reads of the previous chunk's activations are done
-            stage_activations(cc, EARLY, false);
+            stage_activations(cc, false);
         }
-        if constexpr (BDIRECT) {
-            if (tap == 0 || t == s0) __syncthreads(); // the freshly staged patch is visible
-        } else {
-            slab_barrier(); // slab t (and a freshly staged patch) visible; slab t-1 fully consumed
-            fetch_slab((t + 1) & 1);
-        }
-        // the next chunk's first batch of activations is requested before the chunk's last slab
-        // is multiplied and waits in registers; issued after the slab fetch, so that no slab
-        // wait in between forces it to complete early (loads return in order)
-        if (EARLY && tap == early_tap && cc + 1 < a.nchunks) load_act(cc + 1, 0, aregA);
-        if constexpr (BDIRECT) compute_slab_direct();
-        else compute_slab(t);
+        if (tap == 0 || t == s0) __syncthreads(); // the freshly staged patch is visible
+        compute_slab();
         if (++tap == a.taps) {
             tap = 0;
             ++cc;
