@@ -55,8 +55,13 @@ typedef enum {
 } lp_status;
 
 /* stride-s convolution with zero padding `pad` on all four sides;
- * output is N x Ho x Wo x Cout, Ho = (H + 2*pad - R)/stride + 1. */
-typedef struct { int32_t N, H, W, Cin, Cout, R, S, stride, pad; } lp_conv_desc;
+ * output is N x Ho x Wo x Cout, Ho = (H + 2*pad - R)/stride + 1.
+ * pool (0 or 1, may be left out of an initialiser): 1 asks lp_conv_fwd to apply the 2x2 /
+ * stride-2 max-pool that follows the layer ("Pooling" column of Table 1) before storing, so
+ * that y is N x Ho/2 x Wo/2 x Cout and the unpooled codes never reach memory.  Offered only
+ * where the tiling allows it at no loss (else LP_EUNSUPPORTED from every call that takes
+ * the descriptor: run the layer with pool = 0 and lp_maxpool2x2 instead). */
+typedef struct { int32_t N, H, W, Cin, Cout, R, S, stride, pad, pool; } lp_conv_desc;
 
 const char *lp_status_string(lp_status s);
 
@@ -162,12 +167,16 @@ lp_status lp_conv_workspace_bytes(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw,
  *   bias_codes_dev nullable; Cout codes in format qb (int8/int16 by qb.n), qb.f <= f_acc
  *   acc_out_dev   nullable; receives the raw int64 accumulators, N x Ho x Wo x Cout
  *   y_codes_dev   nullable; receives lp_act(acc) in format qy (see lp_act), same shape
- *   zero_count_dev nullable; += zeros among the y codes written; needs workspace_dev
+ *                 (d->pool: the 2x2 maxima of those codes, N x Ho/2 x Wo/2 x Cout)
+ *   zero_count_dev nullable; += zeros among the y codes (d->pool: among the codes before
+ *                 pooling, i.e. the layer's activation sparsity); needs workspace_dev
  *   workspace_dev nullable unless zero_count_dev is given; 16-byte aligned and at least
  *                 lp_conv_workspace_bytes long, else LP_EWORKSPACE
  * At least one of acc_out_dev / y_codes_dev must be given.
  * LP_EUNSUPPORTED: R*S*Cin >= 65536 with 16-bit operands (int32 limb sums
- * could overflow), tensors with 2^31 or more elements.
+ * could overflow), tensors with 2^31 or more elements; d->pool outside its conditions
+ * (16-bit codes out, ReLU, round-half-away, no acc_out_dev, even Ho and Wo, a tile
+ * geometry of even rows and columns as good as the unconstrained one).
  */
 lp_status lp_conv_fwd(const lp_conv_desc *d, const void *x_codes_dev, lp_qfmt qx,
                       const void *w_packed_dev, lp_qfmt qw, const void *bias_codes_dev, lp_qfmt qb,

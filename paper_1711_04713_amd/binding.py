@@ -42,7 +42,7 @@ class PlanInfo(ctypes.Structure):
 
 
 class ConvDesc(ctypes.Structure):
-    _fields_ = [(k, ctypes.c_int32) for k in ("N", "H", "W", "Cin", "Cout", "R", "S", "stride", "pad")]
+    _fields_ = [(k, ctypes.c_int32) for k in ("N", "H", "W", "Cin", "Cout", "R", "S", "stride", "pad", "pool")]
 
 
 _SIGNATURES = {

@@ -38,6 +38,7 @@ enum { PATH_DIRECT = 0, PATH_MFMA = 1 };
 
 struct Plan {
     int path;
+    int pool;    // the epilogue stores 2x2 maxima instead of the codes
     int limbs;   // 1: int8 x int8, 2: 16-bit x 16-bit
     int flat;    // whole window gathered as one K <= 64 slab (tiny Cin)
     int taps, ksteps; // slabs per chunk, K=32 MFMA steps per slab
@@ -69,7 +70,7 @@ static bool desc_ok(const lp_conv_desc *d)
 {
     return d && d->N > 0 && d->H > 0 && d->W > 0 && d->Cin > 0 && d->Cout > 0 && d->R > 0 &&
            d->S > 0 && d->stride > 0 && d->pad >= 0 && d->H + 2 * d->pad >= d->R &&
-           d->W + 2 * d->pad >= d->S;
+           d->W + 2 * d->pad >= d->S && (d->pool == 0 || d->pool == 1);
 }
 
 // LDS layout of staged pixels and weight rows: 64 bytes each, no padding; the four 16-byte
@@ -117,13 +118,13 @@ static void choose_swizzle(int pw, int tw, int rh, int R, int S, int *pitch_px, 
         }
 }
 
-// LDS: tables (3*ntab + 2*BM ints, 3*bn ints of channel constants), staged patch (one plane per
+// LDS: tables (3*ntab + 2*BM ints, 3*bn ints of channel constants, BM pooled offsets), staged patch (one plane per
 // limb); the flat variant also parks the raw patch (at most 8 KB)
 static size_t mfma_lds_bytes(int limbs, int pra, int pw, int pitch_px, int bn, int flat)
 {
     const int ntab = std::max(pra * pw, BM);
     const size_t plane = flat ? (size_t)BM * PS : (size_t)pra * pitch_px * PS;
-    size_t tables = round_up((size_t)(3 * ntab + 2 * BM) * 4, 16) + (size_t)3 * bn * 4;
+    size_t tables = round_up((size_t)(3 * ntab + 2 * BM) * 4, 16) + (size_t)3 * bn * 4 + (size_t)BM * 4;
     return tables + (size_t)limbs * plane + (flat ? (size_t)2 * 64 * PS : 0); // flat: the raw patch
 }
 // LDS budgets tried in turn: three workgroups per CU (160 KB / 3), else two
@@ -164,7 +165,7 @@ struct PlanKey {
     {
         return d.N == o.d.N && d.H == o.d.H && d.W == o.d.W && d.Cin == o.d.Cin && d.Cout == o.d.Cout &&
                d.R == o.d.R && d.S == o.d.S && d.stride == o.d.stride && d.pad == o.d.pad &&
-               x16 == o.x16 && w16 == o.w16;
+               d.pool == o.d.pool && x16 == o.x16 && w16 == o.w16;
     }
 };
 static std::mutex g_plan_mutex;
@@ -217,11 +218,16 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
     p.flat = (!chunked && x16 && K <= 64) ? 1 : 0;
     if (d->stride == 1 && (x16 || !w16) && (chunked || p.flat)) {
         // tile search: RH x TW <= 128 output pixels, minimise wasted MFMA rows, then patch size
+        // With the pooling fused, a 2x2 window must lie inside one 32-row block of one tile: an
+        // even number of tile rows (tiles then start on even stacked rows, and with Ho even a
+        // row pair never straddles two images) and a width that divides 16.  Such a geometry is
+        // taken only if it costs no more than 3 % over the best unconstrained one.
         const int RS = d->R * d->S;
-        double best = 1e300;
+        double best = 1e300, best_free = 1e300;
         for (int pass = 0; pass < 2 && best == 1e300; ++pass)
         for (int tw = 1; tw <= std::min(p.Wo, BM); ++tw)
             for (int rh = std::min(BM / tw, p.FR); rh >= 1; --rh) {
+                const bool poolable = (tw == 2 || tw == 4 || tw == 8 || tw == 16) && rh % 2 == 0;
                 const int tiles_c = (p.Wo + tw - 1) / tw, tiles_r = (p.FR + rh - 1) / rh;
                 const int pw = tw + d->S - 1;
                 // patch rows: the tile's rows, the R-1 halo, and R-1 more per image boundary
@@ -230,8 +236,10 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
                 const int pra = rh + d->R - 1 + cross * (d->R - 1);
                 const int npixa = pra * pw;
                 if (mfma_lds_bytes(p.limbs, pra, pw, d->S == 1 ? pw : pw + 3, p.limbs == 2 ? 64 : 128, p.flat) > kLdsBudgets[pass]) continue;
-                if (p.flat && (size_t)npixa * d->Cin * 2 > (size_t)2 * 64 * PS) continue; // raw patch parks in a weight buffer
+                if (p.flat && (size_t)npixa * d->Cin * 2 > (size_t)2 * 64 * PS) continue; // the raw patch has 8 KB of LDS
                 const double cost = (double)tiles_c * tiles_r * ((double)BM * RS + 0.5 * npixa);
+                best_free = std::min(best_free, cost);
+                if (d->pool && !poolable) continue;
                 if (cost < best) {
                     best = cost;
                     p.RH = rh; p.TW = tw; p.PW = pw; p.PRA = pra; p.NPIXA = npixa;
@@ -239,7 +247,10 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
                 }
             }
         if (best < 1e300) p.path = PATH_MFMA;
+        if (d->pool && (best == 1e300 || best > 1.03 * best_free)) return LP_EUNSUPPORTED;
     }
+    if (d->pool && (p.path != PATH_MFMA || p.Ho % 2 || p.Wo % 2)) return LP_EUNSUPPORTED;
+    p.pool = d->pool;
     if (p.path == PATH_MFMA) {
         p.nchunks = p.flat ? 1 : (d->Cin + CK - 1) / CK;
         p.taps = p.flat ? 1 : d->R * d->S;
@@ -380,6 +391,7 @@ struct ConvArgs {
     unsigned char *partials; // tail tiles' partial accumulators, part_bytes per (tile, part)
     int part_bytes;
     int fast; // 32-bit requantization is exact for this call (see epilogue)
+    int pool; // store the 2x2 maxima of the codes (planner guarantees the tile geometry)
     ActParams act;
 };
 
@@ -496,7 +508,8 @@ __device__ __forceinline__ void build_colterms(const ConvArgs &a, int ntile, int
 // (the same value in every lane).
 template <int LIMBS, int NB, int MB, int THREADS, typename RowSum>
 __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)[MB][NB][LIMBS == 2 ? 3 : 1],
-                                                  RowSum row_sum, const int *outoff, const int *ctab, int ntile)
+                                                  RowSum row_sum, const int *outoff, const int *pooloff,
+                                                  const int *ctab, int ntile)
 {
     constexpr int BN = 64 * NB;
     constexpr int WMC = BM / (32 * MB), WROWS = 32 * MB;
@@ -504,11 +517,12 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
     const int wm = wave % WMC, wn = wave / WMC;
     const int l32 = lane & 31, kg = lane >> 5;
     unsigned nz = 0; // zero codes written by this lane (at most 16 * MB * NB <= 64)
-    int oo[MB], rs[MB];
+    int oo[MB], po[MB], rs[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         const int m = wm * WROWS + mb * 32 + l32;
         oo[mb] = outoff[m];
+        po[mb] = a.pool ? pooloff[m] : -1; // pooled output pixel, at the window's top-left lane only
         rs[mb] = (LIMBS == 2) ? row_sum(m) : 0;
     }
     if (a.fast) {
@@ -549,6 +563,31 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                                 lo16 = C & 65535;
                             }
                             q[e] = requant_relu32<S16>(hi, lo16, s, cmax);
+                        }
+                        if constexpr (Y16) {
+                            if (a.pool) {
+                                // 2x2 maximum across lanes: the horizontal neighbour is the next lane,
+                                // the vertical one sits TW lanes further in the same 32-row block.
+                                // Every lane takes part; only the window's top-left lane stores.
+                                unsigned w0 = (unsigned)q[0] | ((unsigned)q[1] << 16);
+                                unsigned w1 = (unsigned)q[2] | ((unsigned)q[3] << 16);
+                                if (oo[mb] >= 0 && col0 < a.Cout) {
+                                    constexpr unsigned LOW = 0x7fff7fffu;
+                                    nz += __popc(~(((w0 & LOW) + LOW) | w0 | LOW)) + __popc(~(((w1 & LOW) + LOW) | w1 | LOW));
+                                }
+                                auto pkmax = [](unsigned x, unsigned y) __attribute__((always_inline)) {
+                                    return __builtin_bit_cast(unsigned, __builtin_elementwise_max(__builtin_bit_cast(v2s, x),
+                                                                                                  __builtin_bit_cast(v2s, y)));
+                                };
+                                w0 = pkmax(w0, (unsigned)__builtin_amdgcn_mov_dpp((int)w0, 0xB1, 0xF, 0xF, true));
+                                w1 = pkmax(w1, (unsigned)__builtin_amdgcn_mov_dpp((int)w1, 0xB1, 0xF, 0xF, true));
+                                const int below = ((lane + a.TW) & 63) * 4;
+                                w0 = pkmax(w0, (unsigned)__builtin_amdgcn_ds_bpermute(below, (int)w0));
+                                w1 = pkmax(w1, (unsigned)__builtin_amdgcn_ds_bpermute(below, (int)w1));
+                                if (po[mb] >= 0 && col0 < a.Cout)
+                                    *(v2i *)((unsigned char *)a.y + ((size_t)po[mb] * a.Cout + col0) * 2) = (v2i){(int)w0, (int)w1};
+                                continue;
+                            }
                         }
                         if (oo[mb] >= 0 && col0 < a.Cout) {
                             unsigned char *dst = (unsigned char *)a.y + ((size_t)oo[mb] * a.Cout + col0) * ESZ;
@@ -679,7 +718,8 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     int *outoff = apos + a.NTAB;     // tile row -> output pixel index, -1 if not an output
     int *abase_s = outoff + BM;      // tile row -> staged pixel of its (r=0, s=0) tap
     int *ctab = (int *)(smem + (((size_t)(3 * a.NTAB + 2 * BM) * 4 + 15) & ~(size_t)15)); // channel constants
-    unsigned char *Asm = (unsigned char *)(ctab + 3 * BN);
+    int *pooloff = ctab + 3 * BN;    // tile row -> pooled output pixel (top-left rows of 2x2 windows), else -1
+    unsigned char *Asm = (unsigned char *)(pooloff + BM);
     const int APL = a.APLANE;        // bytes per limb plane of the staged activations
     unsigned char *Bsm = Asm + (size_t)LIMBS * APL;
 
@@ -701,8 +741,10 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         const int j = m / a.TW, t = m % a.TW;
         const int fr = fr0 + j, xo = x0 + t;
         const bool ok = j < a.RH && fr < a.FR && xo < a.Wo;
+        const int img = fr / a.Ho, yo = fr % a.Ho;
         outoff[m] = ok ? fr * a.Wo + xo : -1;
-        abase_s[m] = ok ? ((fr / a.Ho) * a.Hp + fr % a.Ho - vr0) * a.PW + t : 0;
+        abase_s[m] = ok ? (img * a.Hp + yo - vr0) * a.PW + t : 0;
+        pooloff[m] = (a.pool && ok && !(j & 1) && !(t & 1)) ? (img * (a.Ho >> 1) + (yo >> 1)) * (a.Wo >> 1) + (xo >> 1) : -1;
     }
     build_colterms<BN, THREADS>(a, ntile, ctab);
 
@@ -1014,7 +1056,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         return;
     }
 
-    unsigned zeros = tile_epilogue<LIMBS, NB, MB, THREADS>(a, acc, row_sum, outoff, ctab, ntile);
+    unsigned zeros = tile_epilogue<LIMBS, NB, MB, THREADS>(a, acc, row_sum, outoff, pooloff, ctab, ntile);
     // one count per workgroup, no atomics: thousands of same-address atomics would serialise
     if (a.zero_partial) {
         if (lane == 0) tab[wave] = (int)zeros; // tab[] was last read while staging
@@ -1039,6 +1081,7 @@ __global__ __launch_bounds__(256) void conv_finish_kernel(const ConvArgs a, int 
     constexpr int NACC = (LIMBS == 2) ? 3 : 1;
     __shared__ int outoff[BM];
     __shared__ int rowsum[BM];
+    __shared__ int pooloff[BM];
     __shared__ __align__(16) int ctab[3 * BN];
     __shared__ unsigned wave_zeros[THREADS / 64];
     const int tid = threadIdx.x;
@@ -1053,7 +1096,10 @@ __global__ __launch_bounds__(256) void conv_finish_kernel(const ConvArgs a, int 
         for (int m = tid; m < BM; m += THREADS) {
             const int j = m / a.TW, t = m % a.TW;
             const int fr = fr0 + j, xo = x0 + t;
-            outoff[m] = (j < a.RH && fr < a.FR && xo < a.Wo) ? fr * a.Wo + xo : -1;
+            const bool ok = j < a.RH && fr < a.FR && xo < a.Wo;
+            outoff[m] = ok ? fr * a.Wo + xo : -1;
+            pooloff[m] = (a.pool && ok && !(j & 1) && !(t & 1))
+                             ? ((fr / a.Ho) * (a.Ho >> 1) + ((fr % a.Ho) >> 1)) * (a.Wo >> 1) + (xo >> 1) : -1;
             rowsum[m] = 0;
         }
         build_colterms<BN, THREADS>(a, ntile, ctab);
@@ -1089,7 +1135,7 @@ __global__ __launch_bounds__(256) void conv_finish_kernel(const ConvArgs a, int 
         }
         __syncthreads();
         const unsigned zeros = tile_epilogue<LIMBS, NB, MB, THREADS>(
-            a, acc, [&](int m) { return rowsum[m]; }, outoff, ctab, ntile);
+            a, acc, [&](int m) { return rowsum[m]; }, outoff, pooloff, ctab, ntile);
         if ((tid & 63) == 0) wave_zeros[tid >> 6] = zeros;
         __syncthreads();
         if (tid == 0)
@@ -1226,6 +1272,8 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     const long long K = (long long)d->R * d->S * d->Cin;
     a.fast = (y && !acc_out && relu && r == LP_ROUND_NEAREST_AWAY && a.act.s >= 1 && a.act.s <= 31 &&
               K <= 8192 && (!bias || a.bias_shift <= 24)) ? 1 : 0;
+    a.pool = p.pool;
+    if (p.pool && !(a.fast && a.y16 && d->Cout % 4 == 0)) return LP_EUNSUPPORTED;
     lp_status st2;
     const int tails = a.split > 1 ? kXCDs * (p.per_xcd - p.full_per_xcd) : 0; // finishing workgroups
     if (p.flat) st2 = launch_mfma<2, 1, true, 2>(a, p, grid, tails, hs);

@@ -17,8 +17,11 @@ class ConvStack:
     """
 
     def __init__(self, weights, pool_after, n_act=16, n_w=16, loss_threshold=0.0, r=lp.LP_ROUND_NEAREST_AWAY,
-                 pad=1):
+                 pad=1, fuse_pool=True):
+        """fuse_pool: let lp_conv_fwd store the 2x2 maxima directly where its tiling allows it
+        (the unpooled codes of such a layer are then never written; layer["y"] is None)."""
         assert len(weights) == len(pool_after)
+        self.fuse_pool = fuse_pool
         self.n_act, self.n_w, self.thr, self.r, self.pad = n_act, n_w, loss_threshold, r, pad
         self.pool_after = list(pool_after)
         self.w_float = weights
@@ -35,9 +38,9 @@ class ConvStack:
         self.qy = []          # per-layer output formats
         self.plans = None
 
-    def _desc(self, i, N, H, W):
+    def _desc(self, i, N, H, W, pool=0):
         cout, R, S, cin = self.w_float[i].shape
-        return lp.ConvDesc(N, H, W, cin, cout, R, S, 1, self.pad)
+        return lp.ConvDesc(N, H, W, cin, cout, R, S, 1, self.pad, pool)
 
     def calibrate(self, x_float):
         """Fix the input format and every layer's output format from the dynamic range seen on
@@ -83,15 +86,24 @@ class ConvStack:
         q_in = self.qx
         for i, pool in enumerate(self.pool_after):
             d = self._desc(i, N, H, W)
+            fused = False
+            if pool and self.fuse_pool and self.n_act > 8:
+                try:                      # status 2: this layer's tiling cannot pool for free
+                    lp.lp_conv_plan_info(self._desc(i, N, H, W, 1), q_in, self.qw[i])
+                    d, fused = self._desc(i, N, H, W, 1), True
+                except lp.LpError as e:
+                    if e.status != 2:
+                        raise
             packed = torch.empty(lp.lp_conv_packed_bytes(d, q_in, self.qw[i]), dtype=torch.uint8, device="cuda")
             lp.lp_conv_pack_weights(d, q_in, self.qw[i], self.w_codes[i], packed)
-            y = torch.empty((N, H, W, d.Cout), dtype=dt, device="cuda")
+            y = None if fused else torch.empty((N, H, W, d.Cout), dtype=dt, device="cuda")
             p = None
             if pool:
                 p = torch.empty((N, H // 2, W // 2, d.Cout), dtype=dt, device="cuda")
             ws = torch.empty(max(lp.lp_conv_workspace_bytes(d, q_in, self.qw[i]), 16), dtype=torch.uint8, device="cuda")
             self.layers.append({"desc": d, "packed": packed, "ws": ws, "qx": q_in, "qw": self.qw[i], "qy": self.qy[i], "y": y,
-                                "pooled": p, "H": H, "W": W, "macs": N * H * W * d.Cout * d.R * d.S * d.Cin,
+                                "pooled": p, "fused_pool": fused, "H": H, "W": W, "y_numel": N * H * W * d.Cout,
+                                "macs": N * H * W * d.Cout * d.R * d.S * d.Cin,
                                 "info": lp.lp_conv_plan_info(d, q_in, self.qw[i])})
             if pool:
                 H, W = H // 2, W // 2
@@ -117,11 +129,12 @@ class ConvStack:
         timed("quantize", lambda: lp.lp_quantize(x_float.reshape(-1), self.x_codes, self.qx, self.r))
         cur = self.x_codes
         for i, L in enumerate(self.layers):
-            timed("conv%d" % i, lambda L=L, cur=cur, i=i: lp.lp_conv_fwd(
-                L["desc"], cur, L["qx"], L["packed"], L["qw"], qy=L["qy"], y_codes=L["y"], relu=True, r=self.r,
+            out = L["pooled"] if L["fused_pool"] else L["y"]
+            timed("conv%d" % i, lambda L=L, cur=cur, i=i, out=out: lp.lp_conv_fwd(
+                L["desc"], cur, L["qx"], L["packed"], L["qw"], qy=L["qy"], y_codes=out, relu=True, r=self.r,
                 zero_count=self.zero_counts[i:i + 1], workspace=L["ws"]))
-            cur = L["y"]
-            if L["pooled"] is not None:
+            cur = out
+            if L["pooled"] is not None and not L["fused_pool"]:
                 d = L["desc"]
                 timed("pool%d" % i, lambda L=L, d=d: lp.lp_maxpool2x2(L["y"], L["pooled"], d.N, L["H"], L["W"], d.Cout,
                                                                        self.n_act))

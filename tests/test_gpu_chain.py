@@ -17,8 +17,8 @@ def _nhwc(a):
     return to_dev(np.ascontiguousarray(a.transpose(0, 2, 3, 1)))
 
 
-def _run_stack(x, ws, pools, n_act=16, n_w=16, calib=None):
-    st = ConvStack([_nhwc(w) for w in ws], pools, n_act=n_act, n_w=n_w)
+def _run_stack(x, ws, pools, n_act=16, n_w=16, calib=None, fuse_pool=False):
+    st = ConvStack([_nhwc(w) for w in ws], pools, n_act=n_act, n_w=n_w, fuse_pool=fuse_pool)
     xd = _nhwc(x)
     st.calibrate(xd[:calib] if calib else xd)
     N, H, W, _ = xd.shape
@@ -34,14 +34,15 @@ def _compare(st, out, want, n_images=None):
     for i, (L, G) in enumerate(zip(want["layers"], st.layers)):
         assert st.qw[i].m == L["mw"], "layer %d weight format" % i
         assert st.qy[i].m == L["mo"], "layer %d output format" % i
-        got = G["y"][sl].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2)
-        assert np.array_equal(got, L["codes"]), "layer %d codes" % i
+        if G["y"] is not None:          # a layer with the pooling fused never writes these
+            got = G["y"][sl].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2)
+            assert np.array_equal(got, L["codes"]), "layer %d codes" % i
         if G["pooled"] is not None:
             gp = G["pooled"][sl].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2)
             assert np.array_equal(gp, L["pooled"]), "layer %d pooled codes" % i
         if n_images is None:
             assert int(st.zero_counts[i].item()) == L["zeros"], "layer %d zero count" % i
-        else:  # the counter covers the whole batch: check it against the codes it counted
+        elif G["y"] is not None:  # the counter covers the whole batch: check it against the codes it counted
             assert int(st.zero_counts[i].item()) == int((G["y"] == 0).sum().item())
     assert np.array_equal(out[sl].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2), want["final"])
 
@@ -56,8 +57,11 @@ def test_small_vgg_like_stack_16bit(oracle):
         pools.append(pool)
         cin = cout // 4
     want = ovgg.conv_stack(x, ws, pools, n=16, threads=8)
-    st, out = _run_stack(x, ws, pools)
-    _compare(st, out, want)
+    for fuse in (False, True):
+        st, out = _run_stack(x, ws, pools, fuse_pool=fuse)
+        _compare(st, out, want)
+        if fuse:                                    # at least the wide early layers pool in the epilogue
+            assert any(G["fused_pool"] for G in st.layers)
     for L in want["layers"]:
         assert 0.2 < L["zeros"] / L["count"] < 0.8       # ~half zeros with zero-mean random weights
 
@@ -68,8 +72,10 @@ def test_vgg16_first_two_blocks_full_resolution(oracle):
     ws = lp_inputs.vgg16_conv_weights(seed=2, layers=["conv1_1", "conv1_2", "conv2_1", "conv2_2"])
     pools = [False, True, False, True]
     want = ovgg.conv_stack(x, ws, pools, n=16, threads=16)
-    st, out = _run_stack(x, ws, pools)
-    _compare(st, out, want)
+    for fuse in (False, True):
+        st, out = _run_stack(x, ws, pools, fuse_pool=fuse)
+        _compare(st, out, want)
+        assert [G["fused_pool"] for G in st.layers] == [False, fuse, False, fuse]
 
 
 def test_frozen_formats_from_a_calibration_subset(oracle):

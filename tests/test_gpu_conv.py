@@ -277,3 +277,41 @@ def test_split_reduction_matches_single_workgroup_tiles(oracle, shape):
         assert np.array_equal(acc.cpu().numpy().transpose(0, 3, 1, 2), want_acc)
         if use_ws:
             assert int(z.item()) == want_z
+
+
+@pytest.mark.parametrize("shape", [(2, 16, 16, 64, 64), (3, 16, 24, 32, 40), (1, 8, 32, 16, 128), (5, 4, 4, 64, 64)])
+def test_fused_maxpool_matches_conv_act_pool(oracle, shape):
+    """d.pool = 1: the stored codes are the 2x2 maxima of LPAct(conv) and the zero count is
+    that of the unpooled codes, as if lp_maxpool2x2 had followed."""
+    import torch
+    from gpu_helpers import to_dev
+
+    N, H, W, Cin, Cout = shape
+    rng = np.random.default_rng(23)
+    x, w = _codes(rng, (N, Cin, H, W), zero_frac=0.4), _codes(rng, (Cout, Cin, 3, 3))
+    d = lp.ConvDesc(N, H, W, Cin, Cout, 3, 3, 1, 1, 1)
+    info = lp.lp_conv_plan_info(d, QX, QW)
+    assert info["tile_rows"] % 2 == 0 and info["tile_cols"] in (2, 4, 8, 16)
+    xd = to_dev(x.transpose(0, 2, 3, 1).astype(np.int16))
+    wd = to_dev(w.transpose(0, 2, 3, 1).astype(np.int16))
+    packed = torch.empty(lp.lp_conv_packed_bytes(d, QX, QW), dtype=torch.uint8, device="cuda")
+    lp.lp_conv_pack_weights(d, QX, QW, wd, packed)
+    ws = torch.full((lp.lp_conv_workspace_bytes(d, QX, QW),), 0x3C, dtype=torch.uint8, device="cuda")
+    y = torch.full((N, H // 2, W // 2, Cout), -7, dtype=torch.int16, device="cuda")
+    z = torch.zeros(1, dtype=torch.int64, device="cuda")
+    lp.lp_conv_fwd(d, xd, QX, packed, QW, qy=QY, y_codes=y, zero_count=z, workspace=ws)
+    torch.cuda.synchronize()
+    codes, zeros = oracle.act(oracle.conv(x, w), 27, *QY, True, oracle.ROUND_AWAY)
+    assert np.array_equal(y.cpu().numpy().transpose(0, 3, 1, 2), oracle.maxpool2x2(codes))
+    assert int(z.item()) == zeros
+    # the fused form has conditions: raw accumulators, no ReLU, 8-bit codes and odd sizes are refused
+    acc = torch.empty((N, H, W, Cout), dtype=torch.int64, device="cuda")
+    with pytest.raises(lp.LpError) as e:
+        lp.lp_conv_fwd(d, xd, QX, packed, QW, acc_out=acc, workspace=ws)
+    assert e.value.status == 2
+    with pytest.raises(lp.LpError) as e:
+        lp.lp_conv_fwd(d, xd, QX, packed, QW, qy=QY, y_codes=y, relu=False, workspace=ws)
+    assert e.value.status == 2
+    with pytest.raises(lp.LpError) as e:
+        lp.lp_conv_plan_info(lp.ConvDesc(N, H + 1, W, Cin, Cout, 3, 3, 1, 1, 1), QX, QW)
+    assert e.value.status == 2

@@ -84,20 +84,33 @@ def test_config3_vgg16_stack_batch32(oracle):
     ws = lp_inputs.vgg16_conv_weights(seed=2)
     pools = [p for (*_, p) in lp_inputs.VGG16_CONV]
     cal = ovgg.conv_stack(x[:1], ws, pools, n=16, threads=16)
-    st = ConvStack([to_dev(np.ascontiguousarray(w.transpose(0, 2, 3, 1))) for w in ws], pools)
     xd = to_dev(np.ascontiguousarray(x.transpose(0, 2, 3, 1)))
-    st.calibrate(xd[:1])
-    assert st.qx.m == cal["mx"]
-    st.prepare(B, 224, 224)
-    out = st.forward(xd)
-    torch.cuda.synchronize()
-    for i, (L, G) in enumerate(zip(cal["layers"], st.layers)):
-        assert (st.qw[i].m, st.qy[i].m) == (L["mw"], L["mo"]), "layer %d formats" % i
-        got = G["y"][:1].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2)
-        assert np.array_equal(got, L["codes"]), "layer %d codes of image 0" % i
-        assert int(st.zero_counts[i].item()) == int((G["y"] == 0).sum().item()), "layer %d zero count" % i
-        assert 0.3 < int(st.zero_counts[i].item()) / G["y"].numel() < 0.8
-    assert np.array_equal(out[:1].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2), cal["final"])
+    counts = {}
+    for fuse in (False, True):         # separate pooling kernels, then the benchmark's fused launches
+        st = ConvStack([to_dev(np.ascontiguousarray(w.transpose(0, 2, 3, 1))) for w in ws], pools, fuse_pool=fuse)
+        st.calibrate(xd[:1])
+        assert st.qx.m == cal["mx"]
+        st.prepare(B, 224, 224)
+        out = st.forward(xd)
+        torch.cuda.synchronize()
+        for i, (L, G) in enumerate(zip(cal["layers"], st.layers)):
+            assert (st.qw[i].m, st.qy[i].m) == (L["mw"], L["mo"]), "layer %d formats" % i
+            if G["y"] is not None:
+                got = G["y"][:1].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2)
+                assert np.array_equal(got, L["codes"]), "layer %d codes of image 0" % i
+                assert int(st.zero_counts[i].item()) == int((G["y"] == 0).sum().item()), "layer %d zero count" % i
+            if G["pooled"] is not None:
+                gp = G["pooled"][:1].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2)
+                assert np.array_equal(gp, L["pooled"]), "layer %d pooled codes of image 0" % i
+            assert 0.3 < int(st.zero_counts[i].item()) / G["y_numel"] < 0.8
+        assert np.array_equal(out[:1].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2), cal["final"])
+        counts[fuse] = st.zero_counts.cpu().numpy().copy()
+        final = out.clone() if not fuse else final
+        if fuse:
+            assert sum(G["fused_pool"] for G in st.layers) >= 3
+            assert torch.equal(out, final)            # the whole batch, not only image 0
+        del st
+    assert np.array_equal(counts[False], counts[True])
 
 
 @pytest.mark.parametrize("index", [0, 1, 3, 4, 6, 8])
