@@ -841,39 +841,56 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     // FLAT: the raw patch (all Cin channels, int16) is parked in the unused second weight
     // buffer, then each tile row's window is gathered from there, 16 consecutive k per piece.
     auto stage_flat = [&]() __attribute__((always_inline)) {
-        const int16_t *x = (const int16_t *)a.x;
         int16_t *raw = (int16_t *)Bsm; // own LDS region behind the gathered windows
         const int nraw = NPIXA * a.Cin;
-        for (int i = tid; i < nraw; i += THREADS) {
-            const int p = i / a.Cin, ci = i - p * a.Cin;
-            const int g = tab[p];
-            raw[i] = g >= 0 ? x[(size_t)g * a.Cin + ci] : (int16_t)0;
+        // raw patch: four codes per thread requested together, pixels outside the image read as 0
+        constexpr int RU = 4;
+        for (int i0 = tid; i0 < nraw; i0 += RU * THREADS) {
+            short v[RU];
+#pragma unroll
+            for (int u = 0; u < RU; ++u) {
+                const int i = min(i0 + u * THREADS, nraw - 1);
+                const int p = i / a.Cin, ci = i - p * a.Cin;
+                const int g = tab[p];
+                const unsigned off = g >= 0 ? (unsigned)(g * a.Cin + ci) * 2u : 0xffffffffu;
+                v[u] = (short)__builtin_amdgcn_raw_buffer_load_b16(xrsrc, (int)off, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < RU; ++u)
+                if (i0 + u * THREADS < nraw) raw[i0 + u * THREADS] = v[u];
         }
         __syncthreads();
-        const int SC = a.S * a.Cin;
-        for (int i = tid; i < BM * 4; i += THREADS) {
-            const int row = i >> 2, k0 = (i & 3) * 16;
-            const int base = abase_s[row];
-            int r = k0 / SC, rem = k0 - r * SC;
-            int s = rem / a.Cin, ci = rem - s * a.Cin;
+        // Window k of a tile row = (r, s, ci) with k = (r*S + s)*Cin + ci: inside one window row
+        // the S*Cin codes are consecutive in the raw patch, and the next window row starts
+        // PW*Cin further.  A thread gathers 16 consecutive k; only the K halves the MFMAs will
+        // read (32 * ksteps of the 64 slab bytes) are built.
+        const int SC = a.S * a.Cin, jump = (a.PW - a.S) * a.Cin;
+        const int pieces = BM * 2 * a.ksteps;
+        for (int i = tid; i < pieces; i += THREADS) {
+            const int row = i >> a.ksteps, k0 = (i & (2 * a.ksteps - 1)) * 16; // 2 * ksteps is 2 or 4
+            const int r0 = k0 / SC;
+            int cnt = k0 - r0 * SC;                                      // position inside the window row
+            int idx = abase_s[row] * a.Cin + r0 * (a.PW * a.Cin) + cnt;  // raw index of window element k0
             unsigned hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
             int sum = 0;
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
-                if (k0 + j < a.Kflat) {
-                    const int val = (int)raw[(base + r * a.PW + s) * a.Cin + ci];
-                    sum += val;
-                    hi[j >> 2] |= (unsigned)((val >> 8) & 255) << (8 * (j & 3));
-                    lo[j >> 2] |= (unsigned)((val & 255) ^ 128) << (8 * (j & 3));
-                    if (++ci == a.Cin) {
-                        ci = 0;
-                        if (++s == a.S) { s = 0; ++r; }
-                    }
+                const int val = (k0 + j < a.Kflat) ? (int)raw[min(idx, nraw - 1)] : 0;
+                sum += val;
+                hi[j >> 2] |= (unsigned)((val >> 8) & 255) << (8 * (j & 3));
+                lo[j >> 2] |= (unsigned)(val & 255) << (8 * (j & 3));
+                ++idx;
+                if (++cnt == SC) {
+                    cnt = 0;
+                    idx += jump;
                 }
             }
             if (sum) atomicAdd(&psum[row], sum);
+            // low limbs are offset by 128 (code 0, also beyond K, is the byte 0x80: it multiplies
+            // zero weights there)
             const v4i vh = {(int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
-            const v4i vl = {(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3]};
+            const v4i vl = {(int)(lo[0] ^ 0x80808080u), (int)(lo[1] ^ 0x80808080u), (int)(lo[2] ^ 0x80808080u),
+                            (int)(lo[3] ^ 0x80808080u)};
             *(v4i *)(Asm + swz(row * PS, k0 >> 4)) = vh;
             *(v4i *)(Asm + APL + swz(row * PS, k0 >> 4)) = vl;
         }
