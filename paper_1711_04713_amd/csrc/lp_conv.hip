@@ -272,9 +272,11 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
         }
         p.lds_bytes = mfma_lds_bytes(p.limbs, p.PRA, p.PW, p.PITCH / PS, p.BN, p.flat);
         {
-            // workgroup slots per die: three waves per SIMD by registers, and what the LDS holds
+            // workgroup slots per die: what registers and LDS allow
             const int total = p.tiles_m * p.tiles_n, nslabs = p.nchunks * p.taps;
-            const int wg_per_cu = (int)std::max<size_t>(1, std::min<size_t>(3, (160 * 1024) / p.lds_bytes));
+            // (two-limb kernel: three waves per SIMD by registers; one-limb kernels: four)
+            const int wg_per_cu =
+                (int)std::max<size_t>(1, std::min<size_t>(p.limbs == 2 ? 3 : 4, (160 * 1024) / p.lds_bytes));
             const int slots = wg_per_cu * (kCUs / kXCDs);
             p.per_xcd = (total + kXCDs - 1) / kXCDs;
             p.full_per_xcd = p.per_xcd / slots * slots;
@@ -676,7 +678,8 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
 // FLAT: the window is gathered as one slab per output pixel instead of staging a patch.
 template <int LIMBS, int NB, bool FLAT, int MB>
 __global__ __launch_bounds__(MB == 2 ? 256 : 512)
-    __attribute__((amdgpu_waves_per_eu(MB == 2 ? 3 : 4, MB == 2 ? 3 : 4))) void conv_mfma_kernel(const ConvArgs a)
+    __attribute__((amdgpu_waves_per_eu(MB == 2 && LIMBS == 2 ? 3 : 4, MB == 2 && LIMBS == 2 ? 3 : 4))) void conv_mfma_kernel(
+        const ConvArgs a)
 {
     // MB: 32-row blocks per wave.  MB = 2: 4 waves (2 x 2) of 64 rows; MB = 1: 8 waves (4 x 2) of
     // 32 rows, half the accumulators per wave, so a fourth wave fits on each SIMD and every
