@@ -37,6 +37,95 @@ def _traffic_for_current_source():
     return TRAFFIC_RECORD["bytes_per_launch"] if sha == TRAFFIC_RECORD["lp_conv_sha256"] else None
 
 
+def measure_extras(lp, torch, lp_inputs, iters=10):
+    """The other steps of the path, each alone against its own roofline: the HBM-bound elementwise
+    kernels at the size of one 8 x 64 x 224 x 224 activation tensor, the single 64->64 layer at
+    batch 8, the 8-bit conv3_1..conv5_3 layers at batch 64 and the three classifier layers at
+    batch 256 (synthetic codes of the right shapes; parity of these is the tests' job)."""
+    import ctypes
+
+    def timed(fn, n=iters):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    out = {}
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    shape = (8, 224, 224, 64)
+    n = 8 * 224 * 224 * 64
+    xf = torch.randn(shape, device="cuda", generator=g).clamp_(min=0)
+    codes = torch.empty(shape, dtype=torch.int16, device="cuda")
+    q = (16, 4, 12)
+    ms = timed(lambda: lp.lp_quantize(xf.reshape(-1), codes, q))
+    out["lp_quantize"] = {"elements": n, "ms": round(ms, 4), "GBps": round(6 * n / ms / 1e6, 1)}
+    rws = torch.empty(lp.LP_RANGE_WORKSPACE_WORDS, dtype=torch.int64, device="cuda")
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        lp.lp_range(xf.reshape(-1), 16, 0.0, rws)              # returns the format: synchronises
+    ms = (time.perf_counter() - t0) * 1e3 / iters
+    out["lp_range"] = {"elements": n, "ms": round(ms, 4), "GBps": round(4 * n / ms / 1e6, 1), "note": "includes the host round trip"}
+    acc = (torch.randn(shape, device="cuda", generator=g) * (1 << 24)).to(torch.int64)
+    ms = timed(lambda: lp.lp_act(acc.reshape(-1), 27, (16, 6, 10), True, codes))
+    out["lp_act"] = {"elements": n, "ms": round(ms, 4), "GBps": round(10 * n / ms / 1e6, 1)}
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        lp.lp_range_acc(acc.reshape(-1), 27, True, 16, 0.0, rws)
+    ms = (time.perf_counter() - t0) * 1e3 / iters
+    out["lp_range_acc"] = {"elements": n, "ms": round(ms, 4), "GBps": round(8 * n / ms / 1e6, 1), "note": "includes the host round trip"}
+    pooled = torch.empty((8, 112, 112, 64), dtype=torch.int16, device="cuda")
+    ms = timed(lambda: lp.lp_maxpool2x2(codes, pooled, 8, 224, 224, 64, 16))
+    out["lp_maxpool2x2"] = {"elements": n, "ms": round(ms, 4), "GBps": round(2.5 * n / ms / 1e6, 1)}
+    del xf, acc, pooled
+
+    def conv_ms(N, hw, cin, cout, bits):
+        dt = torch.int16 if bits > 8 else torch.int8
+        lim = 2000 if bits > 8 else 60
+        x = torch.randint(0, lim, (N, hw, hw, cin), device="cuda", generator=g).to(dt)
+        w = torch.randint(-lim, lim, (cout, 3, 3, cin), device="cuda", generator=g).to(dt)
+        qx, qw, qy = ((16, 4, 12), (16, 1, 15), (16, 6, 10)) if bits > 8 else ((8, 3, 5), (8, 1, 7), (8, 5, 3))
+        d = lp.ConvDesc(N, hw, hw, cin, cout, 3, 3, 1, 1)
+        packed = torch.empty(lp.lp_conv_packed_bytes(d, qx, qw), dtype=torch.uint8, device="cuda")
+        lp.lp_conv_pack_weights(d, qx, qw, w, packed)
+        y = torch.empty((N, hw, hw, cout), dtype=dt, device="cuda")
+        z = torch.zeros(1, dtype=torch.int64, device="cuda")
+        ws = torch.empty(max(lp.lp_conv_workspace_bytes(d, qx, qw), 16), dtype=torch.uint8, device="cuda")
+        return timed(lambda: lp.lp_conv_fwd(d, x, qx, packed, qw, qy=qy, y_codes=y, zero_count=z, workspace=ws))
+
+    ms = conv_ms(8, 224, 64, 64, 16)
+    macs = 8 * 224 * 224 * 64 * 9 * 64
+    out["conv_64to64_224_batch8_16bit"] = {"ms": round(ms, 4), "int8_tops": round(8 * macs / ms / 1e9, 1)}
+    tot_ms, tot_macs = 0.0, 0
+    for (_, cin, cout, hw, _) in lp_inputs.VGG16_CONV[4:]:
+        tot_ms += conv_ms(64, hw, cin, cout, 8)
+        tot_macs += 64 * hw * hw * cout * 9 * cin
+    out["conv3_1_to_conv5_3_batch64_8bit"] = {"ms": round(tot_ms, 4), "int8_tops": round(2 * tot_macs / tot_ms / 1e9, 1)}
+    M = 256
+    fc = {}
+    for name, K, N in (("fc6", 25088, 4096), ("fc7", 4096, 4096), ("fc8", 4096, 1000)):
+        x = torch.randint(0, 2000, (M, K), device="cuda", generator=g).to(torch.int16)
+        w = torch.randint(-300, 300, (N, K), device="cuda", generator=g).to(torch.int16)
+        qx, qw, qy = (16, 4, 12), (16, 1, 15), (16, 8, 8)
+        packed = torch.empty(lp.lp_fc_packed_bytes(M, K, N, qx, qw), dtype=torch.uint8, device="cuda")
+        lp.lp_fc_pack_weights(M, K, N, qx, qw, w, packed)
+        y = torch.empty((M, N), dtype=torch.int16, device="cuda")
+        z = torch.zeros(1, dtype=torch.int64, device="cuda")
+        ws = torch.empty(max(lp.lp_fc_workspace_bytes(M, K, N, qx, qw), 16), dtype=torch.uint8, device="cuda")
+        ms = timed(lambda: lp.lp_fc_fwd(M, K, N, x, qx, packed, qw, qy=qy, y_codes=y, relu=(name != "fc8"),
+                                        zero_count=z, workspace=ws))
+        fc[name] = {"ms": round(ms, 4), "int8_tops": round(8 * M * K * N / ms / 1e9, 1),
+                    "weight_GBps": round(2 * K * N / ms / 1e6, 1)}
+        del x, w, packed
+    out["fc_batch256_16bit"] = fc
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -45,6 +134,7 @@ def main():
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--calib", type=int, default=2, help="images used to fix the per-layer formats")
     ap.add_argument("--cpu-images", type=int, default=2, help="images the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the per-kernel measurements of the other path steps")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (calibrates FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -181,6 +271,8 @@ def main():
             "seconds": round(cpu_s, 2),
             "matches_gpu_final_codes": bool(np.array_equal(got, ref["final"])),
         }
+    if not args.no_extras:
+        out["extras"] = measure_extras(lp, torch, lp_inputs)
     print(json.dumps(out))
 
 

@@ -1,6 +1,8 @@
 // HBM-bound kernels of the low-precision forward pass: quantize, dynamic-range
 // histogram, standalone LPAct, 2x2 max-pool.  Each thread moves 16-byte vectors;
 // counters use the wave ballot (a v_cmp result) + popcount and one atomic per wave.
+#include <algorithm>
+
 #include "lp_device.h"
 
 namespace lp {
@@ -169,16 +171,38 @@ __device__ __forceinline__ int bucket_i64(int64_t a, int f_acc, int relu)
     return b > 17 ? 17 : b;
 }
 
+// Column sums of a block's histogram, then one global atomic per non-empty bucket and block
+// (the launch keeps the number of blocks small: thousands of atomics on 17 addresses would
+// cost more than reading the tensor).
 __device__ __forceinline__ void flush_hist(unsigned *h, unsigned long long *hist_out)
 {
+    __shared__ unsigned long long part_sum[(kBuckets - 1) * 8];
     __syncthreads();
     const int t = threadIdx.x;
     if (t < (kBuckets - 1) * 8) {
         const int b = 1 + t / 8, part = t % 8;
         unsigned long long sum = 0;
         for (int i = 0; i < kThreads / 8; ++i) sum += h[b * kThreads + part * (kThreads / 8) + i];
-        if (sum) atomicAdd(&hist_out[b], sum);
+        part_sum[t] = sum;
     }
+    __syncthreads();
+    if (t < kBuckets - 1) {
+        unsigned long long sum = 0;
+        for (int i = 0; i < 8; ++i) sum += part_sum[t * 8 + i];
+        if (sum) atomicAdd(&hist_out[1 + t], sum);
+    }
+}
+
+// one LDS add without return value per element: nothing to wait for
+__device__ __forceinline__ void count_in(unsigned *h, int bucket)
+{
+    __hip_atomic_fetch_add(&h[bucket * kThreads + threadIdx.x], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+static int range_grid(size_t groups)
+{
+    size_t blocks = (groups + kThreads - 1) / kThreads;
+    return (int)std::min<size_t>(std::max<size_t>(blocks, 1), 256 * 3); // grid-stride beyond three blocks per CU
 }
 
 __global__ __launch_bounds__(kThreads) void range_f32_kernel(const float *__restrict__ x, size_t count,
@@ -191,14 +215,14 @@ __global__ __launch_bounds__(kThreads) void range_f32_kernel(const float *__rest
     for (size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x; g < groups;
          g += (size_t)gridDim.x * kThreads) {
         const v4f a = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(x) + g);
-        h[bucket_f32(a.x) * kThreads + threadIdx.x] += 1;
-        h[bucket_f32(a.y) * kThreads + threadIdx.x] += 1;
-        h[bucket_f32(a.z) * kThreads + threadIdx.x] += 1;
-        h[bucket_f32(a.w) * kThreads + threadIdx.x] += 1;
+        count_in(h, bucket_f32(a.x));
+        count_in(h, bucket_f32(a.y));
+        count_in(h, bucket_f32(a.z));
+        count_in(h, bucket_f32(a.w));
     }
     if (blockIdx.x == 0 && threadIdx.x < 4) {
         const size_t i = groups * 4 + threadIdx.x;
-        if (i < count) h[bucket_f32(x[i]) * kThreads + threadIdx.x] += 1;
+        if (i < count) count_in(h, bucket_f32(x[i]));
     }
     flush_hist(h, hist_out);
 }
@@ -215,11 +239,10 @@ __global__ __launch_bounds__(kThreads) void range_i64_kernel(const int64_t *__re
         const v4i a = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(acc) + g);
         const int64_t a0 = (int64_t)(((uint64_t)(uint32_t)a.y << 32) | (uint32_t)a.x);
         const int64_t a1 = (int64_t)(((uint64_t)(uint32_t)a.w << 32) | (uint32_t)a.z);
-        h[bucket_i64(a0, f_acc, relu) * kThreads + threadIdx.x] += 1;
-        h[bucket_i64(a1, f_acc, relu) * kThreads + threadIdx.x] += 1;
+        count_in(h, bucket_i64(a0, f_acc, relu));
+        count_in(h, bucket_i64(a1, f_acc, relu));
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0 && (count & 1))
-        h[bucket_i64(acc[count - 1], f_acc, relu) * kThreads] += 1;
+    if (blockIdx.x == 0 && threadIdx.x == 0 && (count & 1)) count_in(h, bucket_i64(acc[count - 1], f_acc, relu));
     flush_hist(h, hist_out);
 }
 
@@ -390,7 +413,7 @@ extern "C" lp_status lp_range(const float *x_dev, size_t count, int n, double lo
     unsigned long long *hist = (unsigned long long *)workspace_dev;
     hipLaunchKernelGGL(clear_words_kernel, dim3(1), dim3(64), 0, st, hist, LP_RANGE_WORKSPACE_WORDS);
     if (count)
-        hipLaunchKernelGGL(range_f32_kernel, dim3(grid_for(count / 4)), dim3(kThreads), 0, st, x_dev,
+        hipLaunchKernelGGL(range_f32_kernel, dim3(range_grid(count / 4)), dim3(kThreads), 0, st, x_dev,
                            count, hist);
     return finish_range(hist, count, n, loss_threshold, out_host, lost_host, st);
 }
@@ -407,7 +430,7 @@ extern "C" lp_status lp_range_acc(const int64_t *acc_dev, size_t count, int f_ac
     unsigned long long *hist = (unsigned long long *)workspace_dev;
     hipLaunchKernelGGL(clear_words_kernel, dim3(1), dim3(64), 0, st, hist, LP_RANGE_WORKSPACE_WORDS);
     if (count)
-        hipLaunchKernelGGL(range_i64_kernel, dim3(grid_for(count / 2)), dim3(kThreads), 0, st,
+        hipLaunchKernelGGL(range_i64_kernel, dim3(range_grid(count / 2)), dim3(kThreads), 0, st,
                            acc_dev, count, f_acc, relu ? 1 : 0, hist);
     return finish_range(hist, count, n, loss_threshold, out_host, lost_host, st);
 }
