@@ -681,9 +681,10 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     __attribute__((amdgpu_waves_per_eu(MB == 2 && LIMBS == 2 ? 3 : 4, MB == 2 && LIMBS == 2 ? 3 : 4))) void conv_mfma_kernel(
         const ConvArgs a)
 {
-    // MB: 32-row blocks per wave.  MB = 2: 4 waves (2 x 2) of 64 rows; MB = 1: 8 waves (4 x 2) of
-    // 32 rows, half the accumulators per wave, so a fourth wave fits on each SIMD and every
-    // per-thread phase (staging, epilogue) is half as long.
+    // MB: 32-row blocks per wave.  MB = 2: 4 waves (2 x 2) of 64 rows, the only form launched.
+    // MB = 1 (8 waves of 32 rows, a fourth wave per SIMD) is kept compilable as a tuning knob: with
+    // the weights read per wave it doubles their traffic and measured 14 % slower even on the
+    // smallest grids.
     constexpr int THREADS = (MB == 2) ? 256 : 512;
     constexpr int WMC = BM / (32 * MB);       // waves along the pixel dimension
     constexpr int WROWS = 32 * MB;            // tile rows per wave
