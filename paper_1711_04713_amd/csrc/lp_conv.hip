@@ -508,10 +508,14 @@ __device__ __forceinline__ void build_colterms(const ConvArgs &a, int ntile, int
 // row_sum(m): sum of the codes under tile row m's window (two-limb only); outoff and ctab (see
 // build_colterms) are LDS tables, complete and visible.  Returns the wave's count of zero codes
 // (the same value in every lane).
-template <int LIMBS, int NB, int MB, int THREADS, typename RowSum>
-__device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)[MB][NB][LIMBS == 2 ? 3 : 1],
+// The accumulators passed in cover MBL of the wave's MB row blocks, starting at block mb0, and GL
+// of the four channel groups, starting at group g0 (register 4*gl + e = channel 8*(g0+gl) +
+// 4*(lane/32) + e): the main kernel passes everything (MBL = MB, GL = 4, mb0 = g0 = 0), the
+// finishing kernel one (row block, channel group) at a time.
+template <int LIMBS, int NB, int MB, int THREADS, int MBL, int GL, typename RowSum>
+__device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)[MBL][NB][LIMBS == 2 ? 3 : 1],
                                                   RowSum row_sum, const int *outoff, const int *pooloff,
-                                                  const int *ctab, int ntile)
+                                                  const int *ctab, int ntile, int mb0, int g0)
 {
     constexpr int BN = 64 * NB;
     constexpr int WMC = BM / (32 * MB), WROWS = 32 * MB;
@@ -519,10 +523,10 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
     const int wm = wave % WMC, wn = wave / WMC;
     const int l32 = lane & 31, kg = lane >> 5;
     unsigned nz = 0; // zero codes written by this lane (at most 16 * MB * NB <= 64)
-    int oo[MB], po[MB], rs[MB];
+    int oo[MBL], po[MBL], rs[MBL];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-        const int m = wm * WROWS + mb * 32 + l32;
+    for (int mb = 0; mb < MBL; ++mb) {
+        const int m = wm * WROWS + (mb0 + mb) * 32 + l32;
         oo[mb] = outoff[m];
         po[mb] = a.pool ? pooloff[m] : -1; // pooled output pixel, at the window's top-left lane only
         rs[mb] = (LIMBS == 2) ? row_sum(m) : 0;
@@ -540,18 +544,18 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int cl = wn * (NB * 32) + nb * 32 + 8 * g + 4 * kg; // channel within the tile
+                for (int gl = 0; gl < GL; ++gl) {
+                    const int cl = wn * (NB * 32) + nb * 32 + 8 * (g0 + gl) + 4 * kg; // channel within the tile
                     const int col0 = ntile * BN + cl;
                     const v4i cA = *(const v4i *)(ctab + cl);
                     const v4i cB = *(const v4i *)(ctab + BN + cl);
                     const v4i cC = *(const v4i *)(ctab + 2 * BN + cl);
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) {
+                    for (int mb = 0; mb < MBL; ++mb) {
                         int q[4];
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            const int v = 4 * g + e;
+                            const int v = 4 * gl + e;
                             int hi, lo16 = 0;
                             if constexpr (LIMBS == 2) {
                                 const int C = acc[mb][nb][2][v] + cC[e] + ((rs[mb] & 1) << 7);
@@ -637,15 +641,15 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int cl = wn * (NB * 32) + nb * 32 + 8 * g + 4 * kg;
+            for (int gl = 0; gl < GL; ++gl) {
+                const int cl = wn * (NB * 32) + nb * 32 + 8 * (g0 + gl) + 4 * kg;
                 const int col0 = ntile * BN + cl;
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
+                for (int mb = 0; mb < MBL; ++mb) {
                     const int64_t rt = (LIMBS == 2) ? (int64_t)rs[mb] * 128 : 0;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const int v = 4 * g + e;
+                        const int v = 4 * gl + e;
                         int64_t val;
                         if constexpr (LIMBS == 2)
                             val = ((int64_t)acc[mb][nb][0][v] << 16) + ((int64_t)acc[mb][nb][1][v] << 8) +
@@ -1077,7 +1081,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         return;
     }
 
-    unsigned zeros = tile_epilogue<LIMBS, NB, MB, THREADS>(a, acc, row_sum, outoff, pooloff, ctab, ntile);
+    unsigned zeros = tile_epilogue<LIMBS, NB, MB, THREADS, MB, 4>(a, acc, row_sum, outoff, pooloff, ctab, ntile, 0, 0);
     // one count per workgroup, no atomics: thousands of same-address atomics would serialise
     if (a.zero_partial) {
         if (lane == 0) tab[wave] = (int)zeros; // tab[] was last read while staging
@@ -1091,15 +1095,19 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
 }
 
 
-// Finishes the tail tiles: one workgroup per tile adds up the parts' accumulators and row sums
-// and runs the epilogue; its zero count goes straight to the total (few workgroups).  Workgroup 0
-// also adds the per-workgroup counts of the main kernel.
+// Finishes the tail tiles.  A tile's parts are added up and the epilogue run by 4 * MB workgroups,
+// one per (32-row block, channel group of the MFMA layout): each thread then needs only NB * NACC
+// 16-byte pieces per part, so the pieces of all parts are requested together and the memory
+// latency is paid once.  Zero counts go straight to the total (few workgroups); workgroup 0 also
+// adds the per-workgroup counts of the main kernel.
 template <int LIMBS, int NB, int MB>
 __global__ __launch_bounds__(256) void conv_finish_kernel(const ConvArgs a, int main_grid)
 {
     constexpr int THREADS = 256;
     constexpr int BN = 64 * NB;
     constexpr int NACC = (LIMBS == 2) ? 3 : 1;
+    constexpr int SUB = 4 * MB;       // workgroups per tile
+    constexpr int MAXP = 8;           // most parts a tile is cut into (see choose_split)
     __shared__ int outoff[BM];
     __shared__ int rowsum[BM];
     __shared__ int pooloff[BM];
@@ -1107,13 +1115,29 @@ __global__ __launch_bounds__(256) void conv_finish_kernel(const ConvArgs a, int 
     __shared__ unsigned wave_zeros[THREADS / 64];
     const int tid = threadIdx.x;
     const int tails = a.per_xcd - a.full_per_xcd;
-    const int xcd = blockIdx.x / tails, tl = a.full_per_xcd + blockIdx.x % tails;
+    const int tile_b = blockIdx.x / SUB, sub = blockIdx.x % SUB;
+    const int mb0 = sub >> 2, g0 = sub & 3;
+    const int xcd = tile_b / tails, tl = a.full_per_xcd + tile_b % tails;
     const int wi = xcd * a.per_xcd + tl;
     unsigned long long total = 0;
     if (wi < a.total_work) {
         const int mtile = wi / a.tiles_n, ntile = wi % a.tiles_n;
         const int tile_r = mtile / a.tiles_c, tile_c = mtile % a.tiles_c;
         const int fr0 = tile_r * a.RH, x0 = tile_c * a.TW;
+        // every request first: accumulator pieces and row sums of all parts
+        const unsigned char *slots = a.partials + (size_t)tile_b * a.split * a.part_bytes;
+        v4i piece[MAXP][NB][NACC];
+        int rsp[MAXP];
+#pragma unroll
+        for (int o = 0; o < MAXP; ++o) {
+            const unsigned char *theirs = slots + (size_t)min(o, a.split - 1) * a.part_bytes; // clamped: unconditional loads
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int q = 0; q < NACC; ++q)
+                    piece[o][nb][q] = ((const v4i *)theirs)[((((mb0 * NB + nb) * NACC + q) * 4 + g0) * THREADS) + tid];
+            rsp[o] = (LIMBS == 2 && tid < BM) ? ((const int *)(theirs + (size_t)MB * NB * NACC * 4 * THREADS * 16))[tid] : 0;
+        }
         for (int m = tid; m < BM; m += THREADS) {
             const int j = m / a.TW, t = m % a.TW;
             const int fr = fr0 + j, xo = x0 + t;
@@ -1121,42 +1145,35 @@ __global__ __launch_bounds__(256) void conv_finish_kernel(const ConvArgs a, int 
             outoff[m] = ok ? fr * a.Wo + xo : -1;
             pooloff[m] = (a.pool && ok && !(j & 1) && !(t & 1))
                              ? ((fr / a.Ho) * (a.Ho >> 1) + ((fr % a.Ho) >> 1)) * (a.Wo >> 1) + (xo >> 1) : -1;
-            rowsum[m] = 0;
         }
         build_colterms<BN, THREADS>(a, ntile, ctab);
-        v16i acc[MB][NB][NACC];
+        v16i acc[1][NB][NACC];
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
+            for (int q = 0; q < NACC; ++q)
 #pragma unroll
-                for (int q = 0; q < NACC; ++q)
+                for (int v = 0; v < 16; ++v) acc[0][nb][q][v] = 0;
+        int rs = 0;
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[mb][nb][q][v] = 0;
-        for (int o = 0; o < a.split; ++o) {
-            const v4i *theirs = (const v4i *)(a.partials + ((size_t)blockIdx.x * a.split + o) * a.part_bytes);
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+        for (int o = 0; o < MAXP; ++o) {
+            if (o < a.split) {
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                    for (int q = 0; q < NACC; ++q)
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            const v4i v = theirs[(((mb * NB + nb) * NACC + q) * 4 + g) * THREADS + tid];
-                            acc[mb][nb][q][4 * g] += v.x;
-                            acc[mb][nb][q][4 * g + 1] += v.y;
-                            acc[mb][nb][q][4 * g + 2] += v.z;
-                            acc[mb][nb][q][4 * g + 3] += v.w;
-                        }
-            if constexpr (LIMBS == 2) {
-                const int *rs = (const int *)(theirs + MB * NB * NACC * 4 * THREADS);
-                if (tid < BM) rowsum[tid] += rs[tid]; // each row has one owner: no race
+                    for (int q = 0; q < NACC; ++q) {
+                        acc[0][nb][q][0] += piece[o][nb][q].x;
+                        acc[0][nb][q][1] += piece[o][nb][q].y;
+                        acc[0][nb][q][2] += piece[o][nb][q].z;
+                        acc[0][nb][q][3] += piece[o][nb][q].w;
+                    }
+                rs += rsp[o];
             }
         }
+        if (tid < BM) rowsum[tid] = rs;
         __syncthreads();
-        const unsigned zeros = tile_epilogue<LIMBS, NB, MB, THREADS>(
-            a, acc, [&](int m) { return rowsum[m]; }, outoff, pooloff, ctab, ntile);
+        const unsigned zeros = tile_epilogue<LIMBS, NB, MB, THREADS, 1, 1>(
+            a, acc, [&](int m) { return rowsum[m]; }, outoff, pooloff, ctab, ntile, mb0, g0);
         if ((tid & 63) == 0) wave_zeros[tid >> 6] = zeros;
         __syncthreads();
         if (tid == 0)
@@ -1177,12 +1194,20 @@ __global__ __launch_bounds__(256) void conv_finish_kernel(const ConvArgs a, int 
     if (tid == 0 && total) atomicAdd(a.zero_count, total);
 }
 
+// Adds the per-workgroup zero counts to the caller's counter: a few blocks, eight independent
+// loads per thread and pass, one atomic per block.
 __global__ __launch_bounds__(256) void sum_partials_kernel(const unsigned *__restrict__ partial, int n,
                                                           unsigned long long *out)
 {
     __shared__ unsigned long long part[4];
     unsigned long long s = 0;
-    for (int i = threadIdx.x; i < n; i += 256) s += partial[i];
+    for (int i0 = blockIdx.x * 2048 + threadIdx.x; i0 < n; i0 += gridDim.x * 2048) {
+        unsigned v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = (i0 + j * 256 < n) ? partial[i0 + j * 256] : 0u;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += v[j];
+    }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) s += __shfl_down(s, off, 64);
     if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
@@ -1206,7 +1231,7 @@ static lp_status launch_mfma(const ConvArgs &a, const Plan &p, int grid, int tai
     hipLaunchKernelGGL((conv_mfma_kernel<LIMBS, NB, FLAT, MB>), dim3(grid), dim3(MB == 2 ? 256 : 512),
                        p.lds_bytes, st, a);
     if (tails) // the split tail tiles are merged and written by a second, small kernel
-        hipLaunchKernelGGL((conv_finish_kernel<LIMBS, NB, MB>), dim3(tails), dim3(256), 0, st, a, grid);
+        hipLaunchKernelGGL((conv_finish_kernel<LIMBS, NB, MB>), dim3(tails * 4 * MB), dim3(256), 0, st, a, grid);
     return launch_status();
 }
 
@@ -1301,8 +1326,8 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     else if (p.limbs == 2) st2 = launch_mfma<2, 1, false, 2>(a, p, grid, tails, hs);
     else st2 = p.BN == 128 ? launch_mfma<1, 2, false, 2>(a, p, grid, tails, hs) : launch_mfma<1, 1, false, 2>(a, p, grid, tails, hs);
     if (st2 != LP_OK || tails || !counting) return st2;
-    hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(256), 0, hs, a.zero_partial, grid,
-                       (unsigned long long *)zero_count);
+    hipLaunchKernelGGL(sum_partials_kernel, dim3(std::min((grid + 2047) / 2048, 16)), dim3(256), 0, hs,
+                       a.zero_partial, grid, (unsigned long long *)zero_count);
     return launch_status();
 }
 
