@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0
 # profiles/): average bytes per launch over the 13 launches of one step, already scaled by the
 # copy-kernel factor.  Valid only for the kernel source it was measured on (sha256 of lp_conv.hip);
 # reported as null for any other source.
-TRAFFIC_RECORD = {"lp_conv_sha256": "3a9194022320351bceeac768a0d168f51a1078d73bb4bf8ad835aaf98e154309", "bytes_per_launch": 141750648}
+TRAFFIC_RECORD = {"lp_conv_sha256": "4777c6f3f079a80a771b705d8e2fe290e7002f6858e624383b0733cec6fdfd8b", "bytes_per_launch": 119631452}
 
 
 def _traffic_for_current_source():
