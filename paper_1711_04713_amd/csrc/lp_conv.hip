@@ -908,9 +908,8 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         if constexpr (FLAT) {
             stage_flat();
         } else {
-            // every load is issued, also the one past the end (it reads the last pixel again):
-            // the number of loads in flight is then the same on every path, and each wait
-            // covers exactly the batch about to be parked
+            // two batches of requests in flight; a request past the end reads the last pixel
+            // again and is parked nowhere
             const int total = NPIXA * PIECES;
             int first = 0;
             if (deep) {
@@ -922,64 +921,124 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
 #pragma unroll
                 for (int j = 0; j < DEEP; ++j) store_piece(j * THREADS, d[j]);
                 first = DEEP * THREADS;
-                if (first >= total) return;
+                if (first >= total) {
+                    __builtin_amdgcn_s_waitcnt(0x0F70);
+                    return;
+                }
             }
+            // Two batches of requests are in flight inside the loop; the last two batches are
+            // taken out of it, so that no request is left in flight when the staging is over (its
+            // destination registers are reused in the multiply loop, and the wait that protects
+            // them would sit at the top of every slab, where it would also wait for the weight
+            // operands just requested) and the loop has one way out.
             load_act(cc, first, aregA);
-            for (; first < total; first += 2 * APF * THREADS) {
+            for (; first + 2 * APF * THREADS < total; first += 2 * APF * THREADS) {
                 load_act(cc, first + APF * THREADS, aregB);
                 store_act(first, aregA);
                 load_act(cc, first + 2 * APF * THREADS, aregA);
                 store_act(first + APF * THREADS, aregB);
             }
+            load_act(cc, first + APF * THREADS, aregB);
+            store_act(first, aregA);
+            store_act(first + APF * THREADS, aregB);
         }
+        // vmcnt(0), stated where every path passes (the waits above sit partly inside branches
+        // on lane masks); by now it costs nothing
+        __builtin_amdgcn_s_waitcnt(0x0F70);
     };
     // chunk and tap of the current slab, and the tap's patch offset, kept incrementally
     int cc = s0 / a.taps, tap = s0 % a.taps;
     int tap_r = FLAT ? 0 : tap / a.S, tap_s = FLAT ? 0 : tap % a.S;
     int taprow = tap_r * a.PITCH, tapoff = taprow + tap_s * PS;
-    // Weights go straight from global memory / L2 into the MFMA operand registers, one K=32 half
-    // ahead of their use; with no slab to publish, the waves of a workgroup meet only when a new
-    // patch is staged.  A lane's B operand for (slab, K half, limb, column block) is the 16 bytes at
-    // row (column block + lane % 32), byte 32*half + 16*(lane / 32) of the packed slab.  Two
-    // register sets alternate: X feeds the first half of a slab while Y (second half) is on its
-    // way, then Y feeds the second half while X is refilled from the next slab.
-    v4i bxh[NB], bxl[NB], byh[NB], byl[NB];
-    const unsigned char *bp = a.wp + (size_t)s0 * slab_bytes +
-                              ((size_t)ntile * BN + wn * (NB * 32) + l32) * CK + kg * 16;
-    int bt = s0; // slab bp points into
-    auto bload = [&](const unsigned char *src, v4i *h, v4i *l) __attribute__((always_inline)) {
+    // Weights go straight from global memory / L2 into the MFMA operand registers, NSETS - 1
+    // K=32 halves ahead of their use; with no slab to publish, the waves of a workgroup meet only
+    // when a new patch is staged.  A lane's B operand for (slab, K half, limb, column block) is the
+    // 16 bytes at row (column block + lane % 32), byte 32*half + 16*(lane / 32) of the packed slab.
+    // NSETS register sets rotate: the half being multiplied owns one, the requests for the next
+    // NSETS - 1 halves are in flight into the others.  Which set a half uses is fixed at compile
+    // time, so the loop below is unrolled over a whole rotation (UT slabs).
+    constexpr int NSETS = 3, LEAD = NSETS - 1;
+    constexpr int UT = (NSETS % 2 == 0) ? NSETS / 2 : NSETS;
+    v4i bh[NSETS][NB], bl[NSETS][NB];
+    // One descriptor over the packed weights; a lane's byte offset inside a slab never changes,
+    // the slab (and the limb plane) is a scalar offset, the K half an immediate: no address
+    // arithmetic in vector registers inside the loop.
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<unsigned char *>(a.wp), 0, (int)((unsigned)nslabs * (unsigned)slab_bytes), 0x00020000);
+    const int blane = ((ntile * BN + wn * (NB * 32) + l32) * CK + kg * 16);
+    const int limb_bytes = a.CoutP * CK;
+    // request the operands of K half `half` of slab t (past the last slab the last one is read
+    // again and never used: every path issues the same number of requests)
+    auto bload = [&](int t, int half, v4i *h, v4i *l) __attribute__((always_inline)) {
+        const int slab_off = min(t, s1 - 1) * (int)slab_bytes;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            h[nb] = *(const v4i *)(src + nb * 32 * CK);
-            if constexpr (LIMBS == 2) l[nb] = *(const v4i *)(src + nb * 32 * CK + (size_t)a.CoutP * CK);
+            const auto vh = half ? __builtin_amdgcn_raw_buffer_load_b128(wrsrc, blane + nb * 32 * CK + 32, slab_off, 0)
+                                 : __builtin_amdgcn_raw_buffer_load_b128(wrsrc, blane + nb * 32 * CK, slab_off, 0);
+            h[nb] = (v4i){(int)vh[0], (int)vh[1], (int)vh[2], (int)vh[3]};
+            if constexpr (LIMBS == 2) {
+                const auto vl = half ? __builtin_amdgcn_raw_buffer_load_b128(wrsrc, blane + nb * 32 * CK + 32, slab_off + limb_bytes, 0)
+                                     : __builtin_amdgcn_raw_buffer_load_b128(wrsrc, blane + nb * 32 * CK, slab_off + limb_bytes, 0);
+                l[nb] = (v4i){(int)vl[0], (int)vl[1], (int)vl[2], (int)vl[3]};
+            }
         }
     };
-    auto mfma_half = [&](int k32, const int *afrag, const v4i *bh, const v4i *bl) __attribute__((always_inline)) {
-        v4i ah[MB], al[MB];
+    // The activation fragments (A operands) of a row block stay in registers from their LDS read
+    // to the MFMAs that consume them.  On the patch path they are read one step ahead: as soon as
+    // the MFMAs of row block mb of a K half are issued, the fragments of the same row block for the
+    // next K half (of this slab or the next) are requested, so that the LDS latency runs under the
+    // other row block's MFMAs.  The flat path (a slab per staging) reads them where it uses them.
+    constexpr bool PIPE = !FLAT;
+    v4i ah[MB], al[MB];
+    auto afetch = [&](int mb, int off) __attribute__((always_inline)) {
+        ah[mb] = *(const v4i *)(Asm + off);
+        if constexpr (LIMBS == 2) al[mb] = *(const v4i *)(Asm + APL + off);
+    };
+    auto mfma_mb = [&](int mb, const v4i *wh, const v4i *wl) __attribute__((always_inline)) {
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            ah[mb] = *(const v4i *)(Asm + (afrag[mb] ^ (k32 * 32)));
-            if constexpr (LIMBS == 2) al[mb] = *(const v4i *)(Asm + APL + (afrag[mb] ^ (k32 * 32)));
-        }
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                acc[mb][nb][0] = mfma_i8(bh[nb], ah[mb], acc[mb][nb][0]);
-                if constexpr (LIMBS == 2) {
-                    acc[mb][nb][1] = mfma_i8(bl[nb], ah[mb], acc[mb][nb][1]);
-                    acc[mb][nb][2] = mfma_i8(bl[nb], al[mb], acc[mb][nb][2]);
-                }
+        for (int nb = 0; nb < NB; ++nb) {
+            acc[mb][nb][0] = mfma_i8(wh[nb], ah[mb], acc[mb][nb][0]);
+            if constexpr (LIMBS == 2) {
+                acc[mb][nb][1] = mfma_i8(wl[nb], ah[mb], acc[mb][nb][1]);
+                acc[mb][nb][2] = mfma_i8(wl[nb], al[mb], acc[mb][nb][2]);
             }
+        }
         if constexpr (LIMBS == 2) {
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) acc[mb][nb][1] = mfma_i8(bh[nb], al[mb], acc[mb][nb][1]);
+            for (int nb = 0; nb < NB; ++nb) acc[mb][nb][1] = mfma_i8(wh[nb], al[mb], acc[mb][nb][1]);
         }
     };
-    auto compute_slab = [&]() __attribute__((always_inline)) {
-        int afrag[MB]; // this tap's pixel per row block, slot kg; the second K=32 half is slot kg+2
+    using std::integral_constant;
+    // One K half of slab t, which is slab number P of the current rotation: request the weights
+    // that are LEAD halves ahead, then multiply this half row block by row block.  cur / nxt:
+    // fragment offsets of this slab and the next; pre: the next slab reads the same patch.
+    auto half_step = [&](int t, auto P, auto HH, const int *cur, const int *nxt, bool pre) __attribute__((always_inline)) {
+        constexpr int hh = decltype(HH)::value;
+        constexpr int h = 2 * decltype(P)::value + hh;
+        constexpr int use = h % NSETS, fill = (h + LEAD) % NSETS;
+        constexpr int ahead = hh + LEAD;
+        bload(t + (ahead >> 1), ahead & 1, bh[fill], bl[fill]);
+        // the requests leave before this half's MFMAs, not among them
+        __builtin_amdgcn_sched_barrier(0);
+        const bool on = hh == 0 || !FLAT || a.ksteps > 1; // a flat window of K <= 32 has one half
+        if (!on) // vmcnt: the skipped half's operands have arrived all the same, so that the count
+                 // of requests in flight does not depend on the path taken
+            __builtin_amdgcn_s_waitcnt(0x0F70 | (LEAD * NB * LIMBS));
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            if constexpr (!PIPE) afetch(mb, cur[mb] ^ (hh * 32));
+            if (on) mfma_mb(mb, bh[use], bl[use]);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (PIPE) {
+                if (hh == 0) afetch(mb, cur[mb] ^ 32);
+                else if (pre) afetch(mb, nxt[mb]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+    // fragment offsets of the slab the tap bookkeeping points at: its pixel per row block, slot
+    // kg; the second K=32 half is slot kg+2
+    auto fragment_offsets = [&](int *afrag) __attribute__((always_inline)) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             if constexpr (FLAT) afrag[mb] = swz(aoff[mb], kg);
@@ -989,20 +1048,9 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
                 afrag[mb] = swzk(pix, kg, key);
             }
         }
-        bload(bp + 32, byh, byl);
-        mfma_half(0, afrag, bxh, bxl);
-        // keep the second half's fragment loads behind the first half's MFMAs: both sets live
-        // at once would cost more registers than three waves per SIMD leave
-        __builtin_amdgcn_sched_barrier(0);
-        if (bt + 1 < s1) { // past the last slab the last one is read again (and never used)
-            ++bt;
-            bp += slab_bytes;
-        }
-        bload(bp, bxh, bxl);
-        if (a.ksteps > 1) mfma_half(1, afrag, byh, byl); // a flat window of K <= 32 has one half
-        __builtin_amdgcn_sched_barrier(0);
     };
-    bload(bp, bxh, bxl);
+#pragma unroll
+    for (int j = 0; j < LEAD; ++j) bload(s0 + (j >> 1), j & 1, bh[j], bl[j]);
 
     stage_activations(cc, true);
     own_sums = true; // every later chunk starts at its first tap
@@ -1014,13 +1062,15 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             for (int q = 0; q < NACC; ++q)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[mb][nb][q][v] = 0;
-    auto step = [&](int t) __attribute__((always_inline)) {
-        if (tap == 0 && t != s0) {
-            __syncthreads(); // all reads of the previous chunk's activations are done
-            stage_activations(cc, false);
-        }
-        if (tap == 0 || t == s0) __syncthreads(); // the freshly staged patch is visible
-        compute_slab();
+    int cur[MB];
+    fragment_offsets(cur);
+    __syncthreads(); // the freshly staged patch is visible
+    if constexpr (PIPE) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) afetch(mb, cur[mb]);
+    }
+    auto step = [&](int t, auto P) __attribute__((always_inline)) {
+        // move the bookkeeping on to slab t + 1
         if (++tap == a.taps) {
             tap = 0;
             ++cc;
@@ -1035,15 +1085,39 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
                 tapoff = taprow;
             }
         }
+        int nxt[MB];
+        fragment_offsets(nxt);
+        const bool more = t + 1 < s1;
+        const bool restage = more && tap == 0; // slab t + 1 opens a chunk: a new patch
+        half_step(t, P, integral_constant<int, 0>{}, cur, nxt, false);
+        half_step(t, P, integral_constant<int, 1>{}, cur, nxt, more && tap != 0);
+        if (restage) {
+            __syncthreads(); // all reads of the previous chunk's activations are done
+            stage_activations(cc, false);
+            __syncthreads(); // the freshly staged patch is visible
+            if constexpr (PIPE) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) afetch(mb, nxt[mb]);
+            }
+        }
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) cur[mb] = nxt[mb];
     };
-    // both halves unconditional inside the loop (a skipped half would make the in-flight load
-    // count path dependent); an odd last slab is handled after it
+    // whole rotations inside the loop, the slabs left over after it
     int t = s0;
-    for (; t + 1 < s1; t += 2) {
-        step(t);
-        step(t + 1);
+    for (; t + UT <= s1; t += UT) {
+        step(t, integral_constant<int, 0>{});
+        if constexpr (UT > 1) step(t + 1, integral_constant<int, 1>{});
+        if constexpr (UT > 2) step(t + 2, integral_constant<int, 2>{});
     }
-    if (t < s1) step(t);
+    if constexpr (UT > 1) {
+        if (t < s1) {
+            step(t, integral_constant<int, 0>{});
+            if constexpr (UT > 2) {
+                if (t + 1 < s1) step(t + 1, integral_constant<int, 1>{});
+            }
+        }
+    }
 
     // ---- sum of the codes under a tile row's window (two-limb correction term 128 * sum(a)):
     // the channel sums of its R x S patch pixels, complete since the last chunk was staged
