@@ -534,19 +534,38 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
     if (a.fast) {
         // v = 2^16*A + 2^8*B + C with every piece in int32: the channel constant is split the same
         // way, 128*rowsum = 2^8*(rowsum >> 1) + 128*(rowsum & 1); then carries are pushed upward.
-        // Shift class and code width are compile-time: about ten VALU operations per value.
+        // Shift class, code width and store mode are compile-time: about ten VALU operations per
+        // value.  Stores go through a buffer descriptor that starts at the tile's first output
+        // pixel (the smallest address of the tile) with 32-bit offsets from there; a lane with
+        // nothing to store (a row outside the image, a padded channel, a lane that is not the
+        // top-left of its pooling window) gets an offset past the descriptor and its store is
+        // dropped: no branches, no 64-bit address arithmetic.
         const int s = a.act.s, cmax = a.act.hi;
-        auto requant_tile = [&](auto s16c, auto y16c) __attribute__((always_inline)) {
+        __builtin_assume(cmax >= 0);
+        constexpr unsigned NOWHERE = 0x80000000u; // the descriptor never covers more than 2^31 - 1 bytes
+        auto requant_tile = [&](auto s16c, auto y16c, auto modec) __attribute__((always_inline)) {
             constexpr int S16 = decltype(s16c)::value;
             constexpr bool Y16 = decltype(y16c)::value;
+            constexpr int MODE = decltype(modec)::value; // 0: four codes per store, 1: fused 2x2 max-pool, 2: ragged channels
             constexpr int ESZ = Y16 ? 2 : 1;
-            const bool vec_ok = (a.Cout & 3) == 0; // every group of four channels is aligned
+            const int first = __builtin_amdgcn_readfirstlane(MODE == 1 ? pooloff[0] : outoff[0]);
+            const size_t pixels = MODE == 1 ? (size_t)a.N * (a.Ho >> 1) * (a.Wo >> 1) : (size_t)a.N * a.Ho * a.Wo;
+            const size_t left = (pixels - (size_t)first) * a.Cout * ESZ;
+            const __amdgpu_buffer_rsrc_t yrsrc = __builtin_amdgcn_make_buffer_rsrc(
+                (unsigned char *)a.y + (size_t)first * a.Cout * ESZ, 0, (int)(left < 0x7fffffffu ? left : 0x7fffffffu), 0x00020000);
+            unsigned rel[MBL]; // byte offset of the lane's output pixel from the tile's first one
+#pragma unroll
+            for (int mb = 0; mb < MBL; ++mb) {
+                const int o = MODE == 1 ? po[mb] : oo[mb];
+                rel[mb] = o >= 0 ? (unsigned)((o - first) * a.Cout * ESZ) : NOWHERE;
+            }
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                 for (int gl = 0; gl < GL; ++gl) {
                     const int cl = wn * (NB * 32) + nb * 32 + 8 * (g0 + gl) + 4 * kg; // channel within the tile
                     const int col0 = ntile * BN + cl;
+                    const bool col_ok = col0 < a.Cout;
                     const v4i cA = *(const v4i *)(ctab + cl);
                     const v4i cB = *(const v4i *)(ctab + BN + cl);
                     const v4i cC = *(const v4i *)(ctab + 2 * BN + cl);
@@ -570,17 +589,30 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                             }
                             q[e] = requant_relu32<S16>(hi, lo16, s, cmax);
                         }
-                        if constexpr (Y16) {
-                            if (a.pool) {
+                        const bool counted = oo[mb] >= 0 && col_ok; // the lane's codes exist in the output tensor
+                        if constexpr (MODE == 2) { // ragged channel tail: code by code
+                            if (counted) {
+                                unsigned char *dst = (unsigned char *)a.y + ((size_t)oo[mb] * a.Cout + col0) * ESZ;
+                                const int ncodes = min(4, a.Cout - col0);
+                                for (int e = 0; e < ncodes; ++e) {
+                                    if constexpr (Y16) ((int16_t *)dst)[e] = (int16_t)q[e];
+                                    else ((int8_t *)dst)[e] = (int8_t)q[e];
+                                    nz += (q[e] == 0);
+                                }
+                            }
+                        } else if constexpr (Y16) {
+                            // codes are in [0, cmax]: packing needs no masks.  Exact per-field zero
+                            // test: the top bit of a 16-bit (8-bit) field survives only when every
+                            // bit of the field is clear; no carry crosses fields
+                            unsigned w0 = (unsigned)q[0] | ((unsigned)q[1] << 16);
+                            unsigned w1 = (unsigned)q[2] | ((unsigned)q[3] << 16);
+                            constexpr unsigned LOW = 0x7fff7fffu;
+                            const unsigned z = __popc(~(((w0 & LOW) + LOW) | w0 | LOW)) + __popc(~(((w1 & LOW) + LOW) | w1 | LOW));
+                            nz += counted ? z : 0u;
+                            if constexpr (MODE == 1) {
                                 // 2x2 maximum across lanes: the horizontal neighbour is the next lane,
                                 // the vertical one sits TW lanes further in the same 32-row block.
                                 // Every lane takes part; only the window's top-left lane stores.
-                                unsigned w0 = (unsigned)q[0] | ((unsigned)q[1] << 16);
-                                unsigned w1 = (unsigned)q[2] | ((unsigned)q[3] << 16);
-                                if (oo[mb] >= 0 && col0 < a.Cout) {
-                                    constexpr unsigned LOW = 0x7fff7fffu;
-                                    nz += __popc(~(((w0 & LOW) + LOW) | w0 | LOW)) + __popc(~(((w1 & LOW) + LOW) | w1 | LOW));
-                                }
                                 auto pkmax = [](unsigned x, unsigned y) __attribute__((always_inline)) {
                                     return __builtin_bit_cast(unsigned, __builtin_elementwise_max(__builtin_bit_cast(v2s, x),
                                                                                                   __builtin_bit_cast(v2s, y)));
@@ -590,51 +622,36 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                                 const int below = ((lane + a.TW) & 63) * 4;
                                 w0 = pkmax(w0, (unsigned)__builtin_amdgcn_ds_bpermute(below, (int)w0));
                                 w1 = pkmax(w1, (unsigned)__builtin_amdgcn_ds_bpermute(below, (int)w1));
-                                if (po[mb] >= 0 && col0 < a.Cout)
-                                    *(v2i *)((unsigned char *)a.y + ((size_t)po[mb] * a.Cout + col0) * 2) = (v2i){(int)w0, (int)w1};
-                                continue;
                             }
-                        }
-                        if (oo[mb] >= 0 && col0 < a.Cout) {
-                            unsigned char *dst = (unsigned char *)a.y + ((size_t)oo[mb] * a.Cout + col0) * ESZ;
-                            if (vec_ok) {
-                                // codes are in [0, cmax]: packing needs no masks.  Exact per-field
-                                // zero test: the top bit of a 16-bit (8-bit) field survives only
-                                // when every bit of the field is clear; no carry crosses fields
-                                if constexpr (Y16) {
-                                    const unsigned w0 = (unsigned)q[0] | ((unsigned)q[1] << 16);
-                                    const unsigned w1 = (unsigned)q[2] | ((unsigned)q[3] << 16);
-                                    *(v2i *)dst = (v2i){(int)w0, (int)w1};
-                                    constexpr unsigned LOW = 0x7fff7fffu;
-                                    nz += __popc(~(((w0 & LOW) + LOW) | w0 | LOW)) + __popc(~(((w1 & LOW) + LOW) | w1 | LOW));
-                                } else {
-                                    const unsigned w0 = (unsigned)q[0] | ((unsigned)q[1] << 8) | ((unsigned)q[2] << 16) |
-                                                        ((unsigned)q[3] << 24);
-                                    *(unsigned *)dst = w0;
-                                    constexpr unsigned LOW = 0x7f7f7f7fu;
-                                    nz += __popc(~(((w0 & LOW) + LOW) | w0 | LOW));
-                                }
-                            } else { // ragged channel tail, or rows not aligned
-                                const int ncodes = min(4, a.Cout - col0);
-                                for (int e = 0; e < ncodes; ++e) {
-                                    if constexpr (Y16) ((int16_t *)dst)[e] = (int16_t)q[e];
-                                    else ((int8_t *)dst)[e] = (int8_t)q[e];
-                                    nz += (q[e] == 0);
-                                }
-                            }
+                            const unsigned at = col_ok ? rel[mb] + (unsigned)col0 * 2u : NOWHERE;
+                            __builtin_amdgcn_raw_buffer_store_b64((v2u){w0, w1}, yrsrc, (int)at, 0, 0);
+                        } else {
+                            const unsigned w0 = (unsigned)q[0] | ((unsigned)q[1] << 8) | ((unsigned)q[2] << 16) | ((unsigned)q[3] << 24);
+                            constexpr unsigned LOW = 0x7f7f7f7fu;
+                            const unsigned z = __popc(~(((w0 & LOW) + LOW) | w0 | LOW));
+                            nz += counted ? z : 0u;
+                            const unsigned at = col_ok ? rel[mb] + (unsigned)col0 : NOWHERE;
+                            __builtin_amdgcn_raw_buffer_store_b32(w0, yrsrc, (int)at, 0, 0);
                         }
                     }
                 }
         };
         using std::integral_constant;
+        auto by_mode = [&](auto s16c, auto y16c) __attribute__((always_inline)) {
+            if constexpr (decltype(y16c)::value) {
+                if (a.pool) return requant_tile(s16c, y16c, integral_constant<int, 1>{});
+            }
+            if ((a.Cout & 3) == 0) requant_tile(s16c, y16c, integral_constant<int, 0>{}); // every group of four channels is aligned
+            else requant_tile(s16c, y16c, integral_constant<int, 2>{});
+        };
         if (a.y16) {
-            if (s >= 17) requant_tile(integral_constant<int, 0>{}, integral_constant<bool, true>{});
-            else if (s == 16) requant_tile(integral_constant<int, 1>{}, integral_constant<bool, true>{});
-            else requant_tile(integral_constant<int, 2>{}, integral_constant<bool, true>{});
+            if (s >= 17) by_mode(integral_constant<int, 0>{}, integral_constant<bool, true>{});
+            else if (s == 16) by_mode(integral_constant<int, 1>{}, integral_constant<bool, true>{});
+            else by_mode(integral_constant<int, 2>{}, integral_constant<bool, true>{});
         } else {
-            if (s >= 17) requant_tile(integral_constant<int, 0>{}, integral_constant<bool, false>{});
-            else if (s == 16) requant_tile(integral_constant<int, 1>{}, integral_constant<bool, false>{});
-            else requant_tile(integral_constant<int, 2>{}, integral_constant<bool, false>{});
+            if (s >= 17) by_mode(integral_constant<int, 0>{}, integral_constant<bool, false>{});
+            else if (s == 16) by_mode(integral_constant<int, 1>{}, integral_constant<bool, false>{});
+            else by_mode(integral_constant<int, 2>{}, integral_constant<bool, false>{});
         }
     } else {
         const int64_t *ct64 = (const int64_t *)ctab;
@@ -1125,6 +1142,13 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         if constexpr (FLAT) return psum[m];
         const int base = abase_s[m];
         int sum = 0;
+        if (a.R == 3 && a.S == 3) { // the common window, unrolled: nine independent LDS reads
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int s = 0; s < 3; ++s) sum += psum[base + r * a.PW + s];
+            return sum;
+        }
         for (int r = 0; r < a.R; ++r)
             for (int s = 0; s < a.S; ++s) sum += psum[base + r * a.PW + s];
         return sum;
