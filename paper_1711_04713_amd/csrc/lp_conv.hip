@@ -816,8 +816,9 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         const int ch = cc * CK + apiece * (CK / PIECES);
         const int p = min(apix0 + first / PIECES, NPIXA - 1);
         const int g = tab[p];
-        const unsigned off = (g >= 0 && ch < a.Cin) ? (unsigned)(g * a.Cin + ch) * ESZ_X : 0xffffffffu;
-        const auto v = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)off, 0, 0);
+        const unsigned off = (unsigned)(g * a.Cin + ch) * ESZ_X; // computed on every lane: a select, not a branch
+        const int ok = (g >= 0) & (ch < a.Cin);
+        const auto v = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)(ok ? off : 0xffffffffu), 0, 0);
         reg = (v4i){(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
     };
     auto store_piece = [&](int first, const v4i &reg) __attribute__((always_inline)) {
@@ -1028,8 +1029,11 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     using std::integral_constant;
     // One K half of slab t, which is slab number P of the current rotation: request the weights
     // that are LEAD halves ahead, then multiply this half row block by row block.  cur / nxt:
-    // fragment offsets of this slab and the next; pre: the next slab reads the same patch.
-    auto half_step = [&](int t, auto P, auto HH, const int *cur, const int *nxt, bool pre) __attribute__((always_inline)) {
+    // fragment offsets of this slab and the next.  The second half always requests the next
+    // slab's fragments, also when a new patch comes first (they are then read again after the
+    // staging) or nothing follows: the offsets stay inside the patch, and a request that does
+    // not depend on the path keeps the fragment registers from being doubled.
+    auto half_step = [&](int t, auto P, auto HH, const int *cur, const int *nxt) __attribute__((always_inline)) {
         constexpr int hh = decltype(HH)::value;
         constexpr int h = 2 * decltype(P)::value + hh;
         constexpr int use = h % NSETS, fill = (h + LEAD) % NSETS;
@@ -1048,7 +1052,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (PIPE) {
                 if (hh == 0) afetch(mb, cur[mb] ^ 32);
-                else if (pre) afetch(mb, nxt[mb]);
+                else afetch(mb, nxt[mb]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -1106,8 +1110,8 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         fragment_offsets(nxt);
         const bool more = t + 1 < s1;
         const bool restage = more && tap == 0; // slab t + 1 opens a chunk: a new patch
-        half_step(t, P, integral_constant<int, 0>{}, cur, nxt, false);
-        half_step(t, P, integral_constant<int, 1>{}, cur, nxt, more && tap != 0);
+        half_step(t, P, integral_constant<int, 0>{}, cur, nxt);
+        half_step(t, P, integral_constant<int, 1>{}, cur, nxt);
         if (restage) {
             __syncthreads(); // all reads of the previous chunk's activations are done
             stage_activations(cc, false);
