@@ -292,35 +292,42 @@ __global__ __launch_bounds__(kThreads) void act_kernel(const int64_t *__restrict
                                                       OutT *__restrict__ y, size_t count,
                                                       ActParams p, unsigned long long *zero_count)
 {
-    const size_t groups = count / 8;
+    // A block takes 8 * kThreads consecutive accumulators per trip, as four rows of kThreads
+    // 16-byte pairs: a lane's loads are 16 bytes apart from its neighbours' (1 KB contiguous per
+    // wave and instruction), and it stores the two codes of each pair (4 or 2 bytes, again
+    // contiguous over the wave).
+    const size_t groups = count / 8;            // whole groups of 8; the rest is handled below
+    const size_t trips = groups / kThreads;     // whole block trips
     unsigned zeros = 0;
-    for (size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x; g < groups;
-         g += (size_t)gridDim.x * kThreads) {
-        bool z[8];
-        {
-            int c[8];
+    for (size_t t = blockIdx.x; t < trips; t += gridDim.x) {
+        const size_t pair0 = t * (4 * kThreads) + threadIdx.x;
+        v4i a[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const v4i a = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(acc) + 4 * g + j);
-                const int64_t a0 = (int64_t)(((uint64_t)(uint32_t)a.y << 32) | (uint32_t)a.x);
-                const int64_t a1 = (int64_t)(((uint64_t)(uint32_t)a.w << 32) | (uint32_t)a.z);
-                c[2 * j] = act_one(a0, p);
-                c[2 * j + 1] = act_one(a1, p);
-            }
+        for (int j = 0; j < 4; ++j)
+            a[j] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(acc) + pair0 + j * kThreads);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) z[j] = (c[j] == 0);
-            if (sizeof(OutT) == 2) {
-                v4i o;
-                o.x = (c[0] & 0xffff) | (c[1] << 16);
-                o.y = (c[2] & 0xffff) | (c[3] << 16);
-                o.z = (c[4] & 0xffff) | (c[5] << 16);
-                o.w = (c[6] & 0xffff) | (c[7] << 16);
-                reinterpret_cast<v4i *>(y)[g] = o;
-            } else {
-                v2i o;
-                o.x = (c[0] & 0xff) | ((c[1] & 0xff) << 8) | ((c[2] & 0xff) << 16) | (c[3] << 24);
-                o.y = (c[4] & 0xff) | ((c[5] & 0xff) << 8) | ((c[6] & 0xff) << 16) | (c[7] << 24);
-                reinterpret_cast<v2i *>(y)[g] = o;
+        for (int j = 0; j < 4; ++j) {
+            const int64_t a0 = (int64_t)(((uint64_t)(uint32_t)a[j].y << 32) | (uint32_t)a[j].x);
+            const int64_t a1 = (int64_t)(((uint64_t)(uint32_t)a[j].w << 32) | (uint32_t)a[j].z);
+            const int c0 = act_one(a0, p), c1 = act_one(a1, p);
+            const size_t pair = pair0 + j * kThreads;
+            if (sizeof(OutT) == 2)
+                reinterpret_cast<int *>(y)[pair] = (c0 & 0xffff) | (c1 << 16);
+            else
+                reinterpret_cast<short *>(y)[pair] = (short)((c0 & 0xff) | (c1 << 8));
+            if (zero_count) zeros += wave_count(c0 == 0) + wave_count(c1 == 0);
+        }
+    }
+    // the groups that do not fill a block trip: one group of 8 per thread of block 0
+    if (blockIdx.x == 0) {
+        const size_t g = trips * kThreads + threadIdx.x;
+        bool z[8] = {false, false, false, false, false, false, false, false};
+        if (g < groups) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int c = act_one(acc[8 * g + j], p);
+                y[8 * g + j] = (OutT)c;
+                z[j] = (c == 0);
             }
         }
         if (zero_count) {
@@ -471,7 +478,7 @@ extern "C" lp_status lp_act(const int64_t *acc_dev, size_t count, int f_acc, lp_
     if (!acc_dev || !y_codes_dev || !aligned16(acc_dev) || !aligned16(y_codes_dev)) return LP_EINVAL;
     hipStream_t st = as_stream(stream);
     const ActParams p = make_act_params(f_acc, qy, relu, r);
-    const int grid = grid_for(count / 8);
+    const int grid = grid_for(count / 8); // one trip of the kernel's loop per block, up to the cap
     if (qy.n > 8)
         hipLaunchKernelGGL(act_kernel<int16_t>, dim3(grid), dim3(kThreads), 0, st, acc_dev,
                            (int16_t *)y_codes_dev, count, p, (unsigned long long *)zero_count_dev);
