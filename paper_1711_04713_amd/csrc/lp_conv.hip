@@ -762,16 +762,20 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         tab[p] = g;
         psum[p] = 0;
     }
-    for (int m = tid; m < BM; m += THREADS) {
-        const int j = m / a.TW, t = m % a.TW;
-        const int fr = fr0 + j, xo = x0 + t;
-        const bool ok = j < a.RH && fr < a.FR && xo < a.Wo;
-        const int img = fr / a.Ho, yo = fr % a.Ho;
-        outoff[m] = ok ? fr * a.Wo + xo : -1;
-        abase_s[m] = ok ? (img * a.Hp + yo - vr0) * a.PW + t : 0;
-        pooloff[m] = (a.pool && ok && !(j & 1) && !(t & 1)) ? (img * (a.Ho >> 1) + (yo >> 1)) * (a.Wo >> 1) + (xo >> 1) : -1;
-    }
-    build_colterms<BN, THREADS>(a, ntile, ctab);
+    // The tables of the tile rows and the channel constants are not needed to request the first
+    // patch: they are built while those requests are in flight (see the first staging below).
+    auto row_tables = [&]() __attribute__((always_inline)) {
+        for (int m = tid; m < BM; m += THREADS) {
+            const int j = m / a.TW, t = m % a.TW;
+            const int fr = fr0 + j, xo = x0 + t;
+            const bool ok = j < a.RH && fr < a.FR && xo < a.Wo;
+            const int img = fr / a.Ho, yo = fr % a.Ho;
+            outoff[m] = ok ? fr * a.Wo + xo : -1;
+            abase_s[m] = ok ? (img * a.Hp + yo - vr0) * a.PW + t : 0;
+            pooloff[m] = (a.pool && ok && !(j & 1) && !(t & 1)) ? (img * (a.Ho >> 1) + (yo >> 1)) * (a.Wo >> 1) + (xo >> 1) : -1;
+        }
+        build_colterms<BN, THREADS>(a, ntile, ctab);
+    };
 
     // Weight slabs: slab t = chunk * taps + tap lives at [chunk][tap][limb][CoutP][64], i.e.
     // consecutive in memory in the order they are consumed; they never pass through LDS (see
@@ -779,19 +783,24 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     const int nslabs = a.nchunks * a.taps;
     const int s0 = part * nslabs / nparts, s1 = (part + 1) * nslabs / nparts; // this workgroup's slabs
     const size_t slab_bytes = (size_t)LIMBS * a.CoutP * CK;
-    __syncthreads(); // the tables are complete
+    constexpr bool LATE_ROWS = LIMBS == 2; // (the one-limb kernels' 128 registers leave no room for the overlap)
+    if constexpr (!LATE_ROWS) row_tables();
+    __syncthreads(); // the patch tables are complete
 
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WMC, wn = wave / WMC;
     const int l32 = lane & 31, kg = lane >> 5;
-    int aoff[MB], apr[MB], apc[MB];
+    int aoff[MB], apr[MB], apc[MB]; // filled once the row tables are visible
+    auto lane_constants = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-        const int row = wm * WROWS + mb * 32 + l32;
-        aoff[mb] = FLAT ? row * PS : (apos[abase_s[row]] & ~3); // start of the row's (r=0, s=0) pixel
-        apr[mb] = FLAT ? 0 : abase_s[row] / a.PW;               // its patch row and column
-        apc[mb] = FLAT ? 0 : abase_s[row] % a.PW;
-    }
+        for (int mb = 0; mb < MB; ++mb) {
+            const int row = wm * WROWS + mb * 32 + l32;
+            aoff[mb] = FLAT ? row * PS : (apos[abase_s[row]] & ~3); // start of the row's (r=0, s=0) pixel
+            apr[mb] = FLAT ? 0 : abase_s[row] / a.PW;               // its patch row and column
+            apc[mb] = FLAT ? 0 : abase_s[row] % a.PW;
+        }
+    };
+    if constexpr (!LATE_ROWS) lane_constants();
     v16i acc[MB][NB][NACC]; // zeroed after the first patch is staged: until then its registers are free
 
     // Activations travel global -> registers -> LDS in batches of APF 16-byte pieces per thread,
@@ -922,8 +931,10 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         }
     };
     constexpr int DEEP = 8;
-    auto stage_activations = [&](int cc, bool deep) __attribute__((always_inline)) {
+    // between(): work that does not depend on the patch, done while the first requests fly
+    auto stage_activations = [&](int cc, bool deep, auto between) __attribute__((always_inline)) {
         if constexpr (FLAT) {
+            between();
             stage_flat();
         } else {
             // two batches of requests in flight; a request past the end reads the last pixel
@@ -936,6 +947,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
                 v4i d[DEEP];
 #pragma unroll
                 for (int j = 0; j < DEEP; ++j) load_piece(cc, j * THREADS, d[j]);
+                between();
 #pragma unroll
                 for (int j = 0; j < DEEP; ++j) store_piece(j * THREADS, d[j]);
                 first = DEEP * THREADS;
@@ -1073,7 +1085,9 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
 #pragma unroll
     for (int j = 0; j < LEAD; ++j) bload(s0 + (j >> 1), j & 1, bh[j], bl[j]);
 
-    stage_activations(cc, true);
+    stage_activations(cc, true, [&] {
+        if constexpr (LATE_ROWS) row_tables();
+    });
     own_sums = true; // every later chunk starts at its first tap
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
@@ -1084,8 +1098,12 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[mb][nb][q][v] = 0;
     int cur[MB];
-    fragment_offsets(cur);
-    __syncthreads(); // the freshly staged patch is visible
+    if constexpr (!LATE_ROWS) fragment_offsets(cur);
+    __syncthreads(); // the freshly staged patch and the row tables are visible
+    if constexpr (LATE_ROWS) {
+        lane_constants();
+        fragment_offsets(cur);
+    }
     if constexpr (PIPE) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) afetch(mb, cur[mb]);
@@ -1114,7 +1132,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         half_step(t, P, integral_constant<int, 1>{}, cur, nxt);
         if (restage) {
             __syncthreads(); // all reads of the previous chunk's activations are done
-            stage_activations(cc, false);
+            stage_activations(cc, false, [] {});
             __syncthreads(); // the freshly staged patch is visible
             if constexpr (PIPE) {
 #pragma unroll
