@@ -40,8 +40,8 @@ def _traffic_for_current_source():
 def measure_extras(lp, torch, lp_inputs, iters=10):
     """The other steps of the path, each alone against its own roofline: the HBM-bound elementwise
     kernels at the size of one 8 x 64 x 224 x 224 activation tensor, the single 64->64 layer at
-    batch 8, the 8-bit conv3_1..conv5_3 layers at batch 64 and the three classifier layers at
-    batch 256 (synthetic codes of the right shapes; parity of these is the tests' job)."""
+    batch 8, the 8-bit conv3_1..conv5_3 layers at batch 64, the Giga1Net conv layers of the paper's
+    Table 1 at batch 32 and the three classifier layers at batch 256 (synthetic codes of the right shapes; parity of these is the tests' job)."""
     import ctypes
 
     def timed(fn, n=iters):
@@ -84,16 +84,17 @@ def measure_extras(lp, torch, lp_inputs, iters=10):
     out["lp_maxpool2x2"] = {"elements": n, "ms": round(ms, 4), "GBps": round(2.5 * n / ms / 1e6, 1)}
     del xf, acc, pooled
 
-    def conv_ms(N, hw, cin, cout, bits):
+    def conv_ms(N, hw, cin, cout, bits, k=3, pad=1):
         dt = torch.int16 if bits > 8 else torch.int8
         lim = 2000 if bits > 8 else 60
         x = torch.randint(0, lim, (N, hw, hw, cin), device="cuda", generator=g).to(dt)
-        w = torch.randint(-lim, lim, (cout, 3, 3, cin), device="cuda", generator=g).to(dt)
+        w = torch.randint(-lim, lim, (cout, k, k, cin), device="cuda", generator=g).to(dt)
         qx, qw, qy = ((16, 4, 12), (16, 1, 15), (16, 6, 10)) if bits > 8 else ((8, 3, 5), (8, 1, 7), (8, 5, 3))
-        d = lp.ConvDesc(N, hw, hw, cin, cout, 3, 3, 1, 1)
+        d = lp.ConvDesc(N, hw, hw, cin, cout, k, k, 1, pad)
         packed = torch.empty(lp.lp_conv_packed_bytes(d, qx, qw), dtype=torch.uint8, device="cuda")
         lp.lp_conv_pack_weights(d, qx, qw, w, packed)
-        y = torch.empty((N, hw, hw, cout), dtype=dt, device="cuda")
+        ho = hw + 2 * pad - k + 1
+        y = torch.empty((N, ho, ho, cout), dtype=dt, device="cuda")
         z = torch.zeros(1, dtype=torch.int64, device="cuda")
         ws = torch.empty(max(lp.lp_conv_workspace_bytes(d, qx, qw), 16), dtype=torch.uint8, device="cuda")
         return timed(lambda: lp.lp_conv_fwd(d, x, qx, packed, qw, qy=qy, y_codes=y, zero_count=z, workspace=ws))
@@ -106,6 +107,14 @@ def measure_extras(lp, torch, lp_inputs, iters=10):
         tot_ms += conv_ms(64, hw, cin, cout, 8)
         tot_macs += 64 * hw * hw * cout * 9 * cin
     out["conv3_1_to_conv5_3_batch64_8bit"] = {"ms": round(tot_ms, 4), "int8_tops": round(2 * tot_macs / tot_ms / 1e9, 1)}
+    # Table 1's Giga1Net conv layers (kernel sizes 1/3/5/7, 3..128 channels) at batch 32, 16 bit
+    tot_ms, tot_macs = 0.0, 0
+    for (_, cin, cout, k, hw, pad, _) in lp_inputs.GIGA1NET_CONV:
+        tot_ms += conv_ms(32, hw, cin, cout, 16, k, pad)
+        ho = hw + 2 * pad - k + 1
+        tot_macs += 32 * ho * ho * cout * k * k * cin
+    out["giga1net_conv_layers_batch32_16bit"] = {"ms": round(tot_ms, 4), "int8_tops": round(8 * tot_macs / tot_ms / 1e9, 1),
+                                                   "images_per_s": round(32 / tot_ms * 1e3, 1)}
     M = 256
     fc = {}
     for name, K, N in (("fc6", 25088, 4096), ("fc7", 4096, 4096), ("fc8", 4096, 1000)):

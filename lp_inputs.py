@@ -28,6 +28,24 @@ VGG16_CONV = [
     ("conv5_3", 512, 512, 14, True),
 ]
 
+# Giga1Net convolution layers (Table 1 of the paper): (name, Cin, Cout, kernel size, input
+# width = height, zero padding, 2x2 max-pool after).  The table gives kernel sizes, channel counts,
+# input sizes and where the pools are, not the paddings; the paddings here are the ones that make
+# each layer's input size equal the previous layer's (pooled) output size at stride 1.
+GIGA1NET_CONV = [
+    ("conv1", 3, 16, 1, 224, 0, True),
+    ("conv2", 16, 16, 7, 112, 1, True),
+    ("conv3", 16, 32, 7, 54, 0, True),
+    ("conv4", 32, 64, 5, 24, 1, False),
+    ("conv5", 64, 64, 5, 22, 1, False),
+    ("conv6", 64, 64, 5, 20, 1, False),
+    ("conv7", 64, 128, 3, 18, 1, False),
+    ("conv8", 128, 128, 3, 18, 1, False),
+    ("conv9", 128, 128, 3, 18, 1, False),
+    ("conv10", 128, 128, 3, 18, 1, False),
+    ("conv11", 128, 128, 3, 18, 1, True),
+]
+
 # (name, K, Nout, ReLU after)
 VGG16_FC = [
     ("fc6", 25088, 4096, True),
@@ -78,6 +96,11 @@ def vgg16_conv_weights(seed=2, layers=None):
         if layers is None or name in layers:
             out.append(he_normal_conv(cout, cin, 3, 3, seed, 100 + i))
     return out
+
+
+def giga1net_conv_weights(seed=5):
+    """He-normal weights [Cout,Cin,k,k] for the eleven Giga1Net conv layers."""
+    return [he_normal_conv(cout, cin, k, k, seed, 100 + i) for i, (_, cin, cout, k, *_rest) in enumerate(GIGA1NET_CONV)]
 
 
 def config3_input(seed=2, batch=32, hw=224):

@@ -12,8 +12,9 @@ from . import lp_oracle as orc
 
 
 def conv_stack(x, weights, pool_after, n=16, n_w=None, threshold=0.0, mode=orc.ROUND_AWAY,
-               threads=1, formats=None, keep_codes=True):
-    """x float32 [N,C,H,W]; weights: list of float32 [Cout,Cin,3,3]; pool_after: list of bool.
+               threads=1, formats=None, keep_codes=True, pads=None):
+    """x float32 [N,C,H,W]; weights: list of float32 [Cout,Cin,R,S]; pool_after: list of bool;
+    pads: zero padding per layer (default 1 everywhere: the 3x3 layers of VGG16); stride 1.
 
     formats (optional): list of dicts {"mw","mo"} (+ "mx" in entry 0) to use frozen formats
     instead of measuring them.  Returns {"mx", "layers": [ {mw, fw, mo, fo, f_acc, zeros,
@@ -28,7 +29,7 @@ def conv_stack(x, weights, pool_after, n=16, n_w=None, threshold=0.0, mode=orc.R
         mw = formats[i]["mw"] if formats else orc.range_float(w, n_w, threshold)[0]
         fw = n_w - mw
         wc, _, _ = orc.quantize(w, n_w, mw, fw, mode)
-        acc = orc.conv(cur, wc, stride=1, pad=1, threads=threads)
+        acc = orc.conv(cur, wc, stride=1, pad=1 if pads is None else pads[i], threads=threads)
         f_acc = fx + fw
         mo = formats[i]["mo"] if formats else orc.range_acc(acc, f_acc, True, n, threshold)[0]
         fo = n - mo

@@ -10,10 +10,12 @@ from . import binding as lp
 
 
 class ConvStack:
-    """A chain of 3x3/stride-1/pad-1 low-precision conv layers with frozen per-layer formats.
+    """A chain of stride-1 low-precision conv layers with frozen per-layer formats.
 
-    weights: list of float32 CUDA tensors [Cout][R][S][Cin]; pool_after: list of bool.
-    n_act / n_w: total bits of activations / weights.  Formats are fixed by calibrate().
+    weights: list of float32 CUDA tensors [Cout][R][S][Cin]; pool_after: list of bool; pad: zero
+    padding, one int for all layers or a list (VGG16: 3x3 kernels, pad 1; Table 1's Giga1Net mixes
+    kernel sizes 1/3/5/7).  n_act / n_w: total bits of activations / weights.  Formats are fixed
+    by calibrate().
     """
 
     def __init__(self, weights, pool_after, n_act=16, n_w=16, loss_threshold=0.0, r=lp.LP_ROUND_NEAREST_AWAY,
@@ -22,7 +24,9 @@ class ConvStack:
         (the unpooled codes of such a layer are then never written; layer["y"] is None)."""
         assert len(weights) == len(pool_after)
         self.fuse_pool = fuse_pool
-        self.n_act, self.n_w, self.thr, self.r, self.pad = n_act, n_w, loss_threshold, r, pad
+        self.n_act, self.n_w, self.thr, self.r = n_act, n_w, loss_threshold, r
+        self.pads = list(pad) if isinstance(pad, (list, tuple)) else [pad] * len(weights)
+        assert len(self.pads) == len(weights)
         self.pool_after = list(pool_after)
         self.w_float = weights
         self.range_ws = torch.empty(lp.LP_RANGE_WORKSPACE_WORDS, dtype=torch.int64, device="cuda")
@@ -40,7 +44,11 @@ class ConvStack:
 
     def _desc(self, i, N, H, W, pool=0):
         cout, R, S, cin = self.w_float[i].shape
-        return lp.ConvDesc(N, H, W, cin, cout, R, S, 1, self.pad, pool)
+        return lp.ConvDesc(N, H, W, cin, cout, R, S, 1, self.pads[i], pool)
+
+    def _out_hw(self, i, H, W):
+        _, R, S, _ = self.w_float[i].shape
+        return H + 2 * self.pads[i] - R + 1, W + 2 * self.pads[i] - S + 1
 
     def calibrate(self, x_float):
         """Fix the input format and every layer's output format from the dynamic range seen on
@@ -56,6 +64,7 @@ class ConvStack:
             d = self._desc(i, N, H, W)
             packed = torch.empty(lp.lp_conv_packed_bytes(d, q_in, self.qw[i]), dtype=torch.uint8, device="cuda")
             lp.lp_conv_pack_weights(d, q_in, self.qw[i], self.w_codes[i], packed)
+            H, W = self._out_hw(i, H, W)
             acc = torch.empty((N, H, W, d.Cout), dtype=torch.int64, device="cuda")
             lp.lp_conv_fwd(d, cur, q_in, packed, self.qw[i], acc_out=acc, r=self.r)
             f_acc = q_in.f + self.qw[i].f
@@ -96,6 +105,7 @@ class ConvStack:
                         raise
             packed = torch.empty(lp.lp_conv_packed_bytes(d, q_in, self.qw[i]), dtype=torch.uint8, device="cuda")
             lp.lp_conv_pack_weights(d, q_in, self.qw[i], self.w_codes[i], packed)
+            H, W = self._out_hw(i, H, W)      # from here on: the layer's output size
             y = None if fused else torch.empty((N, H, W, d.Cout), dtype=dt, device="cuda")
             p = None
             if pool:

@@ -17,8 +17,8 @@ def _nhwc(a):
     return to_dev(np.ascontiguousarray(a.transpose(0, 2, 3, 1)))
 
 
-def _run_stack(x, ws, pools, n_act=16, n_w=16, calib=None, fuse_pool=False):
-    st = ConvStack([_nhwc(w) for w in ws], pools, n_act=n_act, n_w=n_w, fuse_pool=fuse_pool)
+def _run_stack(x, ws, pools, n_act=16, n_w=16, calib=None, fuse_pool=False, pad=1):
+    st = ConvStack([_nhwc(w) for w in ws], pools, n_act=n_act, n_w=n_w, fuse_pool=fuse_pool, pad=pad)
     xd = _nhwc(x)
     st.calibrate(xd[:calib] if calib else xd)
     N, H, W, _ = xd.shape
@@ -64,6 +64,28 @@ def test_small_vgg_like_stack_16bit(oracle):
             assert any(G["fused_pool"] for G in st.layers)
     for L in want["layers"]:
         assert 0.2 < L["zeros"] / L["count"] < 0.8       # ~half zeros with zero-mean random weights
+
+
+def test_giga1net_conv_stack_full_resolution(oracle):
+    """The eleven conv layers of Table 1 (kernel sizes 1, 7, 7, 5, 5, 5, 3 x 5; 3..128 channels;
+    224x224 down to 18x18; four pools) at their true shapes, two images: every layer's codes, pooled
+    codes and zero count against the oracle chain, with the pools as separate kernels and fused."""
+    spec = lp_inputs.GIGA1NET_CONV
+    x = lp_inputs.config3_input(seed=5, batch=2)
+    ws = lp_inputs.giga1net_conv_weights(seed=5)
+    pools = [p for (*_, p) in spec]
+    pads = [pad for (*_, pad, _) in spec]
+    hw = 224
+    for (name, cin, cout, k, hw_in, pad, pool), w in zip(spec, ws):   # the table's sizes chain up with these pads
+        assert hw == hw_in and w.shape == (cout, cin, k, k), name
+        hw = hw + 2 * pad - k + 1
+        hw = hw // 2 if pool else hw
+    assert hw == 9
+    want = ovgg.conv_stack(x, ws, pools, n=16, threads=16, pads=pads)
+    for fuse in (False, True):
+        st, out = _run_stack(x, ws, pools, fuse_pool=fuse, pad=pads)
+        _compare(st, out, want)
+        assert all(G["info"]["path"] == 1 for G in st.layers)       # every layer on the MFMA kernel
 
 
 def test_vgg16_first_two_blocks_full_resolution(oracle):
