@@ -273,3 +273,27 @@ def test_conv_stack_chain_properties():
     frozen = [{"mx": out["mx"], "mw": L["mw"], "mo": L["mo"]} for L in out["layers"]]
     again = vgg.conv_stack(x, ws, pools, n=16, formats=frozen)
     assert np.array_equal(again["final"], out["final"])
+
+
+def test_conv_stack_per_layer_kernel_sizes_and_paddings(oracle):
+    """Table 1's Giga1Net mixes kernel sizes 1/7/5/3 with paddings that make the sizes chain up:
+    the chain with per-layer paddings must equal the pinned steps composed by hand, layer by layer."""
+    import lp_inputs
+    from oracle import vgg
+
+    x = lp_inputs.uniform01((2, 3, 20, 20), seed=12)
+    ws = [lp_inputs.he_normal_conv(4, 3, 1, 1, 12, 1), lp_inputs.he_normal_conv(6, 4, 7, 7, 12, 2),
+          lp_inputs.he_normal_conv(5, 6, 5, 5, 12, 3), lp_inputs.he_normal_conv(7, 5, 3, 3, 12, 4)]
+    pools, pads = [True, False, False, True], [0, 1, 1, 1]
+    out = vgg.conv_stack(x, ws, pools, n=16, threads=2, pads=pads)
+    mx = oracle.range_float(x, 16)[0]
+    cur, fx = oracle.quantize(x, 16, mx, 16 - mx)[0], 16 - mx
+    for w, pool, pad, L in zip(ws, pools, pads, out["layers"]):
+        mw = oracle.range_float(w, 16)[0]
+        acc = oracle.conv(cur, oracle.quantize(w, 16, mw, 16 - mw)[0], stride=1, pad=pad)
+        assert acc.shape[2] == cur.shape[2] + 2 * pad - w.shape[2] + 1
+        mo = oracle.range_acc(acc, fx + 16 - mw, True, 16)[0]
+        codes, zeros = oracle.act(acc, fx + 16 - mw, 16, mo, 16 - mo, True, oracle.ROUND_AWAY)
+        assert (L["mw"], L["mo"], L["zeros"]) == (mw, mo, zeros) and np.array_equal(L["codes"], codes)
+        cur, fx = (oracle.maxpool2x2(codes) if pool else codes), 16 - mo
+    assert np.array_equal(out["final"], cur) and out["final"].shape == (2, 7, 2, 2)
