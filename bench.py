@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0
 # profiles/): average bytes per launch over the 13 launches of one step, already scaled by the
 # copy-kernel factor.  Valid only for the kernel source it was measured on (sha256 of lp_conv.hip);
 # reported as null for any other source.
-TRAFFIC_RECORD = {"lp_conv_sha256": "e136ae64cce84a465a3bde95b83bb9c4711a837113711b0b1636a5f2861f77a0", "bytes_per_launch": 123376252}
+TRAFFIC_RECORD = {"lp_conv_sha256": "f07c83177241e9489a914e500d408df452342cf75db83e5d85bbd3f5bb1a6644", "bytes_per_launch": 123324271}
 
 
 def _traffic_for_current_source():
