@@ -41,8 +41,6 @@ struct Plan {
     int pool;    // the epilogue stores 2x2 maxima instead of the codes
     int limbs;   // 1: int8 x int8, 2: 16-bit x 16-bit
     int flat;    // whole window gathered as one K <= 64 slab (tiny Cin)
-    int fc;      // inner product on 16-bit codes: both operands straight into registers (fc_mfma_kernel)
-    int fc_rows, fc_kp; // its input as limb planes: rows x padded K
     int taps, ksteps; // slabs per chunk, K=32 MFMA steps per slab
     int Ho, Wo, Hp, FR;
     int nchunks, CoutP, BN;
@@ -64,7 +62,6 @@ struct Plan {
 // [die][tail tile][part].
 struct WorkspaceLayout {
     size_t partials, total;
-    size_t planes, sums; // inner-product kernel: the input's limb planes and row sums
 };
 
 static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -274,19 +271,12 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
             p.KMUL = k;
         }
         p.lds_bytes = mfma_lds_bytes(p.limbs, p.PRA, p.PW, p.PITCH / PS, p.BN, p.flat);
-        // an inner product (1x1 window on 1x1 images) of 16-bit codes runs in fc_mfma_kernel when
-        // the caller passes a workspace (without one every tile is whole anyway)
-        p.fc_rows = d->N;
-        p.fc_kp = p.nchunks * CK;
-        p.fc = (d->H == 1 && d->W == 1 && d->R == 1 && d->S == 1 && d->pad == 0 && !p.flat && !p.pool && p.limbs == 2 &&
-                p.TW == 1 && 2LL * p.fc_rows * p.fc_kp < (1LL << 31)) ? 1 : 0;
         {
             // workgroup slots per die: what registers and LDS allow
             const int total = p.tiles_m * p.tiles_n, nslabs = p.nchunks * p.taps;
             // (two-limb kernel: three waves per SIMD by registers; one-limb kernels: four)
-            // (the inner-product kernel: one workgroup of eight waves)
             const int wg_per_cu =
-                p.fc ? 1 : (int)std::max<size_t>(1, std::min<size_t>(p.limbs == 2 ? 3 : 4, (160 * 1024) / p.lds_bytes));
+                (int)std::max<size_t>(1, std::min<size_t>(p.limbs == 2 ? 3 : 4, (160 * 1024) / p.lds_bytes));
             const int slots = wg_per_cu * (kCUs / kXCDs);
             p.per_xcd = (total + kXCDs - 1) / kXCDs;
             p.full_per_xcd = p.per_xcd / slots * slots;
@@ -410,10 +400,6 @@ struct ConvArgs {
     int fast; // 32-bit requantization is exact for this call (see epilogue)
     int pool; // store the 2x2 maxima of the codes (planner guarantees the tile geometry)
     ActParams act;
-    // inner-product kernel: the input rows as two int8 limb planes [Kp / 64][K half][rows][32] and their sums
-    const unsigned char *xh, *xl;
-    const int *xsum;
-    int Kp;
 };
 
 __device__ __forceinline__ int64_t bias_term(const ConvArgs &a, int co)
@@ -1233,203 +1219,6 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
 }
 
 
-// ------------------------------------------------------------------- inner product
-// LPInnerProduct on 16-bit codes has nothing to reuse inside a tile row (one "tap" per 64-channel
-// chunk), so staging the rows through LDS once per slab, as the convolution does, costs more than
-// the MFMAs it feeds.  Here both operands go from L2 straight into MFMA operand registers: a
-// small pass first writes the input rows as two int8 limb planes (and their code sums, the
-// 128 * sum(a) correction), then every wave streams its 64 rows and 32 weight rows with no LDS
-// and no barrier in the loop.  Tiling, work split along the reduction, partial sums, epilogue
-// and finishing kernel are the convolution's (a row of the batch is a "pixel").
-template <typename XT>
-__global__ __launch_bounds__(256) void fc_split_kernel(const XT *__restrict__ x, unsigned char *__restrict__ xh,
-                                                       unsigned char *__restrict__ xl, int *__restrict__ xsum,
-                                                       int M, int K, int Kp)
-{
-    // one workgroup per row; 8 codes per thread and trip
-    const int row = blockIdx.x;
-    const short *src = (const short *)x + (size_t)row * K;
-    int sum = 0;
-    for (int k0 = threadIdx.x * 8; k0 < Kp; k0 += 256 * 8) {
-        unsigned h[2] = {0, 0}, l[2] = {0, 0};
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int k = k0 + j;
-            if (k < K) { // beyond K: limbs (0, 0), which drop out of every term
-                const int v = src[k];
-                sum += v;
-                h[j >> 2] |= (unsigned)((v >> 8) & 255) << (8 * (j & 3));
-                l[j >> 2] |= (unsigned)((v & 255) ^ 128) << (8 * (j & 3));
-            }
-        }
-        // slab-major and half-major, like the packed weights: [chunk][K half][row][32], so that the
-        // 16-byte pieces the lanes of a wave request together are consecutive memory
-        const size_t at = (((size_t)(k0 / CK) * 2 + ((k0 % CK) >> 5)) * M + row) * 32 + (k0 & 31);
-        *(v2u *)(xh + at) = (v2u){h[0], h[1]};
-        *(v2u *)(xl + at) = (v2u){l[0], l[1]};
-    }
-    __shared__ int part[4];
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) sum += __shfl_down(sum, off, 64);
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = sum;
-    __syncthreads();
-    if (threadIdx.x == 0) xsum[row] = part[0] + part[1] + part[2] + part[3];
-}
-
-// Eight waves (4 along the rows x 2 along the channels) of 32 x 32 each: 48 accumulator registers
-// per lane leave room for the weight operands of seven K halves and the input operands of three
-// to be in flight per wave, which is what streaming the weights from HBM at its latency takes.
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void fc_mfma_kernel(const ConvArgs a)
-{
-    constexpr int LIMBS = 2, NB = 1, MB = 1, THREADS = 512, BN = 64, NACC = 3;
-    constexpr int WMC = BM / 32; // 4 waves along the rows
-    __shared__ int outoff[BM];
-    __shared__ int rowsum[BM];
-    __shared__ int pooloff[BM]; // no pooling here: all -1
-    __shared__ __align__(16) int ctab[3 * BN];
-    __shared__ unsigned wave_zeros[THREADS / 64];
-    const int tid = threadIdx.x;
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    int tl = slot, part = 0, nparts = 1;
-    if (slot >= a.full_per_xcd) {
-        const int u = slot - a.full_per_xcd;
-        tl = a.full_per_xcd + u / a.split;
-        part = u % a.split;
-        nparts = a.split;
-    }
-    const int wi = xcd * a.per_xcd + tl;
-    if (tl >= a.per_xcd || wi >= a.total_work) {
-        if (a.zero_partial && tid == 0) a.zero_partial[blockIdx.x] = 0;
-        return;
-    }
-    const int mtile = wi / a.tiles_n, ntile = wi % a.tiles_n;
-    const int row0 = mtile * a.RH; // a tile is RH <= BM consecutive rows of the batch
-    const int rows = a.FR;         // = M
-    for (int m = tid; m < BM; m += THREADS) {
-        const bool ok = m < a.RH && row0 + m < rows;
-        outoff[m] = ok ? row0 + m : -1;
-        pooloff[m] = -1;
-        rowsum[m] = ok ? a.xsum[row0 + m] : 0;
-    }
-    build_colterms<BN, THREADS>(a, ntile, ctab);
-    const int nslabs = a.nchunks; // one slab per 64-channel chunk
-    const int s0 = part * nslabs / nparts, s1 = (part + 1) * nslabs / nparts;
-    const int slab_bytes = LIMBS * a.CoutP * CK;
-
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave % WMC, wn = wave / WMC;
-    const int l32 = lane & 31, kg = lane >> 5;
-    // one descriptor per operand; lane offsets never change, the slab is a scalar offset, the
-    // K half an immediate
-    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<unsigned char *>(a.wp), 0, (int)((unsigned)nslabs * (unsigned)slab_bytes), 0x00020000);
-    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<unsigned char *>(a.xh), 0, (int)(2u * (unsigned)rows * (unsigned)a.Kp), 0x00020000);
-    const int plane = (int)(a.xl - a.xh); // the low plane follows the high one
-    const int blane = (ntile * BN + wn * 32 + l32) * 32 + kg * 16;
-    const int limb_bytes = a.CoutP * CK, bhalf = a.CoutP * 32;
-    const int alane = min(row0 + wm * 32 + l32, rows - 1) * 32 + kg * 16;
-    const int aslab = rows * CK, ahalf = rows * 32; // bytes of one chunk / one K half of all rows in a limb plane
-
-    constexpr int NSB = 8, LEADB = 7; // weight sets: seven K halves ahead
-    constexpr int NSA = 4, LEADA = 3; // input-row sets: three K halves ahead
-    constexpr int UT = 4;             // slabs per rotation of both
-    v4i bh[NSB], bl[NSB], ah[NSA], al[NSA];
-    // operands of K half number g of this workgroup's range (slab s0 + g / 2, half g % 2): past the
-    // last slab the last one is read again, never used
-    auto bload = [&](int t, int half, v4i &h, v4i &l) __attribute__((always_inline)) {
-        const int off = min(t, s1 - 1) * slab_bytes + (half ? bhalf : 0);
-        const auto vh = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, blane, off, 0);
-        const auto vl = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, blane, off + limb_bytes, 0);
-        h = (v4i){(int)vh[0], (int)vh[1], (int)vh[2], (int)vh[3]};
-        l = (v4i){(int)vl[0], (int)vl[1], (int)vl[2], (int)vl[3]};
-    };
-    auto aload = [&](int t, int half, v4i &h, v4i &l) __attribute__((always_inline)) {
-        const int off = min(t, s1 - 1) * aslab + (half ? ahalf : 0);
-        const auto vh = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, alane, off, 0);
-        const auto vl = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, alane, off + plane, 0);
-        h = (v4i){(int)vh[0], (int)vh[1], (int)vh[2], (int)vh[3]};
-        l = (v4i){(int)vl[0], (int)vl[1], (int)vl[2], (int)vl[3]};
-    };
-    v16i acc[MB][NB][NACC];
-#pragma unroll
-    for (int q = 0; q < NACC; ++q)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[0][0][q][v] = 0;
-    // in flight before the loop: the first LEADB weight halves and LEADA input halves, in the order
-    // the loop would have requested them
-#pragma unroll
-    for (int g = 0; g < LEADB; ++g) {
-        bload(s0 + (g >> 1), g & 1, bh[g], bl[g]);
-        if (g >= LEADB - LEADA) aload(s0 + ((g - (LEADB - LEADA)) >> 1), (g - (LEADB - LEADA)) & 1, ah[g - (LEADB - LEADA)], al[g - (LEADB - LEADA)]);
-    }
-    using std::integral_constant;
-    auto half_step = [&](int t, auto H) __attribute__((always_inline)) {
-        constexpr int h = decltype(H)::value; // K half number inside the rotation, 0..2*UT-1
-        constexpr int hh = h & 1;
-        constexpr int ub = h % NSB, fb = (h + LEADB) % NSB, ua = h % NSA, fa = (h + LEADA) % NSA;
-        bload(t + ((hh + LEADB) >> 1), (hh + LEADB) & 1, bh[fb], bl[fb]);
-        aload(t + ((hh + LEADA) >> 1), (hh + LEADA) & 1, ah[fa], al[fa]);
-        __builtin_amdgcn_sched_barrier(0); // the requests leave before this half's MFMAs
-        acc[0][0][0] = mfma_i8(bh[ub], ah[ua], acc[0][0][0]);
-        acc[0][0][1] = mfma_i8(bl[ub], ah[ua], acc[0][0][1]);
-        acc[0][0][2] = mfma_i8(bl[ub], al[ua], acc[0][0][2]);
-        acc[0][0][1] = mfma_i8(bh[ub], al[ua], acc[0][0][1]);
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    // one slab = two K halves; whole rotations inside the loop, the slabs left over after it
-    auto slab = [&](int t, auto J) __attribute__((always_inline)) {
-        half_step(t, integral_constant<int, 2 * decltype(J)::value>{});
-        half_step(t, integral_constant<int, 2 * decltype(J)::value + 1>{});
-    };
-    int t = s0;
-    for (; t + UT <= s1; t += UT) {
-        slab(t, integral_constant<int, 0>{});
-        slab(t + 1, integral_constant<int, 1>{});
-        slab(t + 2, integral_constant<int, 2>{});
-        slab(t + 3, integral_constant<int, 3>{});
-    }
-    if (t < s1) {
-        slab(t, integral_constant<int, 0>{});
-        if (t + 1 < s1) {
-            slab(t + 1, integral_constant<int, 1>{});
-            if (t + 2 < s1) slab(t + 2, integral_constant<int, 2>{});
-        }
-    }
-    __syncthreads(); // the tables are complete (nothing in the loop needed them)
-
-    if (nparts > 1) {
-        // a part of a tail tile: accumulators and row sums for the finishing kernel, in the layout
-        // of the convolution kernel's 2 x 2 waves of 64 x 32 (this wave's rows are row block wm % 2
-        // of that kernel's wave (wm / 2, wn))
-        const int tail_tile = xcd * (a.per_xcd - a.full_per_xcd) + (tl - a.full_per_xcd);
-        v4i *mine = (v4i *)(a.partials + ((size_t)tail_tile * nparts + part) * a.part_bytes);
-        const int mb2 = wm & 1, tid2 = (wn * 2 + (wm >> 1)) * 64 + lane;
-#pragma unroll
-        for (int q = 0; q < NACC; ++q)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const v16i &c = acc[0][0][q];
-                mine[((mb2 * NACC + q) * 4 + g) * 256 + tid2] = (v4i){c[4 * g], c[4 * g + 1], c[4 * g + 2], c[4 * g + 3]};
-            }
-        int *rs = (int *)(mine + 2 * NACC * 4 * 256);
-        for (int m = tid; m < BM; m += THREADS) rs[m] = part == 0 ? rowsum[m] : 0; // the parts' sums are added up
-        if (a.zero_partial && tid == 0) a.zero_partial[blockIdx.x] = 0;
-        return;
-    }
-    const unsigned zeros = tile_epilogue<LIMBS, NB, MB, THREADS, MB, 4>(
-        a, acc, [&](int m) { return rowsum[m]; }, outoff, pooloff, ctab, ntile, 0, 0);
-    if (a.zero_partial) {
-        if (lane == 0) wave_zeros[wave] = zeros;
-        __syncthreads();
-        if (tid == 0) {
-            unsigned total = 0;
-            for (int w = 0; w < THREADS / 64; ++w) total += wave_zeros[w];
-            a.zero_partial[blockIdx.x] = total;
-        }
-    }
-}
-
 // Finishes the tail tiles.  A tile's parts are added up and the epilogue run by 4 * MB workgroups,
 // one per (32-row block, channel group of the MFMA layout): each thread then needs only NB * NACC
 // 16-byte pieces per part, so the pieces of all parts are requested together and the memory
@@ -1572,16 +1361,11 @@ static lp_status launch_mfma(const ConvArgs &a, const Plan &p, int grid, int tai
 
 static WorkspaceLayout workspace_layout(const Plan &p)
 {
-    WorkspaceLayout w = {0, 0, 0, 0};
+    WorkspaceLayout w = {0, 0};
     if (p.path != PATH_MFMA) return w;
     const size_t tails = (size_t)kXCDs * (p.per_xcd - p.full_per_xcd);
     w.partials = round_up((size_t)p.grid * sizeof(unsigned), 256);
     w.total = w.partials + tails * p.split * p.part_bytes;
-    if (p.fc) {
-        w.planes = round_up(w.total, 256);
-        w.sums = w.planes + round_up((size_t)2 * p.fc_rows * p.fc_kp, 256);
-        w.total = w.sums + round_up((size_t)p.fc_rows * sizeof(int), 256);
-    }
     return w;
 }
 
@@ -1662,20 +1446,7 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     if (p.pool && !(a.fast && a.y16 && d->Cout % 4 == 0)) return LP_EUNSUPPORTED;
     lp_status st2;
     const int tails = a.split > 1 ? kXCDs * (p.per_xcd - p.full_per_xcd) : 0; // finishing workgroups
-    if (p.fc && workspace) {
-        // limb planes and row sums of the input rows, then both operands from registers
-        unsigned char *planes = (unsigned char *)workspace + wl.planes;
-        a.xh = planes;
-        a.xl = planes + (size_t)p.fc_rows * p.fc_kp;
-        a.xsum = (const int *)((unsigned char *)workspace + wl.sums);
-        a.Kp = p.fc_kp;
-        hipLaunchKernelGGL(fc_split_kernel<int16_t>, dim3(p.fc_rows), dim3(256), 0, hs, (const int16_t *)x,
-                           planes, planes + (size_t)p.fc_rows * p.fc_kp, (int *)((unsigned char *)workspace + wl.sums),
-                           p.fc_rows, d->Cin, p.fc_kp);
-        hipLaunchKernelGGL(fc_mfma_kernel, dim3(grid), dim3(512), 0, hs, a);
-        if (tails) hipLaunchKernelGGL((conv_finish_kernel<2, 1, 2>), dim3(tails * 8), dim3(256), 0, hs, a, grid);
-        st2 = launch_status();
-    } else if (p.flat) st2 = launch_mfma<2, 1, true, 2>(a, p, grid, tails, hs);
+    if (p.flat) st2 = launch_mfma<2, 1, true, 2>(a, p, grid, tails, hs);
     else if (p.limbs == 2) st2 = launch_mfma<2, 1, false, 2>(a, p, grid, tails, hs);
     else st2 = p.BN == 128 ? launch_mfma<1, 2, false, 2>(a, p, grid, tails, hs) : launch_mfma<1, 1, false, 2>(a, p, grid, tails, hs);
     if (st2 != LP_OK || tails || !counting) return st2;
