@@ -1440,8 +1440,12 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     // a right shift of 1..31 bits, and sums small enough that no int32 piece can overflow
     // (K <= 8192 keeps |HH|, |HL+LH| and the folded constants below 2^29).
     const long long K = (long long)d->R * d->S * d->Cin;
+    // Its stores address the output with 32-bit byte offsets from the tile's first pixel: the
+    // pixels of a tile (RH rows of the stacked output, all columns in between) must span less
+    // than 2^31 bytes, which only fails for absurdly wide rows.
+    const bool span_ok = (unsigned long long)p.RH * p.Wo * d->Cout * (a.y16 ? 2 : 1) < (1ull << 31);
     a.fast = (y && !acc_out && relu && r == LP_ROUND_NEAREST_AWAY && a.act.s >= 1 && a.act.s <= 31 &&
-              K <= 8192 && (!bias || a.bias_shift <= 24)) ? 1 : 0;
+              K <= 8192 && (!bias || a.bias_shift <= 24) && span_ok) ? 1 : 0;
     a.pool = p.pool;
     if (p.pool && !(a.fast && a.y16 && d->Cout % 4 == 0)) return LP_EUNSUPPORTED;
     lp_status st2;
