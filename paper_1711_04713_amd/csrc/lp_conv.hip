@@ -118,12 +118,29 @@ static void choose_swizzle(int pw, int tw, int rh, int R, int S, int *pitch_px, 
         }
 }
 
+// 16-byte pieces a thread requests per batch while staging a patch (two batches are in flight).
+// Three fit the two-limb kernel's registers as well, but the patches of the VGG16 layers are 6 to
+// 7 pieces per thread, which batches of two cover in 8 and batches of three in 12 (measured: 2 %
+// slower); four, which would put a whole patch in flight at once, spill.
+constexpr int kStageBatch = 2;
+
+// Entries of the per-pixel patch tables.  The staging loops run whole batches of pieces, so they
+// overshoot the patch by less than two double batches and the first, deep batch covers 8 * 256
+// pieces whatever the patch size; the entries past the patch send those pieces to a source
+// offset that reads as zeros and to a parking slot behind the plane.
+static int patch_table_len(int limbs, int npixa, int flat)
+{
+    if (flat) return std::max(npixa, BM);
+    const int per_pass = 256 / (limbs == 2 ? 8 : 4); // pixels a pass of all threads covers
+    return std::max(npixa + 2 * kStageBatch * per_pass, 8 * per_pass);
+}
+
 // LDS: tables (3*ntab + 2*BM ints, 3*bn ints of channel constants, BM pooled offsets), staged patch (one plane per
 // limb); the flat variant also parks the raw patch (at most 8 KB)
 static size_t mfma_lds_bytes(int limbs, int pra, int pw, int pitch_px, int bn, int flat)
 {
-    const int ntab = std::max(pra * pw, BM);
-    const size_t plane = flat ? (size_t)BM * PS : (size_t)pra * pitch_px * PS;
+    const int ntab = patch_table_len(limbs, pra * pw, flat);
+    const size_t plane = flat ? (size_t)BM * PS : (size_t)pra * pitch_px * PS + PS; // + the slot overshoot pieces are parked in
     size_t tables = round_up((size_t)(3 * ntab + 2 * BM) * 4, 16) + (size_t)3 * bn * 4 + (size_t)BM * 4;
     return tables + (size_t)limbs * plane + (flat ? (size_t)2 * 64 * PS : 0); // flat: the raw patch
 }
@@ -742,9 +759,10 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     const int vr0 = (fr0 / a.Ho) * a.Hp + fr0 % a.Ho;
 
     const int NPIXA = a.NPIXA;
-    int *tab = (int *)smem;          // staged pixel -> input pixel index, -1 outside the image
+    int *tab = (int *)smem;          // staged pixel -> byte offset of its codes in x, all ones outside the image
+                                     // (FLAT: input pixel index, -1 outside)
     int *psum = tab + a.NTAB;        // per staged pixel (FLAT: per tile row): sum of its codes
-    int *apos = psum + a.NTAB;       // staged pixel -> byte offset inside a limb plane
+    int *apos = psum + a.NTAB;       // staged pixel -> byte offset inside a limb plane | swizzle key << 4
     int *outoff = apos + a.NTAB;     // tile row -> output pixel index, -1 if not an output
     int *abase_s = outoff + BM;      // tile row -> staged pixel of its (r=0, s=0) tap
     int *ctab = (int *)(smem + (((size_t)(3 * a.NTAB + 2 * BM) * 4 + 15) & ~(size_t)15)); // channel constants
@@ -754,17 +772,21 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     unsigned char *Bsm = Asm + (size_t)LIMBS * APL;
 
     const int tid = threadIdx.x;
+    // Entries past the patch (the staging loops overshoot it by up to a few batches) read as
+    // zeros and are parked in the spare slot at the end of a plane.
+    const unsigned px_bytes = (unsigned)a.Cin * (LIMBS == 2 ? 2u : 1u);
     for (int p = tid; p < a.NTAB; p += THREADS) {
-        int g = -1;
+        int g = -1, pos = APL - PS;
         if (p < NPIXA) {
             const int pr = p / a.PW, pc = p % a.PW;
             const int off = pr * a.PITCH + pc * PS;
-            apos[p] = off | ((a.KMUL == 4 ? off >> 8 : (pc >> 2) + a.KMUL * pr) & 3); // offset | swizzle key
+            pos = off | (((a.KMUL == 4 ? off >> 8 : (pc >> 2) + a.KMUL * pr) & 3) << 4);
             const int vr = vr0 + pr;
             const int n = vr / a.Hp, iy = vr % a.Hp - a.pad, ix = x0 - a.pad + pc;
             if (n < a.N && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) g = (n * a.H + iy) * a.W + ix;
         }
-        tab[p] = g;
+        tab[p] = FLAT ? g : (g >= 0 ? (int)((unsigned)g * px_bytes) : -1);
+        apos[p] = pos;
         psum[p] = 0;
     }
     // The tables of the tile rows and the channel constants are not needed to request the first
@@ -800,7 +822,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             const int row = wm * WROWS + mb * 32 + l32;
-            aoff[mb] = FLAT ? row * PS : (apos[abase_s[row]] & ~3); // start of the row's (r=0, s=0) pixel
+            aoff[mb] = FLAT ? row * PS : (apos[abase_s[row]] & ~0x30); // start of the row's (r=0, s=0) pixel
             apr[mb] = FLAT ? 0 : abase_s[row] / a.PW;               // its patch row and column
             apc[mb] = FLAT ? 0 : abase_s[row] % a.PW;
         }
@@ -815,7 +837,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     // A chunk's channel sums are collected by the part that holds the chunk's first tap, so that
     // parts which share a chunk do not count it twice.
     bool own_sums = (s0 % a.taps) == 0;
-    constexpr int APF = 2;
+    constexpr int APF = kStageBatch;
     constexpr int PIECES = (LIMBS == 2) ? 8 : 4;
     constexpr int ESZ_X = (LIMBS == 2) ? 2 : 1;
     v4i aregA[APF], aregB[APF];
@@ -826,48 +848,43 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<void *>(a.x), 0, (int)((unsigned)(a.N * a.H * a.W) * (unsigned)a.Cin * ESZ_X), 0x00020000);
     // piece number `first + tid` of chunk cc: request it / unpack it and park it in LDS
+    // A staged pixel's table entries carry everything that does not depend on the chunk, so a
+    // piece costs one table read and one add on the way in, one table read and one xor on the
+    // way out: the source offset is the pixel's entry plus the piece's channel offset (a
+    // saturating add: either being all ones, the sum is all ones and the piece reads as zeros),
+    // the LDS position is the pixel's entry with the thread's piece folded in by an xor (the
+    // swizzle key sits at bit 4, the piece's slot at bits 4..5, its half at bit 3).
+    const int piece_xor = LIMBS == 2 ? ((apiece >> 1) << 4) | ((apiece & 1) << 3) : apiece << 4;
     auto load_piece = [&](int cc, int first, v4i &reg) __attribute__((always_inline)) {
         const int ch = cc * CK + apiece * (CK / PIECES);
-        const int p = min(apix0 + first / PIECES, NPIXA - 1);
-        const int g = tab[p];
-        const unsigned off = (unsigned)(g * a.Cin + ch) * ESZ_X; // computed on every lane: a select, not a branch
-        const int ok = (g >= 0) & (ch < a.Cin);
-        const auto v = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)(ok ? off : 0xffffffffu), 0, 0);
+        const unsigned chb = ch < a.Cin ? (unsigned)ch * ESZ_X : 0xffffffffu;
+        const unsigned off = __builtin_elementwise_add_sat((unsigned)tab[apix0 + first / PIECES], chb);
+        const auto v = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)off, 0, 0);
         reg = (v4i){(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
     };
     auto store_piece = [&](int first, const v4i &reg) __attribute__((always_inline)) {
-        {
-            const int p = apix0 + first / PIECES;
-            const bool live = p < NPIXA;
-            const int pos = apos[min(p, NPIXA - 1)];
-            const v4i v = reg;
-            if constexpr (LIMBS == 2) {
-                v2i hi, lo;
-                hi.x = (int)__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x07050301u);
-                hi.y = (int)__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x07050301u);
-                lo.x = (int)(__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x06040200u) ^ 0x80808080u);
-                lo.y = (int)(__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x06040200u) ^ 0x80808080u);
-                // sum of the eight codes: four two-element dot products with (1, 1)
-                const v2s ones = {1, 1};
-                const int w0 = v.x, w1 = v.y, w2 = v.z, w3 = v.w;
-                int sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, w0), ones, 0, false);
-                sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, w1), ones, sum, false);
-                sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, w2), ones, sum, false);
-                sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, w3), ones, sum, false);
-                // the 8 pieces of a pixel sit in 8 adjacent lanes: add them up with DPP lane
-                // exchanges (xor 1, xor 2 inside quads, then mirror inside the half row)
-                sum += __builtin_amdgcn_mov_dpp(sum, 0xB1, 0xF, 0xF, true);
-                sum += __builtin_amdgcn_mov_dpp(sum, 0x4E, 0xF, 0xF, true);
-                sum += __builtin_amdgcn_mov_dpp(sum, 0x141, 0xF, 0xF, true);
-                if (live) {
-                    if (apiece == 0 && sum && own_sums) atomicAdd(&psum[p], sum); // single owner; no value returned
-                    const int at = swzk(pos & ~3, apiece >> 1, pos) + (apiece & 1) * 8;
-                    *(v2i *)(Asm + at) = hi;
-                    *(v2i *)(Asm + APL + at) = lo;
-                }
-            } else {
-                if (live) *(v4i *)(Asm + swzk(pos & ~3, apiece, pos)) = v;
-            }
+        const int p = apix0 + first / PIECES;
+        const int at = apos[p] ^ piece_xor;
+        const v4i v = reg;
+        if constexpr (LIMBS == 2) {
+            v2i hi, lo;
+            hi.x = (int)__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x07050301u);
+            hi.y = (int)__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x07050301u);
+            lo.x = (int)(__builtin_amdgcn_perm((unsigned)v.y, (unsigned)v.x, 0x06040200u) ^ 0x80808080u);
+            lo.y = (int)(__builtin_amdgcn_perm((unsigned)v.w, (unsigned)v.z, 0x06040200u) ^ 0x80808080u);
+            // sum of the eight codes: four two-element dot products with (1, 1); each of a
+            // pixel's eight pieces adds its share to the pixel's sum
+            const v2s ones = {1, 1};
+            const int w0 = v.x, w1 = v.y, w2 = v.z, w3 = v.w;
+            int sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, w0), ones, 0, false);
+            sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, w1), ones, sum, false);
+            sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, w2), ones, sum, false);
+            sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, w3), ones, sum, false);
+            if (own_sums) atomicAdd(&psum[p], sum); // no value returned
+            *(v2i *)(Asm + at) = hi;
+            *(v2i *)(Asm + APL + at) = lo;
+        } else {
+            *(v4i *)(Asm + at) = v;
         }
     };
     auto load_act = [&](int cc, int first, v4i *reg) __attribute__((always_inline)) {
@@ -942,8 +959,8 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             between();
             stage_flat();
         } else {
-            // two batches of requests in flight; a request past the end reads the last pixel
-            // again and is parked nowhere
+            // two batches of requests in flight; a request past the end of the patch reads as
+            // zeros and is parked in the spare slot (see the patch tables)
             const int total = NPIXA * PIECES;
             int first = 0;
             if (deep) {
@@ -1411,10 +1428,10 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
         return launch_status();
     }
     a.RH = p.RH; a.TW = p.TW; a.PW = p.PW; a.NPIXA = p.NPIXA;
-    a.NTAB = std::max(p.NPIXA, BM);
+    a.NTAB = patch_table_len(p.limbs, p.NPIXA, p.flat);
     a.PITCH = p.PITCH;
     a.KMUL = p.KMUL;
-    a.APLANE = p.flat ? BM * PS : p.PRA * p.PITCH;
+    a.APLANE = p.flat ? BM * PS : p.PRA * p.PITCH + PS; // the last slot of a plane parks overshoot pieces
     a.tiles_c = p.tiles_c; a.tiles_n = p.tiles_n; a.CoutP = p.CoutP; a.nchunks = p.nchunks;
     a.taps = p.taps; a.ksteps = p.ksteps; a.Kflat = d->R * d->S * d->Cin;
     a.total_work = p.tiles_m * p.tiles_n;
