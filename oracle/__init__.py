@@ -8,6 +8,7 @@ from .lp_oracle import (  # noqa: F401
     ROUND_AWAY,
     ROUND_EVEN,
     act,
+    act_stochastic,
     build,
     conv,
     conv_sampled,

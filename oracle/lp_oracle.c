@@ -28,6 +28,8 @@
  *   orc_act        LPAct (+ ReLU) on exact accumulators: requantize to the
  *                  layer's output Qm.f (Sec. 2.1 workflow), count zeros
  *                  (sparsity = zeros / elements, Sec. 3.1).
+ *   orc_act_stochastic
+ *                  the same with the STOCHASTIC rounding_scheme (Sec. 2.4).
  *   orc_maxpool2x2 the 2x2/stride-2 pooling between VGG16 blocks (VGG16 is the
  *                  paper's benchmark network; "Pooling" column of Table 1).
  *
@@ -347,6 +349,48 @@ int orc_act(const int64_t *acc, int64_t count, int f_acc, int n, int m, int fo, 
             }
         } else {
             /* multiply by 2^-s >= 1; a magnitude already beyond the code range stays beyond */
+            if (v > hi) r = hi + 1;
+            else if (v < lo) r = lo - 1;
+            else r = v * ((int64_t)1 << (-s));
+        }
+        if (r < lo) r = lo;
+        if (r > hi) r = hi;
+        code[i] = (int32_t)r;
+        zeros += (r == 0);
+    }
+    if (zero_count) *zero_count = zeros;
+    return 0;
+}
+
+/* LPAct with the STOCHASTIC rounding_scheme of Sec. 2.4, then as orc_act.  u[i]
+ * in [0,1) is the random number drawn for element i (passed in).  With
+ * t = max(acc,0) / 2^s the code is floor(t) + 1 if u < t - floor(t), else
+ * floor(t); s <= 0 needs no rounding.  The comparison is exact: t - floor(t) is
+ * rem / 2^s with an integer rem < 2^62, so u * 2^s (a power-of-two scaling) is
+ * compared with rem in long double (64-bit significand, asserted below). */
+int orc_act_stochastic(const int64_t *acc, const double *u, int64_t count, int f_acc, int n, int m,
+                       int fo, int relu, int32_t *code, uint64_t *zero_count)
+{
+    _Static_assert(__LDBL_MANT_DIG__ >= 64, "long double must hold a 62-bit integer exactly");
+    if (!fmt_ok(n, m, fo) || count < 0 || f_acc < 0) return -1;
+    const int s = f_acc - fo;
+    if (s > 62 || s < -31) return -1;
+    const int64_t lo = code_min(n), hi = code_max(n);
+    const int64_t bound = (int64_t)1 << 62;
+    uint64_t zeros = 0;
+    for (int64_t i = 0; i < count; ++i) {
+        int64_t v = acc[i];
+        if (v >= bound || v <= -bound) return -2;
+        if (!(u[i] >= 0.0 && u[i] < 1.0)) return -3;
+        if (relu && v < 0) v = 0;
+        int64_t r;
+        if (s > 0) {
+            const int64_t d = (int64_t)1 << s;
+            int64_t q = v / d, rem = v % d;
+            if (rem < 0) { q -= 1; rem += d; } /* floor division */
+            if ((long double)ldexp(u[i], s) < (long double)rem) q += 1;
+            r = q;
+        } else {
             if (v > hi) r = hi + 1;
             else if (v < lo) r = lo - 1;
             else r = v * ((int64_t)1 << (-s));

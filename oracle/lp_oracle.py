@@ -165,6 +165,19 @@ def act(acc, f_acc, n, m, fo, relu=True, mode=ROUND_AWAY):
     return code, int(z.value)
 
 
+def act_stochastic(acc, u, f_acc, n, m, fo, relu=True):
+    """int64 accumulators, u in [0,1) per element -> (int32 codes, zero_count) (Sec. 2.4)."""
+    acc = np.ascontiguousarray(acc, dtype=np.int64)
+    u = np.ascontiguousarray(u, dtype=np.float64)
+    assert u.shape == acc.shape
+    code = np.empty(acc.shape, dtype=np.int32)
+    z = ctypes.c_uint64(0)
+    rc = _load().orc_act_stochastic(_ptr(acc), _ptr(u), ctypes.c_int64(acc.size), f_acc, n, m, fo,
+                                    int(bool(relu)), _ptr(code), ctypes.byref(z))
+    _check(rc, "act_stochastic")
+    return code, int(z.value)
+
+
 def maxpool2x2(x):
     x = _i32(x)
     N, C, H, W = x.shape

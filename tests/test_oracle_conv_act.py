@@ -220,6 +220,69 @@ def test_act_commutes_with_relu_and_matches_quantize(oracle):
         assert np.array_equal(quant_first, q)
 
 
+# ------------------------------------------------------- stochastic rounding in LPAct
+
+@pytest.mark.parametrize("s", [1, 5, 12, 31, 40, 62])
+def test_act_stochastic_against_exact_rationals(oracle, s):
+    """Sec. 2.4 on accumulators: floor(t) + [u < frac(t)], t = max(acc, 0) / 2^s, decided in exact
+    rational arithmetic (Python Fractions; u is a double, hence an exact rational)."""
+    from fractions import Fraction
+    rng = np.random.default_rng(40 + s)
+    fo = 4
+    mag = min(61, s + 14)
+    acc = rng.integers(-(1 << mag), 1 << mag, 400, dtype=np.int64)
+    # remainders next to 0 and next to 2^s, and draws next to the remainder
+    special = [0, 1, (1 << s) - 1, 1 << s, (1 << s) + 1, -1, -(1 << s), 3 * (1 << s) - 1]
+    special = [v for v in special if abs(v) < (1 << 62)]            # the supported accumulator width
+    acc[:len(special)] = special
+    u = rng.random(400)
+    u[:4] = [0.0, 1.0 - 2.0 ** -53, 0.5, 2.0 ** -40]
+    for relu in (True, False):
+        code, zeros = oracle.act_stochastic(acc, u, fo + s, 16, 12, fo, relu)
+        want = []
+        for a, uu in zip(acc.tolist(), u.tolist()):
+            v = max(a, 0) if relu else a
+            t = Fraction(v, 1 << s)
+            fl = t.numerator // t.denominator
+            r = fl + (1 if Fraction(uu) < t - fl else 0)
+            want.append(min(max(r, -32768), 32767))
+        assert code.tolist() == want
+        assert zeros == sum(1 for w in want if w == 0)
+
+
+def test_act_stochastic_degenerate_draws_expectation_and_float_quantizer(oracle):
+    rng = np.random.default_rng(50)
+    acc = rng.integers(-(1 << 20), 1 << 20, 3000, dtype=np.int64)
+    s, fo = 9, 6
+    fl = acc >> s                                                   # floor division
+    on_grid = (acc & ((1 << s) - 1)) == 0
+    # u = 0 rounds everything off the grid up, u just below 1 rounds everything down
+    up, _ = oracle.act_stochastic(acc, np.zeros(acc.shape), fo + s, 16, 10, fo, False)
+    down, _ = oracle.act_stochastic(acc, np.full(acc.shape, 1.0 - 2.0 ** -53), fo + s, 16, 10, fo, False)
+    assert np.array_equal(up, np.where(on_grid, fl, fl + 1)) and np.array_equal(down, fl)
+    # no rounding to do when the output has at least the accumulator's fraction bits
+    c, _ = oracle.act_stochastic(np.array([-3, 0, 5, 40000]), np.array([0.1, 0.9, 0.5, 0.5]), 4, 16, 10, 6, False)
+    assert c.tolist() == [-12, 0, 20, 32767]
+    # expectation: E[code] = acc / 2^s
+    draws = 200000
+    a = np.full(draws, 5 * (1 << s) + 333, dtype=np.int64)          # fractional part 333/512
+    c, _ = oracle.act_stochastic(a, rng.random(draws), fo + s, 16, 10, fo, True)
+    p = 333 / 512
+    assert set(np.unique(c).tolist()) == {5, 6}
+    assert abs(c.mean() - (5 + p)) < 4 * np.sqrt(p * (1 - p) / draws)
+    # an accumulator that is exactly a float (24 significant bits) goes through the float
+    # quantizer of the same section to the same code for the same draw
+    a = rng.integers(-(1 << 23), 1 << 23, 2000, dtype=np.int64)
+    u = rng.random(2000)
+    f_acc = 20
+    x = (a.astype(np.float64) * 2.0 ** -f_acc).astype(np.float32)   # exact
+    via_float, _, _ = oracle.quantize_stochastic(x, u, 16, 8, 8)
+    via_acc, _ = oracle.act_stochastic(a, u, f_acc, 16, 8, 8, False)
+    assert np.array_equal(via_float, via_acc)
+    with pytest.raises(ValueError):
+        oracle.act_stochastic(np.array([1]), np.array([1.0]), 12, 16, 8, 8)   # u outside [0, 1)
+
+
 def test_act_rejects_out_of_range(oracle):
     with pytest.raises(ValueError):
         oracle.act(np.array([1 << 62]), 20, 16, 8, 8)
