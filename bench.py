@@ -65,6 +65,8 @@ def measure_extras(lp, torch, lp_inputs, iters=10):
     q = (16, 4, 12)
     ms = timed(lambda: lp.lp_quantize(xf.reshape(-1), codes, q))
     out["lp_quantize"] = {"elements": n, "ms": round(ms, 4), "GBps": round(6 * n / ms / 1e6, 1)}
+    ms = timed(lambda: lp.lp_quantize(xf.reshape(-1), codes, q, r=lp.LP_ROUND_STOCHASTIC, seed=1))
+    out["lp_quantize_stochastic"] = {"elements": n, "ms": round(ms, 4), "GBps": round(6 * n / ms / 1e6, 1)}
     rws = torch.empty(lp.LP_RANGE_WORKSPACE_WORDS, dtype=torch.int64, device="cuda")
     t0 = time.perf_counter()
     for _ in range(iters):
@@ -74,6 +76,9 @@ def measure_extras(lp, torch, lp_inputs, iters=10):
     acc = (torch.randn(shape, device="cuda", generator=g) * (1 << 24)).to(torch.int64)
     ms = timed(lambda: lp.lp_act(acc.reshape(-1), 27, (16, 6, 10), True, codes))
     out["lp_act"] = {"elements": n, "ms": round(ms, 4), "GBps": round(10 * n / ms / 1e6, 1)}
+    ms = timed(lambda: lp.lp_act_stochastic(acc.reshape(-1), 27, (16, 6, 10), True, 1, codes))
+    out["lp_act_stochastic"] = {"elements": n, "ms": round(ms, 4), "GBps": round(10 * n / ms / 1e6, 1),
+                                "note": "one Philox4x32-10 block per element: bound by integer multiplies"}
     t0 = time.perf_counter()
     for _ in range(iters):
         lp.lp_range_acc(acc.reshape(-1), 27, True, 16, 0.0, rws)

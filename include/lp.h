@@ -43,7 +43,7 @@ typedef struct { int32_t n, m, f; } lp_qfmt; /* n == m + f, 1 <= m <= n, 2 <= n 
 typedef enum {
     LP_ROUND_NEAREST_AWAY = 0, /* halfway cases away from zero (default) */
     LP_ROUND_NEAREST_EVEN = 1, /* halfway cases to the even code */
-    LP_ROUND_STOCHASTIC = 2    /* lp_quantize only; see lp_quantize */
+    LP_ROUND_STOCHASTIC = 2    /* lp_quantize and lp_act_stochastic only */
 } lp_round;
 
 typedef enum {
@@ -116,6 +116,20 @@ lp_status lp_quantize(const float *x_dev, void *codes_dev, size_t count, lp_qfmt
  */
 lp_status lp_act(const int64_t *acc_dev, size_t count, int f_acc, lp_qfmt qy, int relu, lp_round r,
                  void *y_codes_dev, uint64_t *zero_count_dev, void *stream);
+
+/*
+ * lp_act_stochastic -- lp_act with the stochastic rounding_scheme (Sec. 2.4):
+ * with t = max(acc,0) / 2^(f_acc - qy.f) (ReLU only if relu != 0) the code is
+ * clip(floor(t) + [u < t - floor(t)]), u as in lp_quantize: 2^-32 * the first
+ * word of Philox4x32-10 with key (seed lo, seed hi) and counter (i lo, i hi, 0, 0)
+ * for element index i.  The comparison is exact (integers).  f_acc <= qy.f
+ * needs no rounding and gives lp_act's result.  Other arguments, limits and
+ * errors as lp_act.  lp_conv_fwd / lp_fc_fwd do not fuse this scheme: pass
+ * their acc_out_dev here.
+ */
+lp_status lp_act_stochastic(const int64_t *acc_dev, size_t count, int f_acc, lp_qfmt qy, int relu,
+                            uint64_t seed, void *y_codes_dev, uint64_t *zero_count_dev,
+                            void *stream);
 
 /*
  * Weight packing for lp_conv_fwd / lp_fc_fwd.  Done once per layer, outside

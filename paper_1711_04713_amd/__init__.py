@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     lib_path,
     load,
     lp_act,
+    lp_act_stochastic,
     lp_conv_fwd,
     lp_conv_pack_weights,
     lp_conv_packed_bytes,

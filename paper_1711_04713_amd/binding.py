@@ -56,6 +56,8 @@ _SIGNATURES = {
                                    ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
     "lp_act": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, QFmt, ctypes.c_int, ctypes.c_int,
                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
+    "lp_act_stochastic": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, QFmt, ctypes.c_int,
+                                         ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
     "lp_conv_packed_bytes": (ctypes.c_int, [ctypes.POINTER(ConvDesc), QFmt, QFmt, ctypes.POINTER(ctypes.c_size_t)]),
     "lp_conv_plan_info": (ctypes.c_int, [ctypes.POINTER(ConvDesc), QFmt, QFmt, ctypes.POINTER(PlanInfo)]),
     "lp_conv_pack_weights": (ctypes.c_int, [ctypes.POINTER(ConvDesc), QFmt, QFmt, ctypes.c_void_p, ctypes.c_void_p,
@@ -158,6 +160,11 @@ def lp_quantize(x, codes, q, r=LP_ROUND_NEAREST_AWAY, seed=0, zero_count=None, s
 def lp_act(acc, f_acc, qy, relu, y_codes, r=LP_ROUND_NEAREST_AWAY, zero_count=None):
     _check(load().lp_act(_ptr(acc), acc.numel(), f_acc, _q(qy), int(bool(relu)), r, _ptr(y_codes), _ptr(zero_count),
                          _stream()), "lp_act")
+
+
+def lp_act_stochastic(acc, f_acc, qy, relu, seed, y_codes, zero_count=None):
+    _check(load().lp_act_stochastic(_ptr(acc), acc.numel(), f_acc, _q(qy), int(bool(relu)), seed, _ptr(y_codes),
+                                    _ptr(zero_count), _stream()), "lp_act_stochastic")
 
 
 def lp_conv_packed_bytes(desc, qx, qw):

@@ -287,11 +287,39 @@ static lp_status finish_range(unsigned long long *hist_dev, size_t count, int n,
 
 // ----------------------------------------------------------------------------- act
 
-template <typename OutT>
+// Sec. 2.4 on an accumulator: floor(v / 2^s) + [u < frac], u = 2^-32 * the first Philox word for
+// the element's index; the comparison u * 2^s < rem is done in integers (rem < 2^s <= 2^62).
+__device__ __forceinline__ int act_one_stochastic(int64_t v, const ActParams &p, uint64_t index, uint64_t seed)
+{
+    if (p.relu && v < 0) v = 0;
+    int64_t r;
+    if (p.s > 0) {
+        int64_t q = v >> p.s; // floor
+        const uint64_t rem = (uint64_t)v & (((uint64_t)1 << p.s) - 1);
+        const uint64_t w = philox4x32_10_word0(index, seed);
+        const bool up = p.s >= 32 ? (w << (p.s - 32)) < rem : w < (rem << (32 - p.s));
+        r = q + (up ? 1 : 0);
+    } else {
+        int64_t c = v;
+        if (c > p.hi) c = p.hi;
+        if (c < p.lo) c = p.lo;
+        r = c * ((int64_t)1 << (-p.s));
+    }
+    if (r > p.hi) r = p.hi;
+    if (r < p.lo) r = p.lo;
+    return (int)r;
+}
+
+template <typename OutT, bool STOCH>
 __global__ __launch_bounds__(kThreads) void act_kernel(const int64_t *__restrict__ acc,
                                                       OutT *__restrict__ y, size_t count,
-                                                      ActParams p, unsigned long long *zero_count)
+                                                      ActParams p, uint64_t seed,
+                                                      unsigned long long *zero_count)
 {
+    auto one = [&](int64_t v, size_t index) {
+        if constexpr (STOCH) return act_one_stochastic(v, p, index, seed);
+        else return act_one(v, p);
+    };
     // A block takes 8 * kThreads consecutive accumulators per trip, as four rows of kThreads
     // 16-byte pairs: a lane's loads are 16 bytes apart from its neighbours' (1 KB contiguous per
     // wave and instruction), and it stores the two codes of each pair (4 or 2 bytes, again
@@ -309,8 +337,8 @@ __global__ __launch_bounds__(kThreads) void act_kernel(const int64_t *__restrict
         for (int j = 0; j < 4; ++j) {
             const int64_t a0 = (int64_t)(((uint64_t)(uint32_t)a[j].y << 32) | (uint32_t)a[j].x);
             const int64_t a1 = (int64_t)(((uint64_t)(uint32_t)a[j].w << 32) | (uint32_t)a[j].z);
-            const int c0 = act_one(a0, p), c1 = act_one(a1, p);
             const size_t pair = pair0 + j * kThreads;
+            const int c0 = one(a0, 2 * pair), c1 = one(a1, 2 * pair + 1);
             if (sizeof(OutT) == 2)
                 reinterpret_cast<int *>(y)[pair] = (c0 & 0xffff) | (c1 << 16);
             else
@@ -325,7 +353,7 @@ __global__ __launch_bounds__(kThreads) void act_kernel(const int64_t *__restrict
         if (g < groups) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const int c = act_one(acc[8 * g + j], p);
+                const int c = one(acc[8 * g + j], 8 * g + j);
                 y[8 * g + j] = (OutT)c;
                 z[j] = (c == 0);
             }
@@ -339,7 +367,7 @@ __global__ __launch_bounds__(kThreads) void act_kernel(const int64_t *__restrict
         const size_t i = groups * 8 + threadIdx.x;
         bool z = false;
         if (threadIdx.x < 8 && i < count) {
-            const int c = act_one(acc[i], p);
+            const int c = one(acc[i], i);
             y[i] = (OutT)c;
             z = (c == 0);
         }
@@ -467,11 +495,11 @@ extern "C" lp_status lp_quantize(const float *x_dev, void *codes_dev, size_t cou
     return launch_status();
 }
 
-extern "C" lp_status lp_act(const int64_t *acc_dev, size_t count, int f_acc, lp_qfmt qy, int relu,
-                            lp_round r, void *y_codes_dev, uint64_t *zero_count_dev, void *stream)
+static lp_status act_launch(const int64_t *acc_dev, size_t count, int f_acc, lp_qfmt qy, int relu,
+                            lp_round r, uint64_t seed, void *y_codes_dev, uint64_t *zero_count_dev,
+                            void *stream)
 {
-    if (!fmt_ok(qy) || f_acc < 0 || (r != LP_ROUND_NEAREST_AWAY && r != LP_ROUND_NEAREST_EVEN))
-        return LP_EINVAL;
+    if (!fmt_ok(qy) || f_acc < 0) return LP_EINVAL;
     const int s = f_acc - qy.f;
     if (s > 62 || s < -31) return LP_EINVAL;
     if (count == 0) return LP_OK;
@@ -479,13 +507,33 @@ extern "C" lp_status lp_act(const int64_t *acc_dev, size_t count, int f_acc, lp_
     hipStream_t st = as_stream(stream);
     const ActParams p = make_act_params(f_acc, qy, relu, r);
     const int grid = grid_for(count / 8); // one trip of the kernel's loop per block, up to the cap
-    if (qy.n > 8)
-        hipLaunchKernelGGL(act_kernel<int16_t>, dim3(grid), dim3(kThreads), 0, st, acc_dev,
-                           (int16_t *)y_codes_dev, count, p, (unsigned long long *)zero_count_dev);
-    else
-        hipLaunchKernelGGL(act_kernel<int8_t>, dim3(grid), dim3(kThreads), 0, st, acc_dev,
-                           (int8_t *)y_codes_dev, count, p, (unsigned long long *)zero_count_dev);
+#define LP_A(T, STOCH) \
+    hipLaunchKernelGGL((act_kernel<T, STOCH>), dim3(grid), dim3(kThreads), 0, st, acc_dev, \
+                       (T *)y_codes_dev, count, p, seed, (unsigned long long *)zero_count_dev)
+    if (r == LP_ROUND_STOCHASTIC) {
+        if (qy.n > 8) LP_A(int16_t, true);
+        else LP_A(int8_t, true);
+    } else {
+        if (qy.n > 8) LP_A(int16_t, false);
+        else LP_A(int8_t, false);
+    }
+#undef LP_A
     return launch_status();
+}
+
+extern "C" lp_status lp_act(const int64_t *acc_dev, size_t count, int f_acc, lp_qfmt qy, int relu,
+                            lp_round r, void *y_codes_dev, uint64_t *zero_count_dev, void *stream)
+{
+    if (r != LP_ROUND_NEAREST_AWAY && r != LP_ROUND_NEAREST_EVEN) return LP_EINVAL;
+    return act_launch(acc_dev, count, f_acc, qy, relu, r, 0, y_codes_dev, zero_count_dev, stream);
+}
+
+extern "C" lp_status lp_act_stochastic(const int64_t *acc_dev, size_t count, int f_acc, lp_qfmt qy,
+                                       int relu, uint64_t seed, void *y_codes_dev,
+                                       uint64_t *zero_count_dev, void *stream)
+{
+    return act_launch(acc_dev, count, f_acc, qy, relu, LP_ROUND_STOCHASTIC, seed, y_codes_dev,
+                      zero_count_dev, stream);
 }
 
 extern "C" lp_status lp_maxpool2x2(const void *x_codes_dev, void *y_codes_dev, int N, int H, int W,

@@ -179,6 +179,66 @@ def test_act_extremes(oracle):
     assert np.array_equal(y.cpu().numpy().astype(np.int32), want) and int(z.item()) == wz
 
 
+@pytest.mark.parametrize("count,f_acc,qy,relu", [
+    (0, 23, (16, 8, 8), True), (1, 23, (16, 8, 8), True), (9, 23, (16, 8, 8), False),
+    (4099, 27, (16, 4, 12), True), (70001, 27, (16, 4, 12), False), (33000, 12, (8, 3, 5), True),
+    (5000, 50, (16, 8, 8), False), (5000, 64, (16, 14, 2), True), (3000, 5, (16, 8, 8), False),
+])
+def test_act_stochastic_matches_oracle(oracle, count, f_acc, qy, relu):
+    """Stochastic rounding of accumulators (Sec. 2.4): the draws are the generator's words for
+    the element indices, fed to the oracle as numbers; shifts below and above 32 bits, a shift
+    of 62, and an output finer than the accumulator (nothing to round)."""
+    n, m, fo = qy
+    s = f_acc - fo
+    rng = np.random.default_rng(count * 11 + f_acc)
+    mag = min(61, max(s, 0) + n - 2)
+    acc = rng.integers(-(1 << mag), 1 << mag, count, dtype=np.int64) if count else np.zeros(0, np.int64)
+    if count > 8 and 0 < s <= 60:
+        acc[:4] = [0, (1 << s) - 1, 1 << s, -1]           # remainders 0, 2^s - 1, 0, 2^s - 1
+    seed = 0xC0FFEE1234567
+    u = _philox4x32_10_word0(np.arange(count), seed).astype(np.float64) * 2.0 ** -32
+    want, wz = oracle.act_stochastic(acc, u, f_acc, n, m, fo, relu)
+    y = torch.empty(count, dtype=code_torch_dtype(n), device="cuda")
+    z = counter()
+    lp.lp_act_stochastic(to_dev(acc), f_acc, qy, relu, seed, y, z)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().astype(np.int32)
+    assert np.array_equal(got, want) and int(z.item()) == wz
+    if count > 1000 and s > 0:
+        y2 = torch.empty(count, dtype=code_torch_dtype(n), device="cuda")
+        lp.lp_act_stochastic(to_dev(acc), f_acc, qy, relu, seed + 1, y2)
+        torch.cuda.synchronize()
+        assert not np.array_equal(y2.cpu().numpy().astype(np.int32), got)      # the seed matters
+    if s <= 0 and count:
+        y3 = torch.empty(count, dtype=code_torch_dtype(n), device="cuda")
+        lp.lp_act(to_dev(acc), f_acc, qy, relu, y3)
+        torch.cuda.synchronize()
+        assert torch.equal(y3, y)
+
+
+def test_act_stochastic_after_conv_accumulators(oracle):
+    """The unfused route for a layer with stochastic rounding: lp_conv_fwd's exact accumulators,
+    then lp_act_stochastic, against the oracle's conv followed by its stochastic act."""
+    from gpu_helpers import conv
+    rng = np.random.default_rng(91)
+    x = rng.integers(0, 3000, (2, 64, 12, 12)).astype(np.int32)
+    w = rng.integers(-3000, 3000, (64, 64, 3, 3)).astype(np.int32)
+    qx, qw, qy = (16, 4, 12), (16, 1, 15), (16, 6, 10)
+    got = conv(x, qx, w, qw, qy=qy)
+    want_acc = oracle.conv(x, w, threads=8)
+    assert np.array_equal(got["acc"], want_acc)
+    acc_nhwc = np.ascontiguousarray(want_acc.transpose(0, 2, 3, 1))
+    seed = 77
+    u = _philox4x32_10_word0(np.arange(acc_nhwc.size), seed).astype(np.float64) * 2.0 ** -32
+    want, wz = oracle.act_stochastic(acc_nhwc.reshape(-1), u, 27, *qy, True)
+    acc_dev = to_dev(np.ascontiguousarray(got["acc"].transpose(0, 2, 3, 1)).reshape(-1))
+    y = torch.empty(acc_nhwc.size, dtype=torch.int16, device="cuda")
+    z = counter()
+    lp.lp_act_stochastic(acc_dev, 27, qy, True, seed, y, z)
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().numpy().astype(np.int32), want) and int(z.item()) == wz
+
+
 # ------------------------------------------------------------------------------- maxpool
 
 @pytest.mark.parametrize("N,C,H,W,n", [(1, 8, 2, 2, 16), (2, 64, 8, 12, 16), (3, 24, 6, 4, 16), (2, 5, 4, 6, 16),
