@@ -841,6 +841,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     constexpr int PIECES = (LIMBS == 2) ? 8 : 4;
     constexpr int ESZ_X = (LIMBS == 2) ? 2 : 1;
     v4i aregA[APF], aregB[APF];
+    int atA[APF], atB[APF];
     const int apiece = tid & (PIECES - 1), apix0 = tid / PIECES;
     // Loads go through a buffer descriptor that covers exactly the input tensor: a piece outside
     // the image or past the last channel is given an offset beyond it and reads as zeros, the
@@ -855,16 +856,20 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     // the LDS position is the pixel's entry with the thread's piece folded in by an xor (the
     // swizzle key sits at bit 4, the piece's slot at bits 4..5, its half at bit 3).
     const int piece_xor = LIMBS == 2 ? ((apiece >> 1) << 4) | ((apiece & 1) << 3) : apiece << 4;
-    auto load_piece = [&](int cc, int first, v4i &reg) __attribute__((always_inline)) {
+    // The LDS position is read together with the source offset, when the piece is requested:
+    // read where the piece is parked, it would wait for the LDS writes of the piece before it
+    // (LDS operations complete in order), a round trip per piece.
+    auto load_piece = [&](int cc, int first, v4i &reg, int &at) __attribute__((always_inline)) {
         const int ch = cc * CK + apiece * (CK / PIECES);
         const unsigned chb = ch < a.Cin ? (unsigned)ch * ESZ_X : 0xffffffffu;
-        const unsigned off = __builtin_elementwise_add_sat((unsigned)tab[apix0 + first / PIECES], chb);
+        const int p = apix0 + first / PIECES;
+        const unsigned off = __builtin_elementwise_add_sat((unsigned)tab[p], chb);
+        at = apos[p] ^ piece_xor;
         const auto v = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)off, 0, 0);
         reg = (v4i){(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
     };
-    auto store_piece = [&](int first, const v4i &reg) __attribute__((always_inline)) {
+    auto store_piece = [&](int first, const v4i &reg, int at) __attribute__((always_inline)) {
         const int p = apix0 + first / PIECES;
-        const int at = apos[p] ^ piece_xor;
         const v4i v = reg;
         if constexpr (LIMBS == 2) {
             v2i hi, lo;
@@ -887,13 +892,13 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             *(v4i *)(Asm + at) = v;
         }
     };
-    auto load_act = [&](int cc, int first, v4i *reg) __attribute__((always_inline)) {
+    auto load_act = [&](int cc, int first, v4i *reg, int *at) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < APF; ++j) load_piece(cc, first + j * THREADS, reg[j]);
+        for (int j = 0; j < APF; ++j) load_piece(cc, first + j * THREADS, reg[j], at[j]);
     };
-    auto store_act = [&](int first, const v4i *reg) __attribute__((always_inline)) {
+    auto store_act = [&](int first, const v4i *reg, const int *at) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < APF; ++j) store_piece(first + j * THREADS, reg[j]);
+        for (int j = 0; j < APF; ++j) store_piece(first + j * THREADS, reg[j], at[j]);
     };
     // FLAT: the raw patch (all Cin channels, int16) is parked in the unused second weight
     // buffer, then each tile row's window is gathered from there, 16 consecutive k per piece.
@@ -967,11 +972,12 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
                 // the accumulators are not live yet: request the first DEEP pieces of every
                 // thread at once and pay the memory latency a single time
                 v4i d[DEEP];
+                int dat[DEEP];
 #pragma unroll
-                for (int j = 0; j < DEEP; ++j) load_piece(cc, j * THREADS, d[j]);
+                for (int j = 0; j < DEEP; ++j) load_piece(cc, j * THREADS, d[j], dat[j]);
                 between();
 #pragma unroll
-                for (int j = 0; j < DEEP; ++j) store_piece(j * THREADS, d[j]);
+                for (int j = 0; j < DEEP; ++j) store_piece(j * THREADS, d[j], dat[j]);
                 first = DEEP * THREADS;
                 if (first >= total) {
                     __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -983,16 +989,16 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             // destination registers are reused in the multiply loop, and the wait that protects
             // them would sit at the top of every slab, where it would also wait for the weight
             // operands just requested) and the loop has one way out.
-            load_act(cc, first, aregA);
+            load_act(cc, first, aregA, atA);
             for (; first + 2 * APF * THREADS < total; first += 2 * APF * THREADS) {
-                load_act(cc, first + APF * THREADS, aregB);
-                store_act(first, aregA);
-                load_act(cc, first + 2 * APF * THREADS, aregA);
-                store_act(first + APF * THREADS, aregB);
+                load_act(cc, first + APF * THREADS, aregB, atB);
+                store_act(first, aregA, atA);
+                load_act(cc, first + 2 * APF * THREADS, aregA, atA);
+                store_act(first + APF * THREADS, aregB, atB);
             }
-            load_act(cc, first + APF * THREADS, aregB);
-            store_act(first, aregA);
-            store_act(first + APF * THREADS, aregB);
+            load_act(cc, first + APF * THREADS, aregB, atB);
+            store_act(first, aregA, atA);
+            store_act(first + APF * THREADS, aregB, atB);
         }
         // vmcnt(0), stated where every path passes (the waits above sit partly inside branches
         // on lane masks); by now it costs nothing
