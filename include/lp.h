@@ -149,16 +149,15 @@ lp_status lp_conv_pack_weights(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, co
  * implicit GEMM.  For path 1: limbs (1 = int8 codes, 2 = 16-bit codes as two int8
  * limbs), the workgroup tile (128 output pixels = tile_rows consecutive rows of the
  * N*Ho stacked output rows x tile_cols columns, times bn output channels), the staged
- * input patch (patch_rows x patch_cols pixels, 64 bytes per pixel and limb, rows
- * patch_pitch bytes apart; the 16-byte slots of a pixel are stored in the order
- * slot ^ (((patch_col >> 2) + swizzle_kmul * patch_row) & 3)), tile counts and LDS bytes per
- * workgroup; the launch: workgroups in the grid, and split = parts into which each tile of the
+ * input patch (patch_rows x patch_cols pixels; a pixel takes patch_pixel bytes per limb, 64 of
+ * codes and the rest padding that spreads consecutive pixels over the LDS banks; rows are
+ * patch_pitch bytes apart), tile counts and LDS bytes per workgroup; the launch: workgroups in the grid, and split = parts into which each tile of the
  * last, partly filled round of workgroup slots is cut along the reduction (1 = none; used
  * only when a workspace is passed).
  */
 typedef struct {
     int32_t path, limbs, bn, tile_rows, tile_cols, patch_rows, patch_cols, tiles_m, tiles_n;
-    int32_t lds_bytes, patch_pitch, swizzle_kmul, workgroups, split;
+    int32_t lds_bytes, patch_pitch, patch_pixel, workgroups, split;
 } lp_plan_info;
 lp_status lp_conv_plan_info(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, lp_plan_info *out_host);
 

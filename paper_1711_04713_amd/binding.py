@@ -34,7 +34,7 @@ class QFmt(ctypes.Structure):
 
 class PlanInfo(ctypes.Structure):
     _fields_ = [(k, ctypes.c_int32) for k in ("path", "limbs", "bn", "tile_rows", "tile_cols", "patch_rows",
-                                               "patch_cols", "tiles_m", "tiles_n", "lds_bytes", "patch_pitch", "swizzle_kmul",
+                                               "patch_cols", "tiles_m", "tiles_n", "lds_bytes", "patch_pitch", "patch_pixel",
                                                "workgroups", "split")]
 
     def asdict(self):

@@ -29,7 +29,9 @@ namespace lp {
 
 constexpr int BM = 128;      // output pixels per workgroup
 constexpr int CK = 64;       // channels (bytes per limb) per staged chunk
-constexpr int PS = 64;       // LDS bytes per staged pixel / weight row and limb (swizzled, see swz)
+constexpr int PS = 64;       // LDS bytes per gathered window row and limb on the flat path (swizzled, see swz)
+constexpr int PSP = 80;      // LDS bytes per staged patch pixel and limb: 64 of codes and 16 of padding, so that
+                             // consecutive pixels start 20 banks apart (see choose_pitch)
 constexpr int kConvThreads = 256;
 constexpr int kCUs = 256;    // compute units of the chip the launch geometry is tuned for
 constexpr int kXCDs = 8;     // consecutive workgroup ids go round-robin to this many dies
@@ -46,7 +48,6 @@ struct Plan {
     int nchunks, CoutP, BN;
     int RH, TW, PW, PRA, NPIXA;
     int PITCH;   // LDS bytes between staged patch rows
-    int KMUL;    // row multiplier of the patch swizzle key (4: one-dimensional key)
     int tiles_r, tiles_c, tiles_m, tiles_n;
     // Launch geometry.  Every die gets per_xcd consecutive tiles.  The first full_per_xcd of
     // them (a whole number of rounds of the die's workgroup slots) are computed by one workgroup
@@ -83,7 +84,13 @@ static bool desc_ok(const lp_conv_desc *d)
 // pitch pixels apart, or, for kmul == 4, the one-dimensional (pixel number >> 2) & 3 (best when
 // PW == TW, e.g. 1x1 kernels and the FC layers); pitch (PW..PW+3) and kmul (0..4) are chosen
 // per plan by counting the conflicts of every 16-lane group at every tap.
-static int swizzle_conflicts(int pw, int tw, int rh, int R, int S, int pitch_px, int kmul)
+// Bank conflicts of the fragment reads for a patch whose rows are pitch16 * 16 bytes apart.  A
+// 16-byte read is served 16 lanes at a time, the 64 banks covering 256 bytes: the 16 lanes (16
+// consecutive tile rows, the same 16-byte slot of their pixels at one tap) must fall into 16
+// different 16-byte groups modulo 256 bytes.  A pixel is PSP = 80 bytes, so the group of pixel
+// (prow, pcol) is prow * pitch16 + 5 * pcol: along a patch row the groups never collide (5 is odd),
+// and the pitch decides how the rows of a narrow tile interleave.
+static int pitch_conflicts(int tw, int rh, int R, int S, int pitch16)
 {
     int cost = 0;
     const int rows = rh * tw;
@@ -94,28 +101,25 @@ static int swizzle_conflicts(int pw, int tw, int rh, int R, int S, int pitch_px,
                 int worst = 0;
                 for (int m = m0; m < std::min(m0 + 16, rows); ++m) {
                     const int prow = m / tw + r, pcol = m % tw + s;
-                    const int key = (kmul == 4 ? (prow * pitch_px + pcol) >> 2 : (pcol >> 2) + kmul * prow) & 3;
-                    const int group = (4 * (prow * pitch_px + pcol) + key) & 15; // slot 0; others permute
-                    worst = std::max(worst, ++seen[group]);
+                    worst = std::max(worst, ++seen[(prow * pitch16 + 5 * pcol) & 15]);
                 }
                 cost += worst - 1;
             }
-    (void)pw;
     return cost;
 }
 
-static void choose_swizzle(int pw, int tw, int rh, int R, int S, int *pitch_px, int *kmul)
+// Smallest row pitch (in 16-byte units, at most 15 units of padding) with the fewest conflicts.
+static int choose_pitch(int pw, int tw, int rh, int R, int S)
 {
-    int best = 1 << 30;
-    for (int px = pw; px < (S == 1 ? pw + 1 : pw + 4); ++px) // without horizontal taps the 1-D key is exact
-        for (int k = 0; k < 5; ++k) {
-            const int c = swizzle_conflicts(pw, tw, rh, R, S, px, k) * 64 + (px - pw); // ties: less padding
-            if (c < best) {
-                best = c;
-                *pitch_px = px;
-                *kmul = k;
-            }
+    int best = 1 << 30, best_pitch = pw * (PSP / 16);
+    for (int p16 = pw * (PSP / 16); p16 < pw * (PSP / 16) + 16; ++p16) {
+        const int c = pitch_conflicts(tw, rh, R, S, p16);
+        if (c < best) {
+            best = c;
+            best_pitch = p16;
         }
+    }
+    return best_pitch;
 }
 
 // 16-byte pieces a thread requests per batch while staging a patch (two batches are in flight).
@@ -137,10 +141,10 @@ static int patch_table_len(int limbs, int npixa, int flat)
 
 // LDS: tables (3*ntab + 2*BM ints, 3*bn ints of channel constants, BM pooled offsets), staged patch (one plane per
 // limb); the flat variant also parks the raw patch (at most 8 KB)
-static size_t mfma_lds_bytes(int limbs, int pra, int pw, int pitch_px, int bn, int flat)
+static size_t mfma_lds_bytes(int limbs, int pra, int pw, int pitch_bytes, int bn, int flat)
 {
     const int ntab = patch_table_len(limbs, pra * pw, flat);
-    const size_t plane = flat ? (size_t)BM * PS : (size_t)pra * pitch_px * PS + PS; // + the slot overshoot pieces are parked in
+    const size_t plane = flat ? (size_t)BM * PS : (size_t)pra * pitch_bytes + PSP; // + the slot overshoot pieces are parked in
     size_t tables = round_up((size_t)(3 * ntab + 2 * BM) * 4, 16) + (size_t)3 * bn * 4 + (size_t)BM * 4;
     return tables + (size_t)limbs * plane + (flat ? (size_t)2 * 64 * PS : 0); // flat: the raw patch
 }
@@ -252,9 +256,16 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
                 const int cross = (p.Ho % rh == 0) ? 0 : std::min((rh - 1 + p.Ho - 1) / p.Ho, d->N - 1);
                 const int pra = rh + d->R - 1 + cross * (d->R - 1);
                 const int npixa = pra * pw;
-                if (mfma_lds_bytes(p.limbs, pra, pw, d->S == 1 ? pw : pw + 3, p.limbs == 2 ? 64 : 128, p.flat) > kLdsBudgets[pass]) continue;
-                if (p.flat && (size_t)npixa * d->Cin * 2 > (size_t)2 * 64 * PS) continue; // the raw patch has 8 KB of LDS
                 const double cost = (double)tiles_c * tiles_r * ((double)BM * RS + 0.5 * npixa);
+                if (cost >= best_free && (cost >= best || (d->pool && !poolable))) continue; // improves nothing
+                // LDS need: first with the smallest row pitch, then (the pitch search is the
+                // expensive part) with the pitch this geometry would get
+                const int bn_max = p.limbs == 2 ? 64 : 128;
+                if (mfma_lds_bytes(p.limbs, pra, pw, pw * PSP, bn_max, p.flat) > kLdsBudgets[pass]) continue;
+                if (!p.flat &&
+                    mfma_lds_bytes(p.limbs, pra, pw, 16 * choose_pitch(pw, tw, rh, d->R, d->S), bn_max, 0) > kLdsBudgets[pass])
+                    continue;
+                if (p.flat && (size_t)npixa * d->Cin * 2 > (size_t)2 * 64 * PS) continue; // the raw patch has 8 KB of LDS
                 best_free = std::min(best_free, cost);
                 if (d->pool && !poolable) continue;
                 if (cost < best) {
@@ -281,13 +292,8 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
         // registers for the prefetch pipeline, so it always runs 64-wide
         if (p.limbs == 2) p.BN = 64;
         p.tiles_n = p.CoutP / p.BN;
-        {
-            int px = p.PW, k = 0;
-            if (!p.flat) choose_swizzle(p.PW, p.TW, p.RH, d->R, d->S, &px, &k);
-            p.PITCH = px * PS;
-            p.KMUL = k;
-        }
-        p.lds_bytes = mfma_lds_bytes(p.limbs, p.PRA, p.PW, p.PITCH / PS, p.BN, p.flat);
+        p.PITCH = p.flat ? p.PW * PS : 16 * choose_pitch(p.PW, p.TW, p.RH, d->R, d->S);
+        p.lds_bytes = mfma_lds_bytes(p.limbs, p.PRA, p.PW, p.PITCH, p.BN, p.flat);
         {
             // workgroup slots per die: what registers and LDS allow
             const int total = p.tiles_m * p.tiles_n, nslabs = p.nchunks * p.taps;
@@ -409,7 +415,7 @@ struct ConvArgs {
     unsigned *zero_partial; // one count per workgroup (MFMA path), summed by a second kernel
     int N, H, W, Cin, Cout, R, S, stride, pad;
     int Ho, Wo, Hp, FR;
-    int RH, TW, PW, NPIXA, NTAB, APLANE, PITCH, KMUL;
+    int RH, TW, PW, NPIXA, NTAB, APLANE, PITCH;
     int tiles_c, tiles_n, CoutP, nchunks, taps, ksteps, Kflat;
     int total_work, per_xcd, full_per_xcd, split;
     unsigned char *partials; // tail tiles' partial accumulators, part_bytes per (tile, part)
@@ -475,11 +481,9 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(const ConvArgs a)
 
 // -------------------------------------------------------------------------- MFMA path
 
-// byte offset of 16-byte slot q of the pixel / weight row that starts at byte offset pix (a
-// multiple of 64) in the swizzled layout
+// byte offset of 16-byte slot q of the gathered window row that starts at byte offset pix (a
+// multiple of 64) in the swizzled layout of the flat path
 __device__ __forceinline__ int swz(int pix, int q) { return pix + (((q ^ (pix >> 8)) & 3) << 4); }
-// the same with an explicit key (patch pixels: key from patch row and column)
-__device__ __forceinline__ int swzk(int pix, int q, int key) { return pix + (((q ^ key) & 3) << 4); }
 
 __device__ __forceinline__ v16i mfma_i8(v4i a, v4i b, v16i c)
 {
@@ -762,7 +766,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     int *tab = (int *)smem;          // staged pixel -> byte offset of its codes in x, all ones outside the image
                                      // (FLAT: input pixel index, -1 outside)
     int *psum = tab + a.NTAB;        // per staged pixel (FLAT: per tile row): sum of its codes
-    int *apos = psum + a.NTAB;       // staged pixel -> byte offset inside a limb plane | swizzle key << 4
+    int *apos = psum + a.NTAB;       // staged pixel -> byte offset inside a limb plane
     int *outoff = apos + a.NTAB;     // tile row -> output pixel index, -1 if not an output
     int *abase_s = outoff + BM;      // tile row -> staged pixel of its (r=0, s=0) tap
     int *ctab = (int *)(smem + (((size_t)(3 * a.NTAB + 2 * BM) * 4 + 15) & ~(size_t)15)); // channel constants
@@ -776,11 +780,10 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     // zeros and are parked in the spare slot at the end of a plane.
     const unsigned px_bytes = (unsigned)a.Cin * (LIMBS == 2 ? 2u : 1u);
     for (int p = tid; p < a.NTAB; p += THREADS) {
-        int g = -1, pos = APL - PS;
+        int g = -1, pos = APL - PSP;
         if (p < NPIXA) {
             const int pr = p / a.PW, pc = p % a.PW;
-            const int off = pr * a.PITCH + pc * PS;
-            pos = off | (((a.KMUL == 4 ? off >> 8 : (pc >> 2) + a.KMUL * pr) & 3) << 4);
+            pos = pr * a.PITCH + pc * PSP;
             const int vr = vr0 + pr;
             const int n = vr / a.Hp, iy = vr % a.Hp - a.pad, ix = x0 - a.pad + pc;
             if (n < a.N && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) g = (n * a.H + iy) * a.W + ix;
@@ -817,14 +820,13 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WMC, wn = wave / WMC;
     const int l32 = lane & 31, kg = lane >> 5;
-    int aoff[MB], apr[MB], apc[MB]; // filled once the row tables are visible
+    int aoff[MB]; // filled once the row tables are visible
     auto lane_constants = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             const int row = wm * WROWS + mb * 32 + l32;
-            aoff[mb] = FLAT ? row * PS : (apos[abase_s[row]] & ~0x30); // start of the row's (r=0, s=0) pixel
-            apr[mb] = FLAT ? 0 : abase_s[row] / a.PW;               // its patch row and column
-            apc[mb] = FLAT ? 0 : abase_s[row] % a.PW;
+            // the row's (r=0, s=0) pixel; patch path: the lane's 16-byte slot of the first K half in it
+            aoff[mb] = FLAT ? row * PS : apos[abase_s[row]] + kg * 16;
         }
     };
     if constexpr (!LATE_ROWS) lane_constants();
@@ -850,12 +852,12 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         const_cast<void *>(a.x), 0, (int)((unsigned)(a.N * a.H * a.W) * (unsigned)a.Cin * ESZ_X), 0x00020000);
     // piece number `first + tid` of chunk cc: request it / unpack it and park it in LDS
     // A staged pixel's table entries carry everything that does not depend on the chunk, so a
-    // piece costs one table read and one add on the way in, one table read and one xor on the
+    // piece costs one table read and one add on the way in, one table read and one add on the
     // way out: the source offset is the pixel's entry plus the piece's channel offset (a
     // saturating add: either being all ones, the sum is all ones and the piece reads as zeros),
-    // the LDS position is the pixel's entry with the thread's piece folded in by an xor (the
-    // swizzle key sits at bit 4, the piece's slot at bits 4..5, its half at bit 3).
-    const int piece_xor = LIMBS == 2 ? ((apiece >> 1) << 4) | ((apiece & 1) << 3) : apiece << 4;
+    // the LDS position is the pixel's entry plus the place of the thread's piece in the pixel
+    // (16-byte slot, and for limb bytes the 8-byte half of it).
+    const int piece_at = LIMBS == 2 ? ((apiece >> 1) << 4) | ((apiece & 1) << 3) : apiece << 4;
     // The LDS position is read together with the source offset, when the piece is requested:
     // read where the piece is parked, it would wait for the LDS writes of the piece before it
     // (LDS operations complete in order), a round trip per piece.
@@ -864,7 +866,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         const unsigned chb = ch < a.Cin ? (unsigned)ch * ESZ_X : 0xffffffffu;
         const int p = apix0 + first / PIECES;
         const unsigned off = __builtin_elementwise_add_sat((unsigned)tab[p], chb);
-        at = apos[p] ^ piece_xor;
+        at = apos[p] + piece_at;
         const auto v = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)off, 0, 0);
         reg = (v4i){(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
     };
@@ -1007,7 +1009,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     // chunk and tap of the current slab, and the tap's patch offset, kept incrementally
     int cc = s0 / a.taps, tap = s0 % a.taps;
     int tap_r = FLAT ? 0 : tap / a.S, tap_s = FLAT ? 0 : tap % a.S;
-    int taprow = tap_r * a.PITCH, tapoff = taprow + tap_s * PS;
+    int taprow = tap_r * a.PITCH, tapoff = taprow + tap_s * PSP;
     // Weights go straight from global memory / L2 into the MFMA operand registers, NSETS - 1
     // K=32 halves ahead of their use; with no slab to publish, the waves of a workgroup meet only
     // when a new patch is staged.  A lane's B operand for (slab, K half, limb, column block) is the
@@ -1065,6 +1067,8 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             for (int nb = 0; nb < NB; ++nb) acc[mb][nb][1] = mfma_i8(wh[nb], al[mb], acc[mb][nb][1]);
         }
     };
+    constexpr int HALF2 = 32;
+    auto second_half = [&](int off) __attribute__((always_inline)) { return FLAT ? off ^ HALF2 : off + HALF2; };
     using std::integral_constant;
     // One K half of slab t, which is slab number P of the current rotation: request the weights
     // that are LEAD halves ahead, then multiply this half row block by row block.  cur / nxt:
@@ -1086,28 +1090,23 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             __builtin_amdgcn_s_waitcnt(0x0F70 | (LEAD * NB * LIMBS));
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            if constexpr (!PIPE) afetch(mb, cur[mb] ^ (hh * 32));
+            if constexpr (!PIPE) afetch(mb, hh ? second_half(cur[mb]) : cur[mb]);
             if (on) mfma_mb(mb, bh[use], bl[use]);
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (PIPE) {
-                if (hh == 0) afetch(mb, cur[mb] ^ 32);
+                if (hh == 0) afetch(mb, second_half(cur[mb]));
                 else afetch(mb, nxt[mb]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
     };
-    // fragment offsets of the slab the tap bookkeeping points at: its pixel per row block, slot
-    // kg; the second K=32 half is slot kg+2
+    // fragment offsets of the slab the tap bookkeeping points at: the lane's slot (kg) of its
+    // pixel per row block; the second K=32 half is slot kg+2, 32 bytes further (flat path: the
+    // swizzled slot, i.e. the offset with bit 5 flipped).  On the patch path a tap moves every
+    // lane by the same amount, so a slab costs one add per row block.
     auto fragment_offsets = [&](int *afrag) __attribute__((always_inline)) {
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            if constexpr (FLAT) afrag[mb] = swz(aoff[mb], kg);
-            else {
-                const int pix = aoff[mb] + tapoff;
-                const int key = a.KMUL == 4 ? pix >> 8 : ((apc[mb] + tap_s) >> 2) + a.KMUL * (apr[mb] + tap_r);
-                afrag[mb] = swzk(pix, kg, key);
-            }
-        }
+        for (int mb = 0; mb < MB; ++mb) afrag[mb] = FLAT ? swz(aoff[mb], kg) : aoff[mb] + tapoff;
     };
 #pragma unroll
     for (int j = 0; j < LEAD; ++j) bload(s0 + (j >> 1), j & 1, bh[j], bl[j]);
@@ -1148,7 +1147,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             tap_s = tap_r = 0;
             tapoff = taprow = 0;
         } else if (!FLAT) {
-            tapoff += PS;
+            tapoff += PSP;
             if (++tap_s == a.S) {
                 tap_s = 0;
                 ++tap_r;
@@ -1444,8 +1443,7 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     a.RH = p.RH; a.TW = p.TW; a.PW = p.PW; a.NPIXA = p.NPIXA;
     a.NTAB = patch_table_len(p.limbs, p.NPIXA, p.flat);
     a.PITCH = p.PITCH;
-    a.KMUL = p.KMUL;
-    a.APLANE = p.flat ? BM * PS : p.PRA * p.PITCH + PS; // the last slot of a plane parks overshoot pieces
+    a.APLANE = p.flat ? BM * PS : p.PRA * p.PITCH + PSP; // the last slot of a plane parks overshoot pieces
     a.tiles_c = p.tiles_c; a.tiles_n = p.tiles_n; a.CoutP = p.CoutP; a.nchunks = p.nchunks;
     a.taps = p.taps; a.ksteps = p.ksteps; a.Kflat = d->R * d->S * d->Cin;
     a.total_work = p.tiles_m * p.tiles_n;
@@ -1585,7 +1583,7 @@ extern "C" lp_status lp_conv_plan_info(const lp_conv_desc *d, lp_qfmt qx, lp_qfm
         o.bn = p.BN; o.tile_rows = p.RH; o.tile_cols = p.TW; o.patch_rows = p.PRA; o.patch_cols = p.PW;
         o.tiles_m = p.tiles_m; o.tiles_n = p.tiles_n; o.lds_bytes = (int32_t)p.lds_bytes;
         o.patch_pitch = p.PITCH;
-        o.swizzle_kmul = p.KMUL;
+        o.patch_pixel = p.flat ? PS : PSP;
         o.workgroups = p.grid;
         o.split = p.split;
     }

@@ -110,15 +110,14 @@ def test_tile_geometry_addresses_the_right_pixels(N, H, W, Cin, Cout, R, S, pad)
     assert info["tiles_m"] == tiles_r * tiles_c
     assert info["lds_bytes"] <= 80 * 1024
     NPIXA = PRA * PW
-    pitch, kmul = info["patch_pitch"], info["swizzle_kmul"]
-    assert PW * 64 <= pitch <= (PW + 3) * 64 and pitch % 64 == 0
+    pitch, pix = info["patch_pitch"], info["patch_pixel"]
     if Cin >= 16:
+        assert pix == 80 and pitch % 16 == 0 and PW * pix <= pitch < PW * pix + 256
         # fragment reads: 16 lanes = 16 consecutive tile rows m read the same 16-byte slot q of
         # their pixel (patch_row, patch_col) at tap (r, s), stored at patch_row * pitch +
-        # patch_col * 64 + ((q ^ key) & 3) * 16 with key = (patch_col >> 2) + kmul * patch_row
-        # (kmul == 4: key = pixel number >> 2).
-        # The 64 LDS banks serve 256 bytes per pass: count lanes that share a 16-byte bank group.
-        # Power-of-two tile widths must be conflict-free; odd widths may keep a 2-way conflict.
+        # patch_col * 80 + 16 * q.  The 64 LDS banks serve 256 bytes per pass: count lanes that
+        # share a 16-byte bank group.  Power-of-two tile widths must be conflict-free; odd widths
+        # may keep a 2-way conflict.
         worst = 0
         for r in range(R):
             for s_ in range(S):
@@ -126,9 +125,7 @@ def test_tile_geometry_addresses_the_right_pixels(N, H, W, Cin, Cout, R, S, pad)
                     groups = {}
                     for m in range(m0, min(m0 + 16, RH * TW)):
                         prow, pcol = m // TW + r, m % TW + s_
-                        key = (prow * pitch // 64 + pcol) >> 2 if kmul == 4 else (pcol >> 2) + kmul * prow
-                        off = prow * pitch + pcol * 64 + ((key & 3) << 4)
-                        g = (off // 16) % 16
+                        g = ((prow * pitch + pcol * pix) // 16) % 16
                         groups[g] = groups.get(g, 0) + 1
                     worst = max(worst, max(groups.values()))
         assert worst <= (1 if TW in (1, 2, 4, 8, 16, 32, 64, 128) else 2)
