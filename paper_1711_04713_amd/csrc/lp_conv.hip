@@ -821,12 +821,14 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     const int wm = wave % WMC, wn = wave / WMC;
     const int l32 = lane & 31, kg = lane >> 5;
     int aoff[MB]; // filled once the row tables are visible
+    // LDS address of the staged planes (patch path: fragment offsets are kept as LDS addresses)
+    const int planes_lds = (int)(unsigned long)(__attribute__((address_space(3))) unsigned char *)Asm;
     auto lane_constants = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             const int row = wm * WROWS + mb * 32 + l32;
             // the row's (r=0, s=0) pixel; patch path: the lane's 16-byte slot of the first K half in it
-            aoff[mb] = FLAT ? row * PS : apos[abase_s[row]] + kg * 16;
+            aoff[mb] = FLAT ? row * PS : planes_lds + apos[abase_s[row]] + kg * 16;
         }
     };
     if constexpr (!LATE_ROWS) lane_constants();
@@ -1049,9 +1051,17 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     // other row block's MFMAs.  The flat path (a slab per staging) reads them where it uses them.
     constexpr bool PIPE = !FLAT;
     v4i ah[MB], al[MB];
-    auto afetch = [&](int mb, int off) __attribute__((always_inline)) {
-        ah[mb] = *(const v4i *)(Asm + off);
-        if constexpr (LIMBS == 2) al[mb] = *(const v4i *)(Asm + APL + off);
+    // Patch path: off / offl are the LDS addresses themselves (high and low plane), so that a
+    // read costs no address arithmetic; flat path: off is relative to the planes.
+    typedef __attribute__((address_space(3))) const v4i lds_cv4i;
+    auto afetch = [&](int mb, int off, int offl) __attribute__((always_inline)) {
+        if constexpr (FLAT) {
+            ah[mb] = *(const v4i *)(Asm + off);
+            if constexpr (LIMBS == 2) al[mb] = *(const v4i *)(Asm + APL + off);
+        } else {
+            ah[mb] = *(lds_cv4i *)(unsigned)off;
+            if constexpr (LIMBS == 2) al[mb] = *(lds_cv4i *)(unsigned)offl;
+        }
     };
     auto mfma_mb = [&](int mb, const v4i *wh, const v4i *wl) __attribute__((always_inline)) {
 #pragma unroll
@@ -1076,7 +1086,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     // slab's fragments, also when a new patch comes first (they are then read again after the
     // staging) or nothing follows: the offsets stay inside the patch, and a request that does
     // not depend on the path keeps the fragment registers from being doubled.
-    auto half_step = [&](int t, auto P, auto HH, const int *cur, const int *nxt) __attribute__((always_inline)) {
+    auto half_step = [&](int t, auto P, auto HH, const int *cur, const int *curl, const int *nxt, const int *nxtl) __attribute__((always_inline)) {
         constexpr int hh = decltype(HH)::value;
         constexpr int h = 2 * decltype(P)::value + hh;
         constexpr int use = h % NSETS, fill = (h + LEAD) % NSETS;
@@ -1090,12 +1100,12 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             __builtin_amdgcn_s_waitcnt(0x0F70 | (LEAD * NB * LIMBS));
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            if constexpr (!PIPE) afetch(mb, hh ? second_half(cur[mb]) : cur[mb]);
+            if constexpr (!PIPE) afetch(mb, hh ? second_half(cur[mb]) : cur[mb], 0);
             if (on) mfma_mb(mb, bh[use], bl[use]);
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (PIPE) {
-                if (hh == 0) afetch(mb, second_half(cur[mb]));
-                else afetch(mb, nxt[mb]);
+                if (hh == 0) afetch(mb, second_half(cur[mb]), second_half(curl[mb]));
+                else afetch(mb, nxt[mb], nxtl[mb]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -1104,9 +1114,12 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     // pixel per row block; the second K=32 half is slot kg+2, 32 bytes further (flat path: the
     // swizzled slot, i.e. the offset with bit 5 flipped).  On the patch path a tap moves every
     // lane by the same amount, so a slab costs one add per row block.
-    auto fragment_offsets = [&](int *afrag) __attribute__((always_inline)) {
+    auto fragment_offsets = [&](int *afrag, int *afragl) __attribute__((always_inline)) {
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) afrag[mb] = FLAT ? swz(aoff[mb], kg) : aoff[mb] + tapoff;
+        for (int mb = 0; mb < MB; ++mb) {
+            afrag[mb] = FLAT ? swz(aoff[mb], kg) : aoff[mb] + tapoff;
+            afragl[mb] = afrag[mb] + APL;
+        }
     };
 #pragma unroll
     for (int j = 0; j < LEAD; ++j) bload(s0 + (j >> 1), j & 1, bh[j], bl[j]);
@@ -1123,8 +1136,8 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             for (int q = 0; q < NACC; ++q)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[mb][nb][q][v] = 0;
-    int cur[MB];
-    if constexpr (!LATE_ROWS) fragment_offsets(cur);
+    int cur[MB], curl[MB];
+    if constexpr (!LATE_ROWS) fragment_offsets(cur, curl);
     __syncthreads(); // the freshly staged patch and the row tables are visible
     // Inside the multiply loop a wave runs at raised priority: the waves of the other workgroups
     // on the SIMD that are staging a patch or storing a tile mostly wait for memory, and the
@@ -1133,11 +1146,11 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     __builtin_amdgcn_s_setprio(3);
     if constexpr (LATE_ROWS) {
         lane_constants();
-        fragment_offsets(cur);
+        fragment_offsets(cur, curl);
     }
     if constexpr (PIPE) {
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) afetch(mb, cur[mb]);
+        for (int mb = 0; mb < MB; ++mb) afetch(mb, cur[mb], curl[mb]);
     }
     auto step = [&](int t, auto P) __attribute__((always_inline)) {
         // move the bookkeeping on to slab t + 1
@@ -1155,12 +1168,12 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
                 tapoff = taprow;
             }
         }
-        int nxt[MB];
-        fragment_offsets(nxt);
+        int nxt[MB], nxtl[MB];
+        fragment_offsets(nxt, nxtl);
         const bool more = t + 1 < s1;
         const bool restage = more && tap == 0; // slab t + 1 opens a chunk: a new patch
-        half_step(t, P, integral_constant<int, 0>{}, cur, nxt);
-        half_step(t, P, integral_constant<int, 1>{}, cur, nxt);
+        half_step(t, P, integral_constant<int, 0>{}, cur, curl, nxt, nxtl);
+        half_step(t, P, integral_constant<int, 1>{}, cur, curl, nxt, nxtl);
         if (restage) {
             __builtin_amdgcn_s_setprio(0);
             __syncthreads(); // all reads of the previous chunk's activations are done
@@ -1169,11 +1182,14 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             __builtin_amdgcn_s_setprio(3);
             if constexpr (PIPE) {
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) afetch(mb, nxt[mb]);
+                for (int mb = 0; mb < MB; ++mb) afetch(mb, nxt[mb], nxtl[mb]);
             }
         }
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) cur[mb] = nxt[mb];
+        for (int mb = 0; mb < MB; ++mb) {
+            cur[mb] = nxt[mb];
+            curl[mb] = nxtl[mb];
+        }
     };
     // whole rotations inside the loop, the slabs left over after it
     int t = s0;
