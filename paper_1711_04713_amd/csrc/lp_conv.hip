@@ -502,7 +502,9 @@ __device__ __forceinline__ int requant_relu32(int hi, int lo16, int s, int cmax)
     } else if (S16 == 1) {
         q = hi + (lo16 >> 15);
     } else {
-        const int h = hi < 32768 ? hi : 32768; // beyond this the result saturates anyway
+        // beyond 32768 the result saturates anyway, below 0 it is 0 anyway: kept inside, the
+        // shifted value cannot leave 32 bits
+        const int h = min(max(hi, -1), 32768);
         q = (h << (16 - s)) + ((lo16 + (1 << (s - 1))) >> s);
     }
     return min(max(q, 0), cmax); // compiles to v_med3_i32
@@ -511,14 +513,16 @@ __device__ __forceinline__ int requant_relu32(int hi, int lo16, int s, int cmax)
 // Per-channel constants of a tile (weight correction + bias) into LDS, in the form the epilogue
 // wants: three int32 planes (bits 16.., 8..15, 0..7) for the 32-bit epilogue, else int64.
 template <int BN, int THREADS>
-__device__ __forceinline__ void build_colterms(const ConvArgs &a, int ntile, int *ctab)
+__device__ __forceinline__ void build_colterms(const ConvArgs &a, int ntile, int *ctab, int limbs)
 {
     for (int c = threadIdx.x; c < BN; c += THREADS) {
         const int colg = ntile * BN + c;
         const int64_t t = colg < a.Cout ? a.corr[colg] + bias_term(a, colg) : 0;
         if (a.fast) {
+            // (two limbs, shifts 9..16: the epilogue's rounding half 2^(s-1) rides in the middle plane)
+            const int half9 = (limbs == 2 && a.act.s >= 9 && a.act.s <= 16) ? 1 << (a.act.s - 9) : 0;
             ctab[c] = (int)(t >> 16);
-            ctab[BN + c] = (int)((t >> 8) & 255);
+            ctab[BN + c] = (int)((t >> 8) & 255) + half9;
             ctab[2 * BN + c] = (int)(t & 255);
         } else {
             ((int64_t *)ctab)[c] = t;
@@ -602,7 +606,20 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                         for (int e = 0; e < 4; ++e) {
                             const int v = 4 * gl + e;
                             int hi, lo16 = 0;
-                            if constexpr (LIMBS == 2) {
+                            if constexpr (LIMBS == 2 && S16 == 3) {
+                                // Shifts 9..16 (above, only the top plane matters and the class-0 form is
+                                // shorter).  With W = floor(v / 256) the code is (W + 2^(s-9)) >> (s-8):
+                                // the dropped low byte of v cannot carry into a multiple of 256.  W =
+                                // 256*A + B + (C >> 8) + (rowsum >> 1) in 32 bits: A is clamped to +-2^22
+                                // first (beyond that the code saturates for every s <= 22, and |B + ...|
+                                // stays below 2^29 for K <= 8192); the half is part of cB.
+                                const int C = acc[mb][nb][2][v] + cC[e] + ((rs[mb] & 1) << 7);
+                                const int T = acc[mb][nb][1][v] + cB[e] + (C >> 8);
+                                const int A = min(max(acc[mb][nb][0][v] + cA[e], -(1 << 22)), 1 << 22);
+                                const int W = (A << 8) + T + (rs[mb] >> 1);
+                                q[e] = min(max(W >> (s - 8), 0), cmax);
+                                continue;
+                            } else if constexpr (LIMBS == 2) {
                                 const int C = acc[mb][nb][2][v] + cC[e] + ((rs[mb] & 1) << 7);
                                 const int B = acc[mb][nb][1][v] + cB[e] + (rs[mb] >> 1) + (C >> 8);
                                 hi = acc[mb][nb][0][v] + cA[e] + (B >> 8);
@@ -613,7 +630,7 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                                 hi = cA[e] + (C >> 16);
                                 lo16 = C & 65535;
                             }
-                            q[e] = requant_relu32<S16>(hi, lo16, s, cmax);
+                            q[e] = requant_relu32<S16 == 3 ? 2 : S16>(hi, lo16, s, cmax);
                         }
                         const bool counted = oo[mb] >= 0 && col_ok; // the lane's codes exist in the output tensor
                         if constexpr (MODE == 2) { // ragged channel tail: code by code
@@ -670,12 +687,18 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
             if ((a.Cout & 3) == 0) requant_tile(s16c, y16c, integral_constant<int, 0>{}); // every group of four channels is aligned
             else requant_tile(s16c, y16c, integral_constant<int, 2>{});
         };
+        // shift classes: two limbs 9..16 (the usual ones) -> 3; else >= 17 -> 0, 16 -> 1, <= 15 -> 2
+        const bool mid = LIMBS == 2 && s >= 9 && s <= 16;
         if (a.y16) {
-            if (s >= 17) by_mode(integral_constant<int, 0>{}, integral_constant<bool, true>{});
+            if (mid) {
+                if constexpr (LIMBS == 2) by_mode(integral_constant<int, 3>{}, integral_constant<bool, true>{});
+            } else if (s >= 17) by_mode(integral_constant<int, 0>{}, integral_constant<bool, true>{});
             else if (s == 16) by_mode(integral_constant<int, 1>{}, integral_constant<bool, true>{});
             else by_mode(integral_constant<int, 2>{}, integral_constant<bool, true>{});
         } else {
-            if (s >= 17) by_mode(integral_constant<int, 0>{}, integral_constant<bool, false>{});
+            if (mid) {
+                if constexpr (LIMBS == 2) by_mode(integral_constant<int, 3>{}, integral_constant<bool, false>{});
+            } else if (s >= 17) by_mode(integral_constant<int, 0>{}, integral_constant<bool, false>{});
             else if (s == 16) by_mode(integral_constant<int, 1>{}, integral_constant<bool, false>{});
             else by_mode(integral_constant<int, 2>{}, integral_constant<bool, false>{});
         }
@@ -804,7 +827,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             abase_s[m] = ok ? (img * a.Hp + yo - vr0) * a.PW + t : 0;
             pooloff[m] = (a.pool && ok && !(j & 1) && !(t & 1)) ? (img * (a.Ho >> 1) + (yo >> 1)) * (a.Wo >> 1) + (xo >> 1) : -1;
         }
-        build_colterms<BN, THREADS>(a, ntile, ctab);
+        build_colterms<BN, THREADS>(a, ntile, ctab, LIMBS);
     };
 
     // Weight slabs: slab t = chunk * taps + tap lives at [chunk][tap][limb][K half][CoutP][32], i.e.
@@ -1316,7 +1339,7 @@ __global__ __launch_bounds__(256) void conv_finish_kernel(const ConvArgs a, int 
             pooloff[m] = (a.pool && ok && !(j & 1) && !(t & 1))
                              ? ((fr / a.Ho) * (a.Ho >> 1) + ((fr % a.Ho) >> 1)) * (a.Wo >> 1) + (xo >> 1) : -1;
         }
-        build_colterms<BN, THREADS>(a, ntile, ctab);
+        build_colterms<BN, THREADS>(a, ntile, ctab, LIMBS);
         v16i acc[1][NB][NACC];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)

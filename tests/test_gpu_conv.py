@@ -153,6 +153,31 @@ def test_conv_requantization_shift_sweep(oracle, fo):
         assert 0 < z < y.size
 
 
+@pytest.mark.parametrize("fo", [12, 11, 10, 7, 5, 4, 3])
+def test_conv_requantization_short_form_boundaries(oracle, fo):
+    """Right shifts 8, 9, 10, 13, 15, 16 and 17 (f_acc = 20): the edges of the range in which the
+    fused epilogue uses its shorter 32-bit form, with codes on every side of the rounding
+    boundaries, and with outputs whose top limb sum is far beyond what that form keeps (all-maximum
+    and all-minimum weights against an all-maximum image: saturated and zero codes)."""
+    rng = np.random.default_rng(70 + fo)
+    qx, qw = (16, 8, 8), (16, 4, 12)
+    f_acc = 20
+    x = np.maximum(_codes(rng, (2, 64, 10, 12), full_range=False), 0)
+    x[0] = 32767
+    w = _codes(rng, (64, 64, 3, 3), full_range=False) >> 6
+    w[0], w[1], w[2] = 32767, -32768, 1
+    w[3] = 0
+    w[3, 0, 1, 1] = 1 << (f_acc - fo - 1) if f_acc - fo - 1 < 15 else 1    # products that land on exact halves
+    bias = _codes(rng, (64,), n=12)
+    qy = (16, 16 - fo, fo)
+    _check(oracle, x, w, qx, qw, qy, bias=bias, qb=(16, 8, 8), expect_path=1)
+    got = conv(x, qx, w, qw, qy=qy, bias=bias, qb=(16, 8, 8), want_acc=False)          # 32-bit epilogue
+    acc = oracle.conv(x, w, bias=bias, f_acc=f_acc, fb=8)
+    y, z = oracle.act(acc, f_acc, *qy, True, oracle.ROUND_AWAY)
+    assert np.array_equal(got["y"], y) and got["zeros"] == z
+    assert (y[0, 0] == 32767).all() and (y[0, 1] == 0).all() and 0 < z < y.size
+
+
 def test_conv_int8_wide_tiles(oracle):
     rng = np.random.default_rng(12)
     x = np.maximum(_codes(rng, (66, 64, 32, 32), n=8), 0)
