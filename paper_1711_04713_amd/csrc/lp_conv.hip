@@ -799,6 +799,8 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     unsigned char *Bsm = Asm + (size_t)LIMBS * APL;
 
     const int tid = threadIdx.x;
+    // LDS address of the staged planes (patch path: positions and fragment offsets are kept as LDS addresses)
+    const int planes_lds = (int)(unsigned long)(__attribute__((address_space(3))) unsigned char *)Asm;
     // Entries past the patch (the staging loops overshoot it by up to a few batches) read as
     // zeros and are parked in the spare slot at the end of a plane.
     const unsigned px_bytes = (unsigned)a.Cin * (LIMBS == 2 ? 2u : 1u);
@@ -812,7 +814,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             if (n < a.N && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) g = (n * a.H + iy) * a.W + ix;
         }
         tab[p] = FLAT ? g : (g >= 0 ? (int)((unsigned)g * px_bytes) : -1);
-        apos[p] = pos;
+        apos[p] = planes_lds + pos; // as an LDS address: parking a piece then costs no base add
         psum[p] = 0;
     }
     // The tables of the tile rows and the channel constants are not needed to request the first
@@ -844,14 +846,12 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     const int wm = wave % WMC, wn = wave / WMC;
     const int l32 = lane & 31, kg = lane >> 5;
     int aoff[MB]; // filled once the row tables are visible
-    // LDS address of the staged planes (patch path: fragment offsets are kept as LDS addresses)
-    const int planes_lds = (int)(unsigned long)(__attribute__((address_space(3))) unsigned char *)Asm;
     auto lane_constants = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             const int row = wm * WROWS + mb * 32 + l32;
             // the row's (r=0, s=0) pixel; patch path: the lane's 16-byte slot of the first K half in it
-            aoff[mb] = FLAT ? row * PS : planes_lds + apos[abase_s[row]] + kg * 16;
+            aoff[mb] = FLAT ? row * PS : apos[abase_s[row]] + kg * 16;
         }
     };
     if constexpr (!LATE_ROWS) lane_constants();
@@ -886,9 +886,9 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     // The LDS position is read together with the source offset, when the piece is requested:
     // read where the piece is parked, it would wait for the LDS writes of the piece before it
     // (LDS operations complete in order), a round trip per piece.
-    auto load_piece = [&](int cc, int first, v4i &reg, int &at) __attribute__((always_inline)) {
-        const int ch = cc * CK + apiece * (CK / PIECES);
-        const unsigned chb = ch < a.Cin ? (unsigned)ch * ESZ_X : 0xffffffffu;
+    // chb: byte offset of the thread's piece inside a pixel for the chunk being staged (see
+    // channel_offset)
+    auto load_piece = [&](unsigned chb, int first, v4i &reg, int &at) __attribute__((always_inline)) {
         const int p = apix0 + first / PIECES;
         const unsigned off = __builtin_elementwise_add_sat((unsigned)tab[p], chb);
         at = apos[p] + piece_at;
@@ -913,15 +913,21 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, w2), ones, sum, false);
             sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, w3), ones, sum, false);
             if (own_sums) atomicAdd(&psum[p], sum); // no value returned
-            *(v2i *)(Asm + at) = hi;
-            *(v2i *)(Asm + APL + at) = lo;
+            *(__attribute__((address_space(3))) v2i *)(unsigned)at = hi;
+            *(__attribute__((address_space(3))) v2i *)(unsigned)(at + APL) = lo;
         } else {
-            *(v4i *)(Asm + at) = v;
+            *(__attribute__((address_space(3))) v4i *)(unsigned)at = v;
         }
     };
-    auto load_act = [&](int cc, int first, v4i *reg, int *at) __attribute__((always_inline)) {
+    auto channel_offset = [&](int cc) __attribute__((always_inline)) {
+        const int ch = cc * CK + apiece * (CK / PIECES);
+        unsigned chb = ch < a.Cin ? (unsigned)ch * ESZ_X : 0xffffffffu;
+        asm volatile("" : "+v"(chb)); // opaque: one select per staging, not one per piece behind the saturating add
+        return chb;
+    };
+    auto load_act = [&](unsigned chb, int first, v4i *reg, int *at) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < APF; ++j) load_piece(cc, first + j * THREADS, reg[j], at[j]);
+        for (int j = 0; j < APF; ++j) load_piece(chb, first + j * THREADS, reg[j], at[j]);
     };
     auto store_act = [&](int first, const v4i *reg, const int *at) __attribute__((always_inline)) {
 #pragma unroll
@@ -994,6 +1000,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             // two batches of requests in flight; a request past the end of the patch reads as
             // zeros and is parked in the spare slot (see the patch tables)
             const int total = NPIXA * PIECES;
+            const unsigned chb = channel_offset(cc);
             int first = 0;
             if (deep) {
                 // the accumulators are not live yet: request the first DEEP pieces of every
@@ -1001,7 +1008,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
                 v4i d[DEEP];
                 int dat[DEEP];
 #pragma unroll
-                for (int j = 0; j < DEEP; ++j) load_piece(cc, j * THREADS, d[j], dat[j]);
+                for (int j = 0; j < DEEP; ++j) load_piece(chb, j * THREADS, d[j], dat[j]);
                 between();
 #pragma unroll
                 for (int j = 0; j < DEEP; ++j) store_piece(j * THREADS, d[j], dat[j]);
@@ -1016,14 +1023,14 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             // destination registers are reused in the multiply loop, and the wait that protects
             // them would sit at the top of every slab, where it would also wait for the weight
             // operands just requested) and the loop has one way out.
-            load_act(cc, first, aregA, atA);
+            load_act(chb, first, aregA, atA);
             for (; first + 2 * APF * THREADS < total; first += 2 * APF * THREADS) {
-                load_act(cc, first + APF * THREADS, aregB, atB);
+                load_act(chb, first + APF * THREADS, aregB, atB);
                 store_act(first, aregA, atA);
-                load_act(cc, first + 2 * APF * THREADS, aregA, atA);
+                load_act(chb, first + 2 * APF * THREADS, aregA, atA);
                 store_act(first + APF * THREADS, aregB, atB);
             }
-            load_act(cc, first + APF * THREADS, aregB, atB);
+            load_act(chb, first + APF * THREADS, aregB, atB);
             store_act(first, aregA, atA);
             store_act(first + APF * THREADS, aregB, atB);
         }
