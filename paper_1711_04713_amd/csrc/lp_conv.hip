@@ -553,6 +553,7 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
     const int wm = wave % WMC, wn = wave / WMC;
     const int l32 = lane & 31, kg = lane >> 5;
     unsigned nz = 0; // zero codes written by this lane (at most 16 * MB * NB <= 64)
+    unsigned wz = 0; // zero codes counted for the whole wave (a scalar: ballots and popcounts)
     int oo[MBL], po[MBL], rs[MBL];
 #pragma unroll
     for (int mb = 0; mb < MBL; ++mb) {
@@ -644,14 +645,15 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                                 }
                             }
                         } else if constexpr (Y16) {
-                            // codes are in [0, cmax]: packing needs no masks.  Exact per-field zero
-                            // test: the top bit of a 16-bit (8-bit) field survives only when every
-                            // bit of the field is clear; no carry crosses fields
+                            // codes are in [0, cmax]: packing needs no masks
                             unsigned w0 = (unsigned)q[0] | ((unsigned)q[1] << 16);
                             unsigned w1 = (unsigned)q[2] | ((unsigned)q[3] << 16);
-                            constexpr unsigned LOW = 0x7fff7fffu;
-                            const unsigned z = __popc(~(((w0 & LOW) + LOW) | w0 | LOW)) + __popc(~(((w1 & LOW) + LOW) | w1 | LOW));
-                            nz += counted ? z : 0u;
+                            // zeros: one compare per code into a lane mask, masks counted by the
+                            // scalar unit (codes of lanes whose pixel or channels do not exist are
+                            // masked out)
+                            const unsigned long long live = __builtin_amdgcn_ballot_w64(counted);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) wz += __builtin_popcountll(__builtin_amdgcn_ballot_w64(q[e] == 0) & live);
                             if constexpr (MODE == 1) {
                                 // 2x2 maximum across lanes: the horizontal neighbour is the next lane,
                                 // the vertical one sits TW lanes further in the same 32-row block.
@@ -670,9 +672,9 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                             __builtin_amdgcn_raw_buffer_store_b64((v2u){w0, w1}, yrsrc, (int)at, 0, 0);
                         } else {
                             const unsigned w0 = (unsigned)q[0] | ((unsigned)q[1] << 8) | ((unsigned)q[2] << 16) | ((unsigned)q[3] << 24);
-                            constexpr unsigned LOW = 0x7f7f7f7fu;
-                            const unsigned z = __popc(~(((w0 & LOW) + LOW) | w0 | LOW));
-                            nz += counted ? z : 0u;
+                            const unsigned long long live = __builtin_amdgcn_ballot_w64(counted);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) wz += __builtin_popcountll(__builtin_amdgcn_ballot_w64(q[e] == 0) & live);
                             const unsigned at = col_ok ? rel[mb] + (unsigned)col0 : NOWHERE;
                             __builtin_amdgcn_raw_buffer_store_b32(w0, yrsrc, (int)at, 0, 0);
                         }
@@ -737,7 +739,7 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
             }
     }
     // wave total of the per-lane counts, bit plane by bit plane: ballot + popcount
-    unsigned zeros = 0;
+    unsigned zeros = wz;
 #pragma unroll
     for (int b = 0; b < 7; ++b) zeros += wave_count((nz >> b) & 1) << b;
     return zeros;
