@@ -420,10 +420,29 @@ struct ConvArgs {
     int total_work, per_xcd, full_per_xcd, split;
     unsigned char *partials; // tail tiles' partial accumulators, part_bytes per (tile, part)
     int part_bytes;
+    // floor(2^32 / d) for the divisors the kernel's index arithmetic uses (see udivmod)
+    unsigned mg_tiles_n, mg_tiles_c, mg_Ho, mg_Hp, mg_PW, mg_TW, mg_taps, mg_S;
     int fast; // 32-bit requantization is exact for this call (see epilogue)
     int pool; // store the 2x2 maxima of the codes (planner guarantees the tile geometry)
     ActParams act;
 };
+
+// x / d and x % d for 0 <= x < 2^31, d >= 1, with m = floor(2^32 / d) from the host: the high half
+// of x * m is the quotient or one below it, one compare settles it.  Five cheap operations
+// instead of the float-reciprocal sequence a division by a run-time value compiles to (on scalars
+// they run on the scalar unit).
+__host__ inline unsigned udiv_magic(int d) { return d <= 1 ? 0xffffffffu : (unsigned)((1ull << 32) / (unsigned)d); }
+__device__ __forceinline__ void udivmod(int x, int d, unsigned m, int &q, int &r)
+{
+    unsigned qq = __umulhi((unsigned)x, m);
+    unsigned rr = (unsigned)x - qq * (unsigned)d;
+    if (rr >= (unsigned)d) {
+        ++qq;
+        rr -= (unsigned)d;
+    }
+    q = (int)qq;
+    r = (int)rr;
+}
 
 __device__ __forceinline__ int64_t bias_term(const ConvArgs &a, int co)
 {
@@ -782,10 +801,12 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         if (a.zero_partial && threadIdx.x == 0) a.zero_partial[blockIdx.x] = 0;
         return;
     }
-    const int mtile = wi / a.tiles_n, ntile = wi % a.tiles_n;
-    const int tile_r = mtile / a.tiles_c, tile_c = mtile % a.tiles_c;
+    int mtile, ntile, tile_r, tile_c, img0, yo0;
+    udivmod(wi, a.tiles_n, a.mg_tiles_n, mtile, ntile);
+    udivmod(mtile, a.tiles_c, a.mg_tiles_c, tile_r, tile_c);
     const int fr0 = tile_r * a.RH, x0 = tile_c * a.TW;
-    const int vr0 = (fr0 / a.Ho) * a.Hp + fr0 % a.Ho;
+    udivmod(fr0, a.Ho, a.mg_Ho, img0, yo0);
+    const int vr0 = img0 * a.Hp + yo0;
 
     const int NPIXA = a.NPIXA;
     int *tab = (int *)smem;          // staged pixel -> byte offset of its codes in x, all ones outside the image
@@ -809,10 +830,12 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     for (int p = tid; p < a.NTAB; p += THREADS) {
         int g = -1, pos = APL - PSP;
         if (p < NPIXA) {
-            const int pr = p / a.PW, pc = p % a.PW;
+            int pr, pc, n, iy;
+            udivmod(p, a.PW, a.mg_PW, pr, pc);
             pos = pr * a.PITCH + pc * PSP;
-            const int vr = vr0 + pr;
-            const int n = vr / a.Hp, iy = vr % a.Hp - a.pad, ix = x0 - a.pad + pc;
+            udivmod(vr0 + pr, a.Hp, a.mg_Hp, n, iy);
+            iy -= a.pad;
+            const int ix = x0 - a.pad + pc;
             if (n < a.N && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) g = (n * a.H + iy) * a.W + ix;
         }
         tab[p] = FLAT ? g : (g >= 0 ? (int)((unsigned)g * px_bytes) : -1);
@@ -823,10 +846,11 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     // patch: they are built while those requests are in flight (see the first staging below).
     auto row_tables = [&]() __attribute__((always_inline)) {
         for (int m = tid; m < BM; m += THREADS) {
-            const int j = m / a.TW, t = m % a.TW;
+            int j, t, img, yo;
+            udivmod(m, a.TW, a.mg_TW, j, t);
             const int fr = fr0 + j, xo = x0 + t;
             const bool ok = j < a.RH && fr < a.FR && xo < a.Wo;
-            const int img = fr / a.Ho, yo = fr % a.Ho;
+            udivmod(fr, a.Ho, a.mg_Ho, img, yo);
             outoff[m] = ok ? fr * a.Wo + xo : -1;
             abase_s[m] = ok ? (img * a.Hp + yo - vr0) * a.PW + t : 0;
             pooloff[m] = (a.pool && ok && !(j & 1) && !(t & 1)) ? (img * (a.Ho >> 1) + (yo >> 1)) * (a.Wo >> 1) + (xo >> 1) : -1;
@@ -1041,8 +1065,9 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         __builtin_amdgcn_s_waitcnt(0x0F70);
     };
     // chunk and tap of the current slab, and the tap's patch offset, kept incrementally
-    int cc = s0 / a.taps, tap = s0 % a.taps;
-    int tap_r = FLAT ? 0 : tap / a.S, tap_s = FLAT ? 0 : tap % a.S;
+    int cc, tap, tap_r = 0, tap_s = 0;
+    udivmod(s0, a.taps, a.mg_taps, cc, tap);
+    if constexpr (!FLAT) udivmod(tap, a.S, a.mg_S, tap_r, tap_s);
     int taprow = tap_r * a.PITCH, tapoff = taprow + tap_s * PSP;
     // Weights go straight from global memory / L2 into the MFMA operand registers, NSETS - 1
     // K=32 halves ahead of their use; with no slab to publish, the waves of a workgroup meet only
@@ -1494,6 +1519,10 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     a.APLANE = p.flat ? BM * PS : p.PRA * p.PITCH + PSP; // the last slot of a plane parks overshoot pieces
     a.tiles_c = p.tiles_c; a.tiles_n = p.tiles_n; a.CoutP = p.CoutP; a.nchunks = p.nchunks;
     a.taps = p.taps; a.ksteps = p.ksteps; a.Kflat = d->R * d->S * d->Cin;
+    a.mg_tiles_n = udiv_magic(a.tiles_n); a.mg_tiles_c = udiv_magic(a.tiles_c);
+    a.mg_Ho = udiv_magic(a.Ho); a.mg_Hp = udiv_magic(a.Hp);
+    a.mg_PW = udiv_magic(a.PW); a.mg_TW = udiv_magic(a.TW);
+    a.mg_taps = udiv_magic(a.taps); a.mg_S = udiv_magic(d->S);
     a.total_work = p.tiles_m * p.tiles_n;
     a.per_xcd = p.per_xcd;
     a.full_per_xcd = p.full_per_xcd;
