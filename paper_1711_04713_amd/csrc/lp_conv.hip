@@ -509,6 +509,15 @@ __device__ __forceinline__ v16i mfma_i8(v4i a, v4i b, v16i c)
     return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
 }
 
+// min(max(q, 0), cmax) for 0 <= cmax as the one instruction the hardware has for it (with cmax in
+// a scalar register the compiler emits a max and a min).
+__device__ __forceinline__ int clamp_code(int q, int cmax)
+{
+    int r;
+    asm("v_med3_i32 %0, %1, 0, %2" : "=v"(r) : "v"(q), "s"(cmax));
+    return r;
+}
+
 // Requantization of v = 65536*hi + lo16 (hi = floor(v / 65536), 0 <= lo16 < 65536) to
 // clamp(floor((v + 2^(s-1)) / 2^s), 0, cmax) in 32-bit arithmetic, 1 <= s <= 31.  Negative v
 // give 0 (ReLU).  S16: 0 for s >= 17 (lo16 cannot matter), 1 for s == 16, 2 for s <= 15.
@@ -526,7 +535,7 @@ __device__ __forceinline__ int requant_relu32(int hi, int lo16, int s, int cmax)
         const int h = min(max(hi, -1), 32768);
         q = (h << (16 - s)) + ((lo16 + (1 << (s - 1))) >> s);
     }
-    return min(max(q, 0), cmax); // compiles to v_med3_i32
+    return clamp_code(q, cmax);
 }
 
 // Per-channel constants of a tile (weight correction + bias) into LDS, in the form the epilogue
@@ -604,10 +613,12 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
             const __amdgpu_buffer_rsrc_t yrsrc = __builtin_amdgcn_make_buffer_rsrc(
                 (unsigned char *)a.y + (size_t)first * a.Cout * ESZ, 0, (int)(left < 0x7fffffffu ? left : 0x7fffffffu), 0x00020000);
             unsigned rel[MBL]; // byte offset of the lane's output pixel from the tile's first one
+            unsigned long long rowmask[MBL]; // lanes whose output pixel exists (zero count)
 #pragma unroll
             for (int mb = 0; mb < MBL; ++mb) {
                 const int o = MODE == 1 ? po[mb] : oo[mb];
                 rel[mb] = o >= 0 ? (unsigned)((o - first) * a.Cout * ESZ) : NOWHERE;
+                rowmask[mb] = __builtin_amdgcn_ballot_w64(oo[mb] >= 0);
             }
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
@@ -616,6 +627,7 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                     const int cl = wn * (NB * 32) + nb * 32 + 8 * (g0 + gl) + 4 * kg; // channel within the tile
                     const int col0 = ntile * BN + cl;
                     const bool col_ok = col0 < a.Cout;
+                    const unsigned long long colmask = __builtin_amdgcn_ballot_w64(col_ok); // lanes whose channels exist
                     const v4i cA = *(const v4i *)(ctab + cl);
                     const v4i cB = *(const v4i *)(ctab + BN + cl);
                     const v4i cC = *(const v4i *)(ctab + 2 * BN + cl);
@@ -637,7 +649,7 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                                 const int T = acc[mb][nb][1][v] + cB[e] + (C >> 8);
                                 const int A = min(max(acc[mb][nb][0][v] + cA[e], -(1 << 22)), 1 << 22);
                                 const int W = (A << 8) + T + (rs[mb] >> 1);
-                                q[e] = min(max(W >> (s - 8), 0), cmax);
+                                q[e] = clamp_code(W >> (s - 8), cmax);
                                 continue;
                             } else if constexpr (LIMBS == 2) {
                                 const int C = acc[mb][nb][2][v] + cC[e] + ((rs[mb] & 1) << 7);
@@ -670,7 +682,7 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                             // zeros: one compare per code into a lane mask, masks counted by the
                             // scalar unit (codes of lanes whose pixel or channels do not exist are
                             // masked out)
-                            const unsigned long long live = __builtin_amdgcn_ballot_w64(counted);
+                            const unsigned long long live = rowmask[mb] & colmask;
 #pragma unroll
                             for (int e = 0; e < 4; ++e) wz += __builtin_popcountll(__builtin_amdgcn_ballot_w64(q[e] == 0) & live);
                             if constexpr (MODE == 1) {
@@ -691,7 +703,7 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                             __builtin_amdgcn_raw_buffer_store_b64((v2u){w0, w1}, yrsrc, (int)at, 0, 0);
                         } else {
                             const unsigned w0 = (unsigned)q[0] | ((unsigned)q[1] << 8) | ((unsigned)q[2] << 16) | ((unsigned)q[3] << 24);
-                            const unsigned long long live = __builtin_amdgcn_ballot_w64(counted);
+                            const unsigned long long live = rowmask[mb] & colmask;
 #pragma unroll
                             for (int e = 0; e < 4; ++e) wz += __builtin_popcountll(__builtin_amdgcn_ballot_w64(q[e] == 0) & live);
                             const unsigned at = col_ok ? rel[mb] + (unsigned)col0 : NOWHERE;
