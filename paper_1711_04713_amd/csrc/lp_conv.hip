@@ -547,11 +547,22 @@ __device__ __forceinline__ void build_colterms(const ConvArgs &a, int ntile, int
         const int colg = ntile * BN + c;
         const int64_t t = colg < a.Cout ? a.corr[colg] + bias_term(a, colg) : 0;
         if (a.fast) {
-            // (two limbs, shifts 9..16: the epilogue's rounding half 2^(s-1) rides in the middle plane)
-            const int half9 = (limbs == 2 && a.act.s >= 9 && a.act.s <= 16) ? 1 << (a.act.s - 9) : 0;
-            ctab[c] = (int)(t >> 16);
-            ctab[BN + c] = (int)((t >> 8) & 255) + half9;
-            ctab[2 * BN + c] = (int)(t & 255);
+            // (shifts 9..16: the epilogue's rounding half 2^(s-1) rides in the constants, as 2^(s-9)
+            // at the scale of v / 256; one limb: the top plane arrives clamped and at that scale,
+            // the middle plane holds the low 16 bits)
+            const bool mid = a.act.s >= 9 && a.act.s <= 16;
+            const int half9 = mid ? 1 << (a.act.s - 9) : 0;
+            if (mid && limbs == 1) {
+                const int64_t top = t >> 16;
+                const int topc = (int)(top > (1 << 22) ? (1 << 22) : top < -(1 << 22) ? -(1 << 22) : top);
+                ctab[c] = topc * 256 + half9;
+                ctab[BN + c] = (int)(t & 65535);
+                ctab[2 * BN + c] = 0;
+            } else {
+                ctab[c] = (int)(t >> 16);
+                ctab[BN + c] = (int)((t >> 8) & 255) + (limbs == 2 ? half9 : 0);
+                ctab[2 * BN + c] = (int)(t & 255);
+            }
         } else {
             ((int64_t *)ctab)[c] = t;
         }
@@ -651,6 +662,12 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                                 const int W = (A << 8) + T + (rs[mb] >> 1);
                                 q[e] = clamp_code(W >> (s - 8), cmax);
                                 continue;
+                            } else if constexpr (S16 == 3) {
+                                // one limb, shifts 9..16: the same with v = 65536*cA + (acc + low 16
+                                // bits of the constant); cA arrives clamped, times 256, plus the half
+                                const int W = ((acc[mb][nb][0][v] + cB[e]) >> 8) + cA[e];
+                                q[e] = clamp_code(W >> (s - 8), cmax);
+                                continue;
                             } else if constexpr (LIMBS == 2) {
                                 const int C = acc[mb][nb][2][v] + cC[e] + ((rs[mb] & 1) << 7);
                                 const int B = acc[mb][nb][1][v] + cB[e] + (rs[mb] >> 1) + (C >> 8);
@@ -720,17 +737,17 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
             if ((a.Cout & 3) == 0) requant_tile(s16c, y16c, integral_constant<int, 0>{}); // every group of four channels is aligned
             else requant_tile(s16c, y16c, integral_constant<int, 2>{});
         };
-        // shift classes: two limbs 9..16 (the usual ones) -> 3; else >= 17 -> 0, 16 -> 1, <= 15 -> 2
-        const bool mid = LIMBS == 2 && s >= 9 && s <= 16;
+        // shift classes: 9..16 (the usual ones) -> 3; else >= 17 -> 0, 16 -> 1, <= 15 -> 2
+        const bool mid = s >= 9 && s <= 16;
         if (a.y16) {
             if (mid) {
-                if constexpr (LIMBS == 2) by_mode(integral_constant<int, 3>{}, integral_constant<bool, true>{});
+                by_mode(integral_constant<int, 3>{}, integral_constant<bool, true>{});
             } else if (s >= 17) by_mode(integral_constant<int, 0>{}, integral_constant<bool, true>{});
             else if (s == 16) by_mode(integral_constant<int, 1>{}, integral_constant<bool, true>{});
             else by_mode(integral_constant<int, 2>{}, integral_constant<bool, true>{});
         } else {
             if (mid) {
-                if constexpr (LIMBS == 2) by_mode(integral_constant<int, 3>{}, integral_constant<bool, false>{});
+                by_mode(integral_constant<int, 3>{}, integral_constant<bool, false>{});
             } else if (s >= 17) by_mode(integral_constant<int, 0>{}, integral_constant<bool, false>{});
             else if (s == 16) by_mode(integral_constant<int, 1>{}, integral_constant<bool, false>{});
             else by_mode(integral_constant<int, 2>{}, integral_constant<bool, false>{});
