@@ -74,6 +74,57 @@ def test_conv_two_limb_shapes(oracle, N, Cin, H, W, Cout, R, S, pad):
     _check(oracle, x, w, QX, QW, (16, 12, 4), pad=pad, expect_path=1)
 
 
+def _random_shapes(count, seed):
+    """Seeded draw of small layer shapes the MFMA path accepts: every kernel size of Table 1, odd
+    widths and heights (tile widths of every kind, patches of many pitches), 1..3 channel chunks,
+    ragged channel tiles, with and without padding."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        R = int(rng.choice([1, 3, 3, 3, 5, 7]))
+        S = R if rng.random() < 0.8 else int(rng.choice([1, 3, 5]))
+        pad = int(rng.integers(0, (max(R, S) + 1) // 2 + 1))
+        H, W = int(rng.integers(max(R - 2 * pad, 1), 40)), int(rng.integers(max(S - 2 * pad, 1), 40))
+        if H + 2 * pad < R or W + 2 * pad < S:
+            continue
+        Cin = int(rng.choice([16, 24, 32, 64, 72, 128, 136, 192]))
+        Cout = int(rng.choice([8, 16, 40, 64, 100, 128, 192]))
+        N = int(rng.integers(1, 6))
+        if N * H * W * Cin * R * S * Cout > 6e9:          # keep the oracle under a few seconds
+            continue
+        out.append((N, Cin, H, W, Cout, R, S, pad))
+    return out
+
+
+@pytest.mark.parametrize("N,Cin,H,W,Cout,R,S,pad", _random_shapes(24, 2024))
+def test_conv_random_shapes_16bit(oracle, N, Cin, H, W, Cout, R, S, pad):
+    rng = np.random.default_rng(N * 7 + Cin + 3 * H + W)
+    x = _codes(rng, (N, Cin, H, W), zero_frac=0.4)
+    w = _codes(rng, (Cout, Cin, R, S))
+    _check(oracle, x, w, QX, QW, (16, 13, 3), pad=pad, expect_path=1)          # int64 epilogue and raw sums
+    xs = np.maximum(_codes(rng, (N, Cin, H, W), full_range=False), 0)
+    ws = _codes(rng, (Cout, Cin, R, S), full_range=False) >> 3
+    got = conv(xs, QX, ws, QW, qy=(16, 4, 12), pad=pad, want_acc=False)         # fused 32-bit epilogue
+    acc = oracle.conv(xs, ws, pad=pad, threads=8)
+    y, z = oracle.act(acc, 27, 16, 4, 12, True, oracle.ROUND_AWAY)
+    assert np.array_equal(got["y"], y) and got["zeros"] == z
+
+
+@pytest.mark.parametrize("N,Cin,H,W,Cout,R,S,pad", _random_shapes(10, 77))
+def test_conv_random_shapes_8bit(oracle, N, Cin, H, W, Cout, R, S, pad):
+    if Cin % 16:
+        Cin += 16 - Cin % 16
+    rng = np.random.default_rng(N + Cin + H + W)
+    x = np.maximum(_codes(rng, (N, Cin, H, W), n=8), 0)
+    w = _codes(rng, (Cout, Cin, R, S), n=8)
+    qx, qw, qy = (8, 3, 5), (8, 1, 7), (8, 5, 3)
+    got = conv(x, qx, w, qw, qy=qy, pad=pad, want_acc=False)
+    acc = oracle.conv(x, w, pad=pad, threads=8)
+    y, z = oracle.act(acc, 12, *qy, True, oracle.ROUND_AWAY)
+    assert got["info"]["path"] == 1 and got["info"]["limbs"] == 1
+    assert np.array_equal(got["y"], y) and got["zeros"] == z
+
+
 def test_conv_realistic_values_and_bias(oracle):
     rng = np.random.default_rng(5)
     x = np.maximum(_codes(rng, (2, 64, 18, 18), full_range=False), 0)
