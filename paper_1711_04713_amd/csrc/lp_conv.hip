@@ -421,7 +421,7 @@ struct ConvArgs {
     unsigned char *partials; // tail tiles' partial accumulators, part_bytes per (tile, part)
     int part_bytes;
     // floor(2^32 / d) for the divisors the kernel's index arithmetic uses (see udivmod)
-    unsigned mg_tiles_n, mg_tiles_c, mg_Ho, mg_Hp, mg_PW, mg_TW, mg_taps, mg_S;
+    unsigned mg_tiles_n, mg_tiles_c, mg_Ho, mg_Hp, mg_PW, mg_TW, mg_taps, mg_S, mg_Cin, mg_SC;
     int fast; // 32-bit requantization is exact for this call (see epilogue)
     int pool; // store the 2x2 maxima of the codes (planner guarantees the tile geometry)
     ActParams act;
@@ -1000,7 +1000,8 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
 #pragma unroll
             for (int u = 0; u < RU; ++u) {
                 const int i = min(i0 + u * THREADS, nraw - 1);
-                const int p = i / a.Cin, ci = i - p * a.Cin;
+                int p, ci;
+                udivmod(i, a.Cin, a.mg_Cin, p, ci);
                 const int g = tab[p];
                 const unsigned off = g >= 0 ? (unsigned)(g * a.Cin + ci) * 2u : 0xffffffffu;
                 v[u] = (short)__builtin_amdgcn_raw_buffer_load_b16(xrsrc, (int)off, 0, 0);
@@ -1009,38 +1010,62 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             for (int u = 0; u < RU; ++u)
                 if (i0 + u * THREADS < nraw) raw[i0 + u * THREADS] = v[u];
         }
+        // Window element k of a tile row = (r, s, ci) with k = (r*S + s)*Cin + ci sits
+        // koff[k] = r * PW*Cin + (k - r * S*Cin) codes behind the row's first window element in
+        // the raw patch, the same for every row: a table of byte offsets, one entry per k (it
+        // lives in the position table, which this variant does not use; entries past K repeat
+        // entry 0 and their codes are masked out below).
+        int *koff = apos;
+        const int SC = a.S * a.Cin;
+        for (int k = tid; k < 64; k += THREADS) {
+            int r, rem;
+            udivmod(k, SC, a.mg_SC, r, rem);
+            koff[k] = k < a.Kflat ? 2 * (r * a.PW * a.Cin + rem) : 0;
+        }
         __syncthreads();
-        // Window k of a tile row = (r, s, ci) with k = (r*S + s)*Cin + ci: inside one window row
-        // the S*Cin codes are consecutive in the raw patch, and the next window row starts
-        // PW*Cin further.  A thread gathers 16 consecutive k; only the K halves the MFMAs will
-        // read (32 * ksteps of the 64 slab bytes) are built.
-        const int SC = a.S * a.Cin, jump = (a.PW - a.S) * a.Cin;
+        // A thread gathers 16 consecutive k of one tile row: two codes per register (16-bit LDS
+        // reads into the two halves), then the byte permutes and two-element dot products of the
+        // patch path.  Only the K halves the MFMAs will read (32 * ksteps of the 64 slab bytes)
+        // are built.  Piece i: row i % BM, k0 = 16 * (i / BM), so k0 is the same for a whole wave
+        // and the mask for codes past K is scalar work.
         const int pieces = BM * 2 * a.ksteps;
+        const unsigned char *rawb = (const unsigned char *)raw;
         for (int i = tid; i < pieces; i += THREADS) {
-            const int row = i >> a.ksteps, k0 = (i & (2 * a.ksteps - 1)) * 16; // 2 * ksteps is 2 or 4
-            const int r0 = k0 / SC;
-            int cnt = k0 - r0 * SC;                                      // position inside the window row
-            int idx = abase_s[row] * a.Cin + r0 * (a.PW * a.Cin) + cnt;  // raw index of window element k0
-            unsigned hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
-            int sum = 0;
+            const int row = i & (BM - 1);
+            const int k0 = __builtin_amdgcn_readfirstlane(i / BM) * 16;
+            const int base = abase_s[row] * a.Cin * 2; // byte offset of the row's first window element
+            const v4i o0 = *(const v4i *)(koff + k0), o1 = *(const v4i *)(koff + k0 + 4);
+            const v4i o2 = *(const v4i *)(koff + k0 + 8), o3 = *(const v4i *)(koff + k0 + 12);
+            const int o[16] = {o0.x, o0.y, o0.z, o0.w, o1.x, o1.y, o1.z, o1.w, o2.x, o2.y, o2.z, o2.w, o3.x, o3.y, o3.z, o3.w};
+            unsigned pr[8];
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int val = (k0 + j < a.Kflat) ? (int)raw[min(idx, nraw - 1)] : 0;
-                sum += val;
-                hi[j >> 2] |= (unsigned)((val >> 8) & 255) << (8 * (j & 3));
-                lo[j >> 2] |= (unsigned)(val & 255) << (8 * (j & 3));
-                ++idx;
-                if (++cnt == SC) {
-                    cnt = 0;
-                    idx += jump;
+            for (int q = 0; q < 8; ++q) {
+                const v2s two = {*(const short *)(rawb + base + o[2 * q]), *(const short *)(rawb + base + o[2 * q + 1])};
+                pr[q] = __builtin_bit_cast(unsigned, two);
+            }
+            const int nv = a.Kflat - k0; // codes of this piece that exist
+            if (nv < 16) {
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const int m = min(max(nv - 2 * q, 0), 2);
+                    pr[q] &= m == 2 ? 0xffffffffu : m == 1 ? 0xffffu : 0u;
                 }
             }
-            if (sum) atomicAdd(&psum[row], sum);
+            unsigned hi[4], lo[4];
+            int sum = 0;
+            const v2s ones = {1, 1};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                hi[q] = __builtin_amdgcn_perm(pr[2 * q + 1], pr[2 * q], 0x07050301u);
+                lo[q] = __builtin_amdgcn_perm(pr[2 * q + 1], pr[2 * q], 0x06040200u) ^ 0x80808080u;
+                sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, pr[2 * q]), ones, sum, false);
+                sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, pr[2 * q + 1]), ones, sum, false);
+            }
+            atomicAdd(&psum[row], sum);
             // low limbs are offset by 128 (code 0, also beyond K, is the byte 0x80: it multiplies
             // zero weights there)
             const v4i vh = {(int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
-            const v4i vl = {(int)(lo[0] ^ 0x80808080u), (int)(lo[1] ^ 0x80808080u), (int)(lo[2] ^ 0x80808080u),
-                            (int)(lo[3] ^ 0x80808080u)};
+            const v4i vl = {(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3]};
             *(v4i *)(Asm + swz(row * PS, k0 >> 4)) = vh;
             *(v4i *)(Asm + APL + swz(row * PS, k0 >> 4)) = vl;
         }
@@ -1552,6 +1577,7 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     a.mg_Ho = udiv_magic(a.Ho); a.mg_Hp = udiv_magic(a.Hp);
     a.mg_PW = udiv_magic(a.PW); a.mg_TW = udiv_magic(a.TW);
     a.mg_taps = udiv_magic(a.taps); a.mg_S = udiv_magic(d->S);
+    a.mg_Cin = udiv_magic(d->Cin); a.mg_SC = udiv_magic(d->S * d->Cin);
     a.total_work = p.tiles_m * p.tiles_n;
     a.per_xcd = p.per_xcd;
     a.full_per_xcd = p.full_per_xcd;
