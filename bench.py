@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0
 # profiles/): average bytes per launch over the 13 launches of one step, already scaled by the
 # copy-kernel factor.  Valid only for the kernel source it was measured on (sha256 of lp_conv.hip);
 # reported as null for any other source.
-TRAFFIC_RECORD = {"lp_conv_sha256": "06c0ddd53f41e22bf275f0c494bed35c8c347e298ff57b434d7e88a8e94e5c85", "bytes_per_launch": 124049043}
+TRAFFIC_RECORD = {"lp_conv_sha256": "caccb01219f08003652f6ede410da5dc0129d64a3383208d82e5cce2e05eb061", "bytes_per_launch": 123912139}
 
 
 def _traffic_for_current_source():
