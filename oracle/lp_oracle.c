@@ -318,9 +318,12 @@ int orc_fc(int M, int K, int Nout, const int32_t *x, const int32_t *w, const int
  * is divided by 2^s, s = f_acc - fo, rounded to nearest and saturated to n
  * bits.  ReLU and this quantizer commute (it is monotone and maps 0 to 0), so
  * max(acc, 0) is taken first.  zero_count = number of output codes equal to 0
- * (Sec. 3.1: sparsity is zeros over elements). */
+ * (Sec. 3.1: sparsity is zeros over elements).  sat_count (optional) = number
+ * of elements whose rounded value lay outside the code range and was clipped:
+ * the share of activations the layer's format loses (Sec. 2.3 keeps that
+ * share under a user threshold when it places the point). */
 int orc_act(const int64_t *acc, int64_t count, int f_acc, int n, int m, int fo, int relu, int mode,
-            int32_t *code, uint64_t *zero_count)
+            int32_t *code, uint64_t *zero_count, uint64_t *sat_count)
 {
     if (!fmt_ok(n, m, fo) || count < 0 || f_acc < 0 || (mode != ORC_ROUND_AWAY && mode != ORC_ROUND_EVEN))
         return -1;
@@ -328,7 +331,7 @@ int orc_act(const int64_t *acc, int64_t count, int f_acc, int n, int m, int fo, 
     if (s > 62 || s < -31) return -1;
     const int64_t lo = code_min(n), hi = code_max(n);
     const int64_t bound = (int64_t)1 << 62;
-    uint64_t zeros = 0;
+    uint64_t zeros = 0, sats = 0;
     for (int64_t i = 0; i < count; ++i) {
         int64_t v = acc[i];
         if (v >= bound || v <= -bound) return -2; /* outside the supported accumulator width */
@@ -353,12 +356,13 @@ int orc_act(const int64_t *acc, int64_t count, int f_acc, int n, int m, int fo, 
             else if (v < lo) r = lo - 1;
             else r = v * ((int64_t)1 << (-s));
         }
-        if (r < lo) r = lo;
-        if (r > hi) r = hi;
+        if (r < lo) { r = lo; ++sats; }
+        if (r > hi) { r = hi; ++sats; }
         code[i] = (int32_t)r;
         zeros += (r == 0);
     }
     if (zero_count) *zero_count = zeros;
+    if (sat_count) *sat_count = sats;
     return 0;
 }
 
@@ -369,7 +373,7 @@ int orc_act(const int64_t *acc, int64_t count, int f_acc, int n, int m, int fo, 
  * rem / 2^s with an integer rem < 2^62, so u * 2^s (a power-of-two scaling) is
  * compared with rem in long double (64-bit significand, asserted below). */
 int orc_act_stochastic(const int64_t *acc, const double *u, int64_t count, int f_acc, int n, int m,
-                       int fo, int relu, int32_t *code, uint64_t *zero_count)
+                       int fo, int relu, int32_t *code, uint64_t *zero_count, uint64_t *sat_count)
 {
     _Static_assert(__LDBL_MANT_DIG__ >= 64, "long double must hold a 62-bit integer exactly");
     if (!fmt_ok(n, m, fo) || count < 0 || f_acc < 0) return -1;
@@ -377,7 +381,7 @@ int orc_act_stochastic(const int64_t *acc, const double *u, int64_t count, int f
     if (s > 62 || s < -31) return -1;
     const int64_t lo = code_min(n), hi = code_max(n);
     const int64_t bound = (int64_t)1 << 62;
-    uint64_t zeros = 0;
+    uint64_t zeros = 0, sats = 0;
     for (int64_t i = 0; i < count; ++i) {
         int64_t v = acc[i];
         if (v >= bound || v <= -bound) return -2;
@@ -395,12 +399,13 @@ int orc_act_stochastic(const int64_t *acc, const double *u, int64_t count, int f
             else if (v < lo) r = lo - 1;
             else r = v * ((int64_t)1 << (-s));
         }
-        if (r < lo) r = lo;
-        if (r > hi) r = hi;
+        if (r < lo) { r = lo; ++sats; }
+        if (r > hi) { r = hi; ++sats; }
         code[i] = (int32_t)r;
         zeros += (r == 0);
     }
     if (zero_count) *zero_count = zeros;
+    if (sat_count) *sat_count = sats;
     return 0;
 }
 

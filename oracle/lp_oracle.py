@@ -154,28 +154,29 @@ def fc(x, w, bias=None, f_acc=0, fb=0, threads=1):
     return acc
 
 
-def act(acc, f_acc, n, m, fo, relu=True, mode=ROUND_AWAY):
-    """int64 accumulators -> (int32 codes, zero_count)."""
+def act(acc, f_acc, n, m, fo, relu=True, mode=ROUND_AWAY, with_sat=False):
+    """int64 accumulators -> (int32 codes, zero_count), plus the count of clipped values if with_sat."""
     acc = np.ascontiguousarray(acc, dtype=np.int64)
     code = np.empty(acc.shape, dtype=np.int32)
-    z = ctypes.c_uint64(0)
+    z, s = ctypes.c_uint64(0), ctypes.c_uint64(0)
     rc = _load().orc_act(_ptr(acc), ctypes.c_int64(acc.size), f_acc, n, m, fo, int(bool(relu)), mode,
-                         _ptr(code), ctypes.byref(z))
+                         _ptr(code), ctypes.byref(z), ctypes.byref(s))
     _check(rc, "act")
-    return code, int(z.value)
+    return (code, int(z.value), int(s.value)) if with_sat else (code, int(z.value))
 
 
-def act_stochastic(acc, u, f_acc, n, m, fo, relu=True):
-    """int64 accumulators, u in [0,1) per element -> (int32 codes, zero_count) (Sec. 2.4)."""
+def act_stochastic(acc, u, f_acc, n, m, fo, relu=True, with_sat=False):
+    """int64 accumulators, u in [0,1) per element -> (int32 codes, zero_count) (Sec. 2.4), plus the
+    count of clipped values if with_sat."""
     acc = np.ascontiguousarray(acc, dtype=np.int64)
     u = np.ascontiguousarray(u, dtype=np.float64)
     assert u.shape == acc.shape
     code = np.empty(acc.shape, dtype=np.int32)
-    z = ctypes.c_uint64(0)
+    z, s = ctypes.c_uint64(0), ctypes.c_uint64(0)
     rc = _load().orc_act_stochastic(_ptr(acc), _ptr(u), ctypes.c_int64(acc.size), f_acc, n, m, fo,
-                                    int(bool(relu)), _ptr(code), ctypes.byref(z))
+                                    int(bool(relu)), _ptr(code), ctypes.byref(z), ctypes.byref(s))
     _check(rc, "act_stochastic")
-    return code, int(z.value)
+    return (code, int(z.value), int(s.value)) if with_sat else (code, int(z.value))
 
 
 def maxpool2x2(x):

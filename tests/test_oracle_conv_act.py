@@ -108,6 +108,27 @@ def test_conv_linear_in_weights_and_bias_alignment(oracle):
         oracle.conv(x, w1, bias=bias, f_acc=10, fb=12)     # bias finer than the accumulator
 
 
+def test_fc_bias_alignment_per_output_column(oracle):
+    """LPInnerProduct with the quantized bias blob (Sec. 2.1): bias[o] joins column o of the
+    accumulator as bias * 2^(f_acc - fb); checked against an int64 library matmul, with M != Nout
+    and distinct bias entries so that a row/column mix-up cannot pass."""
+    rng = np.random.default_rng(16)
+    M, K, Nout = 5, 37, 9
+    x, w = _codes(rng, (M, K)), _codes(rng, (Nout, K))
+    bias = (np.arange(Nout, dtype=np.int32) - 4) * 1000 + 7          # all different, both signs
+    fx, fw, fb = 9, 15, 11
+    got = oracle.fc(x, w, bias=bias, f_acc=fx + fw, fb=fb)
+    want = x.astype(np.int64) @ w.astype(np.int64).T + (bias.astype(np.int64) << (fx + fw - fb))[None, :]
+    assert got.shape == (M, Nout) and np.array_equal(got, want)
+    # fb == f_acc: the bias is added as it is
+    assert np.array_equal(oracle.fc(x, w, bias=bias, f_acc=fb, fb=fb) - oracle.fc(x, w),
+                          np.broadcast_to(bias.astype(np.int64)[None, :], (M, Nout)))
+    # threads only spread the outer loop
+    assert np.array_equal(oracle.fc(x, w, bias=bias, f_acc=fx + fw, fb=fb, threads=3), want)
+    with pytest.raises(ValueError):
+        oracle.fc(x, w, bias=bias, f_acc=10, fb=12)                  # bias finer than the accumulator
+
+
 def test_extreme_values_need_the_int64_width(oracle):
     """All codes at -32768 over K = 25088: 25088 * 2^30, far beyond int32 and exact in int64."""
     K = 25088
@@ -138,8 +159,8 @@ def test_conv_sampled_and_threads_agree_with_full(oracle):
 
 # -------------------------------------------------------------------------- act
 
-def _exact_act(v, s, n, relu, mode):
-    """Round v / 2^s with Fractions (s may be negative), clip to n bits."""
+def _exact_round(v, s, relu, mode):
+    """Round v / 2^s with Fractions (s may be negative); no clipping."""
     if relu and v < 0:
         v = 0
     t = Fraction(v) / (Fraction(2) ** s) if s >= 0 else Fraction(v) * (2 ** -s)
@@ -153,7 +174,11 @@ def _exact_act(v, s, n, relu, mode):
         r = fl + 1 if t > 0 else fl
     else:
         r = fl if fl % 2 == 0 else fl + 1
-    return max(-(1 << (n - 1)), min((1 << (n - 1)) - 1, r))
+    return r
+
+
+def _exact_act(v, s, n, relu, mode):
+    return max(-(1 << (n - 1)), min((1 << (n - 1)) - 1, _exact_round(v, s, relu, mode)))
 
 
 @pytest.mark.parametrize("s", [1, 2, 8, 15, 23, 30, 0, -3])
@@ -170,10 +195,15 @@ def test_act_against_exact_rational_arithmetic(oracle, s, relu):
         np.array([0, 1, -1, span, -span, span - 1, -span - 1, (1 << 61), -(1 << 61)]),
     ]).astype(np.int64)
     for mode, name in ((oracle.ROUND_AWAY, "away"), (oracle.ROUND_EVEN, "even")):
-        code, zeros = oracle.act(acc, f_acc, n, n - fo, fo, relu, mode)
+        code, zeros, sats = oracle.act(acc, f_acc, n, n - fo, fo, relu, mode, with_sat=True)
         want = [_exact_act(int(v), s, n, relu, name) for v in acc]
         assert list(code) == want
         assert zeros == want.count(0)
+        # clipped = the exactly rounded value lies outside the n-bit code range (Sec. 2.3: the
+        # values a format loses); the sample holds values beyond both ends
+        unclipped = [_exact_round(int(v), s, relu, name) for v in acc]
+        want_sats = sum(1 for r in unclipped if r < -(1 << (n - 1)) or r > (1 << (n - 1)) - 1)
+        assert sats == want_sats and want_sats > (0 if relu else 2)
 
 
 def test_act_closed_form_zero_count(oracle):
@@ -238,16 +268,18 @@ def test_act_stochastic_against_exact_rationals(oracle, s):
     u = rng.random(400)
     u[:4] = [0.0, 1.0 - 2.0 ** -53, 0.5, 2.0 ** -40]
     for relu in (True, False):
-        code, zeros = oracle.act_stochastic(acc, u, fo + s, 16, 12, fo, relu)
-        want = []
+        code, zeros, sats = oracle.act_stochastic(acc, u, fo + s, 16, 12, fo, relu, with_sat=True)
+        want, clipped = [], 0
         for a, uu in zip(acc.tolist(), u.tolist()):
             v = max(a, 0) if relu else a
             t = Fraction(v, 1 << s)
             fl = t.numerator // t.denominator
             r = fl + (1 if Fraction(uu) < t - fl else 0)
+            clipped += (r < -32768 or r > 32767)
             want.append(min(max(r, -32768), 32767))
         assert code.tolist() == want
         assert zeros == sum(1 for w in want if w == 0)
+        assert sats == clipped
 
 
 def test_act_stochastic_degenerate_draws_expectation_and_float_quantizer(oracle):
@@ -360,3 +392,33 @@ def test_conv_stack_per_layer_kernel_sizes_and_paddings(oracle):
         assert (L["mw"], L["mo"], L["zeros"]) == (mw, mo, zeros) and np.array_equal(L["codes"], codes)
         cur, fx = (oracle.maxpool2x2(codes) if pool else codes), 16 - mo
     assert np.array_equal(out["final"], cur) and out["final"].shape == (2, 7, 2, 2)
+
+
+def test_fc_stack_equals_hand_composed_steps(oracle):
+    """The classifier chain (LPInnerProduct -> LPAct, ReLU on all but the last layer) must equal
+    the pinned steps composed by hand, layer by layer, including which layers apply ReLU."""
+    import lp_inputs
+    from oracle import vgg
+
+    x = lp_inputs.relu_normal((6, 40), seed=13)
+    ws = lp_inputs.config5_weights(seed=13, dims=[(40, 24), (24, 24), (24, 10)])
+    ws = [w * np.float32(12.0) for w in ws]                       # large enough for non-trivial codes
+    relus = [True, True, False]
+    out = vgg.fc_stack(x, ws, relus, n=16, threads=2)
+    mx = oracle.range_float(x, 16)[0]
+    assert out["mx"] == mx
+    cur, fx = oracle.quantize(x, 16, mx, 16 - mx)[0], 16 - mx
+    assert np.array_equal(out["x_codes"], cur)
+    for w, relu, L in zip(ws, relus, out["layers"]):
+        mw = oracle.range_float(w, 16)[0]
+        wc = oracle.quantize(w, 16, mw, 16 - mw)[0]
+        acc = cur.astype(np.int64) @ wc.astype(np.int64).T            # library matmul
+        f_acc = fx + 16 - mw
+        mo = oracle.range_acc(acc, f_acc, relu, 16)[0]
+        codes, zeros = oracle.act(acc, f_acc, 16, mo, 16 - mo, relu, oracle.ROUND_AWAY)
+        assert (L["mw"], L["mo"], L["f_acc"], L["zeros"]) == (mw, mo, f_acc, zeros)
+        assert np.array_equal(L["acc"], acc) and np.array_equal(L["codes"], codes)
+        cur, fx = codes, 16 - mo
+    assert np.array_equal(out["final"], cur) and out["final"].shape == (6, 10)
+    assert out["layers"][0]["codes"].min() >= 0 and out["final"].min() < 0      # ReLU on fc6/fc7 only
+    assert all(L["codes"].any() for L in out["layers"])
