@@ -209,6 +209,7 @@ def main():
         per.setdefault(label, []).append(a.elapsed_time(b))
     avg = {k: sum(v) / len(v) for k, v in per.items()}
     zeros = stack.zero_counts.cpu().numpy()
+    sats = stack.sat_counts.cpu().numpy()
     layers = []
     total_macs = 0
     kern_ops, kern_ms = {}, {}
@@ -225,7 +226,8 @@ def main():
         kern_ms[kname] = kern_ms.get(kname, 0.0) + ms
         layers.append({
             "layer": name, "ms": round(ms, 4), "format_in": repr(L["qx"]), "format_w": repr(L["qw"]),
-            "format_out": repr(L["qy"]), "sparsity": round(float(zeros[i]) / L["y_numel"], 4), "pool_fused": bool(L["fused_pool"]),
+            "format_out": repr(L["qy"]), "sparsity": round(float(zeros[i]) / L["y_numel"], 4),
+            "saturated": round(float(sats[i]) / L["y_numel"], 6), "pool_fused": bool(L["fused_pool"]),
             "int8_tops": round(8 * macs / (ms * 1e-3) / 1e12, 1), "kernel": kname,
             "tile": [info["tile_rows"], info["tile_cols"], info["bn"]], "workgroups": info["workgroups"],
             "split": info["split"],

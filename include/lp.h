@@ -112,10 +112,14 @@ lp_status lp_quantize(const float *x_dev, void *codes_dev, size_t count, lp_qfmt
  * qy.f fraction bits: code = clip(round(max(acc,0) / 2^(f_acc - qy.f))).
  * |acc| must be below 2^62; -31 <= f_acc - qy.f <= 62.
  * zero_count_dev (nullable): += number of zero output codes (Sec. 3.1 defines
- * sparsity as zeros over elements).  r: NEAREST_AWAY or NEAREST_EVEN.
+ * sparsity as zeros over elements).  sat_count_dev (nullable): += number of
+ * values whose rounded result lay outside the code range and was clipped, i.e.
+ * the activations this format loses (Sec. 2.3 keeps their share under a
+ * threshold when it places the point; Sec. 2.5: they saturate).  After ReLU
+ * only the upper end can clip.  r: NEAREST_AWAY or NEAREST_EVEN.
  */
 lp_status lp_act(const int64_t *acc_dev, size_t count, int f_acc, lp_qfmt qy, int relu, lp_round r,
-                 void *y_codes_dev, uint64_t *zero_count_dev, void *stream);
+                 void *y_codes_dev, uint64_t *zero_count_dev, uint64_t *sat_count_dev, void *stream);
 
 /*
  * lp_act_stochastic -- lp_act with the stochastic rounding_scheme (Sec. 2.4):
@@ -129,7 +133,7 @@ lp_status lp_act(const int64_t *acc_dev, size_t count, int f_acc, lp_qfmt qy, in
  */
 lp_status lp_act_stochastic(const int64_t *acc_dev, size_t count, int f_acc, lp_qfmt qy, int relu,
                             uint64_t seed, void *y_codes_dev, uint64_t *zero_count_dev,
-                            void *stream);
+                            uint64_t *sat_count_dev, void *stream);
 
 /*
  * Weight packing for lp_conv_fwd / lp_fc_fwd.  Done once per layer, outside
@@ -153,17 +157,21 @@ lp_status lp_conv_pack_weights(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, co
  * codes and the rest padding that spreads consecutive pixels over the LDS banks; rows are
  * patch_pitch bytes apart), tile counts and LDS bytes per workgroup; the launch: workgroups in the grid, and split = parts into which each tile of the
  * last, partly filled round of workgroup slots is cut along the reduction (1 = none; used
- * only when a workspace is passed).
+ * only when a workspace is passed).  Work item wi = pixel tile * tiles_n + channel tile (pixel
+ * tiles row-major over stacked output rows x columns); die j of the chip's eight owns the items
+ * j * items_per_die ... (j + 1) * items_per_die - 1, of which the first whole_items_per_die are
+ * computed by one workgroup each and the rest are the split ones.
  */
 typedef struct {
     int32_t path, limbs, bn, tile_rows, tile_cols, patch_rows, patch_cols, tiles_m, tiles_n;
     int32_t lds_bytes, patch_pitch, patch_pixel, workgroups, split;
+    int32_t items_per_die, whole_items_per_die;
 } lp_plan_info;
 lp_status lp_conv_plan_info(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, lp_plan_info *out_host);
 
 /* Bytes of device workspace lp_conv_fwd uses for this problem (may be 0): per-workgroup
  * partial zero counts, and room for the partial sums of tiles whose reduction is shared
- * between workgroups.  The workspace is required when zero_count_dev is given; otherwise it
+ * between workgroups.  The workspace is required when zero_count_dev or sat_count_dev is given; otherwise it
  * is optional, and without it every tile is reduced by a single workgroup (same results,
  * idle CUs in the last round).  Its contents need no initialisation and carry nothing from
  * call to call; calls that share one workspace must not overlap in time. */
@@ -183,7 +191,9 @@ lp_status lp_conv_workspace_bytes(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw,
  *                 (d->pool: the 2x2 maxima of those codes, N x Ho/2 x Wo/2 x Cout)
  *   zero_count_dev nullable; += zeros among the y codes (d->pool: among the codes before
  *                 pooling, i.e. the layer's activation sparsity); needs workspace_dev
- *   workspace_dev nullable unless zero_count_dev is given; 16-byte aligned and at least
+ *   sat_count_dev nullable; += y codes that were clipped (see lp_act; counted before pooling
+ *                 too); needs workspace_dev
+ *   workspace_dev nullable unless a counter is given; 16-byte aligned and at least
  *                 lp_conv_workspace_bytes long, else LP_EWORKSPACE
  * At least one of acc_out_dev / y_codes_dev must be given.
  * LP_EUNSUPPORTED: R*S*Cin >= 65536 with 16-bit operands (int32 limb sums
@@ -194,8 +204,8 @@ lp_status lp_conv_workspace_bytes(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw,
 lp_status lp_conv_fwd(const lp_conv_desc *d, const void *x_codes_dev, lp_qfmt qx,
                       const void *w_packed_dev, lp_qfmt qw, const void *bias_codes_dev, lp_qfmt qb,
                       int64_t *acc_out_dev, void *y_codes_dev, lp_qfmt qy, int relu, lp_round r,
-                      uint64_t *zero_count_dev, void *workspace_dev, size_t workspace_bytes,
-                      void *stream);
+                      uint64_t *zero_count_dev, uint64_t *sat_count_dev, void *workspace_dev,
+                      size_t workspace_bytes, void *stream);
 
 /*
  * lp_fc_fwd -- LPInnerProduct forward (Sec. 2) with the same fused tail:
@@ -209,8 +219,8 @@ lp_status lp_fc_workspace_bytes(int M, int K, int Nout, lp_qfmt qx, lp_qfmt qw, 
 lp_status lp_fc_fwd(int M, int K, int Nout, const void *x_codes_dev, lp_qfmt qx,
                     const void *w_packed_dev, lp_qfmt qw, const void *bias_codes_dev, lp_qfmt qb,
                     int64_t *acc_out_dev, void *y_codes_dev, lp_qfmt qy, int relu, lp_round r,
-                    uint64_t *zero_count_dev, void *workspace_dev, size_t workspace_bytes,
-                    void *stream);
+                    uint64_t *zero_count_dev, uint64_t *sat_count_dev, void *workspace_dev,
+                    size_t workspace_bytes, void *stream);
 
 /*
  * lp_maxpool2x2 -- 2x2 max, stride 2, on NHWC codes (the pooling between VGG16

@@ -18,7 +18,8 @@ def conv_stack(x, weights, pool_after, n=16, n_w=None, threshold=0.0, mode=orc.R
 
     formats (optional): list of dicts {"mw","mo"} (+ "mx" in entry 0) to use frozen formats
     instead of measuring them.  Returns {"mx", "layers": [ {mw, fw, mo, fo, f_acc, zeros,
-    count, codes (LPAct output, NCHW), pooled (or None)} ... ], "x_codes"}.
+    sats (values clipped by the output format), count, codes (LPAct output, NCHW), pooled (or
+    None)} ... ], "x_codes"}.
     """
     n_w = n_w or n
     mx = formats[0]["mx"] if formats else orc.range_float(x, n, threshold)[0]
@@ -33,10 +34,10 @@ def conv_stack(x, weights, pool_after, n=16, n_w=None, threshold=0.0, mode=orc.R
         f_acc = fx + fw
         mo = formats[i]["mo"] if formats else orc.range_acc(acc, f_acc, True, n, threshold)[0]
         fo = n - mo
-        codes, zeros = orc.act(acc, f_acc, n, mo, fo, True, mode)
+        codes, zeros, sats = orc.act(acc, f_acc, n, mo, fo, True, mode, with_sat=True)
         pooled = orc.maxpool2x2(codes) if pool else None
         out["layers"].append({
-            "mw": mw, "fw": fw, "mo": mo, "fo": fo, "f_acc": f_acc, "zeros": zeros,
+            "mw": mw, "fw": fw, "mo": mo, "fo": fo, "f_acc": f_acc, "zeros": zeros, "sats": sats,
             "count": int(codes.size), "w_codes": wc if keep_codes else None,
             "codes": codes if keep_codes else None, "pooled": pooled if keep_codes else None,
         })
@@ -60,8 +61,8 @@ def fc_stack(x, weights, relu_after, n=16, threshold=0.0, mode=orc.ROUND_AWAY, t
         f_acc = fx + fw
         mo = orc.range_acc(acc, f_acc, relu, n, threshold)[0]
         fo = n - mo
-        codes, zeros = orc.act(acc, f_acc, n, mo, fo, relu, mode)
-        out["layers"].append({"mw": mw, "fw": fw, "mo": mo, "fo": fo, "f_acc": f_acc, "zeros": zeros,
+        codes, zeros, sats = orc.act(acc, f_acc, n, mo, fo, relu, mode, with_sat=True)
+        out["layers"].append({"mw": mw, "fw": fw, "mo": mo, "fo": fo, "f_acc": f_acc, "zeros": zeros, "sats": sats,
                               "count": int(codes.size), "w_codes": wc, "acc": acc, "codes": codes})
         cur, fx = codes, fo
     out["final"] = cur

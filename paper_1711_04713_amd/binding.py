@@ -35,7 +35,7 @@ class QFmt(ctypes.Structure):
 class PlanInfo(ctypes.Structure):
     _fields_ = [(k, ctypes.c_int32) for k in ("path", "limbs", "bn", "tile_rows", "tile_cols", "patch_rows",
                                                "patch_cols", "tiles_m", "tiles_n", "lds_bytes", "patch_pitch", "patch_pixel",
-                                               "workgroups", "split")]
+                                               "workgroups", "split", "items_per_die", "whole_items_per_die")]
 
     def asdict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}
@@ -55,9 +55,10 @@ _SIGNATURES = {
     "lp_quantize": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, QFmt, ctypes.c_int,
                                    ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
     "lp_act": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, QFmt, ctypes.c_int, ctypes.c_int,
-                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
+                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
     "lp_act_stochastic": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, QFmt, ctypes.c_int,
-                                         ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
+                                         ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_void_p]),
     "lp_conv_packed_bytes": (ctypes.c_int, [ctypes.POINTER(ConvDesc), QFmt, QFmt, ctypes.POINTER(ctypes.c_size_t)]),
     "lp_conv_plan_info": (ctypes.c_int, [ctypes.POINTER(ConvDesc), QFmt, QFmt, ctypes.POINTER(PlanInfo)]),
     "lp_conv_pack_weights": (ctypes.c_int, [ctypes.POINTER(ConvDesc), QFmt, QFmt, ctypes.c_void_p, ctypes.c_void_p,
@@ -66,7 +67,7 @@ _SIGNATURES = {
                                                ctypes.POINTER(ctypes.c_size_t)]),
     "lp_conv_fwd": (ctypes.c_int, [ctypes.POINTER(ConvDesc), ctypes.c_void_p, QFmt, ctypes.c_void_p, QFmt,
                                    ctypes.c_void_p, QFmt, ctypes.c_void_p, ctypes.c_void_p, QFmt, ctypes.c_int,
-                                   ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                   ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                                    ctypes.c_void_p]),
     "lp_fc_packed_bytes": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.c_int, QFmt, QFmt,
                                           ctypes.POINTER(ctypes.c_size_t)]),
@@ -76,7 +77,8 @@ _SIGNATURES = {
                                              ctypes.POINTER(ctypes.c_size_t)]),
     "lp_fc_fwd": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, QFmt, ctypes.c_void_p,
                                  QFmt, ctypes.c_void_p, QFmt, ctypes.c_void_p, ctypes.c_void_p, QFmt, ctypes.c_int,
-                                 ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+                                 ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                 ctypes.c_void_p]),
     "lp_maxpool2x2": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                      ctypes.c_int, ctypes.c_int, ctypes.c_void_p]),
 }
@@ -157,14 +159,14 @@ def lp_quantize(x, codes, q, r=LP_ROUND_NEAREST_AWAY, seed=0, zero_count=None, s
                               _stream()), "lp_quantize")
 
 
-def lp_act(acc, f_acc, qy, relu, y_codes, r=LP_ROUND_NEAREST_AWAY, zero_count=None):
+def lp_act(acc, f_acc, qy, relu, y_codes, r=LP_ROUND_NEAREST_AWAY, zero_count=None, sat_count=None):
     _check(load().lp_act(_ptr(acc), acc.numel(), f_acc, _q(qy), int(bool(relu)), r, _ptr(y_codes), _ptr(zero_count),
-                         _stream()), "lp_act")
+                         _ptr(sat_count), _stream()), "lp_act")
 
 
-def lp_act_stochastic(acc, f_acc, qy, relu, seed, y_codes, zero_count=None):
+def lp_act_stochastic(acc, f_acc, qy, relu, seed, y_codes, zero_count=None, sat_count=None):
     _check(load().lp_act_stochastic(_ptr(acc), acc.numel(), f_acc, _q(qy), int(bool(relu)), seed, _ptr(y_codes),
-                                    _ptr(zero_count), _stream()), "lp_act_stochastic")
+                                    _ptr(zero_count), _ptr(sat_count), _stream()), "lp_act_stochastic")
 
 
 def lp_conv_packed_bytes(desc, qx, qw):
@@ -192,12 +194,12 @@ def lp_conv_workspace_bytes(desc, qx, qw):
 
 
 def lp_conv_fwd(desc, x_codes, qx, w_packed, qw, qy=None, y_codes=None, acc_out=None, relu=True,
-                r=LP_ROUND_NEAREST_AWAY, bias_codes=None, qb=None, zero_count=None, workspace=None):
+                r=LP_ROUND_NEAREST_AWAY, bias_codes=None, qb=None, zero_count=None, workspace=None, sat_count=None):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().lp_conv_fwd(ctypes.byref(desc), _ptr(x_codes), _q(qx), _ptr(w_packed), _q(qw), _ptr(bias_codes),
                               _q(qb) if qb is not None else QFmt(), _ptr(acc_out), _ptr(y_codes),
                               _q(qy) if qy is not None else QFmt(), int(bool(relu)), r, _ptr(zero_count),
-                              _ptr(workspace), ws_bytes, _stream()), "lp_conv_fwd")
+                              _ptr(sat_count), _ptr(workspace), ws_bytes, _stream()), "lp_conv_fwd")
 
 
 def lp_fc_packed_bytes(M, K, Nout, qx, qw):
@@ -218,12 +220,12 @@ def lp_fc_workspace_bytes(M, K, Nout, qx, qw):
 
 
 def lp_fc_fwd(M, K, Nout, x_codes, qx, w_packed, qw, qy=None, y_codes=None, acc_out=None, relu=True,
-              r=LP_ROUND_NEAREST_AWAY, bias_codes=None, qb=None, zero_count=None, workspace=None):
+              r=LP_ROUND_NEAREST_AWAY, bias_codes=None, qb=None, zero_count=None, workspace=None, sat_count=None):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().lp_fc_fwd(M, K, Nout, _ptr(x_codes), _q(qx), _ptr(w_packed), _q(qw), _ptr(bias_codes),
                             _q(qb) if qb is not None else QFmt(), _ptr(acc_out), _ptr(y_codes),
                             _q(qy) if qy is not None else QFmt(), int(bool(relu)), r, _ptr(zero_count),
-                            _ptr(workspace), ws_bytes, _stream()), "lp_fc_fwd")
+                            _ptr(sat_count), _ptr(workspace), ws_bytes, _stream()), "lp_fc_fwd")
 
 
 def lp_maxpool2x2(x_codes, y_codes, N, H, W, C, n_bits):

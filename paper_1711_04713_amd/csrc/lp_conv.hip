@@ -411,8 +411,11 @@ struct ConvArgs {
     int64_t *acc_out;
     void *y;
     int y16;
-    unsigned long long *zero_count;
-    unsigned *zero_partial; // one count per workgroup (MFMA path), summed by a second kernel
+    unsigned long long *zero_count, *sat_count; // either may be null
+    unsigned *zero_partial; // per workgroup (MFMA path): [grid] zero counts, then [grid] counts of clipped
+                            // values; summed by a second kernel
+    int partial_stride;     // = grid
+    int count_sat;          // sat_count is wanted: the epilogue also counts the values it clips
     int N, H, W, Cin, Cout, R, S, stride, pad;
     int Ho, Wo, Hp, FR;
     int RH, TW, PW, NPIXA, NTAB, APLANE, PITCH;
@@ -460,10 +463,10 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(const ConvArgs a)
     const size_t total = (size_t)a.FR * a.Wo * a.Cout;
     const XT *x = (const XT *)a.x;
     const int16_t *w = (const int16_t *)a.wp;
-    unsigned zeros = 0;
+    unsigned zeros = 0, sats = 0;
     for (size_t i0 = (size_t)blockIdx.x * 256; i0 < total; i0 += (size_t)gridDim.x * 256) {
         const size_t i = i0 + threadIdx.x;
-        bool z = false;
+        bool z = false, sat = false;
         if (i < total) {
             const int co = (int)(i % a.Cout);
             size_t t = i / a.Cout;
@@ -486,16 +489,19 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(const ConvArgs a)
             acc += bias_term(a, co);
             if (a.acc_out) a.acc_out[i] = acc;
             if (a.y) {
-                const int c = act_one(acc, a.act);
+                const int c = act_one(acc, a.act, sat);
                 if (a.y16) ((int16_t *)a.y)[i] = (int16_t)c;
                 else ((int8_t *)a.y)[i] = (int8_t)c;
                 z = (c == 0);
             }
         }
         zeros += wave_count(z);
+        sats += wave_count(sat);
     }
-    if (a.zero_count && a.y && (threadIdx.x & 63) == 0 && zeros)
-        atomicAdd(a.zero_count, (unsigned long long)zeros);
+    if (a.y && (threadIdx.x & 63) == 0) {
+        if (a.zero_count && zeros) atomicAdd(a.zero_count, (unsigned long long)zeros);
+        if (a.sat_count && sats) atomicAdd(a.sat_count, (unsigned long long)sats);
+    }
 }
 
 // -------------------------------------------------------------------------- MFMA path
@@ -519,10 +525,12 @@ __device__ __forceinline__ int clamp_code(int q, int cmax)
 }
 
 // Requantization of v = 65536*hi + lo16 (hi = floor(v / 65536), 0 <= lo16 < 65536) to
-// clamp(floor((v + 2^(s-1)) / 2^s), 0, cmax) in 32-bit arithmetic, 1 <= s <= 31.  Negative v
-// give 0 (ReLU).  S16: 0 for s >= 17 (lo16 cannot matter), 1 for s == 16, 2 for s <= 15.
+// floor((v + 2^(s-1)) / 2^s) in 32-bit arithmetic, 1 <= s <= 31; the caller clamps to [0, cmax]
+// (negative v give 0: ReLU).  The value returned is exact wherever it lies inside the code range
+// and stays on the same side of it wherever it does not.  S16: 0 for s >= 17 (lo16 cannot
+// matter), 1 for s == 16, 2 for s <= 15.
 template <int S16>
-__device__ __forceinline__ int requant_relu32(int hi, int lo16, int s, int cmax)
+__device__ __forceinline__ int requant_relu32(int hi, int lo16, int s)
 {
     int q;
     if (S16 == 0) {
@@ -535,7 +543,7 @@ __device__ __forceinline__ int requant_relu32(int hi, int lo16, int s, int cmax)
         const int h = min(max(hi, -1), 32768);
         q = (h << (16 - s)) + ((lo16 + (1 << (s - 1))) >> s);
     }
-    return clamp_code(q, cmax);
+    return q;
 }
 
 // Per-channel constants of a tile (weight correction + bias) into LDS, in the form the epilogue
@@ -575,14 +583,18 @@ __device__ __forceinline__ void build_colterms(const ConvArgs &a, int ntile, int
 // and, in register v, channel 8*(v/4) + 4*(lane/32) + v%4 of its 32-channel block: four
 // consecutive channels per group of four registers, which leave as one 8-byte (4-byte) store.
 // row_sum(m): sum of the codes under tile row m's window (two-limb only); outoff and ctab (see
-// build_colterms) are LDS tables, complete and visible.  Returns the wave's count of zero codes
-// (the same value in every lane).
+// build_colterms) are LDS tables, complete and visible.  Returns the wave's counts of zero codes
+// and (when a.count_sat) of values clipped at an end of the code range, the same in every lane.
 // The accumulators passed in cover MBL of the wave's MB row blocks, starting at block mb0, and GL
 // of the four channel groups, starting at group g0 (register 4*gl + e = channel 8*(g0+gl) +
 // 4*(lane/32) + e): the main kernel passes everything (MBL = MB, GL = 4, mb0 = g0 = 0), the
 // finishing kernel one (row block, channel group) at a time.
+struct TileCounts {
+    unsigned zeros, sats;
+};
+
 template <int LIMBS, int NB, int MB, int THREADS, int MBL, int GL, typename RowSum>
-__device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)[MBL][NB][LIMBS == 2 ? 3 : 1],
+__device__ __forceinline__ TileCounts tile_epilogue(const ConvArgs &a, v16i (&acc)[MBL][NB][LIMBS == 2 ? 3 : 1],
                                                   RowSum row_sum, const int *outoff, const int *pooloff,
                                                   const int *ctab, int ntile, int mb0, int g0)
 {
@@ -591,8 +603,8 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WMC, wn = wave / WMC;
     const int l32 = lane & 31, kg = lane >> 5;
-    unsigned nz = 0; // zero codes written by this lane (at most 16 * MB * NB <= 64)
-    unsigned wz = 0; // zero codes counted for the whole wave (a scalar: ballots and popcounts)
+    unsigned nz = 0, ns = 0; // zero codes written / values clipped by this lane (at most 16 * MB * NB <= 64 each)
+    unsigned wz = 0, wsat = 0; // counted for the whole wave (scalars: ballots and popcounts)
     int oo[MBL], po[MBL], rs[MBL];
 #pragma unroll
     for (int mb = 0; mb < MBL; ++mb) {
@@ -613,10 +625,11 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
         const int s = a.act.s, cmax = a.act.hi;
         __builtin_assume(cmax >= 0);
         constexpr unsigned NOWHERE = 0x80000000u; // the descriptor never covers more than 2^31 - 1 bytes
-        auto requant_tile = [&](auto s16c, auto y16c, auto modec) __attribute__((always_inline)) {
+        auto requant_tile = [&](auto s16c, auto y16c, auto modec, auto satc) __attribute__((always_inline)) {
             constexpr int S16 = decltype(s16c)::value;
             constexpr bool Y16 = decltype(y16c)::value;
             constexpr int MODE = decltype(modec)::value; // 0: four codes per store, 1: fused 2x2 max-pool, 2: ragged channels
+            constexpr bool SAT = decltype(satc)::value;  // also count the values clipped at cmax (with ReLU the only end)
             constexpr int ESZ = Y16 ? 2 : 1;
             const int first = __builtin_amdgcn_readfirstlane(MODE == 1 ? pooloff[0] : outoff[0]);
             const size_t pixels = MODE == 1 ? (size_t)a.N * (a.Ho >> 1) * (a.Wo >> 1) : (size_t)a.N * a.Ho * a.Wo;
@@ -644,7 +657,7 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                     const v4i cC = *(const v4i *)(ctab + 2 * BN + cl);
 #pragma unroll
                     for (int mb = 0; mb < MBL; ++mb) {
-                        int q[4];
+                        int q[4], raw[4]; // codes, and the rounded values before clipping
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             const int v = 4 * gl + e;
@@ -660,13 +673,15 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                                 const int T = acc[mb][nb][1][v] + cB[e] + (C >> 8);
                                 const int A = min(max(acc[mb][nb][0][v] + cA[e], -(1 << 22)), 1 << 22);
                                 const int W = (A << 8) + T + (rs[mb] >> 1);
-                                q[e] = clamp_code(W >> (s - 8), cmax);
+                                raw[e] = W >> (s - 8);
+                                q[e] = clamp_code(raw[e], cmax);
                                 continue;
                             } else if constexpr (S16 == 3) {
                                 // one limb, shifts 9..16: the same with v = 65536*cA + (acc + low 16
                                 // bits of the constant); cA arrives clamped, times 256, plus the half
                                 const int W = ((acc[mb][nb][0][v] + cB[e]) >> 8) + cA[e];
-                                q[e] = clamp_code(W >> (s - 8), cmax);
+                                raw[e] = W >> (s - 8);
+                                q[e] = clamp_code(raw[e], cmax);
                                 continue;
                             } else if constexpr (LIMBS == 2) {
                                 const int C = acc[mb][nb][2][v] + cC[e] + ((rs[mb] & 1) << 7);
@@ -679,7 +694,8 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                                 hi = cA[e] + (C >> 16);
                                 lo16 = C & 65535;
                             }
-                            q[e] = requant_relu32<S16 == 3 ? 2 : S16>(hi, lo16, s, cmax);
+                            raw[e] = requant_relu32<S16 == 3 ? 2 : S16>(hi, lo16, s);
+                            q[e] = clamp_code(raw[e], cmax);
                         }
                         const bool counted = oo[mb] >= 0 && col_ok; // the lane's codes exist in the output tensor
                         if constexpr (MODE == 2) { // ragged channel tail: code by code
@@ -690,6 +706,7 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                                     if constexpr (Y16) ((int16_t *)dst)[e] = (int16_t)q[e];
                                     else ((int8_t *)dst)[e] = (int8_t)q[e];
                                     nz += (q[e] == 0);
+                                    if constexpr (SAT) ns += (raw[e] > cmax);
                                 }
                             }
                         } else if constexpr (Y16) {
@@ -702,6 +719,10 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                             const unsigned long long live = rowmask[mb] & colmask;
 #pragma unroll
                             for (int e = 0; e < 4; ++e) wz += __builtin_popcountll(__builtin_amdgcn_ballot_w64(q[e] == 0) & live);
+                            if constexpr (SAT) {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) wsat += __builtin_popcountll(__builtin_amdgcn_ballot_w64(raw[e] > cmax) & live);
+                            }
                             if constexpr (MODE == 1) {
                                 // 2x2 maximum across lanes: the horizontal neighbour is the next lane,
                                 // the vertical one sits TW lanes further in the same 32-row block.
@@ -723,6 +744,10 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                             const unsigned long long live = rowmask[mb] & colmask;
 #pragma unroll
                             for (int e = 0; e < 4; ++e) wz += __builtin_popcountll(__builtin_amdgcn_ballot_w64(q[e] == 0) & live);
+                            if constexpr (SAT) {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) wsat += __builtin_popcountll(__builtin_amdgcn_ballot_w64(raw[e] > cmax) & live);
+                            }
                             const unsigned at = col_ok ? rel[mb] + (unsigned)col0 : NOWHERE;
                             __builtin_amdgcn_raw_buffer_store_b32(w0, yrsrc, (int)at, 0, 0);
                         }
@@ -730,12 +755,16 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                 }
         };
         using std::integral_constant;
+        auto by_sat = [&](auto s16c, auto y16c, auto modec) __attribute__((always_inline)) {
+            if (a.count_sat) requant_tile(s16c, y16c, modec, integral_constant<bool, true>{});
+            else requant_tile(s16c, y16c, modec, integral_constant<bool, false>{});
+        };
         auto by_mode = [&](auto s16c, auto y16c) __attribute__((always_inline)) {
             if constexpr (decltype(y16c)::value) {
-                if (a.pool) return requant_tile(s16c, y16c, integral_constant<int, 1>{});
+                if (a.pool) return by_sat(s16c, y16c, integral_constant<int, 1>{});
             }
-            if ((a.Cout & 3) == 0) requant_tile(s16c, y16c, integral_constant<int, 0>{}); // every group of four channels is aligned
-            else requant_tile(s16c, y16c, integral_constant<int, 2>{});
+            if ((a.Cout & 3) == 0) by_sat(s16c, y16c, integral_constant<int, 0>{}); // every group of four channels is aligned
+            else by_sat(s16c, y16c, integral_constant<int, 2>{});
         };
         // shift classes: 9..16 (the usual ones) -> 3; else >= 17 -> 0, 16 -> 1, <= 15 -> 2
         const bool mid = s >= 9 && s <= 16;
@@ -776,10 +805,12 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
                             const size_t idx = (size_t)oo[mb] * a.Cout + col0 + e;
                             if (a.acc_out) a.acc_out[idx] = val;
                             if (a.y) {
-                                const int c = act_one(val, a.act);
+                                bool sat;
+                                const int c = act_one(val, a.act, sat);
                                 if (a.y16) ((int16_t *)a.y)[idx] = (int16_t)c;
                                 else ((int8_t *)a.y)[idx] = (int8_t)c;
                                 nz += (c == 0);
+                                ns += sat;
                             }
                         }
                     }
@@ -787,10 +818,14 @@ __device__ __forceinline__ unsigned tile_epilogue(const ConvArgs &a, v16i (&acc)
             }
     }
     // wave total of the per-lane counts, bit plane by bit plane: ballot + popcount
-    unsigned zeros = wz;
+    TileCounts t = {wz, wsat};
 #pragma unroll
-    for (int b = 0; b < 7; ++b) zeros += wave_count((nz >> b) & 1) << b;
-    return zeros;
+    for (int b = 0; b < 7; ++b) t.zeros += wave_count((nz >> b) & 1) << b;
+    if (a.count_sat) {
+#pragma unroll
+        for (int b = 0; b < 7; ++b) t.sats += wave_count((ns >> b) & 1) << b;
+    }
+    return t;
 }
 
 // LIMBS: 1 (int8 codes) or 2 (16-bit codes as two int8 limbs).  NB: 32-column blocks per
@@ -827,7 +862,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     }
     const int wi = xcd * a.per_xcd + tl;
     if (tl >= a.per_xcd || wi >= a.total_work) {
-        if (a.zero_partial && threadIdx.x == 0) a.zero_partial[blockIdx.x] = 0;
+        if (a.zero_partial && threadIdx.x == 0) a.zero_partial[blockIdx.x] = a.zero_partial[a.partial_stride + blockIdx.x] = 0;
         return;
     }
     int mtile, ntile, tile_r, tile_c, img0, yo0;
@@ -1358,19 +1393,22 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             int *rs = (int *)(mine + MB * NB * NACC * 4 * THREADS);
             for (int m = tid; m < BM; m += THREADS) rs[m] = row_sum(m);
         }
-        if (a.zero_partial && tid == 0) a.zero_partial[blockIdx.x] = 0;
+        if (a.zero_partial && tid == 0) a.zero_partial[blockIdx.x] = a.zero_partial[a.partial_stride + blockIdx.x] = 0;
         return;
     }
 
-    unsigned zeros = tile_epilogue<LIMBS, NB, MB, THREADS, MB, 4>(a, acc, row_sum, outoff, pooloff, ctab, ntile, 0, 0);
-    // one count per workgroup, no atomics: thousands of same-address atomics would serialise
+    const TileCounts counts = tile_epilogue<LIMBS, NB, MB, THREADS, MB, 4>(a, acc, row_sum, outoff, pooloff, ctab, ntile, 0, 0);
+    // one pair of counts per workgroup, no atomics: thousands of same-address atomics would serialise
     if (a.zero_partial) {
-        if (lane == 0) tab[wave] = (int)zeros; // tab[] was last read while staging
+        if (lane == 0) { // tab[] was last read while staging
+            tab[wave] = (int)counts.zeros;
+            tab[THREADS / 64 + wave] = (int)counts.sats;
+        }
         __syncthreads();
-        if (tid == 0) {
+        if (tid < 2) {
             unsigned total = 0;
-            for (int w = 0; w < THREADS / 64; ++w) total += (unsigned)tab[w];
-            a.zero_partial[blockIdx.x] = total;
+            for (int w = 0; w < THREADS / 64; ++w) total += (unsigned)tab[tid * (THREADS / 64) + w];
+            a.zero_partial[tid * a.partial_stride + blockIdx.x] = total;
         }
     }
 }
@@ -1393,14 +1431,14 @@ __global__ __launch_bounds__(256) void conv_finish_kernel(const ConvArgs a, int 
     __shared__ int rowsum[BM];
     __shared__ int pooloff[BM];
     __shared__ __align__(16) int ctab[3 * BN];
-    __shared__ unsigned wave_zeros[THREADS / 64];
+    __shared__ unsigned wave_zeros[2][THREADS / 64]; // [zeros, clipped][wave]
     const int tid = threadIdx.x;
     const int tails = a.per_xcd - a.full_per_xcd;
     const int tile_b = blockIdx.x / SUB, sub = blockIdx.x % SUB;
     const int mb0 = sub >> 2, g0 = sub & 3;
     const int xcd = tile_b / tails, tl = a.full_per_xcd + tile_b % tails;
     const int wi = xcd * a.per_xcd + tl;
-    unsigned long long total = 0;
+    unsigned long long total = 0; // thread 0: zeros, thread 1: clipped values
     if (wi < a.total_work) {
         const int mtile = wi / a.tiles_n, ntile = wi % a.tiles_n;
         const int tile_r = mtile / a.tiles_c, tile_c = mtile % a.tiles_c;
@@ -1453,34 +1491,51 @@ __global__ __launch_bounds__(256) void conv_finish_kernel(const ConvArgs a, int 
         }
         if (tid < BM) rowsum[tid] = rs;
         __syncthreads();
-        const unsigned zeros = tile_epilogue<LIMBS, NB, MB, THREADS, 1, 1>(
+        const TileCounts counts = tile_epilogue<LIMBS, NB, MB, THREADS, 1, 1>(
             a, acc, [&](int m) { return rowsum[m]; }, outoff, pooloff, ctab, ntile, mb0, g0);
-        if ((tid & 63) == 0) wave_zeros[tid >> 6] = zeros;
+        if ((tid & 63) == 0) {
+            wave_zeros[0][tid >> 6] = counts.zeros;
+            wave_zeros[1][tid >> 6] = counts.sats;
+        }
         __syncthreads();
-        if (tid == 0)
-            for (int w = 0; w < THREADS / 64; ++w) total += wave_zeros[w];
+        if (tid < 2)
+            for (int w = 0; w < THREADS / 64; ++w) total += wave_zeros[tid][w];
     }
     if (!a.zero_partial) return;
     if (blockIdx.x == 0) {
-        unsigned long long sum = 0;
-        for (int i = tid; i < main_grid; i += THREADS) sum += a.zero_partial[i];
+        unsigned long long sum[2] = {0, 0};
+        for (int i = tid; i < main_grid; i += THREADS) {
+            sum[0] += a.zero_partial[i];
+            sum[1] += a.zero_partial[a.partial_stride + i];
+        }
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) sum += __shfl_down(sum, off, 64);
+        for (int off = 32; off >= 1; off >>= 1) {
+            sum[0] += __shfl_down(sum[0], off, 64);
+            sum[1] += __shfl_down(sum[1], off, 64);
+        }
         __syncthreads(); // wave_zeros[] has been read
-        if ((tid & 63) == 0) wave_zeros[tid >> 6] = (unsigned)sum; // a launch has fewer than 2^32 outputs
+        if ((tid & 63) == 0) { // a launch has fewer than 2^32 outputs
+            wave_zeros[0][tid >> 6] = (unsigned)sum[0];
+            wave_zeros[1][tid >> 6] = (unsigned)sum[1];
+        }
         __syncthreads();
-        if (tid == 0)
-            for (int w = 0; w < THREADS / 64; ++w) total += wave_zeros[w];
+        if (tid < 2)
+            for (int w = 0; w < THREADS / 64; ++w) total += wave_zeros[tid][w];
     }
-    if (tid == 0 && total) atomicAdd(a.zero_count, total);
+    if (tid == 0 && total && a.zero_count) atomicAdd(a.zero_count, total);
+    if (tid == 1 && total && a.sat_count) atomicAdd(a.sat_count, total);
 }
 
-// Adds the per-workgroup zero counts to the caller's counter: a few blocks, eight independent
-// loads per thread and pass, one atomic per block.
-__global__ __launch_bounds__(256) void sum_partials_kernel(const unsigned *__restrict__ partial, int n,
-                                                          unsigned long long *out)
+// Adds the per-workgroup counts to the caller's counters: blockIdx.y = 0 the zero counts, 1 the
+// counts of clipped values (launched only when wanted); a few blocks, eight independent loads per
+// thread and pass, one atomic per block.  Either counter may be null.
+__global__ __launch_bounds__(256) void sum_partials_kernel(const unsigned *__restrict__ partials, int n,
+                                                          unsigned long long *out_zero, unsigned long long *out_sat)
 {
     __shared__ unsigned long long part[4];
+    const unsigned *partial = partials + (size_t)blockIdx.y * n;
+    unsigned long long *out = blockIdx.y ? out_sat : out_zero;
+    if (!out) return;
     unsigned long long s = 0;
     for (int i0 = blockIdx.x * 2048 + threadIdx.x; i0 < n; i0 += gridDim.x * 2048) {
         unsigned v[8];
@@ -1521,15 +1576,15 @@ static WorkspaceLayout workspace_layout(const Plan &p)
     WorkspaceLayout w = {0, 0};
     if (p.path != PATH_MFMA) return w;
     const size_t tails = (size_t)kXCDs * (p.per_xcd - p.full_per_xcd);
-    w.partials = round_up((size_t)p.grid * sizeof(unsigned), 256);
+    w.partials = round_up((size_t)2 * p.grid * sizeof(unsigned), 256); // zero counts, counts of clipped values
     w.total = w.partials + tails * p.split * p.part_bytes;
     return w;
 }
 
 static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, const void *wp,
                               lp_qfmt qw, const void *bias, lp_qfmt qb, int64_t *acc_out, void *y,
-                              lp_qfmt qy, int relu, lp_round r, uint64_t *zero_count, void *workspace,
-                              size_t workspace_bytes, void *stream)
+                              lp_qfmt qy, int relu, lp_round r, uint64_t *zero_count, uint64_t *sat_count,
+                              void *workspace, size_t workspace_bytes, void *stream)
 {
     Plan p;
     lp_status st = make_plan(d, qx, qw, &p);
@@ -1556,6 +1611,8 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     a.acc_out = acc_out;
     a.y = y;
     a.zero_count = (unsigned long long *)zero_count;
+    a.sat_count = (unsigned long long *)sat_count;
+    a.count_sat = (sat_count && y) ? 1 : 0;
     a.N = d->N; a.H = d->H; a.W = d->W; a.Cin = d->Cin; a.Cout = d->Cout;
     a.R = d->R; a.S = d->S; a.stride = d->stride; a.pad = d->pad;
     a.Ho = p.Ho; a.Wo = p.Wo; a.Hp = p.Hp; a.FR = p.FR;
@@ -1583,11 +1640,12 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     a.full_per_xcd = p.full_per_xcd;
     a.split = p.split;
     int grid = p.grid;
-    const bool counting = zero_count && y;
+    const bool counting = (zero_count || sat_count) && y;
     const WorkspaceLayout wl = workspace_layout(p);
     if (workspace) {
         if (workspace_bytes < wl.total || !aligned16(workspace)) return LP_EWORKSPACE;
         if (counting) a.zero_partial = (unsigned *)workspace;
+        a.partial_stride = grid;
         a.partials = (unsigned char *)workspace + wl.partials;
         a.part_bytes = (int)p.part_bytes;
     } else {
@@ -1615,8 +1673,8 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     else if (p.limbs == 2) st2 = launch_mfma<2, 1, false, 2>(a, p, grid, tails, hs);
     else st2 = p.BN == 128 ? launch_mfma<1, 2, false, 2>(a, p, grid, tails, hs) : launch_mfma<1, 1, false, 2>(a, p, grid, tails, hs);
     if (st2 != LP_OK || tails || !counting) return st2;
-    hipLaunchKernelGGL(sum_partials_kernel, dim3(std::min((grid + 2047) / 2048, 16)), dim3(256), 0, hs,
-                       a.zero_partial, grid, (unsigned long long *)zero_count);
+    hipLaunchKernelGGL(sum_partials_kernel, dim3(std::min((grid + 2047) / 2048, 16), sat_count ? 2 : 1), dim3(256), 0, hs,
+                       a.zero_partial, grid, (unsigned long long *)zero_count, (unsigned long long *)sat_count);
     return launch_status();
 }
 
@@ -1718,6 +1776,8 @@ extern "C" lp_status lp_conv_plan_info(const lp_conv_desc *d, lp_qfmt qx, lp_qfm
         o.patch_pixel = p.flat ? PS : PSP;
         o.workgroups = p.grid;
         o.split = p.split;
+        o.items_per_die = p.per_xcd;
+        o.whole_items_per_die = p.full_per_xcd;
     }
     *out_host = o;
     return LP_OK;
@@ -1736,11 +1796,11 @@ extern "C" lp_status lp_conv_workspace_bytes(const lp_conv_desc *d, lp_qfmt qx, 
 extern "C" lp_status lp_conv_fwd(const lp_conv_desc *d, const void *x_codes_dev, lp_qfmt qx,
                                  const void *w_packed_dev, lp_qfmt qw, const void *bias_codes_dev,
                                  lp_qfmt qb, int64_t *acc_out_dev, void *y_codes_dev, lp_qfmt qy,
-                                 int relu, lp_round r, uint64_t *zero_count_dev, void *workspace_dev,
-                                 size_t workspace_bytes, void *stream)
+                                 int relu, lp_round r, uint64_t *zero_count_dev, uint64_t *sat_count_dev,
+                                 void *workspace_dev, size_t workspace_bytes, void *stream)
 {
     return conv_forward(d, x_codes_dev, qx, w_packed_dev, qw, bias_codes_dev, qb, acc_out_dev,
-                        y_codes_dev, qy, relu, r, zero_count_dev, workspace_dev, workspace_bytes, stream);
+                        y_codes_dev, qy, relu, r, zero_count_dev, sat_count_dev, workspace_dev, workspace_bytes, stream);
 }
 
 extern "C" lp_status lp_fc_packed_bytes(int M, int K, int Nout, lp_qfmt qx, lp_qfmt qw,
@@ -1768,10 +1828,10 @@ extern "C" lp_status lp_fc_workspace_bytes(int M, int K, int Nout, lp_qfmt qx, l
 extern "C" lp_status lp_fc_fwd(int M, int K, int Nout, const void *x_codes_dev, lp_qfmt qx,
                                const void *w_packed_dev, lp_qfmt qw, const void *bias_codes_dev,
                                lp_qfmt qb, int64_t *acc_out_dev, void *y_codes_dev, lp_qfmt qy,
-                               int relu, lp_round r, uint64_t *zero_count_dev, void *workspace_dev,
-                               size_t workspace_bytes, void *stream)
+                               int relu, lp_round r, uint64_t *zero_count_dev, uint64_t *sat_count_dev,
+                               void *workspace_dev, size_t workspace_bytes, void *stream)
 {
     const lp_conv_desc d = fc_desc(M, K, Nout);
     return conv_forward(&d, x_codes_dev, qx, w_packed_dev, qw, bias_codes_dev, qb, acc_out_dev,
-                        y_codes_dev, qy, relu, r, zero_count_dev, workspace_dev, workspace_bytes, stream);
+                        y_codes_dev, qy, relu, r, zero_count_dev, sat_count_dev, workspace_dev, workspace_bytes, stream);
 }

@@ -35,8 +35,9 @@ __host__ inline ActParams make_act_params(int f_acc, lp_qfmt qy, int relu, lp_ro
     return a;
 }
 
-// One accumulator -> one output code.  |v| < 2^62.
-__device__ __forceinline__ int act_one(int64_t v, const ActParams &p)
+// One accumulator -> one output code.  |v| < 2^62.  sat: the rounded value lay outside
+// [lo, hi] and was clipped.
+__device__ __forceinline__ int act_one(int64_t v, const ActParams &p, bool &sat)
 {
     if (p.relu && v < 0) v = 0;
     int64_t r;
@@ -53,14 +54,22 @@ __device__ __forceinline__ int act_one(int64_t v, const ActParams &p)
             r = q;
         }
     } else {
+        // beyond the code range the product stays beyond it: one step outside keeps it in 64 bits
         int64_t c = v;
-        if (c > p.hi) c = p.hi;
-        if (c < p.lo) c = p.lo;
+        if (c > p.hi) c = (int64_t)p.hi + 1;
+        if (c < p.lo) c = (int64_t)p.lo - 1;
         r = c * ((int64_t)1 << (-p.s));
     }
+    sat = r > p.hi || r < p.lo;
     if (r > p.hi) r = p.hi;
     if (r < p.lo) r = p.lo;
     return (int)r;
+}
+
+__device__ __forceinline__ int act_one(int64_t v, const ActParams &p)
+{
+    bool sat;
+    return act_one(v, p, sat);
 }
 
 // Number of lanes of the wavefront for which pred holds (ballot + popcount).

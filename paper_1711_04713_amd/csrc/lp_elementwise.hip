@@ -53,10 +53,12 @@ __device__ __forceinline__ int quantize_one(float x, float scale, float lo, floa
     } else if (MODE == LP_ROUND_NEAREST_EVEN) {
         r = rintf(t);
     } else {
+        // the fractional part in double: t has 24 significant bits, and for a negative t just
+        // below zero t - floor(t) needs more than float holds (-0.25 + 2^-26 -> 0.75 + 2^-26)
         const float fl = floorf(t);
-        const float frac = t - fl; // exact
+        const double frac = (double)t - (double)fl; // exact
         const uint32_t w = philox4x32_10_word0(index, seed);
-        r = ((double)w < (double)frac * 4294967296.0) ? fl + 1.0f : fl;
+        r = ((double)w < frac * 4294967296.0) ? fl + 1.0f : fl;
     }
     if (t != t) r = 0.0f;
     sat = (r < lo) || (r > hi);
@@ -289,7 +291,8 @@ static lp_status finish_range(unsigned long long *hist_dev, size_t count, int n,
 
 // Sec. 2.4 on an accumulator: floor(v / 2^s) + [u < frac], u = 2^-32 * the first Philox word for
 // the element's index; the comparison u * 2^s < rem is done in integers (rem < 2^s <= 2^62).
-__device__ __forceinline__ int act_one_stochastic(int64_t v, const ActParams &p, uint64_t index, uint64_t seed)
+__device__ __forceinline__ int act_one_stochastic(int64_t v, const ActParams &p, uint64_t index, uint64_t seed,
+                                                  bool &sat)
 {
     if (p.relu && v < 0) v = 0;
     int64_t r;
@@ -301,10 +304,11 @@ __device__ __forceinline__ int act_one_stochastic(int64_t v, const ActParams &p,
         r = q + (up ? 1 : 0);
     } else {
         int64_t c = v;
-        if (c > p.hi) c = p.hi;
-        if (c < p.lo) c = p.lo;
+        if (c > p.hi) c = (int64_t)p.hi + 1;
+        if (c < p.lo) c = (int64_t)p.lo - 1;
         r = c * ((int64_t)1 << (-p.s));
     }
+    sat = r > p.hi || r < p.lo;
     if (r > p.hi) r = p.hi;
     if (r < p.lo) r = p.lo;
     return (int)r;
@@ -314,11 +318,15 @@ template <typename OutT, bool STOCH>
 __global__ __launch_bounds__(kThreads) void act_kernel(const int64_t *__restrict__ acc,
                                                       OutT *__restrict__ y, size_t count,
                                                       ActParams p, uint64_t seed,
-                                                      unsigned long long *zero_count)
+                                                      unsigned long long *zero_count,
+                                                      unsigned long long *sat_count)
 {
-    auto one = [&](int64_t v, size_t index) {
-        if constexpr (STOCH) return act_one_stochastic(v, p, index, seed);
-        else return act_one(v, p);
+    // counts are kept when either counter is wanted; a wave's totals are scalars
+    const bool counting = zero_count || sat_count;
+    unsigned sats = 0;
+    auto one = [&](int64_t v, size_t index, bool &sat) {
+        if constexpr (STOCH) return act_one_stochastic(v, p, index, seed, sat);
+        else return act_one(v, p, sat);
     };
     // A block takes 8 * kThreads consecutive accumulators per trip, as four rows of kThreads
     // 16-byte pairs: a lane's loads are 16 bytes apart from its neighbours' (1 KB contiguous per
@@ -338,43 +346,56 @@ __global__ __launch_bounds__(kThreads) void act_kernel(const int64_t *__restrict
             const int64_t a0 = (int64_t)(((uint64_t)(uint32_t)a[j].y << 32) | (uint32_t)a[j].x);
             const int64_t a1 = (int64_t)(((uint64_t)(uint32_t)a[j].w << 32) | (uint32_t)a[j].z);
             const size_t pair = pair0 + j * kThreads;
-            const int c0 = one(a0, 2 * pair), c1 = one(a1, 2 * pair + 1);
+            bool s0, s1;
+            const int c0 = one(a0, 2 * pair, s0), c1 = one(a1, 2 * pair + 1, s1);
             if (sizeof(OutT) == 2)
                 reinterpret_cast<int *>(y)[pair] = (c0 & 0xffff) | (c1 << 16);
             else
                 reinterpret_cast<short *>(y)[pair] = (short)((c0 & 0xff) | (c1 << 8));
-            if (zero_count) zeros += wave_count(c0 == 0) + wave_count(c1 == 0);
+            if (counting) {
+                zeros += wave_count(c0 == 0) + wave_count(c1 == 0);
+                sats += wave_count(s0) + wave_count(s1);
+            }
         }
     }
     // the groups that do not fill a block trip: one group of 8 per thread of block 0
     if (blockIdx.x == 0) {
         const size_t g = trips * kThreads + threadIdx.x;
         bool z[8] = {false, false, false, false, false, false, false, false};
+        bool st[8] = {false, false, false, false, false, false, false, false};
         if (g < groups) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const int c = one(acc[8 * g + j], 8 * g + j);
+                const int c = one(acc[8 * g + j], 8 * g + j, st[j]);
                 y[8 * g + j] = (OutT)c;
                 z[j] = (c == 0);
             }
         }
-        if (zero_count) {
+        if (counting) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) zeros += wave_count(z[j]);
+            for (int j = 0; j < 8; ++j) {
+                zeros += wave_count(z[j]);
+                sats += wave_count(st[j]);
+            }
         }
     }
     if (blockIdx.x == 0 && threadIdx.x < 64) {
         const size_t i = groups * 8 + threadIdx.x;
-        bool z = false;
+        bool z = false, st = false;
         if (threadIdx.x < 8 && i < count) {
-            const int c = one(acc[i], i);
+            const int c = one(acc[i], i, st);
             y[i] = (OutT)c;
             z = (c == 0);
         }
-        if (zero_count) zeros += wave_count(z);
+        if (counting) {
+            zeros += wave_count(z);
+            sats += wave_count(st);
+        }
     }
-    if (zero_count && (threadIdx.x & 63) == 0 && zeros)
-        atomicAdd(zero_count, (unsigned long long)zeros);
+    if ((threadIdx.x & 63) == 0) {
+        if (zero_count && zeros) atomicAdd(zero_count, (unsigned long long)zeros);
+        if (sat_count && sats) atomicAdd(sat_count, (unsigned long long)sats);
+    }
 }
 
 // ------------------------------------------------------------------------- maxpool
@@ -497,7 +518,7 @@ extern "C" lp_status lp_quantize(const float *x_dev, void *codes_dev, size_t cou
 
 static lp_status act_launch(const int64_t *acc_dev, size_t count, int f_acc, lp_qfmt qy, int relu,
                             lp_round r, uint64_t seed, void *y_codes_dev, uint64_t *zero_count_dev,
-                            void *stream)
+                            uint64_t *sat_count_dev, void *stream)
 {
     if (!fmt_ok(qy) || f_acc < 0) return LP_EINVAL;
     const int s = f_acc - qy.f;
@@ -509,7 +530,8 @@ static lp_status act_launch(const int64_t *acc_dev, size_t count, int f_acc, lp_
     const int grid = grid_for(count / 8); // one trip of the kernel's loop per block, up to the cap
 #define LP_A(T, STOCH) \
     hipLaunchKernelGGL((act_kernel<T, STOCH>), dim3(grid), dim3(kThreads), 0, st, acc_dev, \
-                       (T *)y_codes_dev, count, p, seed, (unsigned long long *)zero_count_dev)
+                       (T *)y_codes_dev, count, p, seed, (unsigned long long *)zero_count_dev, \
+                       (unsigned long long *)sat_count_dev)
     if (r == LP_ROUND_STOCHASTIC) {
         if (qy.n > 8) LP_A(int16_t, true);
         else LP_A(int8_t, true);
@@ -522,18 +544,19 @@ static lp_status act_launch(const int64_t *acc_dev, size_t count, int f_acc, lp_
 }
 
 extern "C" lp_status lp_act(const int64_t *acc_dev, size_t count, int f_acc, lp_qfmt qy, int relu,
-                            lp_round r, void *y_codes_dev, uint64_t *zero_count_dev, void *stream)
+                            lp_round r, void *y_codes_dev, uint64_t *zero_count_dev,
+                            uint64_t *sat_count_dev, void *stream)
 {
     if (r != LP_ROUND_NEAREST_AWAY && r != LP_ROUND_NEAREST_EVEN) return LP_EINVAL;
-    return act_launch(acc_dev, count, f_acc, qy, relu, r, 0, y_codes_dev, zero_count_dev, stream);
+    return act_launch(acc_dev, count, f_acc, qy, relu, r, 0, y_codes_dev, zero_count_dev, sat_count_dev, stream);
 }
 
 extern "C" lp_status lp_act_stochastic(const int64_t *acc_dev, size_t count, int f_acc, lp_qfmt qy,
                                        int relu, uint64_t seed, void *y_codes_dev,
-                                       uint64_t *zero_count_dev, void *stream)
+                                       uint64_t *zero_count_dev, uint64_t *sat_count_dev, void *stream)
 {
     return act_launch(acc_dev, count, f_acc, qy, relu, LP_ROUND_STOCHASTIC, seed, y_codes_dev,
-                      zero_count_dev, stream);
+                      zero_count_dev, sat_count_dev, stream);
 }
 
 extern "C" lp_status lp_maxpool2x2(const void *x_codes_dev, void *y_codes_dev, int N, int H, int W,

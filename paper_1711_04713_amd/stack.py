@@ -19,11 +19,13 @@ class ConvStack:
     """
 
     def __init__(self, weights, pool_after, n_act=16, n_w=16, loss_threshold=0.0, r=lp.LP_ROUND_NEAREST_AWAY,
-                 pad=1, fuse_pool=True):
+                 pad=1, fuse_pool=True, count_sat=True):
         """fuse_pool: let lp_conv_fwd store the 2x2 maxima directly where its tiling allows it
-        (the unpooled codes of such a layer are then never written; layer["y"] is None)."""
+        (the unpooled codes of such a layer are then never written; layer["y"] is None).
+        count_sat: also count, per layer, the activations the frozen output format clips
+        (sat_counts; Sec. 2.3's share of lost values, measured on the running batch)."""
         assert len(weights) == len(pool_after)
-        self.fuse_pool = fuse_pool
+        self.fuse_pool, self.count_sat = fuse_pool, count_sat
         self.n_act, self.n_w, self.thr, self.r = n_act, n_w, loss_threshold, r
         self.pads = list(pad) if isinstance(pad, (list, tuple)) else [pad] * len(weights)
         assert len(self.pads) == len(weights)
@@ -91,6 +93,8 @@ class ConvStack:
         self.in_shape = (N, H, W, self.w_float[0].shape[3])
         self.x_codes = torch.empty(self.in_shape, dtype=dt, device="cuda")
         self.zero_counts = torch.zeros(len(self.pool_after), dtype=torch.int64, device="cuda")
+        self.sat_counts = torch.zeros(len(self.pool_after), dtype=torch.int64, device="cuda")
+        self.input_sat = torch.zeros(1, dtype=torch.int64, device="cuda")
         self.layers = []
         q_in = self.qx
         for i, pool in enumerate(self.pool_after):
@@ -125,6 +129,9 @@ class ConvStack:
         pools.  events (optional): list to which (label, start_event, end_event) are appended."""
         assert tuple(x_float.shape) == self.in_shape
         self.zero_counts.zero_()
+        if self.count_sat:
+            self.sat_counts.zero_()
+            self.input_sat.zero_()
 
         def timed(label, fn):
             if events is None:
@@ -136,13 +143,15 @@ class ConvStack:
             b.record()
             events.append((label, a, b))
 
-        timed("quantize", lambda: lp.lp_quantize(x_float.reshape(-1), self.x_codes, self.qx, self.r))
+        timed("quantize", lambda: lp.lp_quantize(x_float.reshape(-1), self.x_codes, self.qx, self.r,
+                                                 sat_count=self.input_sat if self.count_sat else None))
         cur = self.x_codes
         for i, L in enumerate(self.layers):
             out = L["pooled"] if L["fused_pool"] else L["y"]
             timed("conv%d" % i, lambda L=L, cur=cur, i=i, out=out: lp.lp_conv_fwd(
                 L["desc"], cur, L["qx"], L["packed"], L["qw"], qy=L["qy"], y_codes=out, relu=True, r=self.r,
-                zero_count=self.zero_counts[i:i + 1], workspace=L["ws"]))
+                zero_count=self.zero_counts[i:i + 1], workspace=L["ws"],
+                sat_count=self.sat_counts[i:i + 1] if self.count_sat else None))
             cur = out
             if L["pooled"] is not None and not L["fused_pool"]:
                 d = L["desc"]

@@ -34,7 +34,7 @@ def quantize(x, q, r=lp.LP_ROUND_NEAREST_AWAY, seed=0, counters=True):
 
 
 def conv(x_codes, qx, w_codes, qw, qy=None, relu=True, r=lp.LP_ROUND_NEAREST_AWAY, bias=None, qb=None,
-         stride=1, pad=1, want_acc=True, want_y=True):
+         stride=1, pad=1, want_acc=True, want_y=True, count_sat=True):
     """x_codes [N,Cin,H,W], w_codes [Cout,Cin,R,S] (numpy ints, oracle layout).
     Returns dict(acc=[N,Cout,Ho,Wo] int64 or None, y=int32 codes or None, zeros=int, info=plan)."""
     N, Cin, H, W = x_codes.shape
@@ -48,16 +48,16 @@ def conv(x_codes, qx, w_codes, qw, qy=None, relu=True, r=lp.LP_ROUND_NEAREST_AWA
     bd = to_dev(np.asarray(bias).astype(code_np_dtype(qb[0]))) if bias is not None else None
     acc = torch.empty((N, Ho, Wo, Cout), dtype=torch.int64, device="cuda") if want_acc else None
     y = torch.empty((N, Ho, Wo, Cout), dtype=code_torch_dtype(qy[0]), device="cuda") if (want_y and qy) else None
-    z = counter()
+    z, sat = counter(), counter()
     # filled with junk: the library must not rely on the workspace's previous contents
     ws = torch.full((max(lp.lp_conv_workspace_bytes(d, qx, qw), 16),), 0xA5, dtype=torch.uint8, device="cuda")
     lp.lp_conv_fwd(d, xd, qx, packed, qw, qy=qy, y_codes=y, acc_out=acc, relu=relu, r=r, bias_codes=bd, qb=qb,
-                   zero_count=z, workspace=ws)
+                   zero_count=z, workspace=ws, sat_count=sat if count_sat else None)
     torch.cuda.synchronize()
     return {
         "acc": acc.cpu().numpy().transpose(0, 3, 1, 2) if acc is not None else None,
         "y": y.cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2) if y is not None else None,
-        "zeros": int(z.item()),
+        "zeros": int(z.item()), "sats": int(sat.item()) if count_sat else None,
         "info": lp.lp_conv_plan_info(d, qx, qw),
     }
 
@@ -73,10 +73,42 @@ def fc(x_codes, qx, w_codes, qw, qy=None, relu=True, r=lp.LP_ROUND_NEAREST_AWAY,
     bd = to_dev(np.asarray(bias).astype(code_np_dtype(qb[0]))) if bias is not None else None
     acc = torch.empty((M, Nout), dtype=torch.int64, device="cuda") if want_acc else None
     y = torch.empty((M, Nout), dtype=code_torch_dtype(qy[0]), device="cuda") if qy else None
-    z = counter()
+    z, sat = counter(), counter()
     ws = torch.full((max(lp.lp_fc_workspace_bytes(M, K, Nout, qx, qw), 16),), 0xA5, dtype=torch.uint8, device="cuda")
     lp.lp_fc_fwd(M, K, Nout, xd, qx, packed, qw, qy=qy, y_codes=y, acc_out=acc, relu=relu, r=r, bias_codes=bd,
-                 qb=qb, zero_count=z, workspace=ws)
+                 qb=qb, zero_count=z, workspace=ws, sat_count=sat)
     torch.cuda.synchronize()
     return {"acc": acc.cpu().numpy() if acc is not None else None,
-            "y": y.cpu().numpy().astype(np.int32) if y is not None else None, "zeros": int(z.item())}
+            "y": y.cpu().numpy().astype(np.int32) if y is not None else None, "zeros": int(z.item()),
+            "sats": int(sat.item())}
+
+
+def split_tile_positions(info, N, Ho, Wo, Cout, per_die, rng):
+    """Output positions (n, yo, xo, co) that lie in the tiles whose reduction is shared between
+    workgroups (lp_plan_info: the items past whole_items_per_die of every die), per_die of them
+    for each of the eight dies that has such tiles.  Returns (positions int64 [k,4], dies covered)."""
+    if info["path"] != 1 or info["split"] <= 1:
+        return np.zeros((0, 4), np.int64), 0
+    per, whole = info["items_per_die"], info["whole_items_per_die"]
+    rh, tw, bn, tiles_n = info["tile_rows"], info["tile_cols"], info["bn"], info["tiles_n"]
+    tiles_c = (Wo + tw - 1) // tw
+    total = info["tiles_m"] * tiles_n
+    out, dies = [], 0
+    for die in range(8):
+        items = [die * per + t for t in range(whole, per) if die * per + t < total]
+        if not items:
+            continue
+        dies += 1
+        k = 0
+        while k < per_die:
+            wi = int(items[rng.integers(0, len(items))])
+            mtile, ntile = divmod(wi, tiles_n)
+            tile_r, tile_c = divmod(mtile, tiles_c)
+            fr = tile_r * rh + int(rng.integers(0, rh))
+            xo = tile_c * tw + int(rng.integers(0, tw))
+            co = ntile * bn + int(rng.integers(0, bn))
+            if fr >= N * Ho or xo >= Wo or co >= Cout:
+                continue                                  # padding of a ragged tile
+            out.append((fr // Ho, fr % Ho, xo, co))
+            k += 1
+    return np.array(out, np.int64).reshape(-1, 4), dies

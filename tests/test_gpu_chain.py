@@ -42,6 +42,7 @@ def _compare(st, out, want, n_images=None):
             assert np.array_equal(gp, L["pooled"]), "layer %d pooled codes" % i
         if n_images is None:
             assert int(st.zero_counts[i].item()) == L["zeros"], "layer %d zero count" % i
+            assert int(st.sat_counts[i].item()) == L["sats"], "layer %d count of clipped values" % i
         elif G["y"] is not None:  # the counter covers the whole batch: check it against the codes it counted
             assert int(st.zero_counts[i].item()) == int((G["y"] == 0).sum().item())
     assert np.array_equal(out[sl].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2), want["final"])
@@ -114,6 +115,8 @@ def test_frozen_formats_from_a_calibration_subset(oracle):
     st, out = _run_stack(x, ws, pools, calib=1)
     _compare(st, out, want)
     assert (want["x_codes"] == 32767).any()       # the input really saturated
+    assert int(st.input_sat.item()) == oracle.quantize(x, 16, cal["mx"], 16 - cal["mx"])[2] > 0
+    assert sum(L["sats"] for L in want["layers"]) > 0      # and so did activations (compared per layer above)
 
 
 def test_int8_stack_conv3_to_conv5_shapes_small(oracle):
@@ -150,5 +153,5 @@ def test_fc_classifier_chain_reduced(oracle):
         qy, _ = lp.lp_range_acc(to_dev(got["acc"].reshape(-1)), L["f_acc"], relu, 16, 0.0, ws_dev)
         assert qy.m == L["mo"]
         got = fc(cur, q_in, L["w_codes"], qw.astuple(), qy=qy.astuple(), relu=relu, want_acc=False)
-        assert np.array_equal(got["y"], L["codes"]) and got["zeros"] == L["zeros"]
+        assert np.array_equal(got["y"], L["codes"]) and (got["zeros"], got["sats"]) == (L["zeros"], L["sats"])
         cur, q_in = got["y"], qy.astuple()

@@ -34,9 +34,9 @@ def _check(oracle, x, w, qx, qw, qy, relu=True, bias=None, qb=None, stride=1, pa
         if expect_path is not None:
             assert got["info"]["path"] == expect_path
         assert np.array_equal(got["acc"], want_acc)
-        want_y, want_z = oracle.act(want_acc, f_acc, qy[0], qy[1], qy[2], relu, r_cpu)
+        want_y, want_z, want_s = oracle.act(want_acc, f_acc, qy[0], qy[1], qy[2], relu, r_cpu, with_sat=True)
         assert np.array_equal(got["y"], want_y)
-        assert got["zeros"] == want_z
+        assert (got["zeros"], got["sats"]) == (want_z, want_s)        # zero codes, clipped values
     return got
 
 
@@ -106,8 +106,8 @@ def test_conv_random_shapes_16bit(oracle, N, Cin, H, W, Cout, R, S, pad):
     ws = _codes(rng, (Cout, Cin, R, S), full_range=False) >> 3
     got = conv(xs, QX, ws, QW, qy=(16, 4, 12), pad=pad, want_acc=False)         # fused 32-bit epilogue
     acc = oracle.conv(xs, ws, pad=pad, threads=8)
-    y, z = oracle.act(acc, 27, 16, 4, 12, True, oracle.ROUND_AWAY)
-    assert np.array_equal(got["y"], y) and got["zeros"] == z
+    y, z, sat = oracle.act(acc, 27, 16, 4, 12, True, oracle.ROUND_AWAY, with_sat=True)
+    assert np.array_equal(got["y"], y) and (got["zeros"], got["sats"]) == (z, sat)
 
 
 @pytest.mark.parametrize("N,Cin,H,W,Cout,R,S,pad", _random_shapes(10, 77))
@@ -120,9 +120,9 @@ def test_conv_random_shapes_8bit(oracle, N, Cin, H, W, Cout, R, S, pad):
     qx, qw, qy = (8, 3, 5), (8, 1, 7), (8, 5, 3)
     got = conv(x, qx, w, qw, qy=qy, pad=pad, want_acc=False)
     acc = oracle.conv(x, w, pad=pad, threads=8)
-    y, z = oracle.act(acc, 12, *qy, True, oracle.ROUND_AWAY)
+    y, z, sat = oracle.act(acc, 12, *qy, True, oracle.ROUND_AWAY, with_sat=True)
     assert got["info"]["path"] == 1 and got["info"]["limbs"] == 1
-    assert np.array_equal(got["y"], y) and got["zeros"] == z
+    assert np.array_equal(got["y"], y) and (got["zeros"], got["sats"]) == (z, sat)
 
 
 def test_conv_realistic_values_and_bias(oracle):
@@ -199,8 +199,8 @@ def test_conv_requantization_shift_sweep(oracle, fo):
         _check(oracle, x, w, QX, QW, q16, bias=bias, qb=(16, 4, 12), expect_path=1)
         got = conv(x, QX, w, QW, qy=q16, bias=bias, qb=(16, 4, 12), want_acc=False)       # 32-bit epilogue
         acc = oracle.conv(x, w, bias=bias, f_acc=f_acc, fb=12)
-        y, z = oracle.act(acc, f_acc, *q16, True, oracle.ROUND_AWAY)
-        assert np.array_equal(got["y"], y) and got["zeros"] == z
+        y, z, sat = oracle.act(acc, f_acc, *q16, True, oracle.ROUND_AWAY, with_sat=True)
+        assert np.array_equal(got["y"], y) and (got["zeros"], got["sats"]) == (z, sat)
         assert 0 < z < y.size
 
 
@@ -224,9 +224,9 @@ def test_conv_requantization_short_form_boundaries(oracle, fo):
     _check(oracle, x, w, qx, qw, qy, bias=bias, qb=(16, 8, 8), expect_path=1)
     got = conv(x, qx, w, qw, qy=qy, bias=bias, qb=(16, 8, 8), want_acc=False)          # 32-bit epilogue
     acc = oracle.conv(x, w, bias=bias, f_acc=f_acc, fb=8)
-    y, z = oracle.act(acc, f_acc, *qy, True, oracle.ROUND_AWAY)
-    assert np.array_equal(got["y"], y) and got["zeros"] == z
-    assert (y[0, 0] == 32767).all() and (y[0, 1] == 0).all() and 0 < z < y.size
+    y, z, sat = oracle.act(acc, f_acc, *qy, True, oracle.ROUND_AWAY, with_sat=True)
+    assert np.array_equal(got["y"], y) and (got["zeros"], got["sats"]) == (z, sat)
+    assert (y[0, 0] == 32767).all() and (y[0, 1] == 0).all() and 0 < z < y.size and sat >= y[0, 0].size
 
 
 def test_conv_int8_wide_tiles(oracle):
@@ -236,8 +236,8 @@ def test_conv_int8_wide_tiles(oracle):
     got = conv(x, (8, 3, 5), w, (8, 1, 7), qy=(8, 5, 3), want_acc=False)
     assert got["info"]["bn"] == 128 and got["info"]["limbs"] == 1
     acc = oracle.conv(x, w, threads=16)
-    y, z = oracle.act(acc, 12, 8, 5, 3, True, oracle.ROUND_AWAY)
-    assert np.array_equal(got["y"], y) and got["zeros"] == z
+    y, z, sat = oracle.act(acc, 12, 8, 5, 3, True, oracle.ROUND_AWAY, with_sat=True)
+    assert np.array_equal(got["y"], y) and (got["zeros"], got["sats"]) == (z, sat)
 
 
 def test_conv_only_codes_or_only_accumulators(oracle):
@@ -247,7 +247,7 @@ def test_conv_only_codes_or_only_accumulators(oracle):
     got = conv(x, QX, w, QW, qy=None, want_y=False)
     assert got["y"] is None and np.array_equal(got["acc"], acc) and got["zeros"] == 0
     got = conv(x, QX, w, QW, qy=QY, want_acc=False)
-    y, z = oracle.act(acc, 27, *QY, True, oracle.ROUND_AWAY)
+    y, z, sat = oracle.act(acc, 27, *QY, True, oracle.ROUND_AWAY, with_sat=True)
     assert got["acc"] is None and np.array_equal(got["y"], y) and got["zeros"] == z
 
 
@@ -273,8 +273,8 @@ def test_fc_matches_oracle(oracle, M, K, Nout):
     for relu in (True, False):
         got = fc(x, QX, w, QW, qy=(16, 14, 2), relu=relu, bias=bias, qb=(16, 1, 15))
         assert np.array_equal(got["acc"], want)
-        y, z = oracle.act(want, 27, 16, 14, 2, relu, oracle.ROUND_AWAY)
-        assert np.array_equal(got["y"], y) and got["zeros"] == z
+        y, z, sat = oracle.act(want, 27, 16, 14, 2, relu, oracle.ROUND_AWAY, with_sat=True)
+        assert np.array_equal(got["y"], y) and (got["zeros"], got["sats"]) == (z, sat)
 
 
 def test_fc_extreme_k(oracle):
@@ -294,8 +294,8 @@ def test_fc_int8(oracle):
     want = oracle.fc(x, w)
     got = fc(x, (8, 3, 5), w, (8, 1, 7), qy=(8, 8, 0), relu=True)
     assert np.array_equal(got["acc"], want)
-    y, z = oracle.act(want, 12, 8, 8, 0, True, oracle.ROUND_AWAY)
-    assert np.array_equal(got["y"], y) and got["zeros"] == z
+    y, z, sat = oracle.act(want, 12, 8, 8, 0, True, oracle.ROUND_AWAY, with_sat=True)
+    assert np.array_equal(got["y"], y) and (got["zeros"], got["sats"]) == (z, sat)
 
 
 def test_zero_count_needs_workspace_and_accumulates(oracle):
@@ -340,19 +340,20 @@ def test_split_reduction_matches_single_workgroup_tiles(oracle, shape):
     packed = torch.empty(lp.lp_conv_packed_bytes(d, QX, QW), dtype=torch.uint8, device="cuda")
     lp.lp_conv_pack_weights(d, QX, QW, wd, packed)
     want_acc = oracle.conv(x, w)
-    want_y, want_z = oracle.act(want_acc, 27, *QY, True, oracle.ROUND_AWAY)
+    want_y, want_z, want_s = oracle.act(want_acc, 27, *QY, True, oracle.ROUND_AWAY, with_sat=True)
     for use_ws in (False, True):
         ws = torch.full((lp.lp_conv_workspace_bytes(d, QX, QW),), 0x5A, dtype=torch.uint8, device="cuda") if use_ws else None
         y = torch.full((N, H, W, Cout), -7, dtype=torch.int16, device="cuda")
         acc = torch.full((N, H, W, Cout), -7, dtype=torch.int64, device="cuda")
         z = torch.zeros(1, dtype=torch.int64, device="cuda") if use_ws else None
-        lp.lp_conv_fwd(d, xd, QX, packed, QW, qy=QY, y_codes=y, zero_count=z, workspace=ws)         # fast epilogue
+        sc = torch.zeros(1, dtype=torch.int64, device="cuda") if use_ws else None
+        lp.lp_conv_fwd(d, xd, QX, packed, QW, qy=QY, y_codes=y, zero_count=z, workspace=ws, sat_count=sc)   # fast epilogue
         lp.lp_conv_fwd(d, xd, QX, packed, QW, acc_out=acc, workspace=ws)                            # raw accumulators
         torch.cuda.synchronize()
         assert np.array_equal(y.cpu().numpy().transpose(0, 3, 1, 2), want_y)
         assert np.array_equal(acc.cpu().numpy().transpose(0, 3, 1, 2), want_acc)
         if use_ws:
-            assert int(z.item()) == want_z
+            assert int(z.item()) == want_z and int(sc.item()) == want_s and want_s > 0
 
 
 @pytest.mark.parametrize("shape", [(2, 16, 16, 64, 64), (3, 16, 24, 32, 40), (1, 8, 32, 16, 128), (5, 4, 4, 64, 64)])
@@ -375,11 +376,12 @@ def test_fused_maxpool_matches_conv_act_pool(oracle, shape):
     ws = torch.full((lp.lp_conv_workspace_bytes(d, QX, QW),), 0x3C, dtype=torch.uint8, device="cuda")
     y = torch.full((N, H // 2, W // 2, Cout), -7, dtype=torch.int16, device="cuda")
     z = torch.zeros(1, dtype=torch.int64, device="cuda")
-    lp.lp_conv_fwd(d, xd, QX, packed, QW, qy=QY, y_codes=y, zero_count=z, workspace=ws)
+    sc = torch.zeros(1, dtype=torch.int64, device="cuda")
+    lp.lp_conv_fwd(d, xd, QX, packed, QW, qy=QY, y_codes=y, zero_count=z, workspace=ws, sat_count=sc)
     torch.cuda.synchronize()
-    codes, zeros = oracle.act(oracle.conv(x, w), 27, *QY, True, oracle.ROUND_AWAY)
+    codes, zeros, sats = oracle.act(oracle.conv(x, w), 27, *QY, True, oracle.ROUND_AWAY, with_sat=True)
     assert np.array_equal(y.cpu().numpy().transpose(0, 3, 1, 2), oracle.maxpool2x2(codes))
-    assert int(z.item()) == zeros
+    assert int(z.item()) == zeros and int(sc.item()) == sats and sats > 0      # both counted before pooling
     # the fused form has conditions: raw accumulators, no ReLU, 8-bit codes and odd sizes are refused
     acc = torch.empty((N, H, W, Cout), dtype=torch.int64, device="cuda")
     with pytest.raises(lp.LpError) as e:

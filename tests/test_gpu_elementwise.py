@@ -101,6 +101,24 @@ def test_quantize_stochastic_matches_oracle(oracle, q):
     assert not np.array_equal(other, got)
 
 
+def test_quantize_stochastic_fraction_needs_more_than_float32(oracle):
+    """t = x * 2^f = -0.25 + 2^-26 has the fractional part 0.75 + 2^-26, which float32 cannot
+    hold; with a draw in [0.75, 0.75 + 2^-26) the exact decision is "up".  Seed and index were
+    found by searching the test-side generator for a first word in that window."""
+    seed, index, f = 60316096, 5, 8
+    w = int(_philox4x32_10_word0(np.array([index]), seed)[0])
+    assert 3 << 30 <= w < (3 << 30) + 64                    # the draw sits in the window
+    t = np.float32(-0.25) + np.float32(2.0 ** -26)
+    assert float(t) == -0.25 + 2.0 ** -26                   # representable
+    x = np.zeros(64, np.float32)
+    x[index] = t * np.float32(2.0 ** -f)
+    u = _philox4x32_10_word0(np.arange(64), seed).astype(np.float64) * 2.0 ** -32
+    want, _, _ = oracle.quantize_stochastic(x, u, 16, 8, f)
+    assert want[index] == 0                                 # floor is -1, rounded up
+    got, _, _ = quantize(x, (16, 8, f), lp.LP_ROUND_STOCHASTIC, seed=seed)
+    assert np.array_equal(got, want)
+
+
 # --------------------------------------------------------------------------------- range
 
 @pytest.mark.parametrize("count", [0, 1, 3, 4, 5, 1000, 262147])
@@ -160,23 +178,30 @@ def test_act_matches_oracle(oracle, count, f_acc, qy, relu):
     if k and s > 0:   # exact ties
         acc[:k] = (rng.integers(-40000, 40000, k) * 2 + 1) * (1 << (s - 1))
     for mode_gpu, mode_cpu in ((lp.LP_ROUND_NEAREST_AWAY, oracle.ROUND_AWAY), (lp.LP_ROUND_NEAREST_EVEN, oracle.ROUND_EVEN)):
-        want, wz = oracle.act(acc, f_acc, n, m, fo, relu, mode_cpu)
+        want, wz, wsat = oracle.act(acc, f_acc, n, m, fo, relu, mode_cpu, with_sat=True)
         y = torch.empty(count, dtype=code_torch_dtype(n), device="cuda")
-        z = counter()
-        lp.lp_act(to_dev(acc), f_acc, qy, relu, y, mode_gpu, z)
+        z, sat = counter(), counter()
+        lp.lp_act(to_dev(acc), f_acc, qy, relu, y, mode_gpu, z, sat)
         torch.cuda.synchronize()
         assert np.array_equal(y.cpu().numpy().astype(np.int32), want)
-        assert int(z.item()) == wz
+        assert (int(z.item()), int(sat.item())) == (wz, wsat)
+        if count > 4000:
+            assert wsat > 0                              # the sample does reach past the code range
+            sat_only = counter()                         # the clipped-value counter on its own
+            lp.lp_act(to_dev(acc), f_acc, qy, relu, y, mode_gpu, None, sat_only)
+            torch.cuda.synchronize()
+            assert int(sat_only.item()) == wsat
 
 
 def test_act_extremes(oracle):
     acc = np.array([(1 << 62) - 1, -(1 << 62) + 1, 0, 1, -1, 1 << 40, -(1 << 40), (1 << 22), (1 << 22) - 1], np.int64)
-    want, wz = oracle.act(acc, 23, 16, 8, 8, False, oracle.ROUND_AWAY)
+    want, wz, wsat = oracle.act(acc, 23, 16, 8, 8, False, oracle.ROUND_AWAY, with_sat=True)
     y = torch.empty(len(acc), dtype=torch.int16, device="cuda")
-    z = counter()
-    lp.lp_act(to_dev(acc), 23, (16, 8, 8), False, y, zero_count=z)
+    z, sat = counter(), counter()
+    lp.lp_act(to_dev(acc), 23, (16, 8, 8), False, y, zero_count=z, sat_count=sat)
     torch.cuda.synchronize()
     assert np.array_equal(y.cpu().numpy().astype(np.int32), want) and int(z.item()) == wz
+    assert int(sat.item()) == wsat == 4                  # the two ends of the width and +-2^40
 
 
 @pytest.mark.parametrize("count,f_acc,qy,relu", [
@@ -197,13 +222,13 @@ def test_act_stochastic_matches_oracle(oracle, count, f_acc, qy, relu):
         acc[:4] = [0, (1 << s) - 1, 1 << s, -1]           # remainders 0, 2^s - 1, 0, 2^s - 1
     seed = 0xC0FFEE1234567
     u = _philox4x32_10_word0(np.arange(count), seed).astype(np.float64) * 2.0 ** -32
-    want, wz = oracle.act_stochastic(acc, u, f_acc, n, m, fo, relu)
+    want, wz, wsat = oracle.act_stochastic(acc, u, f_acc, n, m, fo, relu, with_sat=True)
     y = torch.empty(count, dtype=code_torch_dtype(n), device="cuda")
-    z = counter()
-    lp.lp_act_stochastic(to_dev(acc), f_acc, qy, relu, seed, y, z)
+    z, sat = counter(), counter()
+    lp.lp_act_stochastic(to_dev(acc), f_acc, qy, relu, seed, y, z, sat)
     torch.cuda.synchronize()
     got = y.cpu().numpy().astype(np.int32)
-    assert np.array_equal(got, want) and int(z.item()) == wz
+    assert np.array_equal(got, want) and (int(z.item()), int(sat.item())) == (wz, wsat)
     if count > 1000 and s > 0:
         y2 = torch.empty(count, dtype=code_torch_dtype(n), device="cuda")
         lp.lp_act_stochastic(to_dev(acc), f_acc, qy, relu, seed + 1, y2)

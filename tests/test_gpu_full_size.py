@@ -8,7 +8,7 @@ import torch
 
 import lp_inputs
 import paper_1711_04713_amd as lp
-from gpu_helpers import to_dev
+from gpu_helpers import split_tile_positions, to_dev
 from oracle import vgg as ovgg
 from paper_1711_04713_amd.stack import ConvStack
 
@@ -75,10 +75,53 @@ def test_config2_conv1_2_layer_full_size(oracle):
     assert 0.3 < zeros / y.numel() < 0.8
 
 
+def _check_layer_over_batch(oracle, x_in, w_codes, G, st, i, samples, rng):
+    """One layer of a prepared ConvStack against the oracle on outputs drawn from the WHOLE batch:
+    the layer's own input codes on the GPU (x_in, NHWC tensor) are handed to the oracle, which
+    recomputes the sampled outputs one by one.  Samples are forced into every die's split tiles
+    (the workgroups that share a reduction and the finishing kernel).  Layers whose pool is
+    fused are checked on their pooled output: the maximum of the oracle's four codes."""
+    N, H, W, _ = x_in.shape
+    Cout = w_codes.shape[0]
+    info = G["info"]
+    pos, dies = split_tile_positions(info, N, H, W, Cout, 40, rng)
+    if info["split"] > 1:
+        assert dies == 8 and len(pos) == 8 * 40, "layer %d: every die has split tiles to sample" % i
+    rnd = np.stack([rng.integers(0, N, samples), rng.integers(0, H, samples), rng.integers(0, W, samples),
+                    rng.integers(0, Cout, samples)], axis=1)
+    rnd[:, 0] = np.maximum(rnd[:, 0], 1)                      # images 1..N-1: image 0 is compared in full
+    pos = np.concatenate([pos, rnd, np.array([[N - 1, H - 1, W - 1, Cout - 1], [N - 1, 0, W - 1, 0]])])
+    x_np = x_in.cpu().numpy().transpose(0, 3, 1, 2).astype(np.int32)
+    qx, qw, qy = G["qx"], G["qw"], G["qy"]
+
+    def oracle_codes(n, yo, xo, co):
+        flat = ((n * Cout + co) * H + yo) * W + xo
+        acc = oracle.conv_sampled(x_np, w_codes, flat)
+        return oracle.act(acc, qx.f + qw.f, qy.n, qy.m, qy.f, True, oracle.ROUND_AWAY)[0]
+
+    n, yo, xo, co = pos.T
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    if G["y"] is not None:
+        got = G["y"][dev(n), dev(yo), dev(xo), dev(co)].cpu().numpy().astype(np.int32)
+        assert np.array_equal(got, oracle_codes(n, yo, xo, co)), "layer %d sampled codes over the batch" % i
+    if G["pooled"] is not None:
+        py, px = yo // 2, xo // 2
+        want = None
+        for dy in (0, 1):
+            for dx in (0, 1):
+                c = oracle_codes(n, 2 * py + dy, 2 * px + dx, co)
+                want = c if want is None else np.maximum(want, c)
+        got = G["pooled"][dev(n), dev(py), dev(px), dev(co)].cpu().numpy().astype(np.int32)
+        assert np.array_equal(got, want), "layer %d sampled pooled codes over the batch" % i
+    return info["split"] > 1
+
+
 def test_config3_vgg16_stack_batch32(oracle):
     """The benchmark's own configuration: 13 conv + 5 pools at batch 32, formats calibrated on the
-    first image; the first image's codes of every layer are compared with the oracle chain, the
-    rest of the batch through the counters."""
+    first image.  The first image's codes of every layer are compared in full with the oracle
+    chain; over the rest of the batch every layer is compared on sampled outputs the oracle
+    recomputes from the layer's own input codes, with samples forced into each die's split tiles;
+    counters are checked against the written codes."""
     B = 32
     x = lp_inputs.config3_input(seed=2, batch=B)
     ws = lp_inputs.vgg16_conv_weights(seed=2)
@@ -93,8 +136,12 @@ def test_config3_vgg16_stack_batch32(oracle):
         st.prepare(B, 224, 224)
         out = st.forward(xd)
         torch.cuda.synchronize()
+        rng = np.random.default_rng(100 + int(fuse))
+        cur, split_layers = st.x_codes, 0
         for i, (L, G) in enumerate(zip(cal["layers"], st.layers)):
             assert (st.qw[i].m, st.qy[i].m) == (L["mw"], L["mo"]), "layer %d formats" % i
+            split_layers += _check_layer_over_batch(oracle, cur, L["w_codes"], G, st, i, 4000, rng)
+            cur = G["pooled"] if G["pooled"] is not None else G["y"]
             if G["y"] is not None:
                 got = G["y"][:1].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2)
                 assert np.array_equal(got, L["codes"]), "layer %d codes of image 0" % i
@@ -104,6 +151,7 @@ def test_config3_vgg16_stack_batch32(oracle):
                 assert np.array_equal(gp, L["pooled"]), "layer %d pooled codes of image 0" % i
             assert 0.3 < int(st.zero_counts[i].item()) / G["y_numel"] < 0.8
         assert np.array_equal(out[:1].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2), cal["final"])
+        assert split_layers >= 4          # the launch geometry under test does use split reductions
         counts[fuse] = st.zero_counts.cpu().numpy().copy()
         final = out.clone() if not fuse else final
         if fuse:
