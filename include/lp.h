@@ -208,6 +208,23 @@ lp_status lp_conv_fwd(const lp_conv_desc *d, const void *x_codes_dev, lp_qfmt qx
                       size_t workspace_bytes, void *stream);
 
 /*
+ * lp_conv_fwd_static -- lp_conv_fwd for callers that cannot allocate device memory (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation): the workspace is
+ * an array of LP_STATIC_WORKSPACE_BYTES that the library's code object holds on every GPU it is
+ * loaded on, until the process ends; the call allocates nothing on host or device through HIP.
+ * Arguments, results and errors as lp_conv_fwd (with that workspace passed); problems whose
+ * lp_conv_workspace_bytes exceeds LP_STATIC_WORKSPACE_BYTES return LP_EWORKSPACE.  The array
+ * used is that of the device current at the call, which must be the stream's device.  All calls
+ * on one GPU share the array: calls that overlap in time on one GPU (different streams or
+ * threads) race; calls on one stream are ordered and safe.  Nothing is carried from call to call.
+ */
+#define LP_STATIC_WORKSPACE_BYTES (64u << 20)
+lp_status lp_conv_fwd_static(const lp_conv_desc *d, const void *x_codes_dev, lp_qfmt qx,
+                             const void *w_packed_dev, lp_qfmt qw, const void *bias_codes_dev, lp_qfmt qb,
+                             int64_t *acc_out_dev, void *y_codes_dev, lp_qfmt qy, int relu, lp_round r,
+                             uint64_t *zero_count_dev, uint64_t *sat_count_dev, void *stream);
+
+/*
  * lp_fc_fwd -- LPInnerProduct forward (Sec. 2) with the same fused tail:
  *   acc[b,o] = sum_k X[b,k] * W[o,k] (+ bias), x [M][K], w packed from [Nout][K].
  * Packing / workspace: the lp_fc_* functions below.  Other arguments as lp_conv_fwd.

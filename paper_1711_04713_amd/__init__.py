@@ -7,6 +7,7 @@ from .binding import (  # noqa: F401
     LP_ROUND_NEAREST_AWAY,
     LP_ROUND_NEAREST_EVEN,
     LP_ROUND_STOCHASTIC,
+    LP_STATIC_WORKSPACE_BYTES,
     ConvDesc,
     LpError,
     QFmt,
@@ -16,6 +17,7 @@ from .binding import (  # noqa: F401
     lp_act,
     lp_act_stochastic,
     lp_conv_fwd,
+    lp_conv_fwd_static,
     lp_conv_pack_weights,
     lp_conv_packed_bytes,
     lp_conv_plan_info,

@@ -69,6 +69,9 @@ _SIGNATURES = {
                                    ctypes.c_void_p, QFmt, ctypes.c_void_p, ctypes.c_void_p, QFmt, ctypes.c_int,
                                    ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                                    ctypes.c_void_p]),
+    "lp_conv_fwd_static": (ctypes.c_int, [ctypes.POINTER(ConvDesc), ctypes.c_void_p, QFmt, ctypes.c_void_p, QFmt,
+                                          ctypes.c_void_p, QFmt, ctypes.c_void_p, ctypes.c_void_p, QFmt, ctypes.c_int,
+                                          ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
     "lp_fc_packed_bytes": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.c_int, QFmt, QFmt,
                                           ctypes.POINTER(ctypes.c_size_t)]),
     "lp_fc_pack_weights": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.c_int, QFmt, QFmt, ctypes.c_void_p,
@@ -200,6 +203,17 @@ def lp_conv_fwd(desc, x_codes, qx, w_packed, qw, qy=None, y_codes=None, acc_out=
                               _q(qb) if qb is not None else QFmt(), _ptr(acc_out), _ptr(y_codes),
                               _q(qy) if qy is not None else QFmt(), int(bool(relu)), r, _ptr(zero_count),
                               _ptr(sat_count), _ptr(workspace), ws_bytes, _stream()), "lp_conv_fwd")
+
+
+LP_STATIC_WORKSPACE_BYTES = 64 << 20
+
+
+def lp_conv_fwd_static(desc, x_codes, qx, w_packed, qw, qy=None, y_codes=None, acc_out=None, relu=True,
+                       r=LP_ROUND_NEAREST_AWAY, bias_codes=None, qb=None, zero_count=None, sat_count=None):
+    _check(load().lp_conv_fwd_static(ctypes.byref(desc), _ptr(x_codes), _q(qx), _ptr(w_packed), _q(qw),
+                                     _ptr(bias_codes), _q(qb) if qb is not None else QFmt(), _ptr(acc_out),
+                                     _ptr(y_codes), _q(qy) if qy is not None else QFmt(), int(bool(relu)), r,
+                                     _ptr(zero_count), _ptr(sat_count), _stream()), "lp_conv_fwd_static")
 
 
 def lp_fc_packed_bytes(M, K, Nout, qx, qw):

@@ -1732,6 +1732,28 @@ static lp_status pack_weights(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, con
     return launch_status();
 }
 
+// Workspace of lp_conv_fwd_static: one array per GPU, part of the loaded code object, for callers
+// that cannot allocate.  The name below is only a host-side handle; the array's device address
+// on the current GPU comes from hipGetSymbolAddress and is looked up once per device.
+static __device__ __align__(256) unsigned char scratch[LP_STATIC_WORKSPACE_BYTES];
+
+static lp_status static_scratch(void **out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mutex;
+    static void *ptr_of_device[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LP_EDEVICE;
+    std::lock_guard<std::mutex> lock(mutex);
+    if (!ptr_of_device[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LP_EDEVICE;
+        ptr_of_device[dev] = p;
+    }
+    *out = ptr_of_device[dev];
+    return LP_OK;
+}
+
 static lp_conv_desc fc_desc(int M, int K, int Nout)
 {
     lp_conv_desc d = {M, 1, 1, K, Nout, 1, 1, 1, 0};
@@ -1801,6 +1823,24 @@ extern "C" lp_status lp_conv_fwd(const lp_conv_desc *d, const void *x_codes_dev,
 {
     return conv_forward(d, x_codes_dev, qx, w_packed_dev, qw, bias_codes_dev, qb, acc_out_dev,
                         y_codes_dev, qy, relu, r, zero_count_dev, sat_count_dev, workspace_dev, workspace_bytes, stream);
+}
+
+extern "C" lp_status lp_conv_fwd_static(const lp_conv_desc *d, const void *x_codes_dev, lp_qfmt qx,
+                                        const void *w_packed_dev, lp_qfmt qw, const void *bias_codes_dev,
+                                        lp_qfmt qb, int64_t *acc_out_dev, void *y_codes_dev, lp_qfmt qy,
+                                        int relu, lp_round r, uint64_t *zero_count_dev,
+                                        uint64_t *sat_count_dev, void *stream)
+{
+    Plan p;
+    const lp_status st = make_plan(d, qx, qw, &p);
+    if (st != LP_OK) return st;
+    if (workspace_layout(p).total > (size_t)LP_STATIC_WORKSPACE_BYTES) return LP_EWORKSPACE;
+    void *ws = nullptr;
+    const lp_status sp = static_scratch(&ws);
+    if (sp != LP_OK) return sp;
+    return conv_forward(d, x_codes_dev, qx, w_packed_dev, qw, bias_codes_dev, qb, acc_out_dev,
+                        y_codes_dev, qy, relu, r, zero_count_dev, sat_count_dev, ws,
+                        (size_t)LP_STATIC_WORKSPACE_BYTES, stream);
 }
 
 extern "C" lp_status lp_fc_packed_bytes(int M, int K, int Nout, lp_qfmt qx, lp_qfmt qw,
