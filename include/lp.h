@@ -227,7 +227,11 @@ lp_status lp_conv_fwd_static(const lp_conv_desc *d, const void *x_codes_dev, lp_
 /*
  * lp_fc_fwd -- LPInnerProduct forward (Sec. 2) with the same fused tail:
  *   acc[b,o] = sum_k X[b,k] * W[o,k] (+ bias), x [M][K], w packed from [Nout][K].
- * Packing / workspace: the lp_fc_* functions below.  Other arguments as lp_conv_fwd.
+ * Packing / workspace: the lp_fc_* functions below.  Other arguments as lp_conv_fwd, except
+ * that the workspace is always required (LP_EWORKSPACE without it): the call first splits the
+ * input rows into int8 limb planes there, then runs a split-K GEMM whose parts meet there.
+ * Its contents need no initialisation and carry nothing from call to call; calls that share
+ * one workspace must not overlap in time.
  */
 lp_status lp_fc_packed_bytes(int M, int K, int Nout, lp_qfmt qx, lp_qfmt qw, size_t *bytes_host);
 lp_status lp_fc_pack_weights(int M, int K, int Nout, lp_qfmt qx, lp_qfmt qw, const void *w_codes_dev,
