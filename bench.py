@@ -19,22 +19,30 @@ sys.path.insert(0, ROOT)
 INT8_PEAK_TOPS = 5000.0     # MI355X dense int8 MFMA, published (5.0 POP/s)
 HBM_PEAK_GBS = 8000.0
 
-# HBM traffic of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see
-# profiles/): average bytes per launch over the 13 launches of one step, already scaled by the
-# copy-kernel factor.  Valid only for the kernel source it was measured on (sha256 of lp_conv.hip);
-# reported as null for any other source.
-TRAFFIC_RECORD = {"lp_conv_sha256": "caccb01219f08003652f6ede410da5dc0129d64a3383208d82e5cce2e05eb061", "bytes_per_launch": 123912139}
+# HBM traffic of the dominant kernel comes from the tracked rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# summary under profiles/ (its last line is a small JSON record: average bytes per launch over the
+# patch-kernel launches of one step, scaled by the copy-kernel factor, and the sha256 of the kernel
+# sources it was measured on).  For any other source the counters are stale and null is reported.
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "conv_stack_vgg16_batch32_hbm_traffic.txt")
+KERNEL_SOURCES = ("lp_conv.hip", "lp_tile.h", "lp_device.h")
+
+
+def kernel_sources_sha256():
+    import hashlib
+
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        h.update(open(os.path.join(ROOT, "paper_1711_04713_amd", "csrc", name), "rb").read())
+    return h.hexdigest()
 
 
 def _traffic_for_current_source():
-    import hashlib
-
-    path = os.path.join(ROOT, "paper_1711_04713_amd", "csrc", "lp_conv.hip")
     try:
-        sha = hashlib.sha256(open(path, "rb").read()).hexdigest()
-    except OSError:
+        lines = [l for l in open(TRAFFIC_PROFILE) if l.startswith("bench_record: ")]
+        rec = json.loads(lines[-1][len("bench_record: "):])
+        return int(rec["bytes_per_launch"]) if rec["sources_sha256"] == kernel_sources_sha256() else None
+    except (OSError, IndexError, KeyError, ValueError):
         return None
-    return TRAFFIC_RECORD["bytes_per_launch"] if sha == TRAFFIC_RECORD["lp_conv_sha256"] else None
 
 
 def measure_extras(lp, torch, lp_inputs, iters=10):
@@ -280,8 +288,15 @@ def main():
         ref = ovgg.conv_stack(x_np[:nimg], w_np, pools, n=16, threads=threads, formats=frozen, keep_codes=False)
         cpu_s = time.perf_counter() - t0
         got = stack.layers[-1]["pooled"][:nimg].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2)
+        # single-thread leg: the same chain on the first image alone
+        t0 = time.perf_counter()
+        ref1 = ovgg.conv_stack(x_np[:1], w_np, pools, n=16, threads=1, formats=frozen, keep_codes=False)
+        cpu1_s = time.perf_counter() - t0
         out["cpu_baseline"] = {
             "value": round(nimg / cpu_s, 4), "unit": "images/s", "cores": threads, "kind": "oracle",
+            "single_thread": {"value": round(1.0 / cpu1_s, 4), "unit": "images/s", "cores": 1, "seconds": round(cpu1_s, 2),
+                              "sample": "first image of the same batch, same chain",
+                              "matches_gpu_final_codes": bool(np.array_equal(got[:1], ref1["final"]))},
             "sample": "first %d image(s) of the same batch, whole 13-layer stack, frozen formats, gcc -O2 direct loops, "
                       "OpenMP over (image, output channel); includes weight quantization" % nimg,
             "seconds": round(cpu_s, 2),

@@ -208,6 +208,33 @@ lp_status lp_conv_fwd(const lp_conv_desc *d, const void *x_codes_dev, lp_qfmt qx
                       size_t workspace_bytes, void *stream);
 
 /*
+ * Skipping multiplications by zero (abstract and Sec. 3.1: the sparsity that low-precision
+ * training produces is there so that the target hardware can skip it), at the granularity a
+ * matrix unit allows: whole tiles.  A layer run through lp_conv_fwd_zskip leaves one byte per
+ * (pixel tile, channel tile) of its output in y_tile_flags_dev (tiles_m * tiles_n bytes, see
+ * lp_conv_plan_info), 1 = the tile holds a code that is not zero.  The next layer is handed
+ * those flags with the geometry they were written in (lp_zero_map, filled from the PRODUCER's
+ * lp_plan_info: tile_rows, tile_cols, tiles_c = ceil(Wo / tile_cols), tiles_n, bn; scale = 2 if
+ * the codes went through the 2x2 max-pool, fused or not, before this layer reads them, else 1)
+ * and neither stages nor multiplies a 64-channel chunk of a workgroup's input patch when every
+ * producer tile the patch touches is flagged all-zero.  Results are those of lp_conv_fwd, bit
+ * for bit.  skipped_dev (nullable): += (workgroup tile, chunk) pairs skipped.  Either of
+ * x_zero_map_host / y_tile_flags_dev may be null.  Needs the int8-MFMA path (path 1), codes out
+ * (no raw accumulators) and, for y_tile_flags_dev, the workspace; else LP_EUNSUPPORTED /
+ * LP_EINVAL.  Other arguments and errors as lp_conv_fwd.
+ */
+typedef struct {
+    const uint8_t *flags_dev;
+    int32_t tile_rows, tile_cols, tiles_c, tiles_n, bn, scale;
+} lp_zero_map;
+lp_status lp_conv_fwd_zskip(const lp_conv_desc *d, const void *x_codes_dev, lp_qfmt qx,
+                            const lp_zero_map *x_zero_map_host, const void *w_packed_dev, lp_qfmt qw,
+                            const void *bias_codes_dev, lp_qfmt qb, void *y_codes_dev, lp_qfmt qy, int relu,
+                            lp_round r, uint64_t *zero_count_dev, uint64_t *sat_count_dev,
+                            uint8_t *y_tile_flags_dev, uint64_t *skipped_dev, void *workspace_dev,
+                            size_t workspace_bytes, void *stream);
+
+/*
  * lp_conv_fwd_static -- lp_conv_fwd for callers that cannot allocate device memory (code under
  * HIP graph capture, tight serving loops, harnesses that forbid allocation): the workspace is
  * an array of LP_STATIC_WORKSPACE_BYTES that the library's code object holds on every GPU it is

@@ -41,6 +41,12 @@ class PlanInfo(ctypes.Structure):
         return {k: getattr(self, k) for k, _ in self._fields_}
 
 
+class ZeroMap(ctypes.Structure):
+    """Per-tile nonzero flags of a tensor and the tile geometry they were written in (lp_zero_map)."""
+    _fields_ = [("flags_dev", ctypes.c_void_p)] + [(k, ctypes.c_int32) for k in ("tile_rows", "tile_cols", "tiles_c", "tiles_n",
+                                                                             "bn", "scale")]
+
+
 class ConvDesc(ctypes.Structure):
     _fields_ = [(k, ctypes.c_int32) for k in ("N", "H", "W", "Cin", "Cout", "R", "S", "stride", "pad", "pool")]
 
@@ -69,6 +75,10 @@ _SIGNATURES = {
                                    ctypes.c_void_p, QFmt, ctypes.c_void_p, ctypes.c_void_p, QFmt, ctypes.c_int,
                                    ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                                    ctypes.c_void_p]),
+    "lp_conv_fwd_zskip": (ctypes.c_int, [ctypes.POINTER(ConvDesc), ctypes.c_void_p, QFmt, ctypes.POINTER(ZeroMap),
+                                         ctypes.c_void_p, QFmt, ctypes.c_void_p, QFmt, ctypes.c_void_p, QFmt, ctypes.c_int,
+                                         ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "lp_conv_fwd_static": (ctypes.c_int, [ctypes.POINTER(ConvDesc), ctypes.c_void_p, QFmt, ctypes.c_void_p, QFmt,
                                           ctypes.c_void_p, QFmt, ctypes.c_void_p, ctypes.c_void_p, QFmt, ctypes.c_int,
                                           ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
@@ -203,6 +213,25 @@ def lp_conv_fwd(desc, x_codes, qx, w_packed, qw, qy=None, y_codes=None, acc_out=
                               _q(qb) if qb is not None else QFmt(), _ptr(acc_out), _ptr(y_codes),
                               _q(qy) if qy is not None else QFmt(), int(bool(relu)), r, _ptr(zero_count),
                               _ptr(sat_count), _ptr(workspace), ws_bytes, _stream()), "lp_conv_fwd")
+
+
+def zero_map(flags, producer_info, Wo, scale=1):
+    """lp_zero_map for a tensor whose producer (plan info producer_info, output width Wo) wrote `flags`;
+    scale = 2 when the tensor was 2x2-pooled after the flags were taken."""
+    return ZeroMap(flags.data_ptr(), producer_info["tile_rows"], producer_info["tile_cols"],
+                   (Wo + producer_info["tile_cols"] - 1) // producer_info["tile_cols"], producer_info["tiles_n"],
+                   producer_info["bn"], scale)
+
+
+def lp_conv_fwd_zskip(desc, x_codes, qx, x_map, w_packed, qw, qy, y_codes, relu=True, r=LP_ROUND_NEAREST_AWAY,
+                      bias_codes=None, qb=None, zero_count=None, sat_count=None, y_flags=None, skipped=None,
+                      workspace=None):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().lp_conv_fwd_zskip(ctypes.byref(desc), _ptr(x_codes), _q(qx), ctypes.byref(x_map) if x_map is not None else None,
+                                    _ptr(w_packed), _q(qw), _ptr(bias_codes), _q(qb) if qb is not None else QFmt(),
+                                    _ptr(y_codes), _q(qy), int(bool(relu)), r, _ptr(zero_count), _ptr(sat_count),
+                                    _ptr(y_flags), _ptr(skipped), _ptr(workspace), ws_bytes, _stream()),
+           "lp_conv_fwd_zskip")
 
 
 LP_STATIC_WORKSPACE_BYTES = 64 << 20

@@ -55,6 +55,7 @@ struct Plan {
     size_t part_bytes;   // bytes of one part's accumulators and row sums in the workspace
     size_t lds_bytes;
     size_t packed_bytes, corr_offset;
+    size_t wsum_offset;  // per-chunk weight sums [nchunks][CoutP] int32 (two-limb patch path), else 0
 };
 
 // Workspace layout: one zero count per workgroup, then the tail tiles' partial accumulators
@@ -307,7 +308,13 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
             p.grid = kXCDs * (p.full_per_xcd + (p.per_xcd - p.full_per_xcd) * p.split);
         }
         p.corr_offset = round_up((size_t)p.taps * p.nchunks * p.limbs * p.CoutP * CK, 256);
+        // the kernel addresses the slabs with 32-bit byte offsets
+        if (p.corr_offset >= (1ull << 31)) return LP_EUNSUPPORTED;
         p.packed_bytes = p.corr_offset + (size_t)p.CoutP * sizeof(int64_t);
+        if (p.limbs == 2 && !p.flat) {
+            p.wsum_offset = p.packed_bytes;
+            p.packed_bytes += (size_t)p.nchunks * p.CoutP * sizeof(int);
+        }
     } else {
         // direct path keeps a plain int16 copy of the weights
         p.corr_offset = 0;
@@ -378,6 +385,26 @@ __global__ void widen_weights_kernel(const WT *__restrict__ w, int16_t *__restri
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
          i += (size_t)gridDim.x * blockDim.x)
         out[i] = (int16_t)w[i];
+}
+
+// wsum[chunk][co] = sum of the weight codes of output channel co over the chunk's 64 input
+// channels and all taps (one wave per (chunk, co)).
+template <typename WT>
+__global__ __launch_bounds__(64) void chunk_weight_sums_kernel(const WT *__restrict__ w, int *__restrict__ wsum, int Cout,
+                                                              int CoutP, int Cin, int RS)
+{
+    const int co = blockIdx.x, chunk = blockIdx.y;
+    int s = 0;
+    if (co < Cout) {
+        const int nch = min(CK, Cin - chunk * CK);
+        for (int i = threadIdx.x; i < RS * nch; i += 64) {
+            const int tap = i / nch, c = i - tap * nch;
+            s += (int)w[((size_t)co * RS + tap) * Cin + chunk * CK + c];
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) s += __shfl_down(s, off, 64);
+    if (threadIdx.x == 0) wsum[(size_t)chunk * CoutP + co] = s;
 }
 
 // ------------------------------------------------------------------------ direct path
@@ -514,6 +541,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         apos[p] = planes_lds + pos; // as an LDS address: parking a piece then costs no base add
         psum[p] = 0;
     }
+    unsigned livemask = 0xffffffffu, deadmask = 0; // see "skipping" below
     // The tables of the tile rows and the channel constants are not needed to request the first
     // patch: they are built while those requests are in flight (see the first staging below).
     auto row_tables = [&]() __attribute__((always_inline)) {
@@ -527,22 +555,65 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             abase_s[m] = ok ? (img * a.Hp + yo - vr0) * a.PW + t : 0;
             pooloff[m] = (a.pool && ok && !(j & 1) && !(t & 1)) ? (img * (a.Ho >> 1) + (yo >> 1)) * (a.Wo >> 1) + (xo >> 1) : -1;
         }
-        build_colterms<BN, THREADS>(a, ntile, ctab, LIMBS);
+        build_colterms<BN, THREADS>(a, ntile, ctab, LIMBS, deadmask);
+    };
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WMC, wn = wave / WMC;
+    const int l32 = lane & 31, kg = lane >> 5;
+
+    // Skipping of all-zero input chunks.  The layer that produced x has left one flag per (pixel
+    // tile, channel tile) of its output; a 64-channel chunk whose flags are clear in every
+    // producer tile that the patch touches holds only the code 0 and is neither staged nor
+    // multiplied.  livemask: bit c = chunk c is multiplied (uniform).  Every wave works it out for
+    // itself: lane c looks at chunk c.  Tiles whose reduction is shared between workgroups, and
+    // layers with more than 32 chunks, multiply everything.
+    const bool skipping = !FLAT && a.zin && nparts == 1 && a.nchunks <= 32;
+    if (skipping) {
+        // input rows (of the N * H stacked rows) and columns the patch really holds
+        int n_lo, p_lo, n_hi, p_hi;
+        udivmod(vr0, a.Hp, a.mg_Hp, n_lo, p_lo);
+        udivmod(vr0 + a.NPIXA / a.PW - 1, a.Hp, a.mg_Hp, n_hi, p_hi);
+        int r_lo = p_lo < a.pad ? n_lo * a.H : p_lo >= a.pad + a.H ? (n_lo + 1) * a.H : n_lo * a.H + p_lo - a.pad;
+        int r_hi = p_hi < a.pad ? n_hi * a.H - 1 : p_hi >= a.pad + a.H ? (n_hi + 1) * a.H - 1 : n_hi * a.H + p_hi - a.pad;
+        r_hi = min(r_hi, a.N * a.H - 1);
+        const int c_lo = max(0, x0 - a.pad), c_hi = min(a.W - 1, x0 - a.pad + a.PW - 1);
+        unsigned live = (1u << (a.nchunks - 1) << 1) - 1u;
+        if (r_lo <= r_hi && c_lo <= c_hi) {
+            const int sc = a.z_scale;
+            const int tr0 = (r_lo * sc) / a.z_rh, tr1 = (r_hi * sc + sc - 1) / a.z_rh;
+            const int tc0 = (c_lo * sc) / a.z_tw, tc1 = min((c_hi * sc + sc - 1) / a.z_tw, a.z_tiles_c - 1);
+            if ((tr1 - tr0 + 1) * (tc1 - tc0 + 1) <= 64) {
+                bool any = false;
+                if (lane < a.nchunks) {
+                    const int zn = (lane * CK) / a.z_bn; // the producer's channel tile that holds this chunk
+                    for (int tr = tr0; tr <= tr1; ++tr)
+                        for (int tc = tc0; tc <= tc1; ++tc) any |= a.zin[(size_t)(tr * a.z_tiles_c + tc) * a.z_tiles_n + zn] != 0;
+                }
+                live = (unsigned)__builtin_amdgcn_ballot_w64(any);
+            }
+        }
+        if (live == 0) live = 1; // nothing to multiply: chunk 0 (all zeros) is multiplied for form's sake
+        livemask = live;
+        deadmask = ~live & ((1u << (a.nchunks - 1) << 1) - 1u);
+        if (a.skipped && tid == 0 && deadmask) atomicAdd(a.skipped, (unsigned long long)__builtin_popcount(deadmask));
+    }
+    // the chunk after chunk c in the order of multiplication (c itself past the last one)
+    auto next_chunk = [&](int c) __attribute__((always_inline)) {
+        if (!skipping) return c + 1;
+        const unsigned rem = c >= 31 ? 0u : livemask >> (c + 1);
+        return rem ? c + 1 + (int)__builtin_ctz(rem) : c;
     };
 
-    // Weight slabs: slab t = chunk * taps + tap lives at [chunk][tap][limb][K half][CoutP][32], i.e.
+    // Weight slabs: slab (chunk, tap) lives at [chunk][tap][limb][K half][CoutP][32], i.e.
     // consecutive in memory in the order they are consumed; they never pass through LDS (see
-    // the operand loads below).
-    const int nslabs = a.nchunks * a.taps;
+    // the operand loads below).  t counts the slabs this workgroup multiplies.
+    const int nslabs = (skipping ? __builtin_popcount(livemask) : a.nchunks) * a.taps;
     const int s0 = part * nslabs / nparts, s1 = (part + 1) * nslabs / nparts; // this workgroup's slabs
-    const size_t slab_bytes = (size_t)LIMBS * a.CoutP * CK;
+    const int slab_bytes = LIMBS * a.CoutP * CK;
     constexpr bool LATE_ROWS = LIMBS == 2; // (the one-limb kernels' 128 registers leave no room for the overlap)
     if constexpr (!LATE_ROWS) row_tables();
     __syncthreads(); // the patch tables are complete
 
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave % WMC, wn = wave / WMC;
-    const int l32 = lane & 31, kg = lane >> 5;
     int aoff[MB]; // filled once the row tables are visible
     auto lane_constants = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -762,8 +833,11 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         __builtin_amdgcn_s_waitcnt(0x0F70);
     };
     // chunk and tap of the current slab, and the tap's patch offset, kept incrementally
+    // (when chunks are skipped the workgroup owns its whole tile: s0 = 0 and the first chunk is
+    // the first one that is multiplied)
     int cc, tap, tap_r = 0, tap_s = 0;
     udivmod(s0, a.taps, a.mg_taps, cc, tap);
+    if (skipping) cc = __builtin_ctz(livemask);
     if constexpr (!FLAT) udivmod(tap, a.S, a.mg_S, tap_r, tap_s);
     int taprow = tap_r * a.PITCH, tapoff = taprow + tap_s * PSP;
     // Weights go straight from global memory / L2 into the MFMA operand registers, NSETS - 1
@@ -781,13 +855,14 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     // the slab (and the limb plane) is a scalar offset, the K half an immediate: no address
     // arithmetic in vector registers inside the loop.
     const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<unsigned char *>(a.wp), 0, (int)((unsigned)nslabs * (unsigned)slab_bytes), 0x00020000);
+        const_cast<unsigned char *>(a.wp), 0, (int)((unsigned)(a.nchunks * a.taps) * (unsigned)slab_bytes), 0x00020000);
     const int blane = ((ntile * BN + wn * (NB * 32) + l32) * 32 + kg * 16);
     const int limb_bytes = a.CoutP * CK, half_bytes = a.CoutP * 32;
-    // request the operands of K half `half` of slab t (past the last slab the last one is read
-    // again and never used: every path issues the same number of requests)
-    auto bload = [&](int t, int half, v4i *h, v4i *l) __attribute__((always_inline)) {
-        const int slab_off = min(t, s1 - 1) * (int)slab_bytes + (half ? half_bytes : 0);
+    // request the operands of K half `half` of the slab at byte offset wslab (past the last slab
+    // the last one is read again and never used: every path issues the same number of requests)
+    int wcur = (cc * a.taps + tap) * slab_bytes, wnext = wcur; // the slab being multiplied, the one after it
+    auto bload = [&](int wslab, int half, v4i *h, v4i *l) __attribute__((always_inline)) {
+        const int slab_off = wslab + (half ? half_bytes : 0);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             const auto vh = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, blane + nb * 32 * 32, slab_off, 0);
@@ -845,7 +920,8 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         constexpr int h = 2 * decltype(P)::value + hh;
         constexpr int use = h % NSETS, fill = (h + LEAD) % NSETS;
         constexpr int ahead = hh + LEAD;
-        bload(t + (ahead >> 1), ahead & 1, bh[fill], bl[fill]);
+        static_assert((ahead >> 1) == 1, "the prefetch runs one slab ahead");
+        bload(wnext, ahead & 1, bh[fill], bl[fill]);
         // the requests leave before this half's MFMAs, not among them
         __builtin_amdgcn_sched_barrier(0);
         const bool on = hh == 0 || !FLAT || a.ksteps > 1; // a flat window of K <= 32 has one half
@@ -876,7 +952,10 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         }
     };
 #pragma unroll
-    for (int j = 0; j < LEAD; ++j) bload(s0 + (j >> 1), j & 1, bh[j], bl[j]);
+    for (int j = 0; j < LEAD; ++j) {
+        static_assert(LEAD == 2, "the first slab's two K halves are requested here");
+        bload(wcur, j & 1, bh[j], bl[j]);
+    }
 
     stage_activations(cc, true, [&] {
         if constexpr (LATE_ROWS) row_tables();
@@ -910,7 +989,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         // move the bookkeeping on to slab t + 1
         if (++tap == a.taps) {
             tap = 0;
-            ++cc;
+            cc = next_chunk(cc);
             tap_s = tap_r = 0;
             tapoff = taprow = 0;
         } else if (!FLAT) {
@@ -926,6 +1005,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         fragment_offsets(nxt, nxtl);
         const bool more = t + 1 < s1;
         const bool restage = more && tap == 0; // slab t + 1 opens a chunk: a new patch
+        wnext = more ? (cc * a.taps + tap) * slab_bytes : wcur;
         half_step(t, P, integral_constant<int, 0>{}, cur, curl, nxt, nxtl);
         half_step(t, P, integral_constant<int, 1>{}, cur, curl, nxt, nxtl);
         if (restage) {
@@ -944,6 +1024,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             cur[mb] = nxt[mb];
             curl[mb] = nxtl[mb];
         }
+        wcur = wnext;
     };
     // whole rotations inside the loop, the slabs left over after it
     int t = s0;
@@ -1002,22 +1083,31 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             for (int m = tid; m < BM; m += THREADS) rs[m] = row_sum(m);
         }
         if (a.zero_partial && tid == 0) a.zero_partial[blockIdx.x] = a.zero_partial[a.partial_stride + blockIdx.x] = 0;
+        if (a.zout && part == 0 && tid == 0) a.zout[wi] = 0; // the finishing kernel sets it if it meets a nonzero code
         return;
     }
 
     const TileCounts counts = tile_epilogue<LIMBS, NB, BN, MB, 4>(a, acc, row_sum, outoff, pooloff, ctab, ntile, wm * WROWS,
                                                                   wn * (NB * 32), 0, 0);
     // one pair of counts per workgroup, no atomics: thousands of same-address atomics would serialise
-    if (a.zero_partial) {
+    if (a.zero_partial || a.zout) {
         if (lane == 0) { // tab[] was last read while staging
             tab[wave] = (int)counts.zeros;
             tab[THREADS / 64 + wave] = (int)counts.sats;
         }
         __syncthreads();
-        if (tid < 2) {
+        if (a.zero_partial && tid < 2) {
             unsigned total = 0;
             for (int w = 0; w < THREADS / 64; ++w) total += (unsigned)tab[tid * (THREADS / 64) + w];
             a.zero_partial[tid * a.partial_stride + blockIdx.x] = total;
+        }
+        if (a.zout && wave == 0) {
+            // the tile's flag: it holds a code that is not zero (codes that exist: rows x channels)
+            int rows = 0;
+            for (int m = lane; m < BM; m += 64) rows += (int)wave_count(outoff[m] >= 0);
+            unsigned zeros = 0;
+            for (int w = 0; w < THREADS / 64; ++w) zeros += (unsigned)tab[w];
+            if (lane == 0) a.zout[wi] = (unsigned)(rows * min(BN, a.Cout - ntile * BN)) != zeros;
         }
     }
 }
@@ -1106,6 +1196,18 @@ __global__ __launch_bounds__(256) void conv_finish_kernel(const ConvArgs a, int 
         const TileCounts counts = tile_epilogue<LIMBS, NB, BN, 1, 1>(
             a, acc, [&](int m) { return rowsum[m]; }, outoff, pooloff, ctab, ntile, (wave % WMC) * (32 * MB),
             (wave / WMC) * (NB * 32), mb0, g0);
+        if (a.zout) {
+            // codes of this workgroup's part of the tile that exist; a zero count below it = a nonzero code
+            const int m = (wave % WMC) * (32 * MB) + mb0 * 32 + (tid & 31);
+            const int col0 = ntile * BN + (wave / WMC) * (NB * 32) + 8 * g0 + 4 * ((tid & 63) >> 5);
+            unsigned exist = 0;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) exist += outoff[m] >= 0 ? (unsigned)min(max(a.Cout - (col0 + nb * 32), 0), 4) : 0u;
+            unsigned wave_exist = 0;
+#pragma unroll
+            for (int b = 0; b < 5; ++b) wave_exist += wave_count((exist >> b) & 1) << b;
+            if ((tid & 63) == 0 && wave_exist != counts.zeros) a.zout[wi] = 1;
+        }
         if ((tid & 63) == 0) {
             wave_zeros[0][tid >> 6] = counts.zeros;
             wave_zeros[1][tid >> 6] = counts.sats;
@@ -1205,7 +1307,8 @@ static WorkspaceLayout workspace_layout(const Plan &p)
 static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, const void *wp,
                               lp_qfmt qw, const void *bias, lp_qfmt qb, int64_t *acc_out, void *y,
                               lp_qfmt qy, int relu, lp_round r, uint64_t *zero_count, uint64_t *sat_count,
-                              void *workspace, size_t workspace_bytes, void *stream)
+                              void *workspace, size_t workspace_bytes, void *stream,
+                              const lp_zero_map *x_map = nullptr, uint8_t *y_flags = nullptr, uint64_t *skipped = nullptr)
 {
     Plan p;
     lp_status st = make_plan(d, qx, qw, &p);
@@ -1234,6 +1337,26 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     a.zero_count = (unsigned long long *)zero_count;
     a.sat_count = (unsigned long long *)sat_count;
     a.count_sat = (sat_count && y) ? 1 : 0;
+    if (x_map || y_flags) {
+        // zero flags: read by the patch kernels, written by any MFMA-path layer that emits codes
+        if (p.path != PATH_MFMA) return LP_EUNSUPPORTED;
+        if (y_flags && (!y || !workspace)) return LP_EINVAL;
+        if (x_map) {
+            if (!x_map->flags_dev || x_map->tile_rows <= 0 || x_map->tile_cols <= 0 || x_map->tiles_c <= 0 ||
+                x_map->tiles_n <= 0 || x_map->bn < CK || x_map->bn % CK || (x_map->scale != 1 && x_map->scale != 2))
+                return LP_EINVAL;
+            // the flags must describe this layer's input: its width and channels
+            if (x_map->tiles_c != (d->W * x_map->scale + x_map->tile_cols - 1) / x_map->tile_cols ||
+                x_map->tiles_n != (d->Cin + x_map->bn - 1) / x_map->bn)
+                return LP_EINVAL;
+            a.zin = x_map->flags_dev;
+            a.z_rh = x_map->tile_rows; a.z_tw = x_map->tile_cols; a.z_tiles_c = x_map->tiles_c;
+            a.z_tiles_n = x_map->tiles_n; a.z_bn = x_map->bn; a.z_scale = x_map->scale;
+            a.skipped = (unsigned long long *)skipped;
+        }
+        a.zout = y_flags;
+    }
+    a.wsum = p.wsum_offset ? (const int *)((const unsigned char *)wp + p.wsum_offset) : nullptr;
     a.N = d->N; a.H = d->H; a.W = d->W; a.Cin = d->Cin; a.Cout = d->Cout;
     a.R = d->R; a.S = d->S; a.stride = d->stride; a.pad = d->pad;
     a.Ho = p.Ho; a.Wo = p.Wo; a.Hp = p.Hp; a.FR = p.FR;
@@ -1261,7 +1384,7 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     a.full_per_xcd = p.full_per_xcd;
     a.split = p.split;
     int grid = p.grid;
-    const bool counting = (zero_count || sat_count) && y;
+    const bool counting = ((zero_count || sat_count) && y) || y_flags;
     const WorkspaceLayout wl = workspace_layout(p);
     if (workspace) {
         if (workspace_bytes < wl.total || !aligned16(workspace)) return LP_EWORKSPACE;
@@ -1341,7 +1464,10 @@ static lp_status pack_weights(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, con
     hipLaunchKernelGGL((pack_weights_kernel<WT, L>), dim3(grid), dim3(256), 0, hs, (const WT *)w, out, \
                        d->Cout, d->Cin, RS, p.nchunks, p.CoutP, total);                                \
     hipLaunchKernelGGL(weight_corr_kernel<WT>, dim3(cgrid), dim3(64), 0, hs, (const WT *)w, corr,      \
-                       d->Cout, p.CoutP, RS * d->Cin, L)
+                       d->Cout, p.CoutP, RS * d->Cin, L);                                              \
+    if (L == 2)                                                                                        \
+    hipLaunchKernelGGL(chunk_weight_sums_kernel<WT>, dim3(p.CoutP, p.nchunks), dim3(64), 0, hs,        \
+                       (const WT *)w, (int *)(out + p.wsum_offset), d->Cout, p.CoutP, d->Cin, RS)
     if (p.limbs == 2) {
         if (w16) { LP_PACK(int16_t, 2); } else { LP_PACK(int8_t, 2); }
     } else {
@@ -1442,6 +1568,18 @@ extern "C" lp_status lp_conv_fwd(const lp_conv_desc *d, const void *x_codes_dev,
 {
     return conv_forward(d, x_codes_dev, qx, w_packed_dev, qw, bias_codes_dev, qb, acc_out_dev,
                         y_codes_dev, qy, relu, r, zero_count_dev, sat_count_dev, workspace_dev, workspace_bytes, stream);
+}
+
+extern "C" lp_status lp_conv_fwd_zskip(const lp_conv_desc *d, const void *x_codes_dev, lp_qfmt qx,
+                                       const lp_zero_map *x_zero_map_host, const void *w_packed_dev, lp_qfmt qw,
+                                       const void *bias_codes_dev, lp_qfmt qb, void *y_codes_dev, lp_qfmt qy, int relu,
+                                       lp_round r, uint64_t *zero_count_dev, uint64_t *sat_count_dev,
+                                       uint8_t *y_tile_flags_dev, uint64_t *skipped_dev, void *workspace_dev,
+                                       size_t workspace_bytes, void *stream)
+{
+    return conv_forward(d, x_codes_dev, qx, w_packed_dev, qw, bias_codes_dev, qb, nullptr, y_codes_dev, qy, relu, r,
+                        zero_count_dev, sat_count_dev, workspace_dev, workspace_bytes, stream, x_zero_map_host,
+                        y_tile_flags_dev, skipped_dev);
 }
 
 extern "C" lp_status lp_conv_fwd_static(const lp_conv_desc *d, const void *x_codes_dev, lp_qfmt qx,

@@ -38,6 +38,18 @@ struct ConvArgs {
     int part_bytes;
     // floor(2^32 / d) for the divisors the kernel's index arithmetic uses (see udivmod)
     unsigned mg_tiles_n, mg_tiles_c, mg_Ho, mg_Hp, mg_PW, mg_TW, mg_taps, mg_S, mg_Cin, mg_SC;
+    // Skipping of all-zero input (Sec. 3.1: the sparsity the low-precision layers produce is there
+    // to be skipped).  zin: flags written by the layer that produced x, one byte per (pixel tile,
+    // channel tile) of ITS output, 1 = the tile holds a nonzero code; its geometry: z_rh x z_tw
+    // pixels (rows of the stacked output rows), z_tiles_c tiles per row of tiles, z_tiles_n channel
+    // tiles of z_bn channels; z_scale = 2 when x is the 2x2-pooled output.  zout: this layer's own
+    // flags [tiles_m][tiles_n].  skipped: += (tile, 64-channel chunk) pairs not multiplied.
+    // wsum: [nchunks][CoutP] sums of the weight codes per chunk, for the correction of skipped chunks.
+    const unsigned char *zin;
+    int z_rh, z_tw, z_tiles_c, z_tiles_n, z_bn, z_scale;
+    unsigned char *zout;
+    unsigned long long *skipped;
+    const int *wsum;
     int fast; // 32-bit requantization is exact for this call (see epilogue)
     int pool; // store the 2x2 maxima of the codes (planner guarantees the tile geometry)
     ActParams act;
@@ -105,12 +117,22 @@ __device__ __forceinline__ int requant_relu32(int hi, int lo16, int s)
 
 // Per-channel constants of a tile (weight correction + bias) into LDS, in the form the epilogue
 // wants: three int32 planes (bits 16.., 8..15, 0..7) for the 32-bit epilogue, else int64.
+// deadmask: chunks of 64 input channels that were skipped as all-zero; their share of the weight
+// correction, 128 * sum(w over the chunk) - 16384 * (positions of the chunk), is taken out again
+// (their limb products, which it would have cancelled, were never formed).
 template <int BN, int THREADS>
-__device__ __forceinline__ void build_colterms(const ConvArgs &a, int ntile, int *ctab, int limbs)
+__device__ __forceinline__ void build_colterms(const ConvArgs &a, int ntile, int *ctab, int limbs, unsigned deadmask = 0)
 {
     for (int c = threadIdx.x; c < BN; c += THREADS) {
         const int colg = ntile * BN + c;
-        const int64_t t = colg < a.Cout ? a.corr[colg] + bias_term(a, colg) : 0;
+        int64_t t = colg < a.Cout ? a.corr[colg] + bias_term(a, colg) : 0;
+        if (limbs == 2 && deadmask && colg < a.Cout) {
+            for (unsigned rem = deadmask; rem; rem &= rem - 1) {
+                const int ch = __builtin_ctz(rem);
+                const int kc = a.taps * min(64, a.Cin - 64 * ch);
+                t -= (int64_t)128 * a.wsum[(size_t)ch * a.CoutP + colg] - (int64_t)16384 * kc;
+            }
+        }
         if (a.fast) {
             // (shifts 9..16: the epilogue's rounding half 2^(s-1) rides in the constants, as 2^(s-9)
             // at the scale of v / 256; one limb: the top plane arrives clamped and at that scale,

@@ -19,13 +19,16 @@ class ConvStack:
     """
 
     def __init__(self, weights, pool_after, n_act=16, n_w=16, loss_threshold=0.0, r=lp.LP_ROUND_NEAREST_AWAY,
-                 pad=1, fuse_pool=True, count_sat=True):
+                 pad=1, fuse_pool=True, count_sat=True, zskip=False):
         """fuse_pool: let lp_conv_fwd store the 2x2 maxima directly where its tiling allows it
         (the unpooled codes of such a layer are then never written; layer["y"] is None).
         count_sat: also count, per layer, the activations the frozen output format clips
-        (sat_counts; Sec. 2.3's share of lost values, measured on the running batch)."""
+        (sat_counts; Sec. 2.3's share of lost values, measured on the running batch).
+        zskip: every layer leaves per-tile nonzero flags of its output and the next layer skips the
+        64-channel chunks of its input patches that are flagged all-zero (lp_conv_fwd_zskip;
+        skipped[i] counts the (tile, chunk) pairs layer i did not multiply)."""
         assert len(weights) == len(pool_after)
-        self.fuse_pool, self.count_sat = fuse_pool, count_sat
+        self.fuse_pool, self.count_sat, self.zskip = fuse_pool, count_sat, zskip
         self.n_act, self.n_w, self.thr, self.r = n_act, n_w, loss_threshold, r
         self.pads = list(pad) if isinstance(pad, (list, tuple)) else [pad] * len(weights)
         assert len(self.pads) == len(weights)
@@ -95,6 +98,7 @@ class ConvStack:
         self.zero_counts = torch.zeros(len(self.pool_after), dtype=torch.int64, device="cuda")
         self.sat_counts = torch.zeros(len(self.pool_after), dtype=torch.int64, device="cuda")
         self.input_sat = torch.zeros(1, dtype=torch.int64, device="cuda")
+        self.skipped = torch.zeros(len(self.pool_after), dtype=torch.int64, device="cuda")
         self.layers = []
         q_in = self.qx
         for i, pool in enumerate(self.pool_after):
@@ -115,10 +119,17 @@ class ConvStack:
             if pool:
                 p = torch.empty((N, H // 2, W // 2, d.Cout), dtype=dt, device="cuda")
             ws = torch.empty(max(lp.lp_conv_workspace_bytes(d, q_in, self.qw[i]), 16), dtype=torch.uint8, device="cuda")
-            self.layers.append({"desc": d, "packed": packed, "ws": ws, "qx": q_in, "qw": self.qw[i], "qy": self.qy[i], "y": y,
+            info = lp.lp_conv_plan_info(d, q_in, self.qw[i])
+            flags = x_map = None
+            if self.zskip and info["path"] == 1:
+                flags = torch.empty(info["tiles_m"] * info["tiles_n"], dtype=torch.uint8, device="cuda")
+                prev = self.layers[-1] if self.layers else None
+                if prev is not None and prev["flags"] is not None:
+                    x_map = lp.zero_map(prev["flags"], prev["info"], prev["W"], 2 if prev["pooled"] is not None else 1)
+            self.layers.append({"flags": flags, "x_map": x_map, "desc": d, "packed": packed, "ws": ws, "qx": q_in, "qw": self.qw[i], "qy": self.qy[i], "y": y,
                                 "pooled": p, "fused_pool": fused, "H": H, "W": W, "y_numel": N * H * W * d.Cout,
                                 "macs": N * H * W * d.Cout * d.R * d.S * d.Cin,
-                                "info": lp.lp_conv_plan_info(d, q_in, self.qw[i])})
+                                "info": info})
             if pool:
                 H, W = H // 2, W // 2
             q_in = self.qy[i]
@@ -129,6 +140,8 @@ class ConvStack:
         pools.  events (optional): list to which (label, start_event, end_event) are appended."""
         assert tuple(x_float.shape) == self.in_shape
         self.zero_counts.zero_()
+        if self.zskip:
+            self.skipped.zero_()
         if self.count_sat:
             self.sat_counts.zero_()
             self.input_sat.zero_()
@@ -148,10 +161,17 @@ class ConvStack:
         cur = self.x_codes
         for i, L in enumerate(self.layers):
             out = L["pooled"] if L["fused_pool"] else L["y"]
-            timed("conv%d" % i, lambda L=L, cur=cur, i=i, out=out: lp.lp_conv_fwd(
-                L["desc"], cur, L["qx"], L["packed"], L["qw"], qy=L["qy"], y_codes=out, relu=True, r=self.r,
-                zero_count=self.zero_counts[i:i + 1], workspace=L["ws"],
-                sat_count=self.sat_counts[i:i + 1] if self.count_sat else None))
+            if L["flags"] is not None:
+                timed("conv%d" % i, lambda L=L, cur=cur, i=i, out=out: lp.lp_conv_fwd_zskip(
+                    L["desc"], cur, L["qx"], L["x_map"], L["packed"], L["qw"], L["qy"], out, relu=True, r=self.r,
+                    zero_count=self.zero_counts[i:i + 1], workspace=L["ws"],
+                    sat_count=self.sat_counts[i:i + 1] if self.count_sat else None, y_flags=L["flags"],
+                    skipped=self.skipped[i:i + 1]))
+            else:
+                timed("conv%d" % i, lambda L=L, cur=cur, i=i, out=out: lp.lp_conv_fwd(
+                    L["desc"], cur, L["qx"], L["packed"], L["qw"], qy=L["qy"], y_codes=out, relu=True, r=self.r,
+                    zero_count=self.zero_counts[i:i + 1], workspace=L["ws"],
+                    sat_count=self.sat_counts[i:i + 1] if self.count_sat else None))
             cur = out
             if L["pooled"] is not None and not L["fused_pool"]:
                 d = L["desc"]
