@@ -45,12 +45,19 @@ def _traffic_for_current_source():
         return None
 
 
-def measure_extras(lp, torch, lp_inputs, iters=10):
-    """The other steps of the path, each alone against its own roofline: the HBM-bound elementwise
-    kernels at the size of one 8 x 64 x 224 x 224 activation tensor, the single 64->64 layer at
-    batch 8, the 8-bit conv3_1..conv5_3 layers at batch 64, the Giga1Net conv layers of the paper's
-    Table 1 at batch 32 and the three classifier layers at batch 256 (synthetic codes of the right shapes; parity of these is the tests' job)."""
-    import ctypes
+EXTRA_SECTIONS = ("elementwise", "conv64", "int8", "giga1net", "fc", "zskip")
+
+
+def measure_extras(lp, torch, lp_inputs, which=EXTRA_SECTIONS, iters=10):
+    """The other steps of the path, each alone against its own roofline (sections, selectable with
+    --extras): "elementwise": the HBM-bound kernels at the size of one 8 x 64 x 224 x 224 activation
+    tensor; "conv64": the single 64->64 layer at batch 8; "int8": the 8-bit conv3_1..conv5_3 layers
+    at batch 64; "giga1net": the conv layers of the paper's Table 1 at batch 32; "fc": the three
+    classifier layers at batch 256; "zskip": one 256->256 layer with and without zero-tile skipping.
+    Inputs have the distributions of the workload configurations (ReLU(N(0,1)) activations,
+    He-normal / N(0, 0.01) weights), quantized by the library with formats from lp_range; parity of
+    these shapes is the tests' job."""
+    import numpy as np
 
     def timed(fn, n=iters):
         fn()
@@ -66,85 +73,157 @@ def measure_extras(lp, torch, lp_inputs, iters=10):
     out = {}
     g = torch.Generator(device="cuda")
     g.manual_seed(7)
-    shape = (8, 224, 224, 64)
-    n = 8 * 224 * 224 * 64
-    xf = torch.randn(shape, device="cuda", generator=g).clamp_(min=0)
-    codes = torch.empty(shape, dtype=torch.int16, device="cuda")
-    q = (16, 4, 12)
-    ms = timed(lambda: lp.lp_quantize(xf.reshape(-1), codes, q))
-    out["lp_quantize"] = {"elements": n, "ms": round(ms, 4), "GBps": round(6 * n / ms / 1e6, 1)}
-    ms = timed(lambda: lp.lp_quantize(xf.reshape(-1), codes, q, r=lp.LP_ROUND_STOCHASTIC, seed=1))
-    out["lp_quantize_stochastic"] = {"elements": n, "ms": round(ms, 4), "GBps": round(6 * n / ms / 1e6, 1)}
     rws = torch.empty(lp.LP_RANGE_WORKSPACE_WORDS, dtype=torch.int64, device="cuda")
-    t0 = time.perf_counter()
-    for _ in range(iters):
-        lp.lp_range(xf.reshape(-1), 16, 0.0, rws)              # returns the format: synchronises
-    ms = (time.perf_counter() - t0) * 1e3 / iters
-    out["lp_range"] = {"elements": n, "ms": round(ms, 4), "GBps": round(4 * n / ms / 1e6, 1), "note": "includes the host round trip"}
-    acc = (torch.randn(shape, device="cuda", generator=g) * (1 << 24)).to(torch.int64)
-    ms = timed(lambda: lp.lp_act(acc.reshape(-1), 27, (16, 6, 10), True, codes))
-    out["lp_act"] = {"elements": n, "ms": round(ms, 4), "GBps": round(10 * n / ms / 1e6, 1)}
-    ms = timed(lambda: lp.lp_act_stochastic(acc.reshape(-1), 27, (16, 6, 10), True, 1, codes))
-    out["lp_act_stochastic"] = {"elements": n, "ms": round(ms, 4), "GBps": round(10 * n / ms / 1e6, 1),
-                                "note": "one Philox4x32-10 block per element: bound by integer multiplies"}
-    t0 = time.perf_counter()
-    for _ in range(iters):
-        lp.lp_range_acc(acc.reshape(-1), 27, True, 16, 0.0, rws)
-    ms = (time.perf_counter() - t0) * 1e3 / iters
-    out["lp_range_acc"] = {"elements": n, "ms": round(ms, 4), "GBps": round(8 * n / ms / 1e6, 1), "note": "includes the host round trip"}
-    pooled = torch.empty((8, 112, 112, 64), dtype=torch.int16, device="cuda")
-    ms = timed(lambda: lp.lp_maxpool2x2(codes, pooled, 8, 224, 224, 64, 16))
-    out["lp_maxpool2x2"] = {"elements": n, "ms": round(ms, 4), "GBps": round(2.5 * n / ms / 1e6, 1)}
-    del xf, acc, pooled
+
+    def codes_of(xf, n):
+        """float tensor on the GPU -> (codes, format) by the Sec. 2.3 rule"""
+        q, _ = lp.lp_range(xf.reshape(-1), n, 0.0, rws)
+        c = torch.empty(xf.shape, dtype=torch.int16 if n > 8 else torch.int8, device="cuda")
+        lp.lp_quantize(xf.reshape(-1), c, q)
+        return c, q
+
+    def relu_normal(shape):
+        return torch.randn(shape, device="cuda", generator=g).clamp_(min=0)
+
+    if "elementwise" in which:
+        shape = (8, 224, 224, 64)
+        n = 8 * 224 * 224 * 64
+        xf = relu_normal(shape)
+        codes = torch.empty(shape, dtype=torch.int16, device="cuda")
+        q = (16, 4, 12)
+        ms = timed(lambda: lp.lp_quantize(xf.reshape(-1), codes, q))
+        out["lp_quantize"] = {"elements": n, "ms": round(ms, 4), "GBps": round(6 * n / ms / 1e6, 1)}
+        ms = timed(lambda: lp.lp_quantize(xf.reshape(-1), codes, q, r=lp.LP_ROUND_STOCHASTIC, seed=1))
+        out["lp_quantize_stochastic"] = {"elements": n, "ms": round(ms, 4), "GBps": round(6 * n / ms / 1e6, 1)}
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            lp.lp_range(xf.reshape(-1), 16, 0.0, rws)              # returns the format: synchronises
+        ms = (time.perf_counter() - t0) * 1e3 / iters
+        out["lp_range"] = {"elements": n, "ms": round(ms, 4), "GBps": round(4 * n / ms / 1e6, 1),
+                           "note": "includes the host round trip; kernel-only figures: profiles/"}
+        acc = (torch.randn(shape, device="cuda", generator=g) * (1 << 24)).to(torch.int64)
+        ms = timed(lambda: lp.lp_act(acc.reshape(-1), 27, (16, 6, 10), True, codes))
+        out["lp_act"] = {"elements": n, "ms": round(ms, 4), "GBps": round(10 * n / ms / 1e6, 1)}
+        ms = timed(lambda: lp.lp_act_stochastic(acc.reshape(-1), 27, (16, 6, 10), True, 1, codes))
+        out["lp_act_stochastic"] = {"elements": n, "ms": round(ms, 4), "GBps": round(10 * n / ms / 1e6, 1),
+                                    "note": "one Philox4x32-10 block per element: bound by integer multiplies"}
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            lp.lp_range_acc(acc.reshape(-1), 27, True, 16, 0.0, rws)
+        ms = (time.perf_counter() - t0) * 1e3 / iters
+        out["lp_range_acc"] = {"elements": n, "ms": round(ms, 4), "GBps": round(8 * n / ms / 1e6, 1),
+                               "note": "includes the host round trip; kernel-only figures: profiles/"}
+        pooled = torch.empty((8, 112, 112, 64), dtype=torch.int16, device="cuda")
+        ms = timed(lambda: lp.lp_maxpool2x2(codes, pooled, 8, 224, 224, 64, 16))
+        out["lp_maxpool2x2"] = {"elements": n, "ms": round(ms, 4), "GBps": round(2.5 * n / ms / 1e6, 1)}
+        del xf, acc, pooled, codes
 
     def conv_ms(N, hw, cin, cout, bits, k=3, pad=1):
-        dt = torch.int16 if bits > 8 else torch.int8
-        lim = 2000 if bits > 8 else 60
-        x = torch.randint(0, lim, (N, hw, hw, cin), device="cuda", generator=g).to(dt)
-        w = torch.randint(-lim, lim, (cout, k, k, cin), device="cuda", generator=g).to(dt)
-        qx, qw, qy = ((16, 4, 12), (16, 1, 15), (16, 6, 10)) if bits > 8 else ((8, 3, 5), (8, 1, 7), (8, 5, 3))
+        """one fused layer: x = ReLU(N(0,1)) codes, He-normal weight codes, output format with 3 integer bits more than x"""
+        x, qx = codes_of(relu_normal((N, hw, hw, cin)), bits)
+        wf = torch.randn((cout, k, k, cin), device="cuda", generator=g) * (2.0 / (cin * k * k)) ** 0.5
+        w, qw = codes_of(wf, bits)
+        m = min(bits, qx.m + 2)
+        qy = (bits, m, bits - m)
         d = lp.ConvDesc(N, hw, hw, cin, cout, k, k, 1, pad)
         packed = torch.empty(lp.lp_conv_packed_bytes(d, qx, qw), dtype=torch.uint8, device="cuda")
         lp.lp_conv_pack_weights(d, qx, qw, w, packed)
         ho = hw + 2 * pad - k + 1
-        y = torch.empty((N, ho, ho, cout), dtype=dt, device="cuda")
+        y = torch.empty((N, ho, ho, cout), dtype=x.dtype, device="cuda")
         z = torch.zeros(1, dtype=torch.int64, device="cuda")
         ws = torch.empty(max(lp.lp_conv_workspace_bytes(d, qx, qw), 16), dtype=torch.uint8, device="cuda")
         return timed(lambda: lp.lp_conv_fwd(d, x, qx, packed, qw, qy=qy, y_codes=y, zero_count=z, workspace=ws))
 
-    ms = conv_ms(8, 224, 64, 64, 16)
-    macs = 8 * 224 * 224 * 64 * 9 * 64
-    out["conv_64to64_224_batch8_16bit"] = {"ms": round(ms, 4), "int8_tops": round(8 * macs / ms / 1e9, 1)}
-    tot_ms, tot_macs = 0.0, 0
-    for (_, cin, cout, hw, _) in lp_inputs.VGG16_CONV[4:]:
-        tot_ms += conv_ms(64, hw, cin, cout, 8)
-        tot_macs += 64 * hw * hw * cout * 9 * cin
-    out["conv3_1_to_conv5_3_batch64_8bit"] = {"ms": round(tot_ms, 4), "int8_tops": round(2 * tot_macs / tot_ms / 1e9, 1)}
-    # Table 1's Giga1Net conv layers (kernel sizes 1/3/5/7, 3..128 channels) at batch 32, 16 bit
-    tot_ms, tot_macs = 0.0, 0
-    for (_, cin, cout, k, hw, pad, _) in lp_inputs.GIGA1NET_CONV:
-        tot_ms += conv_ms(32, hw, cin, cout, 16, k, pad)
-        ho = hw + 2 * pad - k + 1
-        tot_macs += 32 * ho * ho * cout * k * k * cin
-    out["giga1net_conv_layers_batch32_16bit"] = {"ms": round(tot_ms, 4), "int8_tops": round(8 * tot_macs / tot_ms / 1e9, 1),
-                                                   "images_per_s": round(32 / tot_ms * 1e3, 1)}
-    M = 256
-    fc = {}
-    for name, K, N in (("fc6", 25088, 4096), ("fc7", 4096, 4096), ("fc8", 4096, 1000)):
-        x = torch.randint(0, 2000, (M, K), device="cuda", generator=g).to(torch.int16)
-        w = torch.randint(-300, 300, (N, K), device="cuda", generator=g).to(torch.int16)
-        qx, qw, qy = (16, 4, 12), (16, 1, 15), (16, 8, 8)
-        packed = torch.empty(lp.lp_fc_packed_bytes(M, K, N, qx, qw), dtype=torch.uint8, device="cuda")
-        lp.lp_fc_pack_weights(M, K, N, qx, qw, w, packed)
-        y = torch.empty((M, N), dtype=torch.int16, device="cuda")
+    if "conv64" in which:
+        ms = conv_ms(8, 224, 64, 64, 16)
+        macs = 8 * 224 * 224 * 64 * 9 * 64
+        out["conv_64to64_224_batch8_16bit"] = {"ms": round(ms, 4), "int8_tops": round(8 * macs / ms / 1e9, 1)}
+    if "int8" in which:
+        tot_ms, tot_macs, per = 0.0, 0, {}
+        for (name, cin, cout, hw, _) in lp_inputs.VGG16_CONV[4:]:
+            ms = conv_ms(64, hw, cin, cout, 8)
+            per[name] = round(ms, 4)
+            tot_ms += ms
+            tot_macs += 64 * hw * hw * cout * 9 * cin
+        out["conv3_1_to_conv5_3_batch64_8bit"] = {"ms": round(tot_ms, 4), "int8_tops": round(2 * tot_macs / tot_ms / 1e9, 1),
+                                                  "layers_ms": per}
+    if "giga1net" in which:
+        # Table 1's Giga1Net conv layers (kernel sizes 1/3/5/7, 3..128 channels) at batch 32, 16 bit
+        tot_ms, tot_macs, per = 0.0, 0, {}
+        for (name, cin, cout, k, hw, pad, _) in lp_inputs.GIGA1NET_CONV:
+            ms = conv_ms(32, hw, cin, cout, 16, k, pad)
+            per[name] = round(ms, 4)
+            tot_ms += ms
+            ho = hw + 2 * pad - k + 1
+            tot_macs += 32 * ho * ho * cout * k * k * cin
+        out["giga1net_conv_layers_batch32_16bit"] = {"ms": round(tot_ms, 4), "int8_tops": round(8 * tot_macs / tot_ms / 1e9, 1),
+                                                       "images_per_s": round(32 / tot_ms * 1e3, 1), "layers_ms": per}
+    if "fc" in which:
+        M = 256
+        fc = {}
+        for name, K, N, relu in lp_inputs.VGG16_FC:
+            x, qx = codes_of(relu_normal((M, K)), 16)
+            w, qw = codes_of(torch.randn((N, K), device="cuda", generator=g) * 0.01, 16)
+            qy = (16, 8, 8)
+            packed = torch.empty(lp.lp_fc_packed_bytes(M, K, N, qx, qw), dtype=torch.uint8, device="cuda")
+            lp.lp_fc_pack_weights(M, K, N, qx, qw, w, packed)
+            y = torch.empty((M, N), dtype=torch.int16, device="cuda")
+            z = torch.zeros(1, dtype=torch.int64, device="cuda")
+            ws = torch.empty(max(lp.lp_fc_workspace_bytes(M, K, N, qx, qw), 16), dtype=torch.uint8, device="cuda")
+            ms = timed(lambda: lp.lp_fc_fwd(M, K, N, x, qx, packed, qw, qy=qy, y_codes=y, relu=relu,
+                                            zero_count=z, workspace=ws), n=2 * iters)
+            fc[name] = {"ms": round(ms, 4), "int8_tops": round(8 * M * K * N / ms / 1e9, 1),
+                        "weight_GBps": round(2 * K * N / ms / 1e6, 1)}
+            del x, w, packed
+        out["fc_batch256_16bit"] = fc
+    if "zskip" in which:
+        # conv3_2's shape with structured zeros: the producer's tile flags are built from the data
+        B, hw, cin, cout = 32, 56, 256, 256
+        qx, qw, qy = (16, 4, 12), (16, 1, 15), (16, 6, 10)
+        d = lp.ConvDesc(B, hw, hw, cin, cout, 3, 3, 1, 1)
+        info = lp.lp_conv_plan_info(d, qx, qw)
+        w = torch.randint(-2000, 2000, (cout, 3, 3, cin), device="cuda", generator=g).to(torch.int16)
+        packed = torch.empty(lp.lp_conv_packed_bytes(d, qx, qw), dtype=torch.uint8, device="cuda")
+        lp.lp_conv_pack_weights(d, qx, qw, w, packed)
+        y = torch.empty((B, hw, hw, cout), dtype=torch.int16, device="cuda")
         z = torch.zeros(1, dtype=torch.int64, device="cuda")
-        ws = torch.empty(max(lp.lp_fc_workspace_bytes(M, K, N, qx, qw), 16), dtype=torch.uint8, device="cuda")
-        ms = timed(lambda: lp.lp_fc_fwd(M, K, N, x, qx, packed, qw, qy=qy, y_codes=y, relu=(name != "fc8"),
-                                        zero_count=z, workspace=ws))
-        fc[name] = {"ms": round(ms, 4), "int8_tops": round(8 * M * K * N / ms / 1e9, 1),
-                    "weight_GBps": round(2 * K * N / ms / 1e6, 1)}
-        del x, w, packed
-    out["fc_batch256_16bit"] = fc
+        k = torch.zeros(1, dtype=torch.int64, device="cuda")
+        ws = torch.empty(max(lp.lp_conv_workspace_bytes(d, qx, qw), 16), dtype=torch.uint8, device="cuda")
+        fl = torch.empty(info["tiles_m"] * info["tiles_n"], dtype=torch.uint8, device="cuda")
+        rh, tw = info["tile_rows"], info["tile_cols"]      # the producer is given this layer's own tile geometry
+        tr, tc, tn = -(-B * hw // rh), -(-hw // tw), cin // 64
+        res = {}
+        for label, kind in (("dense", 0), ("half_of_elements_zero_unstructured", 1), ("2_of_4_channel_chunks_zero", 2),
+                            ("right_half_of_images_zero", 3)):
+            x = torch.randint(1, 2000, (B * hw, hw, cin), device="cuda", generator=g).to(torch.int16)
+            keep = torch.ones((tr, tc, tn), dtype=torch.bool, device="cuda")
+            if kind == 1:
+                x = x * (torch.rand(x.shape, device="cuda", generator=g) >= 0.5).to(torch.int16)
+            if kind == 2:
+                keep[:, :, tn // 2:] = False
+            if kind == 3:
+                keep[:, tc // 2:, :] = False
+            m = keep.repeat_interleave(rh, 0)[:B * hw].repeat_interleave(tw, 1)[:, :hw].repeat_interleave(64, 2)
+            x = (x * m.to(torch.int16)).reshape(B, hw, hw, cin).contiguous()
+            prod = dict(info, tiles_n=tn, bn=64)
+            xm = lp.zero_map(keep.to(torch.uint8).reshape(-1).contiguous(), prod, hw)
+            run_base = lambda: lp.lp_conv_fwd(d, x, qx, packed, qw, qy=qy, y_codes=y, zero_count=z, workspace=ws)
+            run_skip = lambda: lp.lp_conv_fwd_zskip(d, x, qx, xm, packed, qw, qy, y, zero_count=z, workspace=ws,
+                                                    y_flags=fl, skipped=k)
+            run_base()
+            y0 = y.clone()
+            k.zero_()
+            run_skip()
+            per_call = int(k.item())
+            # alternate the two so that both see the same clocks
+            base = skip = 0.0
+            for _ in range(3):
+                base += timed(run_base, 2 * iters) / 3
+                skip += timed(run_skip, 2 * iters) / 3
+            res[label] = {"lp_conv_fwd_ms": round(base, 4), "zskip_ms": round(skip, 4), "speedup": round(base / skip, 3),
+                          "same_codes": bool(torch.equal(y, y0)),
+                          "chunks_skipped": round(per_call / (info["tiles_m"] * info["tiles_n"] * tn), 3)}
+        out["zskip_conv3_2_batch32"] = res
     return out
 
 
@@ -157,6 +236,9 @@ def main():
     ap.add_argument("--calib", type=int, default=2, help="images used to fix the per-layer formats")
     ap.add_argument("--cpu-images", type=int, default=2, help="images the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-extras", action="store_true", help="skip the per-kernel measurements of the other path steps")
+    ap.add_argument("--extras", default="all", help="comma list of extra sections to run: " + ", ".join(EXTRA_SECTIONS))
+    ap.add_argument("--no-main", action="store_true",
+                    help="only the extra sections (for profiling them alone); prints their JSON, not the benchmark line")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (calibrates FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -178,6 +260,10 @@ def main():
     lp.load()        # raises if liblp.so is not built: there is no fallback
     torch.cuda.set_device(0)
     B = args.batch
+    sections = EXTRA_SECTIONS if args.extras == "all" else tuple(s for s in args.extras.split(",") if s)
+    if args.no_main:
+        print(json.dumps({"extras": measure_extras(lp, torch, lp_inputs, sections)}))
+        return
 
     x_np = lp_inputs.config3_input(seed=2, batch=B)                       # U(0,1) images, NCHW
     w_np = lp_inputs.vgg16_conv_weights(seed=2)                           # He-normal
@@ -303,7 +389,7 @@ def main():
             "matches_gpu_final_codes": bool(np.array_equal(got, ref["final"])),
         }
     if not args.no_extras:
-        out["extras"] = measure_extras(lp, torch, lp_inputs)
+        out["extras"] = measure_extras(lp, torch, lp_inputs, sections)
     print(json.dumps(out))
 
 
