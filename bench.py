@@ -227,6 +227,17 @@ def measure_extras(lp, torch, lp_inputs, which=EXTRA_SECTIONS, iters=10):
     return out
 
 
+def copy_probe(torch):
+    """A plain 1 GiB device-to-device copy: what FETCH_SIZE / WRITE_SIZE read for it calibrates those counters."""
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    src.zero_()
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -263,6 +274,8 @@ def main():
     sections = EXTRA_SECTIONS if args.extras == "all" else tuple(s for s in args.extras.split(",") if s)
     if args.no_main:
         print(json.dumps({"extras": measure_extras(lp, torch, lp_inputs, sections)}))
+        if args.copy_probe:
+            copy_probe(torch)
         return
 
     x_np = lp_inputs.config3_input(seed=2, batch=B)                       # U(0,1) images, NCHW
@@ -289,13 +302,7 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
 
     if args.copy_probe:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
-        src.zero_()
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        copy_probe(torch)
 
     # per-launch durations from the HIP events recorded on the launch stream
     per = {}
