@@ -51,7 +51,8 @@ typedef enum {
     LP_EINVAL = 1,       /* bad format, size, null or misaligned pointer */
     LP_EUNSUPPORTED = 2, /* valid request outside what the kernels cover */
     LP_EWORKSPACE = 3,   /* workspace / packed buffer too small */
-    LP_EDEVICE = 4       /* the HIP runtime reported an error */
+    LP_EDEVICE = 4       /* the HIP runtime reported an error for a launch of this call (an error
+                            that an earlier, unrelated HIP call left pending is dropped at entry) */
 } lp_status;
 
 /* stride-s convolution with zero padding `pad` on all four sides;
@@ -169,6 +170,17 @@ typedef struct {
 } lp_plan_info;
 lp_status lp_conv_plan_info(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, lp_plan_info *out_host);
 
+/*
+ * lp_conv_pool_check -- whether lp_conv_fwd will take this call with d->pool = 1 (host-only
+ * query; the plan-level conditions are those of lp_conv_plan_info).  The fused pool rides on the
+ * 32-bit epilogue: 16-bit codes out, ReLU, round-half-away, a right shift qx.f + qw.f - qy.f of
+ * 1..31 bits, R*S*Cin <= 8192, a bias (has_bias != 0, format qb) whose shift qx.f + qw.f - qb.f
+ * is at most 24 bits, Cout a multiple of 4.  LP_OK, or LP_EUNSUPPORTED: run the layer with
+ * pool = 0 and lp_maxpool2x2.
+ */
+lp_status lp_conv_pool_check(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, int has_bias, lp_qfmt qb, lp_qfmt qy,
+                             int relu, lp_round r);
+
 /* Bytes of device workspace lp_conv_fwd uses for this problem (may be 0): per-workgroup
  * partial zero counts, and room for the partial sums of tiles whose reduction is shared
  * between workgroups.  The workspace is required when zero_count_dev or sat_count_dev is given; otherwise it
@@ -197,9 +209,13 @@ lp_status lp_conv_workspace_bytes(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw,
  *                 lp_conv_workspace_bytes long, else LP_EWORKSPACE
  * At least one of acc_out_dev / y_codes_dev must be given.
  * LP_EUNSUPPORTED: R*S*Cin >= 65536 with 16-bit operands (int32 limb sums
- * could overflow), tensors with 2^31 or more elements; d->pool outside its conditions
- * (16-bit codes out, ReLU, round-half-away, no acc_out_dev, even Ho and Wo, a tile
- * geometry of even rows and columns as good as the unconstrained one).
+ * could overflow), tensors with 2^31 or more elements, packed weights of 2 GiB or more;
+ * d->pool outside its conditions (no acc_out_dev, even Ho and Wo, a tile geometry of even
+ * rows and columns as good as the unconstrained one, and those of lp_conv_pool_check).
+ * Shapes the int8-MFMA kernels do not take (stride > 1, 8-bit activations with 16-bit
+ * weights, Cin neither a multiple of 8 (16 for 8-bit codes) nor small enough for R*S*Cin <= 64)
+ * run on a plain one-thread-per-output kernel, correct but some hundred times slower:
+ * lp_conv_plan_info reports path = 0 for them.
  */
 lp_status lp_conv_fwd(const lp_conv_desc *d, const void *x_codes_dev, lp_qfmt qx,
                       const void *w_packed_dev, lp_qfmt qw, const void *bias_codes_dev, lp_qfmt qb,

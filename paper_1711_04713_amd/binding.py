@@ -69,6 +69,8 @@ _SIGNATURES = {
     "lp_conv_plan_info": (ctypes.c_int, [ctypes.POINTER(ConvDesc), QFmt, QFmt, ctypes.POINTER(PlanInfo)]),
     "lp_conv_pack_weights": (ctypes.c_int, [ctypes.POINTER(ConvDesc), QFmt, QFmt, ctypes.c_void_p, ctypes.c_void_p,
                                             ctypes.c_size_t, ctypes.c_void_p]),
+    "lp_conv_pool_check": (ctypes.c_int, [ctypes.POINTER(ConvDesc), QFmt, QFmt, ctypes.c_int, QFmt, QFmt, ctypes.c_int,
+                                          ctypes.c_int]),
     "lp_conv_workspace_bytes": (ctypes.c_int, [ctypes.POINTER(ConvDesc), QFmt, QFmt,
                                                ctypes.POINTER(ctypes.c_size_t)]),
     "lp_conv_fwd": (ctypes.c_int, [ctypes.POINTER(ConvDesc), ctypes.c_void_p, QFmt, ctypes.c_void_p, QFmt,
@@ -192,6 +194,15 @@ def lp_conv_plan_info(desc, qx, qw):
     out = PlanInfo()
     _check(load().lp_conv_plan_info(ctypes.byref(desc), _q(qx), _q(qw), ctypes.byref(out)), "lp_conv_plan_info")
     return out.asdict()
+
+
+def lp_conv_pool_check(desc, qx, qw, qy, relu=True, r=LP_ROUND_NEAREST_AWAY, qb=None):
+    """True if lp_conv_fwd takes this call with desc.pool = 1."""
+    status = load().lp_conv_pool_check(ctypes.byref(desc), _q(qx), _q(qw), int(qb is not None),
+                                       _q(qb) if qb is not None else QFmt(), _q(qy), int(bool(relu)), r)
+    if status not in (0, 2):
+        raise LpError(status, "lp_conv_pool_check")
+    return status == 0
 
 
 def lp_conv_pack_weights(desc, qx, qw, w_codes, packed):

@@ -18,6 +18,7 @@
 // Layers with very few input channels (the first VGG16 layer, Cin = 3) use the "flat"
 // variant: the whole R*S*Cin window is one K <= 64 slab gathered per output pixel.
 #include <algorithm>
+#include <atomic>
 #include <mutex>
 #include <type_traits>
 #include <utility>
@@ -33,6 +34,8 @@ constexpr int PS = 64;       // LDS bytes per gathered window row and limb on th
 constexpr int PSP = 80;      // LDS bytes per staged patch pixel and limb: 64 of codes and 16 of padding, so that
                              // consecutive pixels start 20 banks apart (see choose_pitch)
 constexpr int kConvThreads = 256;
+
+constexpr int kMaxDevices = 64;
 
 enum { PATH_DIRECT = 0, PATH_MFMA = 1 };
 
@@ -1280,12 +1283,15 @@ lp_status launch_sum_partials(const unsigned *partials, int n, unsigned long lon
 template <int LIMBS, int NB, bool FLAT, int MB>
 static lp_status launch_mfma(const ConvArgs &a, const Plan &p, int grid, int tails, hipStream_t st)
 {
-    static bool attr_set = false; // raise the dynamic LDS limit once per kernel instance
-    if (!attr_set) {
+    // raise the dynamic LDS limit once per kernel instance and device
+    static std::atomic<bool> attr_set[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LP_EDEVICE;
+    if (!attr_set[dev].load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute((const void *)conv_mfma_kernel<LIMBS, NB, FLAT, MB>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
             return LP_EDEVICE;
-        attr_set = true;
+        attr_set[dev].store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((conv_mfma_kernel<LIMBS, NB, FLAT, MB>), dim3(grid), dim3(MB == 2 ? 256 : 512),
                        p.lds_bytes, st, a);
@@ -1302,6 +1308,18 @@ static WorkspaceLayout workspace_layout(const Plan &p)
     w.partials = round_up((size_t)2 * p.grid * sizeof(unsigned), 256); // zero counts, counts of clipped values
     w.total = w.partials + tails * p.split * p.part_bytes;
     return w;
+}
+
+// The 32-bit epilogue (and with it the fused pool) applies when only codes are wanted, with ReLU,
+// round-half-away, a right shift of 1..31 bits, K <= 8192 and a bias shift of at most 24 bits,
+// and when the pixels of a tile span less than 2^31 bytes of output.
+static bool fast_epilogue_ok(const lp_conv_desc *d, const Plan &p, int f_acc, bool has_bias, lp_qfmt qb, lp_qfmt qy, int relu,
+                             lp_round r)
+{
+    const long long K = (long long)d->R * d->S * d->Cin;
+    const int s = f_acc - qy.f;
+    const bool span_ok = (unsigned long long)p.RH * p.Wo * d->Cout * (qy.n > 8 ? 2 : 1) < (1ull << 31);
+    return relu && r == LP_ROUND_NEAREST_AWAY && s >= 1 && s <= 31 && K <= 8192 && (!has_bias || f_acc - qb.f <= 24) && span_ok;
 }
 
 static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, const void *wp,
@@ -1361,6 +1379,7 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     a.R = d->R; a.S = d->S; a.stride = d->stride; a.pad = d->pad;
     a.Ho = p.Ho; a.Wo = p.Wo; a.Hp = p.Hp; a.FR = p.FR;
     hipStream_t hs = as_stream(stream);
+    clear_stale_error();
     if (p.path == PATH_DIRECT) {
         const size_t total = (size_t)p.FR * p.Wo * d->Cout;
         const int grid = (int)std::min<size_t>((total + 255) / 256, 256 * 64);
@@ -1402,13 +1421,7 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     // The 32-bit epilogue is exact when only codes are wanted, with ReLU, round-half-away,
     // a right shift of 1..31 bits, and sums small enough that no int32 piece can overflow
     // (K <= 8192 keeps |HH|, |HL+LH| and the folded constants below 2^29).
-    const long long K = (long long)d->R * d->S * d->Cin;
-    // Its stores address the output with 32-bit byte offsets from the tile's first pixel: the
-    // pixels of a tile (RH rows of the stacked output, all columns in between) must span less
-    // than 2^31 bytes, which only fails for absurdly wide rows.
-    const bool span_ok = (unsigned long long)p.RH * p.Wo * d->Cout * (a.y16 ? 2 : 1) < (1ull << 31);
-    a.fast = (y && !acc_out && relu && r == LP_ROUND_NEAREST_AWAY && a.act.s >= 1 && a.act.s <= 31 &&
-              K <= 8192 && (!bias || a.bias_shift <= 24) && span_ok) ? 1 : 0;
+    a.fast = (y && !acc_out && fast_epilogue_ok(d, p, f_acc, bias != nullptr, qb, qy, relu, r)) ? 1 : 0;
     a.pool = p.pool;
     if (p.pool && !(a.fast && a.y16 && d->Cout % 4 == 0)) return LP_EUNSUPPORTED;
     lp_status st2;
@@ -1429,6 +1442,7 @@ static lp_status pack_weights(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, con
     if (!w || !packed || !aligned16(w) || !aligned16(packed)) return LP_EINVAL;
     if (packed_bytes < p.packed_bytes) return LP_EWORKSPACE;
     hipStream_t hs = as_stream(stream);
+    clear_stale_error();
     const bool w16 = qw.n > 8;
     const int RS = d->R * d->S;
     if (p.path == PATH_DIRECT) {
@@ -1484,7 +1498,6 @@ static __device__ __align__(256) unsigned char scratch[LP_STATIC_WORKSPACE_BYTES
 
 static lp_status static_scratch(void **out)
 {
-    constexpr int kMaxDevices = 64;
     static std::mutex mutex;
     static void *ptr_of_device[kMaxDevices] = {};
     int dev = -1;
@@ -1548,6 +1561,18 @@ extern "C" lp_status lp_conv_plan_info(const lp_conv_desc *d, lp_qfmt qx, lp_qfm
     }
     *out_host = o;
     return LP_OK;
+}
+
+extern "C" lp_status lp_conv_pool_check(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, int has_bias, lp_qfmt qb, lp_qfmt qy,
+                                        int relu, lp_round r)
+{
+    if (!d || !d->pool) return LP_EINVAL;
+    Plan p;
+    const lp_status st = make_plan(d, qx, qw, &p);
+    if (st != LP_OK) return st;
+    if (!fmt_ok(qy) || (has_bias && !fmt_ok(qb))) return LP_EINVAL;
+    const bool ok = fast_epilogue_ok(d, p, qx.f + qw.f, has_bias != 0, qb, qy, relu, r) && qy.n > 8 && d->Cout % 4 == 0;
+    return ok ? LP_OK : LP_EUNSUPPORTED;
 }
 
 extern "C" lp_status lp_conv_workspace_bytes(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw,

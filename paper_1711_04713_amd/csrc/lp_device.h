@@ -87,6 +87,10 @@ inline bool fmt_ok(lp_qfmt q)
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Status of the launches this call has made.  clear_stale_error() at the call's entry drops an
+// error that an earlier, unrelated HIP call left pending, so that it is not reported as this
+// call's.
+inline void clear_stale_error() { (void)hipGetLastError(); }
 inline lp_status launch_status()
 {
     return hipGetLastError() == hipSuccess ? LP_OK : LP_EDEVICE;

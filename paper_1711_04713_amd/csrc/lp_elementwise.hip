@@ -466,6 +466,7 @@ extern "C" lp_status lp_range(const float *x_dev, size_t count, int n, double lo
     if (!out_host || !workspace_dev || n < 2 || n > 16 || !(loss_threshold >= 0.0)) return LP_EINVAL;
     if (count && (!x_dev || !aligned16(x_dev))) return LP_EINVAL;
     hipStream_t st = as_stream(stream);
+    clear_stale_error();
     unsigned long long *hist = (unsigned long long *)workspace_dev;
     hipLaunchKernelGGL(clear_words_kernel, dim3(1), dim3(64), 0, st, hist, LP_RANGE_WORKSPACE_WORDS);
     if (count)
@@ -483,6 +484,7 @@ extern "C" lp_status lp_range_acc(const int64_t *acc_dev, size_t count, int f_ac
         return LP_EINVAL;
     if (count && (!acc_dev || !aligned16(acc_dev))) return LP_EINVAL;
     hipStream_t st = as_stream(stream);
+    clear_stale_error();
     unsigned long long *hist = (unsigned long long *)workspace_dev;
     hipLaunchKernelGGL(clear_words_kernel, dim3(1), dim3(64), 0, st, hist, LP_RANGE_WORKSPACE_WORDS);
     if (count)
@@ -499,6 +501,7 @@ extern "C" lp_status lp_quantize(const float *x_dev, void *codes_dev, size_t cou
     if (count == 0) return LP_OK;
     if (!x_dev || !codes_dev || !aligned16(x_dev) || !aligned16(codes_dev)) return LP_EINVAL;
     hipStream_t st = as_stream(stream);
+    clear_stale_error();
     const float scale = (float)(1 << q.f);
     const float lo = -(float)(1 << (q.n - 1)), hi = (float)((1 << (q.n - 1)) - 1);
     const bool wide = q.n > 8;
@@ -526,6 +529,7 @@ static lp_status act_launch(const int64_t *acc_dev, size_t count, int f_acc, lp_
     if (count == 0) return LP_OK;
     if (!acc_dev || !y_codes_dev || !aligned16(acc_dev) || !aligned16(y_codes_dev)) return LP_EINVAL;
     hipStream_t st = as_stream(stream);
+    clear_stale_error();
     const ActParams p = make_act_params(f_acc, qy, relu, r);
     const int grid = grid_for(count / 8); // one trip of the kernel's loop per block, up to the cap
 #define LP_A(T, STOCH) \
@@ -567,6 +571,7 @@ extern "C" lp_status lp_maxpool2x2(const void *x_codes_dev, void *y_codes_dev, i
     if (!x_codes_dev || !y_codes_dev || !aligned16(x_codes_dev) || !aligned16(y_codes_dev))
         return LP_EINVAL;
     hipStream_t st = as_stream(stream);
+    clear_stale_error();
     const int Ho = H / 2, Wo = W / 2;
     const int per_vec = n_bits > 8 ? 8 : 16;
     typedef short s8v __attribute__((ext_vector_type(8)));

@@ -529,6 +529,7 @@ static lp_status fc_pack(int M, int K, int Nout, lp_qfmt qx, lp_qfmt qw, const v
     if (!w || !packed || !aligned16(w) || !aligned16(packed)) return LP_EINVAL;
     if (packed_bytes < p.packed_bytes) return LP_EWORKSPACE;
     hipStream_t hs = as_stream(stream);
+    clear_stale_error();
     const size_t pieces = (size_t)p.n_tiles * p.KH * 2 * 64;
     const int grid = (int)std::min<size_t>((pieces + 255) / 256, 65535);
     unsigned char *out = (unsigned char *)packed;
@@ -603,6 +604,7 @@ static lp_status fc_forward(int M, int K, int Nout, const void *x, lp_qfmt qx, c
     f.n_tiles = p.n_tiles; f.tiles = p.tiles; f.per_xcd = p.per_xcd; f.total = p.tiles * p.ksplit;
     f.wslab = (unsigned)p.wslab;
     hipStream_t hs = as_stream(stream);
+    clear_stale_error();
     const dim3 sgrid(p.mblocks, p.kc);
     if (p.limbs == 2) {
         hipLaunchKernelGGL((fc_split_x_kernel<int16_t, 2>), sgrid, dim3(64 * kSplitWaves), 0, hs, (const int16_t *)x,

@@ -4,6 +4,8 @@ workflow: quantize -> [LPConvolution -> LPAct+ReLU -> optional 2x2 max-pool] x L
 Only launches and buffer bookkeeping live here; every number is produced by the kernels
 behind include/lp.h.  Activations are NHWC torch tensors on the GPU.
 """
+import warnings
+
 import torch
 
 from . import binding as lp
@@ -105,9 +107,9 @@ class ConvStack:
             d = self._desc(i, N, H, W)
             fused = False
             if pool and self.fuse_pool and self.n_act > 8:
-                try:                      # status 2: this layer's tiling cannot pool for free
-                    lp.lp_conv_plan_info(self._desc(i, N, H, W, 1), q_in, self.qw[i])
-                    d, fused = self._desc(i, N, H, W, 1), True
+                try:                      # status 2: this layer's tiling or arguments cannot pool for free
+                    if lp.lp_conv_pool_check(self._desc(i, N, H, W, 1), q_in, self.qw[i], self.qy[i], True, self.r):
+                        d, fused = self._desc(i, N, H, W, 1), True
                 except lp.LpError as e:
                     if e.status != 2:
                         raise
@@ -120,6 +122,9 @@ class ConvStack:
                 p = torch.empty((N, H // 2, W // 2, d.Cout), dtype=dt, device="cuda")
             ws = torch.empty(max(lp.lp_conv_workspace_bytes(d, q_in, self.qw[i]), 16), dtype=torch.uint8, device="cuda")
             info = lp.lp_conv_plan_info(d, q_in, self.qw[i])
+            if info["path"] != 1:
+                warnings.warn("layer %d (%s) is outside the int8-MFMA kernels' shapes and runs on the plain "
+                              "one-thread-per-output kernel" % (i, tuple(self.w_float[i].shape)), RuntimeWarning)
             flags = x_map = None
             if self.zskip and info["path"] == 1:
                 flags = torch.empty(info["tiles_m"] * info["tiles_n"], dtype=torch.uint8, device="cuda")

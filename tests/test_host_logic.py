@@ -203,3 +203,19 @@ def test_launch_geometry_covers_every_tile_and_slab_once(N, H, W, Cin, Cout, R, 
     ws = lp.lp_conv_workspace_bytes(lp.ConvDesc(N, H, W, Cin, Cout, R, S, 1, pad), Q16, W16)
     tails = 8 * (per_xcd - full)
     assert ws >= grid * 4 + (tails * split * (128 * info["bn"] * 3 * 4 + 512) if split > 1 else 0)
+
+
+def test_pool_check_lists_every_condition_of_the_fused_pool():
+    """lp_conv_pool_check answers on the host what lp_conv_fwd would say to d.pool = 1."""
+    d = lp.ConvDesc(32, 224, 224, 64, 64, 3, 3, 1, 1, 1)
+    assert lp.lp_conv_pool_check(d, Q16, W16, (16, 6, 10))
+    assert not lp.lp_conv_pool_check(d, Q16, W16, (16, 6, 10), relu=False)
+    assert not lp.lp_conv_pool_check(d, Q16, W16, (16, 6, 10), r=lp.LP_ROUND_NEAREST_EVEN)
+    assert not lp.lp_conv_pool_check(d, Q16, W16, (8, 6, 2))                       # 8-bit codes out
+    assert not lp.lp_conv_pool_check(d, Q16, W16, (16, 6, 10), qb=(16, 15, 1))     # bias shift beyond 24 bits
+    assert lp.lp_conv_pool_check(d, Q16, W16, (16, 6, 10), qb=(16, 4, 12))
+    wide = lp.ConvDesc(2, 16, 16, 1024, 64, 3, 3, 1, 1, 1)                         # K = 9216 > 8192
+    try:
+        assert not lp.lp_conv_pool_check(wide, Q16, W16, (16, 6, 10))
+    except lp.LpError as e:                                                        # or no poolable tiling at all
+        assert e.status == 2
