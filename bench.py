@@ -321,8 +321,8 @@ def main():
         total_macs += macs
         info = L["info"]
         flat = info["path"] == 1 and L["desc"].Cin < 16          # whole window as one slab (first layer)
-        kname = ("conv_mfma_kernel<%d,%d,%s>" % (info["limbs"], info["bn"] // 64, "flat" if flat else "patch")
-                 if info["path"] == 1 else "conv_direct_kernel")
+        kname = ("conv_direct_kernel" if info["path"] != 1 else "conv_flat_kernel" if flat
+                 else "conv_mfma_kernel<%d,%d,patch>" % (info["limbs"], info["bn"] // 64))
         kern_ops[kname] = kern_ops.get(kname, 0) + 8 * macs          # 4 int8 limb MACs = 8 int8 ops per 16-bit MAC
         kern_ms[kname] = kern_ms.get(kname, 0.0) + ms
         layers.append({

@@ -15,8 +15,8 @@
 // once per 64-channel chunk and every tap reads it at a shifted offset (implicit GEMM with
 // halo reuse).  Weights are packed one (chunk, tap) slab after the other and are read from
 // global memory / L2 straight into MFMA operand registers, half a slab ahead of their use.
-// Layers with very few input channels (the first VGG16 layer, Cin = 3) use the "flat"
-// variant: the whole R*S*Cin window is one K <= 64 slab gathered per output pixel.
+// Layers with very few input channels (the first VGG16 layer, Cin = 3) run conv_flat_kernel:
+// the whole R*S*Cin window is one K <= 64 slab, gathered per output pixel from the raw patch.
 #include <algorithm>
 #include <atomic>
 #include <mutex>
@@ -30,7 +30,7 @@ namespace lp {
 
 constexpr int BM = 128;      // output pixels per workgroup
 constexpr int CK = 64;       // channels (bytes per limb) per staged chunk
-constexpr int PS = 64;       // LDS bytes per gathered window row and limb on the flat path (swizzled, see swz)
+constexpr int kFlatRawBytes = 8192; // LDS for the raw input patch of the flat-window kernel
 constexpr int PSP = 80;      // LDS bytes per staged patch pixel and limb: 64 of codes and 16 of padding, so that
                              // consecutive pixels start 20 banks apart (see choose_pitch)
 constexpr int kConvThreads = 256;
@@ -74,16 +74,6 @@ static bool desc_ok(const lp_conv_desc *d)
            d->W + 2 * d->pad >= d->S && (d->pool == 0 || d->pool == 1);
 }
 
-// LDS layout of staged pixels and weight rows: 64 bytes each, no padding; the four 16-byte
-// slots of an item are stored in the order slot ^ key.  A 16-byte fragment read is served 16
-// lanes at a time from 64 four-byte banks (256 bytes): an item's number modulo 4 picks its
-// 64-byte quarter, and the key must differ among the (up to four) items of a group that share
-// a quarter.  Weight rows and flat-window rows are numbered consecutively per lane group, so
-// key = (number >> 2) & 3 does it.  Patch pixels are visited tile-row-major (TW pixels, then the
-// next patch row), so their key is ((patch_col >> 2) + kmul * patch_row) & 3 with the rows
-// pitch pixels apart, or, for kmul == 4, the one-dimensional (pixel number >> 2) & 3 (best when
-// PW == TW, e.g. 1x1 kernels and the FC layers); pitch (PW..PW+3) and kmul (0..4) are chosen
-// per plan by counting the conflicts of every 16-lane group at every tap.
 // Bank conflicts of the fragment reads for a patch whose rows are pitch16 * 16 bytes apart.  A
 // 16-byte read is served 16 lanes at a time, the 64 banks covering 256 bytes: the 16 lanes (16
 // consecutive tile rows, the same 16-byte slot of their pixels at one tap) must fall into 16
@@ -140,13 +130,14 @@ static int patch_table_len(int limbs, int npixa, int flat)
 }
 
 // LDS: tables (3*ntab + 2*BM ints, 3*bn ints of channel constants, BM pooled offsets), staged patch (one plane per
-// limb); the flat variant also parks the raw patch (at most 8 KB)
+// limb); the flat-window kernel: its fixed arrays (raw patch, weight operands, tables)
 static size_t mfma_lds_bytes(int limbs, int pra, int pw, int pitch_bytes, int bn, int flat)
 {
+    if (flat) return (size_t)kFlatRawBytes + 8192 + 4096;
     const int ntab = patch_table_len(limbs, pra * pw, flat);
-    const size_t plane = flat ? (size_t)BM * PS : (size_t)pra * pitch_bytes + PSP; // + the slot overshoot pieces are parked in
+    const size_t plane = (size_t)pra * pitch_bytes + PSP; // + the slot overshoot pieces are parked in
     size_t tables = round_up((size_t)(3 * ntab + 2 * BM) * 4, 16) + (size_t)3 * bn * 4 + (size_t)BM * 4;
-    return tables + (size_t)limbs * plane + (flat ? (size_t)2 * 64 * PS : 0); // flat: the raw patch
+    return tables + (size_t)limbs * plane;
 }
 // LDS budgets tried in turn: three workgroups per CU (160 KB / 3), else two
 constexpr size_t kLdsBudgets[2] = {54400, 80000};
@@ -265,7 +256,7 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
                 if (!p.flat &&
                     mfma_lds_bytes(p.limbs, pra, pw, 16 * choose_pitch(pw, tw, rh, d->R, d->S), bn_max, 0) > kLdsBudgets[pass])
                     continue;
-                if (p.flat && (size_t)npixa * d->Cin * 2 > (size_t)2 * 64 * PS) continue; // the raw patch has 8 KB of LDS
+                if (p.flat && (size_t)npixa * d->Cin * 2 > (size_t)kFlatRawBytes) continue;
                 best_free = std::min(best_free, cost);
                 if (d->pool && !poolable) continue;
                 if (cost < best) {
@@ -292,7 +283,7 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
         // registers for the prefetch pipeline, so it always runs 64-wide
         if (p.limbs == 2) p.BN = 64;
         p.tiles_n = p.CoutP / p.BN;
-        p.PITCH = p.flat ? p.PW * PS : 16 * choose_pitch(p.PW, p.TW, p.RH, d->R, d->S);
+        p.PITCH = p.flat ? 0 : 16 * choose_pitch(p.PW, p.TW, p.RH, d->R, d->S);
         p.lds_bytes = mfma_lds_bytes(p.limbs, p.PRA, p.PW, p.PITCH, p.BN, p.flat);
         {
             // workgroup slots per die: what registers and LDS allow
@@ -462,14 +453,9 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(const ConvArgs a)
 
 // -------------------------------------------------------------------------- MFMA path
 
-// byte offset of 16-byte slot q of the gathered window row that starts at byte offset pix (a
-// multiple of 64) in the swizzled layout of the flat path
-__device__ __forceinline__ int swz(int pix, int q) { return pix + (((q ^ (pix >> 8)) & 3) << 4); }
-
 // LIMBS: 1 (int8 codes) or 2 (16-bit codes as two int8 limbs).  NB: 32-column blocks per
 // wave; the workgroup covers BN = 64*NB output channels with 2x2 waves of 64 x 32*NB each.
-// FLAT: the window is gathered as one slab per output pixel instead of staging a patch.
-template <int LIMBS, int NB, bool FLAT, int MB>
+template <int LIMBS, int NB, int MB>
 __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     __attribute__((amdgpu_waves_per_eu(MB == 2 && LIMBS == 2 ? 3 : 4, MB == 2 && LIMBS == 2 ? 3 : 4))) void conv_mfma_kernel(
         const ConvArgs a)
@@ -512,8 +498,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
 
     const int NPIXA = a.NPIXA;
     int *tab = (int *)smem;          // staged pixel -> byte offset of its codes in x, all ones outside the image
-                                     // (FLAT: input pixel index, -1 outside)
-    int *psum = tab + a.NTAB;        // per staged pixel (FLAT: per tile row): sum of its codes
+    int *psum = tab + a.NTAB;        // per staged pixel: sum of its codes
     int *apos = psum + a.NTAB;       // staged pixel -> byte offset inside a limb plane
     int *outoff = apos + a.NTAB;     // tile row -> output pixel index, -1 if not an output
     int *abase_s = outoff + BM;      // tile row -> staged pixel of its (r=0, s=0) tap
@@ -540,7 +525,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             const int ix = x0 - a.pad + pc;
             if (n < a.N && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W) g = (n * a.H + iy) * a.W + ix;
         }
-        tab[p] = FLAT ? g : (g >= 0 ? (int)((unsigned)g * px_bytes) : -1);
+        tab[p] = g >= 0 ? (int)((unsigned)g * px_bytes) : -1;
         apos[p] = planes_lds + pos; // as an LDS address: parking a piece then costs no base add
         psum[p] = 0;
     }
@@ -570,7 +555,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     // multiplied.  livemask: bit c = chunk c is multiplied (uniform).  Every wave works it out for
     // itself: lane c looks at chunk c.  Tiles whose reduction is shared between workgroups, and
     // layers with more than 32 chunks, multiply everything.
-    const bool skipping = !FLAT && a.zin && nparts == 1 && a.nchunks <= 32;
+    const bool skipping = a.zin && nparts == 1 && a.nchunks <= 32;
     if (skipping) {
         // input rows (of the N * H stacked rows) and columns the patch really holds
         int n_lo, p_lo, n_hi, p_hi;
@@ -622,8 +607,8 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             const int row = wm * WROWS + mb * 32 + l32;
-            // the row's (r=0, s=0) pixel; patch path: the lane's 16-byte slot of the first K half in it
-            aoff[mb] = FLAT ? row * PS : apos[abase_s[row]] + kg * 16;
+            // the row's (r=0, s=0) pixel: the lane's 16-byte slot of the first K half in it
+            aoff[mb] = apos[abase_s[row]] + kg * 16;
         }
     };
     if constexpr (!LATE_ROWS) lane_constants();
@@ -705,132 +690,45 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
 #pragma unroll
         for (int j = 0; j < APF; ++j) store_piece(first + j * THREADS, reg[j], at[j]);
     };
-    // FLAT: the raw patch (all Cin channels, int16) is parked in the unused second weight
-    // buffer, then each tile row's window is gathered from there, 16 consecutive k per piece.
-    auto stage_flat = [&]() __attribute__((always_inline)) {
-        int16_t *raw = (int16_t *)Bsm; // own LDS region behind the gathered windows
-        const int nraw = NPIXA * a.Cin;
-        // raw patch: four codes per thread requested together, pixels outside the image read as 0
-        constexpr int RU = 4;
-        for (int i0 = tid; i0 < nraw; i0 += RU * THREADS) {
-            short v[RU];
-#pragma unroll
-            for (int u = 0; u < RU; ++u) {
-                const int i = min(i0 + u * THREADS, nraw - 1);
-                int p, ci;
-                udivmod(i, a.Cin, a.mg_Cin, p, ci);
-                const int g = tab[p];
-                const unsigned off = g >= 0 ? (unsigned)(g * a.Cin + ci) * 2u : 0xffffffffu;
-                v[u] = (short)__builtin_amdgcn_raw_buffer_load_b16(xrsrc, (int)off, 0, 0);
-            }
-#pragma unroll
-            for (int u = 0; u < RU; ++u)
-                if (i0 + u * THREADS < nraw) raw[i0 + u * THREADS] = v[u];
-        }
-        // Window element k of a tile row = (r, s, ci) with k = (r*S + s)*Cin + ci sits
-        // koff[k] = r * PW*Cin + (k - r * S*Cin) codes behind the row's first window element in
-        // the raw patch, the same for every row: a table of byte offsets, one entry per k (it
-        // lives in the position table, which this variant does not use; entries past K repeat
-        // entry 0 and their codes are masked out below).
-        int *koff = apos;
-        const int SC = a.S * a.Cin;
-        for (int k = tid; k < 64; k += THREADS) {
-            int r, rem;
-            udivmod(k, SC, a.mg_SC, r, rem);
-            koff[k] = k < a.Kflat ? 2 * (r * a.PW * a.Cin + rem) : 0;
-        }
-        __syncthreads();
-        // A thread gathers 16 consecutive k of one tile row: two codes per register (16-bit LDS
-        // reads into the two halves), then the byte permutes and two-element dot products of the
-        // patch path.  Only the K halves the MFMAs will read (32 * ksteps of the 64 slab bytes)
-        // are built.  Piece i: row i % BM, k0 = 16 * (i / BM), so k0 is the same for a whole wave
-        // and the mask for codes past K is scalar work.
-        const int pieces = BM * 2 * a.ksteps;
-        const unsigned char *rawb = (const unsigned char *)raw;
-        for (int i = tid; i < pieces; i += THREADS) {
-            const int row = i & (BM - 1);
-            const int k0 = __builtin_amdgcn_readfirstlane(i / BM) * 16;
-            const int base = abase_s[row] * a.Cin * 2; // byte offset of the row's first window element
-            const v4i o0 = *(const v4i *)(koff + k0), o1 = *(const v4i *)(koff + k0 + 4);
-            const v4i o2 = *(const v4i *)(koff + k0 + 8), o3 = *(const v4i *)(koff + k0 + 12);
-            const int o[16] = {o0.x, o0.y, o0.z, o0.w, o1.x, o1.y, o1.z, o1.w, o2.x, o2.y, o2.z, o2.w, o3.x, o3.y, o3.z, o3.w};
-            unsigned pr[8];
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const v2s two = {*(const short *)(rawb + base + o[2 * q]), *(const short *)(rawb + base + o[2 * q + 1])};
-                pr[q] = __builtin_bit_cast(unsigned, two);
-            }
-            const int nv = a.Kflat - k0; // codes of this piece that exist
-            if (nv < 16) {
-#pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    const int m = min(max(nv - 2 * q, 0), 2);
-                    pr[q] &= m == 2 ? 0xffffffffu : m == 1 ? 0xffffu : 0u;
-                }
-            }
-            unsigned hi[4], lo[4];
-            int sum = 0;
-            const v2s ones = {1, 1};
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                hi[q] = __builtin_amdgcn_perm(pr[2 * q + 1], pr[2 * q], 0x07050301u);
-                lo[q] = __builtin_amdgcn_perm(pr[2 * q + 1], pr[2 * q], 0x06040200u) ^ 0x80808080u;
-                sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, pr[2 * q]), ones, sum, false);
-                sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, pr[2 * q + 1]), ones, sum, false);
-            }
-            atomicAdd(&psum[row], sum);
-            // low limbs are offset by 128 (code 0, also beyond K, is the byte 0x80: it multiplies
-            // zero weights there)
-            const v4i vh = {(int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
-            const v4i vl = {(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3]};
-            *(v4i *)(Asm + swz(row * PS, k0 >> 4)) = vh;
-            *(v4i *)(Asm + APL + swz(row * PS, k0 >> 4)) = vl;
-        }
-    };
     constexpr int DEEP = 8;
     // between(): work that does not depend on the patch, done while the first requests fly
     auto stage_activations = [&](int cc, bool deep, auto between) __attribute__((always_inline)) {
-        if constexpr (FLAT) {
+        // two batches of requests in flight; a request past the end of the patch reads as
+        // zeros and is parked in the spare slot (see the patch tables)
+        const int total = NPIXA * PIECES;
+        const unsigned chb = channel_offset(cc);
+        int first = 0;
+        if (deep) {
+            // the accumulators are not live yet: request the first DEEP pieces of every
+            // thread at once and pay the memory latency a single time
+            v4i d[DEEP];
+            int dat[DEEP];
+#pragma unroll
+            for (int j = 0; j < DEEP; ++j) load_piece(chb, j * THREADS, d[j], dat[j]);
             between();
-            stage_flat();
-        } else {
-            // two batches of requests in flight; a request past the end of the patch reads as
-            // zeros and is parked in the spare slot (see the patch tables)
-            const int total = NPIXA * PIECES;
-            const unsigned chb = channel_offset(cc);
-            int first = 0;
-            if (deep) {
-                // the accumulators are not live yet: request the first DEEP pieces of every
-                // thread at once and pay the memory latency a single time
-                v4i d[DEEP];
-                int dat[DEEP];
 #pragma unroll
-                for (int j = 0; j < DEEP; ++j) load_piece(chb, j * THREADS, d[j], dat[j]);
-                between();
-#pragma unroll
-                for (int j = 0; j < DEEP; ++j) store_piece(j * THREADS, d[j], dat[j]);
-                first = DEEP * THREADS;
-                if (first >= total) {
-                    __builtin_amdgcn_s_waitcnt(0x0F70);
-                    return;
-                }
+            for (int j = 0; j < DEEP; ++j) store_piece(j * THREADS, d[j], dat[j]);
+            first = DEEP * THREADS;
+            if (first >= total) {
+                __builtin_amdgcn_s_waitcnt(0x0F70);
+                return;
             }
-            // Two batches of requests are in flight inside the loop; the last two batches are
-            // taken out of it, so that no request is left in flight when the staging is over (its
-            // destination registers are reused in the multiply loop, and the wait that protects
-            // them would sit at the top of every slab, where it would also wait for the weight
-            // operands just requested) and the loop has one way out.
-            load_act(chb, first, aregA, atA);
-            for (; first + 2 * APF * THREADS < total; first += 2 * APF * THREADS) {
-                load_act(chb, first + APF * THREADS, aregB, atB);
-                store_act(first, aregA, atA);
-                load_act(chb, first + 2 * APF * THREADS, aregA, atA);
-                store_act(first + APF * THREADS, aregB, atB);
-            }
+        }
+        // Two batches of requests are in flight inside the loop; the last two batches are
+        // taken out of it, so that no request is left in flight when the staging is over (its
+        // destination registers are reused in the multiply loop, and the wait that protects
+        // them would sit at the top of every slab, where it would also wait for the weight
+        // operands just requested) and the loop has one way out.
+        load_act(chb, first, aregA, atA);
+        for (; first + 2 * APF * THREADS < total; first += 2 * APF * THREADS) {
             load_act(chb, first + APF * THREADS, aregB, atB);
             store_act(first, aregA, atA);
+            load_act(chb, first + 2 * APF * THREADS, aregA, atA);
             store_act(first + APF * THREADS, aregB, atB);
         }
+        load_act(chb, first + APF * THREADS, aregB, atB);
+        store_act(first, aregA, atA);
+        store_act(first + APF * THREADS, aregB, atB);
         // vmcnt(0), stated where every path passes (the waits above sit partly inside branches
         // on lane masks); by now it costs nothing
         __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -841,7 +739,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     int cc, tap, tap_r = 0, tap_s = 0;
     udivmod(s0, a.taps, a.mg_taps, cc, tap);
     if (skipping) cc = __builtin_ctz(livemask);
-    if constexpr (!FLAT) udivmod(tap, a.S, a.mg_S, tap_r, tap_s);
+    udivmod(tap, a.S, a.mg_S, tap_r, tap_s);
     int taprow = tap_r * a.PITCH, tapoff = taprow + tap_s * PSP;
     // Weights go straight from global memory / L2 into the MFMA operand registers, NSETS - 1
     // K=32 halves ahead of their use; with no slab to publish, the waves of a workgroup meet only
@@ -877,23 +775,17 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         }
     };
     // The activation fragments (A operands) of a row block stay in registers from their LDS read
-    // to the MFMAs that consume them.  On the patch path they are read one step ahead: as soon as
-    // the MFMAs of row block mb of a K half are issued, the fragments of the same row block for the
-    // next K half (of this slab or the next) are requested, so that the LDS latency runs under the
-    // other row block's MFMAs.  The flat path (a slab per staging) reads them where it uses them.
-    constexpr bool PIPE = !FLAT;
+    // to the MFMAs that consume them.  They are read one step ahead: as soon as the MFMAs of row
+    // block mb of a K half are issued, the fragments of the same row block for the next K half (of
+    // this slab or the next) are requested, so that the LDS latency runs under the other row
+    // block's MFMAs.
     v4i ah[MB], al[MB];
-    // Patch path: off / offl are the LDS addresses themselves (high and low plane), so that a
-    // read costs no address arithmetic; flat path: off is relative to the planes.
+    // off / offl are the LDS addresses themselves (high and low plane), so that a read costs no
+    // address arithmetic
     typedef __attribute__((address_space(3))) const v4i lds_cv4i;
     auto afetch = [&](int mb, int off, int offl) __attribute__((always_inline)) {
-        if constexpr (FLAT) {
-            ah[mb] = *(const v4i *)(Asm + off);
-            if constexpr (LIMBS == 2) al[mb] = *(const v4i *)(Asm + APL + off);
-        } else {
-            ah[mb] = *(lds_cv4i *)(unsigned)off;
-            if constexpr (LIMBS == 2) al[mb] = *(lds_cv4i *)(unsigned)offl;
-        }
+        ah[mb] = *(lds_cv4i *)(unsigned)off;
+        if constexpr (LIMBS == 2) al[mb] = *(lds_cv4i *)(unsigned)offl;
     };
     auto mfma_mb = [&](int mb, const v4i *wh, const v4i *wl) __attribute__((always_inline)) {
 #pragma unroll
@@ -910,7 +802,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         }
     };
     constexpr int HALF2 = 32;
-    auto second_half = [&](int off) __attribute__((always_inline)) { return FLAT ? off ^ HALF2 : off + HALF2; };
+    auto second_half = [&](int off) __attribute__((always_inline)) { return off + HALF2; };
     using std::integral_constant;
     // One K half of slab t, which is slab number P of the current rotation: request the weights
     // that are LEAD halves ahead, then multiply this half row block by row block.  cur / nxt:
@@ -927,30 +819,22 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         bload(wnext, ahead & 1, bh[fill], bl[fill]);
         // the requests leave before this half's MFMAs, not among them
         __builtin_amdgcn_sched_barrier(0);
-        const bool on = hh == 0 || !FLAT || a.ksteps > 1; // a flat window of K <= 32 has one half
-        if (!on) // vmcnt: the skipped half's operands have arrived all the same, so that the count
-                 // of requests in flight does not depend on the path taken
-            __builtin_amdgcn_s_waitcnt(0x0F70 | (LEAD * NB * LIMBS));
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            if constexpr (!PIPE) afetch(mb, hh ? second_half(cur[mb]) : cur[mb], 0);
-            if (on) mfma_mb(mb, bh[use], bl[use]);
+            mfma_mb(mb, bh[use], bl[use]);
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (PIPE) {
-                if (hh == 0) afetch(mb, second_half(cur[mb]), second_half(curl[mb]));
-                else afetch(mb, nxt[mb], nxtl[mb]);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            if (hh == 0) afetch(mb, second_half(cur[mb]), second_half(curl[mb]));
+            else afetch(mb, nxt[mb], nxtl[mb]);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
     // fragment offsets of the slab the tap bookkeeping points at: the lane's slot (kg) of its
-    // pixel per row block; the second K=32 half is slot kg+2, 32 bytes further (flat path: the
-    // swizzled slot, i.e. the offset with bit 5 flipped).  On the patch path a tap moves every
+    // pixel per row block; the second K=32 half is slot kg+2, 32 bytes further.  A tap moves every
     // lane by the same amount, so a slab costs one add per row block.
     auto fragment_offsets = [&](int *afrag, int *afragl) __attribute__((always_inline)) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            afrag[mb] = FLAT ? swz(aoff[mb], kg) : aoff[mb] + tapoff;
+            afrag[mb] = aoff[mb] + tapoff;
             afragl[mb] = afrag[mb] + APL;
         }
     };
@@ -984,10 +868,8 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
         lane_constants();
         fragment_offsets(cur, curl);
     }
-    if constexpr (PIPE) {
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) afetch(mb, cur[mb], curl[mb]);
-    }
+    for (int mb = 0; mb < MB; ++mb) afetch(mb, cur[mb], curl[mb]);
     auto step = [&](int t, auto P) __attribute__((always_inline)) {
         // move the bookkeeping on to slab t + 1
         if (++tap == a.taps) {
@@ -995,7 +877,7 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             cc = next_chunk(cc);
             tap_s = tap_r = 0;
             tapoff = taprow = 0;
-        } else if (!FLAT) {
+        } else {
             tapoff += PSP;
             if (++tap_s == a.S) {
                 tap_s = 0;
@@ -1017,10 +899,8 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
             stage_activations(cc, false, [] {});
             __syncthreads(); // the freshly staged patch is visible
             __builtin_amdgcn_s_setprio(3);
-            if constexpr (PIPE) {
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) afetch(mb, nxt[mb], nxtl[mb]);
-            }
+            for (int mb = 0; mb < MB; ++mb) afetch(mb, nxt[mb], nxtl[mb]);
         }
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
@@ -1049,7 +929,6 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
     // ---- sum of the codes under a tile row's window (two-limb correction term 128 * sum(a)):
     // the channel sums of its R x S patch pixels, complete since the last chunk was staged
     auto row_sum = [&](int m) __attribute__((always_inline)) {
-        if constexpr (FLAT) return psum[m];
         const int base = abase_s[m];
         int sum = 0;
         if (a.R == 3 && a.S == 3) { // the common window, unrolled: nine independent LDS reads
@@ -1272,6 +1151,186 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(const unsigned *__res
     }
 }
 
+
+// Layers with very few input channels (the first VGG16 layer: Cin = 3, K = 27): the whole R*S*Cin
+// window is one K <= 64 slab, the layer is bound by its output (64 codes written per 27 read) and by
+// the vector instructions of the epilogue, and everything that the patch kernel does between
+// global memory and the MFMA is overhead.  Here a wave owns 32 tile rows x all NCB*32 channels of
+// the tile, and lane (row, K quarter) gathers the 16 window codes of its MFMA operand straight
+// from the raw input patch in LDS into registers: no staged planes, no fragment reads, one
+// barrier.  The sum of a row's codes (offset correction) is the sum over its lanes' gathers.
+// NCB: 32-channel blocks per tile (1 for layers with at most 32 output channels); KS: K halves (1: K <= 32).
+template <int NCB, int KS>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void conv_flat_kernel(
+    const ConvArgs a)
+{
+    constexpr int THREADS = 256, BN = 64;
+    __shared__ __align__(16) short raw[kFlatRawBytes / 2]; // the raw input patch, all channels (the planner keeps it within)
+    __shared__ v4i wlds[KS * 2 * NCB][64];      // weight operands: [(K half, limb, column block)][lane]
+    __shared__ int koff[64];                    // window position k -> byte offset behind the window's first code
+    __shared__ int outoff[BM], pooloff[BM], abase[BM];
+    __shared__ __align__(16) int ctab[3 * BN];
+    __shared__ unsigned wave_counts[2][THREADS / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kg = lane >> 5;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int wi = xcd * a.per_xcd + slot;
+    if (slot >= a.per_xcd || wi >= a.total_work) {
+        if (a.zero_partial && tid == 0) a.zero_partial[blockIdx.x] = a.zero_partial[a.partial_stride + blockIdx.x] = 0;
+        return;
+    }
+    int mtile, ntile, tile_r, tile_c, img0, yo0;
+    udivmod(wi, a.tiles_n, a.mg_tiles_n, mtile, ntile);
+    udivmod(mtile, a.tiles_c, a.mg_tiles_c, tile_r, tile_c);
+    const int fr0 = tile_r * a.RH, x0 = tile_c * a.TW;
+    udivmod(fr0, a.Ho, a.mg_Ho, img0, yo0);
+    const int vr0 = img0 * a.Hp + yo0;
+
+    // weights of the tile: a lane's operand for (K half, limb, column block) is 16 bytes of the row
+    // it owns (see slab_byte).  The waves share the WPIECES operands of 64 lanes each: requested
+    // first, parked in LDS, read back when a column block is multiplied.
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<unsigned char *>(a.wp), 0, 2 * a.CoutP * CK, 0x00020000);
+    constexpr int WPIECES = KS * 2 * NCB, WPT = (WPIECES + 3) / 4; // piece = (h * 2 + limb) * NCB + cb
+    v4i wreg[WPT];
+#pragma unroll
+    for (int i = 0; i < WPT; ++i) {
+        const int piece = wave + 4 * i;
+        const int cb = piece % NCB, hl = piece / NCB, limb = hl & 1, h = hl >> 1;
+        const int at = ((h * a.CoutP + ntile * BN + cb * 32 + l32) * 32) + kg * 16 + limb * a.CoutP * CK;
+        const auto v = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, piece < WPIECES ? at : (int)0x80000000, 0, 0);
+        wreg[i] = (v4i){(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
+    }
+    // raw patch, row by row: a patch row is PW * Cin consecutive codes of an image row (code e of
+    // patch row pr is code (x0 - pad) * Cin + e of that image row); codes outside the image read as 0
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void *>(a.x), 0, (int)((unsigned)(a.N * a.H * a.W) * (unsigned)a.Cin * 2u), 0x00020000);
+    const int nraw = a.NPIXA * a.Cin, rowlen = a.PW * a.Cin, wlen = a.W * a.Cin;
+    const int e0 = (x0 - a.pad) * a.Cin;
+    constexpr int RU = 3; // requests in flight per thread (a 18 x 10 x 3 patch is 2.1 codes per thread)
+    for (int i0 = tid; i0 < nraw; i0 += RU * THREADS) {
+        short v[RU];
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+            const int i = min(i0 + u * THREADS, nraw - 1);
+            int pr, e, n, iy;
+            udivmod(i, rowlen, a.mg_rowlen, pr, e);
+            udivmod(vr0 + pr, a.Hp, a.mg_Hp, n, iy);
+            iy -= a.pad;
+            const int c = e0 + e; // position in the image row, in codes
+            const bool in = n < a.N && iy >= 0 && iy < a.H && c >= 0 && c < wlen;
+            const unsigned off = in ? (unsigned)((n * a.H + iy) * wlen + c) * 2u : 0xffffffffu;
+            v[u] = (short)__builtin_amdgcn_raw_buffer_load_b16(xrsrc, (int)off, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < RU; ++u)
+            if (i0 + u * THREADS < nraw) raw[i0 + u * THREADS] = v[u];
+    }
+    // tables: window position -> offset, tile row -> output pixel / window start, channel constants
+    const int SC = a.S * a.Cin;
+    for (int k = tid; k < 64; k += THREADS) {
+        int r, rem;
+        udivmod(k, SC, a.mg_SC, r, rem);
+        koff[k] = k < a.Kflat ? 2 * (r * a.PW * a.Cin + rem) : 0;
+    }
+    for (int m = tid; m < BM; m += THREADS) {
+        int j, t, img, yo;
+        udivmod(m, a.TW, a.mg_TW, j, t);
+        const int fr = fr0 + j, xo = x0 + t;
+        const bool ok = j < a.RH && fr < a.FR && xo < a.Wo;
+        udivmod(fr, a.Ho, a.mg_Ho, img, yo);
+        outoff[m] = ok ? fr * a.Wo + xo : -1;
+        abase[m] = ok ? ((img * a.Hp + yo - vr0) * a.PW + t) * a.Cin * 2 : 0;
+        pooloff[m] = (a.pool && ok && !(j & 1) && !(t & 1)) ? (img * (a.Ho >> 1) + (yo >> 1)) * (a.Wo >> 1) + (xo >> 1) : -1;
+    }
+    build_colterms<BN, THREADS>(a, ntile, ctab, 2);
+#pragma unroll
+    for (int i = 0; i < WPT; ++i)
+        if (wave + 4 * i < WPIECES) wlds[wave + 4 * i][lane] = wreg[i];
+    __syncthreads();
+
+    const unsigned char *rawb = (const unsigned char *)raw;
+    const int base = abase[wave * 32 + l32];
+    int sum = 0;
+    v4i ah[KS], al[KS];
+#pragma unroll
+    for (int h = 0; h < KS; ++h) {
+        // the lane's 16 window codes k0 .. k0 + 15, two per register, then split into limb bytes
+        const int k0 = h * 32 + kg * 16;
+        const v4i o0 = *(const v4i *)(koff + k0), o1 = *(const v4i *)(koff + k0 + 4);
+        const v4i o2 = *(const v4i *)(koff + k0 + 8), o3 = *(const v4i *)(koff + k0 + 12);
+        const int o[16] = {o0.x, o0.y, o0.z, o0.w, o1.x, o1.y, o1.z, o1.w, o2.x, o2.y, o2.z, o2.w, o3.x, o3.y, o3.z, o3.w};
+        unsigned pr[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const v2s two = {*(const short *)(rawb + base + o[2 * q]), *(const short *)(rawb + base + o[2 * q + 1])};
+            pr[q] = __builtin_bit_cast(unsigned, two);
+        }
+        const int nv = a.Kflat - k0; // codes of this piece that exist (the same for half a wave)
+        if (nv < 16) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int m = min(max(nv - 2 * q, 0), 2);
+                pr[q] &= m == 2 ? 0xffffffffu : m == 1 ? 0xffffu : 0u;
+            }
+        }
+        unsigned hi[4], lo[4];
+        const v2s ones = {1, 1};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            hi[q] = __builtin_amdgcn_perm(pr[2 * q + 1], pr[2 * q], 0x07050301u);
+            lo[q] = __builtin_amdgcn_perm(pr[2 * q + 1], pr[2 * q], 0x06040200u) ^ 0x80808080u;
+            sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, pr[2 * q]), ones, sum, false);
+            sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, pr[2 * q + 1]), ones, sum, false);
+        }
+        // (a position past K is the code 0 = limbs (0, -128) here; it meets zero weights)
+        ah[h] = v4i{(int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+        al[h] = v4i{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3]};
+    }
+    // the row's code sum: its two lanes hold different window positions
+    const int rowsum = sum + __shfl_xor(sum, 32, 64);
+    // one 32-channel block at a time: its three accumulators, then its outputs
+    TileCounts counts = {0, 0};
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+        v16i acc[1][1][3];
+#pragma unroll
+        for (int q = 0; q < 3; ++q)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[0][0][q][v] = 0;
+#pragma unroll
+        for (int h = 0; h < KS; ++h) {
+            const v4i wh = wlds[(h * 2 + 0) * NCB + cb][lane], wl = wlds[(h * 2 + 1) * NCB + cb][lane];
+            acc[0][0][0] = mfma_i8(wh, ah[h], acc[0][0][0]);
+            acc[0][0][1] = mfma_i8(wl, ah[h], acc[0][0][1]);
+            acc[0][0][2] = mfma_i8(wl, al[h], acc[0][0][2]);
+            acc[0][0][1] = mfma_i8(wh, al[h], acc[0][0][1]);
+        }
+        const TileCounts c = tile_epilogue<2, 1, BN, 1, 4>(
+            a, acc, [&](int) { return rowsum; }, outoff, pooloff, ctab, ntile, wave * 32, cb * 32, 0, 0);
+        counts.zeros += c.zeros;
+        counts.sats += c.sats;
+    }
+    if (a.zero_partial || a.zout) {
+        if (lane == 0) {
+            wave_counts[0][wave] = counts.zeros;
+            wave_counts[1][wave] = counts.sats;
+        }
+        __syncthreads();
+        if (a.zero_partial && tid < 2) {
+            unsigned total = 0;
+            for (int w = 0; w < THREADS / 64; ++w) total += wave_counts[tid][w];
+            a.zero_partial[tid * a.partial_stride + blockIdx.x] = total;
+        }
+        if (a.zout && wave == 0) {
+            int rows = 0;
+            for (int m = lane; m < BM; m += 64) rows += (int)wave_count(outoff[m] >= 0);
+            unsigned zeros = 0;
+            for (int w = 0; w < THREADS / 64; ++w) zeros += wave_counts[0][w];
+            if (lane == 0) a.zout[wi] = (unsigned)(rows * min(BN, a.Cout - ntile * BN)) != zeros;
+        }
+    }
+}
+
 lp_status launch_sum_partials(const unsigned *partials, int n, unsigned long long *zero_count,
                               unsigned long long *sat_count, hipStream_t st)
 {
@@ -1280,7 +1339,7 @@ lp_status launch_sum_partials(const unsigned *partials, int n, unsigned long lon
     return launch_status();
 }
 
-template <int LIMBS, int NB, bool FLAT, int MB>
+template <int LIMBS, int NB, int MB>
 static lp_status launch_mfma(const ConvArgs &a, const Plan &p, int grid, int tails, hipStream_t st)
 {
     // raise the dynamic LDS limit once per kernel instance and device
@@ -1288,12 +1347,12 @@ static lp_status launch_mfma(const ConvArgs &a, const Plan &p, int grid, int tai
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LP_EDEVICE;
     if (!attr_set[dev].load(std::memory_order_acquire)) {
-        if (hipFuncSetAttribute((const void *)conv_mfma_kernel<LIMBS, NB, FLAT, MB>,
+        if (hipFuncSetAttribute((const void *)conv_mfma_kernel<LIMBS, NB, MB>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
             return LP_EDEVICE;
         attr_set[dev].store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((conv_mfma_kernel<LIMBS, NB, FLAT, MB>), dim3(grid), dim3(MB == 2 ? 256 : 512),
+    hipLaunchKernelGGL((conv_mfma_kernel<LIMBS, NB, MB>), dim3(grid), dim3(MB == 2 ? 256 : 512),
                        p.lds_bytes, st, a);
     if (tails) // the split tail tiles are merged and written by a second, small kernel
         hipLaunchKernelGGL((conv_finish_kernel<LIMBS, NB, MB>), dim3(tails * 4 * MB), dim3(256), 0, st, a, grid);
@@ -1390,7 +1449,7 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     a.RH = p.RH; a.TW = p.TW; a.PW = p.PW; a.NPIXA = p.NPIXA;
     a.NTAB = patch_table_len(p.limbs, p.NPIXA, p.flat);
     a.PITCH = p.PITCH;
-    a.APLANE = p.flat ? BM * PS : p.PRA * p.PITCH + PSP; // the last slot of a plane parks overshoot pieces
+    a.APLANE = p.flat ? 0 : p.PRA * p.PITCH + PSP; // the last slot of a plane parks overshoot pieces
     a.tiles_c = p.tiles_c; a.tiles_n = p.tiles_n; a.CoutP = p.CoutP; a.nchunks = p.nchunks;
     a.taps = p.taps; a.ksteps = p.ksteps; a.Kflat = d->R * d->S * d->Cin;
     a.mg_tiles_n = udiv_magic(a.tiles_n); a.mg_tiles_c = udiv_magic(a.tiles_c);
@@ -1398,6 +1457,7 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     a.mg_PW = udiv_magic(a.PW); a.mg_TW = udiv_magic(a.TW);
     a.mg_taps = udiv_magic(a.taps); a.mg_S = udiv_magic(d->S);
     a.mg_Cin = udiv_magic(d->Cin); a.mg_SC = udiv_magic(d->S * d->Cin);
+    a.mg_rowlen = udiv_magic(p.PW * d->Cin);
     a.total_work = p.tiles_m * p.tiles_n;
     a.per_xcd = p.per_xcd;
     a.full_per_xcd = p.full_per_xcd;
@@ -1426,9 +1486,20 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     if (p.pool && !(a.fast && a.y16 && d->Cout % 4 == 0)) return LP_EUNSUPPORTED;
     lp_status st2;
     const int tails = a.split > 1 ? kXCDs * (p.per_xcd - p.full_per_xcd) : 0; // finishing workgroups
-    if (p.flat) st2 = launch_mfma<2, 1, true, 2>(a, p, grid, tails, hs);
-    else if (p.limbs == 2) st2 = launch_mfma<2, 1, false, 2>(a, p, grid, tails, hs);
-    else st2 = p.BN == 128 ? launch_mfma<1, 2, false, 2>(a, p, grid, tails, hs) : launch_mfma<1, 1, false, 2>(a, p, grid, tails, hs);
+    if (p.flat) {
+        // one slab: nothing to split; channel tiles of at most 32 channels need one column block
+        const bool narrow = p.tiles_n == 1 && d->Cout <= 32;
+        if (p.ksteps == 1) {
+            if (narrow) hipLaunchKernelGGL((conv_flat_kernel<1, 1>), dim3(grid), dim3(256), 0, hs, a);
+            else hipLaunchKernelGGL((conv_flat_kernel<2, 1>), dim3(grid), dim3(256), 0, hs, a);
+        } else {
+            if (narrow) hipLaunchKernelGGL((conv_flat_kernel<1, 2>), dim3(grid), dim3(256), 0, hs, a);
+            else hipLaunchKernelGGL((conv_flat_kernel<2, 2>), dim3(grid), dim3(256), 0, hs, a);
+        }
+        st2 = launch_status();
+    }
+    else if (p.limbs == 2) st2 = launch_mfma<2, 1, 2>(a, p, grid, tails, hs);
+    else st2 = p.BN == 128 ? launch_mfma<1, 2, 2>(a, p, grid, tails, hs) : launch_mfma<1, 1, 2>(a, p, grid, tails, hs);
     if (st2 != LP_OK || tails || !counting) return st2;
     return launch_sum_partials(a.zero_partial, grid, (unsigned long long *)zero_count, (unsigned long long *)sat_count, hs);
 }
@@ -1553,7 +1624,7 @@ extern "C" lp_status lp_conv_plan_info(const lp_conv_desc *d, lp_qfmt qx, lp_qfm
         o.bn = p.BN; o.tile_rows = p.RH; o.tile_cols = p.TW; o.patch_rows = p.PRA; o.patch_cols = p.PW;
         o.tiles_m = p.tiles_m; o.tiles_n = p.tiles_n; o.lds_bytes = (int32_t)p.lds_bytes;
         o.patch_pitch = p.PITCH;
-        o.patch_pixel = p.flat ? PS : PSP;
+        o.patch_pixel = p.flat ? d->Cin * 2 : PSP;
         o.workgroups = p.grid;
         o.split = p.split;
         o.items_per_die = p.per_xcd;

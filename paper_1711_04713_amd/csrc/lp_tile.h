@@ -37,7 +37,7 @@ struct ConvArgs {
     unsigned char *partials; // tail tiles' partial accumulators, part_bytes per (tile, part)
     int part_bytes;
     // floor(2^32 / d) for the divisors the kernel's index arithmetic uses (see udivmod)
-    unsigned mg_tiles_n, mg_tiles_c, mg_Ho, mg_Hp, mg_PW, mg_TW, mg_taps, mg_S, mg_Cin, mg_SC;
+    unsigned mg_tiles_n, mg_tiles_c, mg_Ho, mg_Hp, mg_PW, mg_TW, mg_taps, mg_S, mg_Cin, mg_SC, mg_rowlen;
     // Skipping of all-zero input (Sec. 3.1: the sparsity the low-precision layers produce is there
     // to be skipped).  zin: flags written by the layer that produced x, one byte per (pixel tile,
     // channel tile) of ITS output, 1 = the tile holds a nonzero code; its geometry: z_rh x z_tw
