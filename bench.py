@@ -320,9 +320,9 @@ def main():
         macs = L["macs"]
         total_macs += macs
         info = L["info"]
-        flat = info["path"] == 1 and L["desc"].Cin < 16          # whole window as one slab (first layer)
-        kname = ("conv_direct_kernel" if info["path"] != 1 else "conv_flat_kernel" if flat
-                 else "conv_mfma_kernel<%d,%d,patch>" % (info["limbs"], info["bn"] // 64))
+        kname = {lp.LP_KERNEL_DIRECT: "conv_direct_kernel", lp.LP_KERNEL_FLAT: "conv_flat_kernel",
+                 lp.LP_KERNEL_ROWS: "conv_rows_kernel",
+                 lp.LP_KERNEL_PATCH: "conv_mfma_kernel<%d,%d,patch>" % (info["limbs"], info["bn"] // 64)}[info["kernel"]]
         kern_ops[kname] = kern_ops.get(kname, 0) + 8 * macs          # 4 int8 limb MACs = 8 int8 ops per 16-bit MAC
         kern_ms[kname] = kern_ms.get(kname, 0.0) + ms
         layers.append({

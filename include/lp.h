@@ -151,10 +151,13 @@ lp_status lp_conv_pack_weights(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, co
 /*
  * lp_conv_plan_info -- how lp_conv_fwd will run this problem (host-only query, for
  * reports and tests).  path: 0 = direct one-thread-per-output kernel, 1 = int8-MFMA
- * implicit GEMM.  For path 1: limbs (1 = int8 codes, 2 = 16-bit codes as two int8
+ * implicit GEMM.  For path 1: kernel (LP_KERNEL_PATCH: 64-channel chunks of a staged patch, every
+ * tap a shifted read; LP_KERNEL_FLAT: fewer than 16 input channels, the whole window as one K <= 64
+ * slab; LP_KERNEL_ROWS: 16-bit codes with 16, 32 or 48 input channels, the reduction runs over
+ * window rows of a densely staged patch), limbs (1 = int8 codes, 2 = 16-bit codes as two int8
  * limbs), the workgroup tile (128 output pixels = tile_rows consecutive rows of the
  * N*Ho stacked output rows x tile_cols columns, times bn output channels), the staged
- * input patch (patch_rows x patch_cols pixels; a pixel takes patch_pixel bytes per limb, 64 of
+ * input patch (patch_rows x patch_cols pixels; a pixel takes patch_pixel bytes per limb -- patch kernel: 64 of
  * codes and the rest padding that spreads consecutive pixels over the LDS banks; rows are
  * patch_pitch bytes apart), tile counts and LDS bytes per workgroup; the launch: workgroups in the grid, and split = parts into which each tile of the
  * last, partly filled round of workgroup slots is cut along the reduction (1 = none; used
@@ -167,7 +170,9 @@ typedef struct {
     int32_t path, limbs, bn, tile_rows, tile_cols, patch_rows, patch_cols, tiles_m, tiles_n;
     int32_t lds_bytes, patch_pitch, patch_pixel, workgroups, split;
     int32_t items_per_die, whole_items_per_die;
+    int32_t kernel;
 } lp_plan_info;
+enum { LP_KERNEL_DIRECT = 0, LP_KERNEL_PATCH = 1, LP_KERNEL_FLAT = 2, LP_KERNEL_ROWS = 3 };
 lp_status lp_conv_plan_info(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, lp_plan_info *out_host);
 
 /*

@@ -13,6 +13,7 @@ LP_ROUND_NEAREST_AWAY = 0
 LP_ROUND_NEAREST_EVEN = 1
 LP_ROUND_STOCHASTIC = 2
 LP_RANGE_WORKSPACE_WORDS = 32
+LP_KERNEL_DIRECT, LP_KERNEL_PATCH, LP_KERNEL_FLAT, LP_KERNEL_ROWS = 0, 1, 2, 3   # lp_plan_info.kernel
 
 
 class LpError(RuntimeError):
@@ -35,7 +36,7 @@ class QFmt(ctypes.Structure):
 class PlanInfo(ctypes.Structure):
     _fields_ = [(k, ctypes.c_int32) for k in ("path", "limbs", "bn", "tile_rows", "tile_cols", "patch_rows",
                                                "patch_cols", "tiles_m", "tiles_n", "lds_bytes", "patch_pitch", "patch_pixel",
-                                               "workgroups", "split", "items_per_die", "whole_items_per_die")]
+                                               "workgroups", "split", "items_per_die", "whole_items_per_die", "kernel")]
 
     def asdict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}

@@ -44,6 +44,8 @@ struct Plan {
     int pool;    // the epilogue stores 2x2 maxima instead of the codes
     int limbs;   // 1: int8 x int8, 2: 16-bit x 16-bit
     int flat;    // whole window gathered as one K <= 64 slab (tiny Cin)
+    int rows;    // reduction over window rows (16-bit codes, 16 / 32 / 48 input channels): conv_rows_kernel
+    int KHR, KHP; // rows: K = 32 pieces per window row, and in all (padded to a multiple of 4)
     int taps, ksteps; // slabs per chunk, K=32 MFMA steps per slab
     int Ho, Wo, Hp, FR;
     int nchunks, CoutP, BN;
@@ -110,6 +112,37 @@ static int choose_pitch(int pw, int tw, int rh, int R, int S)
         }
     }
     return best_pitch;
+}
+
+// Window-row kernel: pixels are Cin bytes per limb and dense along a patch row; the 16 lanes served
+// together read the same 16-byte slot of 16 consecutive tile rows.  Smallest row pitch (bytes,
+// up to 240 of padding) with the fewest conflicts.
+static int rows_pitch(int pw, int tw, int rh, int cin)
+{
+    int best = 1 << 30, best_pitch = pw * cin;
+    const int rows = rh * tw;
+    for (int pitch = pw * cin; pitch < pw * cin + 256; pitch += 16) {
+        int cost = 0;
+        for (int m0 = 0; m0 < rows; m0 += 16) {
+            int seen[16] = {0};
+            int worst = 0;
+            for (int m = m0; m < std::min(m0 + 16, rows); ++m)
+                worst = std::max(worst, ++seen[(((m / tw) * pitch + (m % tw) * cin) >> 4) & 15]);
+            cost += worst - 1;
+        }
+        if (cost < best) {
+            best = cost;
+            best_pitch = pitch;
+        }
+    }
+    return best_pitch;
+}
+
+// LDS of the window-row kernel: unit sums, four row tables, channel constants, wave counts, two planes
+static size_t rows_lds_bytes(int pra, int pw, int cin, int pitch)
+{
+    const size_t nu = (size_t)pra * pw * (cin / 16);
+    return (round_up(nu, 4) + 4 * BM + 3 * 64 + 8) * 4 + 2 * ((size_t)pra * pitch + 32);
 }
 
 // 16-byte pieces a thread requests per batch while staging a patch (two batches are in flight).
@@ -267,12 +300,23 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
             }
         if (best < 1e300) p.path = PATH_MFMA;
         if (d->pool && (best == 1e300 || best > 1.03 * best_free)) return LP_EUNSUPPORTED;
+        if (best < 1e300 && chunked && x16 && d->Cin % 16 == 0 && d->Cin < CK && in_elems < (1LL << 31) - 64) {
+            const int khr = (d->S * d->Cin + 31) / 32;
+            const int pitch = rows_pitch(p.PW, p.TW, p.RH, d->Cin);
+            if (d->R * khr <= 256 && rows_lds_bytes(p.PRA, p.PW, d->Cin, pitch) <= 40 * 1024) {
+                p.rows = 1;
+                p.KHR = khr;
+                p.KHP = (int)round_up((size_t)d->R * khr, 4);
+                p.PITCH = pitch;
+            }
+        }
     }
     if (d->pool && (p.path != PATH_MFMA || p.Ho % 2 || p.Wo % 2)) return LP_EUNSUPPORTED;
     p.pool = d->pool;
     if (p.path == PATH_MFMA) {
-        p.nchunks = p.flat ? 1 : (d->Cin + CK - 1) / CK;
-        p.taps = p.flat ? 1 : d->R * d->S;
+        const bool one_slab = p.flat || p.rows; // nothing to cut along the reduction
+        p.nchunks = one_slab ? 1 : (d->Cin + CK - 1) / CK;
+        p.taps = one_slab ? 1 : d->R * d->S;
         p.ksteps = p.flat ? (int)((K + 31) / 32) : 2;
         p.CoutP = (int)round_up(d->Cout, 64);
         p.tiles_m = p.tiles_r * p.tiles_c;
@@ -283,14 +327,16 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
         // registers for the prefetch pipeline, so it always runs 64-wide
         if (p.limbs == 2) p.BN = 64;
         p.tiles_n = p.CoutP / p.BN;
-        p.PITCH = p.flat ? 0 : 16 * choose_pitch(p.PW, p.TW, p.RH, d->R, d->S);
-        p.lds_bytes = mfma_lds_bytes(p.limbs, p.PRA, p.PW, p.PITCH, p.BN, p.flat);
+        if (!p.rows) p.PITCH = p.flat ? 0 : 16 * choose_pitch(p.PW, p.TW, p.RH, d->R, d->S);
+        p.lds_bytes = p.rows ? rows_lds_bytes(p.PRA, p.PW, d->Cin, p.PITCH)
+                             : mfma_lds_bytes(p.limbs, p.PRA, p.PW, p.PITCH, p.BN, p.flat);
         {
             // workgroup slots per die: what registers and LDS allow
             const int total = p.tiles_m * p.tiles_n, nslabs = p.nchunks * p.taps;
             // (two-limb kernel: three waves per SIMD by registers; one-limb kernels: four)
-            const int wg_per_cu =
-                (int)std::max<size_t>(1, std::min<size_t>(p.limbs == 2 ? 3 : 4, (160 * 1024) / p.lds_bytes));
+            // (window-row kernel: four)
+            const int by_regs = p.rows ? 4 : p.limbs == 2 ? 3 : 4;
+            const int wg_per_cu = (int)std::max<size_t>(1, std::min<size_t>(by_regs, (160 * 1024) / p.lds_bytes));
             const int slots = wg_per_cu * (kCUs / kXCDs);
             p.per_xcd = (total + kXCDs - 1) / kXCDs;
             p.full_per_xcd = p.per_xcd / slots * slots;
@@ -301,11 +347,12 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
             if (p.split == 1) p.full_per_xcd = p.per_xcd;
             p.grid = kXCDs * (p.full_per_xcd + (p.per_xcd - p.full_per_xcd) * p.split);
         }
-        p.corr_offset = round_up((size_t)p.taps * p.nchunks * p.limbs * p.CoutP * CK, 256);
+        p.corr_offset = p.rows ? round_up((size_t)p.KHP * 2 * p.CoutP * 32, 256)
+                               : round_up((size_t)p.taps * p.nchunks * p.limbs * p.CoutP * CK, 256);
         // the kernel addresses the slabs with 32-bit byte offsets
         if (p.corr_offset >= (1ull << 31)) return LP_EUNSUPPORTED;
         p.packed_bytes = p.corr_offset + (size_t)p.CoutP * sizeof(int64_t);
-        if (p.limbs == 2 && !p.flat) {
+        if (p.limbs == 2 && !p.flat && !p.rows) {
             p.wsum_offset = p.packed_bytes;
             p.packed_bytes += (size_t)p.nchunks * p.CoutP * sizeof(int);
         }
@@ -371,6 +418,28 @@ __global__ void pack_weights_flat_kernel(const WT *__restrict__ w, unsigned char
     }
     out[slab_byte(co, kk, CoutP)] = (unsigned char)hi;
     out[(size_t)CoutP * CK + slab_byte(co, kk, CoutP)] = (unsigned char)lo;
+}
+
+// Window-row layout: [piece][limb][CoutP][32]; piece h = (window row h / KHR, 32 positions from
+// 32 * (h % KHR) of that row's S * Cin weights); positions past the row, pad pieces and padded
+// channels hold the bytes (0, 0).
+template <typename WT>
+__global__ void pack_weights_rows_kernel(const WT *__restrict__ w, unsigned char *__restrict__ out, int Cout, int R,
+                                         int SC, int KHR, int KHP, int CoutP)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= KHP * CoutP * 32) return;
+    const int kk = i & 31, co = (i >> 5) % CoutP, h = (i >> 5) / CoutP;
+    const int r = h / KHR, pos = (h % KHR) * 32 + kk;
+    int hi = 0, lo = 0;
+    if (co < Cout && r < R && pos < SC) {
+        const int code = (int)w[((size_t)co * R + r) * SC + pos];
+        hi = code >> 8;
+        lo = (code & 255) - 128;
+    }
+    const size_t at = ((size_t)h * 2 * CoutP + co) * 32 + kk;
+    out[at] = (unsigned char)hi;
+    out[at + (size_t)CoutP * 32] = (unsigned char)lo;
 }
 
 template <typename WT>
@@ -1331,6 +1400,198 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     }
 }
 
+// Layers with 16, 32 or 48 input channels (16-bit codes): a 64-channel chunk would be mostly
+// padding, so the reduction runs over window rows instead.  The patch is staged densely (Cin bytes
+// per pixel and limb), which makes the S * Cin codes under one kernel row of a window consecutive:
+// a window row is KHR = ceil(S * Cin / 32) K = 32 pieces at consecutive addresses.  The positions
+// past S * Cin in a row's last piece read the neighbouring pixels and meet weight bytes (0, 0),
+// which add nothing to any limb product.  A wave owns 32 tile rows and takes the tile's 32-channel
+// blocks one after the other; the weights
+// ([piece][limb][CoutP][32], pieces padded with zeros to a multiple of four) go from L2 straight
+// into one of four rotating operand sets, three pieces ahead of their use.
+// The sum of the codes under a window (offset correction) is gathered from per-unit sums (a unit
+// = 16 consecutive codes of a pixel) left by the staging.
+// NCB: 32-channel blocks a workgroup takes (1 for layers with at most 32 output channels).
+template <int NCB>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void conv_rows_kernel(const ConvArgs a)
+{
+    constexpr int THREADS = 256, BN = 64, NSETS = 4;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int NU = a.NPIXA * a.CU; // units of the patch
+    int *usum = (int *)smem;                    // unit -> sum of its 16 codes
+    int *outoff = usum + ((NU + 3) & ~3);       // tile row -> output pixel index, -1 if not an output
+    int *pooloff = outoff + BM;                 // tile row -> pooled output pixel (top-left rows of 2x2 windows), else -1
+    int *abase = pooloff + BM;                  // tile row -> byte offset of its window's first code in a plane
+    int *ubase = abase + BM;                    // tile row -> unit of its window's first code
+    int *ctab = ubase + BM;                     // channel constants
+    unsigned *wave_counts = (unsigned *)(ctab + 3 * BN); // [zeros, clipped][wave]
+    unsigned char *Asm = (unsigned char *)(wave_counts + 2 * (THREADS / 64)); // high plane, then low plane
+    const int APL = a.APLANE;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, kg = lane >> 5;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int wi = xcd * a.per_xcd + slot;
+    if (slot >= a.per_xcd || wi >= a.total_work) {
+        if (a.zero_partial && tid == 0) a.zero_partial[blockIdx.x] = a.zero_partial[a.partial_stride + blockIdx.x] = 0;
+        return;
+    }
+    int mtile, ntile, tile_r, tile_c, img0, yo0;
+    udivmod(wi, a.tiles_n, a.mg_tiles_n, mtile, ntile);
+    udivmod(mtile, a.tiles_c, a.mg_tiles_c, tile_r, tile_c);
+    const int fr0 = tile_r * a.RH, x0 = tile_c * a.TW;
+    udivmod(fr0, a.Ho, a.mg_Ho, img0, yo0);
+    const int vr0 = img0 * a.Hp + yo0;
+
+    // weight operands: a lane's 16 bytes of (piece, limb, column block) never move inside a piece;
+    // the piece is a scalar offset.  Requests past the last piece read it again and are not used.
+    const int piece_bytes = 2 * a.CoutP * 32;
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<unsigned char *>(a.wp), 0, a.KHP * piece_bytes, 0x00020000);
+    int blane = (ntile * BN + l32) * 32 + kg * 16;
+    v4i bh[NSETS], bl[NSETS];
+    auto bload = [&](int h, v4i &hh, v4i &ll) __attribute__((always_inline)) {
+        const int so = min(h, a.KHP - 1) * piece_bytes;
+        const auto vh = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, blane, so, 0);
+        const auto vl = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, blane, so + a.CoutP * 32, 0);
+        hh = (v4i){(int)vh[0], (int)vh[1], (int)vh[2], (int)vh[3]};
+        ll = (v4i){(int)vl[0], (int)vl[1], (int)vl[2], (int)vl[3]};
+    };
+#pragma unroll
+    for (int h = 0; h < NSETS - 1; ++h) bload(h, bh[h], bl[h]);
+
+    // patch: unit i = (patch row, 16 codes of it) -> limb bytes into the two planes, code sum into usum;
+    // pixels outside the image read as zeros (an offset past the descriptor)
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void *>(a.x), 0, (int)((unsigned)(a.N * a.H * a.W) * (unsigned)a.Cin * 2u), 0x00020000);
+    constexpr int UF = 2; // units in flight per thread
+    for (int i0 = tid; i0 < NU; i0 += UF * THREADS) {
+        v4i c[UF][2];
+        int dst[UF];
+#pragma unroll
+        for (int u = 0; u < UF; ++u) {
+            const int i = min(i0 + u * THREADS, NU - 1);
+            int pr, uu, pc, q, n, iy;
+            udivmod(i, a.UPR, a.mg_UPR, pr, uu);
+            udivmod(uu, a.CU, a.mg_CU, pc, q);
+            udivmod(vr0 + pr, a.Hp, a.mg_Hp, n, iy);
+            iy -= a.pad;
+            const int ix = x0 - a.pad + pc;
+            const bool in = n < a.N && iy >= 0 && iy < a.H && ix >= 0 && ix < a.W;
+            const unsigned off = in ? (unsigned)(((n * a.H + iy) * a.W + ix) * a.Cin + q * 16) * 2u : 0xffffffe0u;
+            const auto v0 = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)off, 0, 0);
+            const auto v1 = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, (int)(off + 16u), 0, 0);
+            c[u][0] = (v4i){(int)v0[0], (int)v0[1], (int)v0[2], (int)v0[3]};
+            c[u][1] = (v4i){(int)v1[0], (int)v1[1], (int)v1[2], (int)v1[3]};
+            dst[u] = pr * a.PITCH + uu * 16;
+        }
+#pragma unroll
+        for (int u = 0; u < UF; ++u) {
+            if (i0 + u * THREADS >= NU) continue;
+            const unsigned pr2[8] = {(unsigned)c[u][0].x, (unsigned)c[u][0].y, (unsigned)c[u][0].z, (unsigned)c[u][0].w,
+                                     (unsigned)c[u][1].x, (unsigned)c[u][1].y, (unsigned)c[u][1].z, (unsigned)c[u][1].w};
+            unsigned hi[4], lo[4];
+            int sum = 0;
+            const v2s ones = {1, 1};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                hi[q] = __builtin_amdgcn_perm(pr2[2 * q + 1], pr2[2 * q], 0x07050301u);
+                lo[q] = __builtin_amdgcn_perm(pr2[2 * q + 1], pr2[2 * q], 0x06040200u) ^ 0x80808080u;
+                sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, pr2[2 * q]), ones, sum, false);
+                sum = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, pr2[2 * q + 1]), ones, sum, false);
+            }
+            *(v4i *)(Asm + dst[u]) = v4i{(int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+            *(v4i *)(Asm + APL + dst[u]) = v4i{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3]};
+            usum[i0 + u * THREADS] = sum;
+        }
+    }
+    for (int m = tid; m < BM; m += THREADS) {
+        int j, t, img, yo;
+        udivmod(m, a.TW, a.mg_TW, j, t);
+        const int fr = fr0 + j, xo = x0 + t;
+        const bool ok = j < a.RH && fr < a.FR && xo < a.Wo;
+        udivmod(fr, a.Ho, a.mg_Ho, img, yo);
+        const int prow = img * a.Hp + yo - vr0;
+        outoff[m] = ok ? fr * a.Wo + xo : -1;
+        abase[m] = ok ? prow * a.PITCH + t * a.Cin : 0;
+        ubase[m] = ok ? prow * a.UPR + t * a.CU : 0;
+        pooloff[m] = (a.pool && ok && !(j & 1) && !(t & 1)) ? (img * (a.Ho >> 1) + (yo >> 1)) * (a.Wo >> 1) + (xo >> 1) : -1;
+    }
+    build_colterms<BN, THREADS>(a, ntile, ctab, 2);
+    __syncthreads();
+
+    // the sum of the codes under the row's window: its two lanes take alternate window rows
+    int sum = 0;
+    {
+        const int ub = ubase[wave * 32 + l32];
+        for (int r = kg; r < a.R; r += 2)
+            for (int u = 0; u < a.SU; ++u) sum += usum[ub + r * a.UPR + u];
+    }
+    const int rowsum = sum + __shfl_xor(sum, 32, 64);
+    // the lane's 16-byte slot of its row's first window code, as an LDS address
+    typedef __attribute__((address_space(3))) const v4i lds_cv4i;
+    const int a_l = (int)(unsigned long)(__attribute__((address_space(3))) unsigned char *)Asm + abase[wave * 32 + l32] + kg * 16;
+    using std::integral_constant;
+    TileCounts counts = {0, 0};
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+        if (cb) { // (the first block's first pieces were requested at the top)
+            blane += 32 * 32;
+#pragma unroll
+            for (int h = 0; h < NSETS - 1; ++h) bload(h, bh[h], bl[h]);
+        }
+        v16i acc[1][1][3];
+#pragma unroll
+        for (int q = 0; q < 3; ++q)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[0][0][q][v] = 0;
+        int kr = 0, kj = 0; // window row and piece within it of the next piece (pad pieces stay on the last row)
+        auto step = [&](int h, auto P) __attribute__((always_inline)) {
+            constexpr int use = decltype(P)::value, fill = (use + NSETS - 1) % NSETS;
+            bload(h + NSETS - 1, bh[fill], bl[fill]);
+            const int at = a_l + min(kr, a.R - 1) * a.PITCH + kj * 32;
+            if (++kj == a.KHR) {
+                kj = 0;
+                ++kr;
+            }
+            const v4i ah = *(lds_cv4i *)(unsigned)at;
+            const v4i al = *(lds_cv4i *)(unsigned)(at + APL);
+            acc[0][0][0] = mfma_i8(bh[use], ah, acc[0][0][0]);
+            acc[0][0][1] = mfma_i8(bl[use], ah, acc[0][0][1]);
+            acc[0][0][2] = mfma_i8(bl[use], al, acc[0][0][2]);
+            acc[0][0][1] = mfma_i8(bh[use], al, acc[0][0][1]);
+        };
+        for (int h = 0; h < a.KHP; h += NSETS) {
+            step(h, integral_constant<int, 0>{});
+            step(h + 1, integral_constant<int, 1>{});
+            step(h + 2, integral_constant<int, 2>{});
+            step(h + 3, integral_constant<int, 3>{});
+        }
+        const TileCounts c = tile_epilogue<2, 1, BN, 1, 4>(
+            a, acc, [&](int) { return rowsum; }, outoff, pooloff, ctab, ntile, wave * 32, cb * 32, 0, 0);
+        counts.zeros += c.zeros;
+        counts.sats += c.sats;
+    }
+    if (a.zero_partial || a.zout) {
+        if (lane == 0) {
+            wave_counts[wave] = counts.zeros;
+            wave_counts[THREADS / 64 + wave] = counts.sats;
+        }
+        __syncthreads();
+        if (a.zero_partial && tid < 2) {
+            unsigned total = 0;
+            for (int w = 0; w < THREADS / 64; ++w) total += wave_counts[tid * (THREADS / 64) + w];
+            a.zero_partial[tid * a.partial_stride + blockIdx.x] = total;
+        }
+        if (a.zout && wave == 0) {
+            int rows = 0;
+            for (int m = lane; m < BM; m += 64) rows += (int)wave_count(outoff[m] >= 0);
+            unsigned zeros = 0;
+            for (int w = 0; w < THREADS / 64; ++w) zeros += wave_counts[w];
+            if (lane == 0) a.zout[wi] = (unsigned)(rows * min(BN, a.Cout - ntile * BN)) != zeros;
+        }
+    }
+}
+
+
 lp_status launch_sum_partials(const unsigned *partials, int n, unsigned long long *zero_count,
                               unsigned long long *sat_count, hipStream_t st)
 {
@@ -1449,7 +1710,10 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     a.RH = p.RH; a.TW = p.TW; a.PW = p.PW; a.NPIXA = p.NPIXA;
     a.NTAB = patch_table_len(p.limbs, p.NPIXA, p.flat);
     a.PITCH = p.PITCH;
-    a.APLANE = p.flat ? 0 : p.PRA * p.PITCH + PSP; // the last slot of a plane parks overshoot pieces
+    a.APLANE = p.flat ? 0 : p.rows ? p.PRA * p.PITCH + 32 : p.PRA * p.PITCH + PSP; // the last slot of a plane parks overshoot pieces
+    a.KHR = p.KHR; a.KHP = p.KHP;
+    a.CU = d->Cin / 16; a.UPR = p.PW * a.CU; a.SU = d->S * a.CU;
+    a.mg_UPR = udiv_magic(a.UPR); a.mg_CU = udiv_magic(a.CU);
     a.tiles_c = p.tiles_c; a.tiles_n = p.tiles_n; a.CoutP = p.CoutP; a.nchunks = p.nchunks;
     a.taps = p.taps; a.ksteps = p.ksteps; a.Kflat = d->R * d->S * d->Cin;
     a.mg_tiles_n = udiv_magic(a.tiles_n); a.mg_tiles_c = udiv_magic(a.tiles_c);
@@ -1486,7 +1750,12 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     if (p.pool && !(a.fast && a.y16 && d->Cout % 4 == 0)) return LP_EUNSUPPORTED;
     lp_status st2;
     const int tails = a.split > 1 ? kXCDs * (p.per_xcd - p.full_per_xcd) : 0; // finishing workgroups
-    if (p.flat) {
+    if (p.rows) {
+        if (p.tiles_n == 1 && d->Cout <= 32) hipLaunchKernelGGL(conv_rows_kernel<1>, dim3(grid), dim3(256), p.lds_bytes, hs, a);
+        else hipLaunchKernelGGL(conv_rows_kernel<2>, dim3(grid), dim3(256), p.lds_bytes, hs, a);
+        st2 = launch_status();
+    }
+    else if (p.flat) {
         // one slab: nothing to split; channel tiles of at most 32 channels need one column block
         const bool narrow = p.tiles_n == 1 && d->Cout <= 32;
         if (p.ksteps == 1) {
@@ -1530,6 +1799,21 @@ static lp_status pack_weights(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt qw, con
     unsigned char *out = (unsigned char *)packed;
     int64_t *corr = (int64_t *)(out + p.corr_offset);
     const int cgrid = p.CoutP; // one wave per output channel
+    if (p.rows) {
+        const int K = RS * d->Cin, rgrid = (p.KHP * p.CoutP * 32 + 255) / 256;
+        if (w16) {
+            hipLaunchKernelGGL(pack_weights_rows_kernel<int16_t>, dim3(rgrid), dim3(256), 0, hs, (const int16_t *)w, out,
+                               d->Cout, d->R, d->S * d->Cin, p.KHR, p.KHP, p.CoutP);
+            hipLaunchKernelGGL(weight_corr_kernel<int16_t>, dim3(cgrid), dim3(64), 0, hs,
+                               (const int16_t *)w, corr, d->Cout, p.CoutP, K, 2);
+        } else {
+            hipLaunchKernelGGL(pack_weights_rows_kernel<int8_t>, dim3(rgrid), dim3(256), 0, hs, (const int8_t *)w, out,
+                               d->Cout, d->R, d->S * d->Cin, p.KHR, p.KHP, p.CoutP);
+            hipLaunchKernelGGL(weight_corr_kernel<int8_t>, dim3(cgrid), dim3(64), 0, hs,
+                               (const int8_t *)w, corr, d->Cout, p.CoutP, K, 2);
+        }
+        return launch_status();
+    }
     if (p.flat) {
         const int K = RS * d->Cin, fgrid = (p.CoutP * CK + 255) / 256;
         if (w16) {
@@ -1624,7 +1908,8 @@ extern "C" lp_status lp_conv_plan_info(const lp_conv_desc *d, lp_qfmt qx, lp_qfm
         o.bn = p.BN; o.tile_rows = p.RH; o.tile_cols = p.TW; o.patch_rows = p.PRA; o.patch_cols = p.PW;
         o.tiles_m = p.tiles_m; o.tiles_n = p.tiles_n; o.lds_bytes = (int32_t)p.lds_bytes;
         o.patch_pitch = p.PITCH;
-        o.patch_pixel = p.flat ? d->Cin * 2 : PSP;
+        o.patch_pixel = p.flat ? d->Cin * 2 : p.rows ? d->Cin : PSP;
+        o.kernel = p.rows ? LP_KERNEL_ROWS : p.flat ? LP_KERNEL_FLAT : LP_KERNEL_PATCH;
         o.workgroups = p.grid;
         o.split = p.split;
         o.items_per_die = p.per_xcd;

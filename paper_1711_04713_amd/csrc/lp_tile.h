@@ -33,11 +33,14 @@ struct ConvArgs {
     int Ho, Wo, Hp, FR;
     int RH, TW, PW, NPIXA, NTAB, APLANE, PITCH;
     int tiles_c, tiles_n, CoutP, nchunks, taps, ksteps, Kflat;
+    // window-row kernel: K = 32 pieces per window row / in all (a multiple of 4), 16-code units per
+    // patch row / per window row / per pixel
+    int KHR, KHP, UPR, SU, CU;
     int total_work, per_xcd, full_per_xcd, split;
     unsigned char *partials; // tail tiles' partial accumulators, part_bytes per (tile, part)
     int part_bytes;
     // floor(2^32 / d) for the divisors the kernel's index arithmetic uses (see udivmod)
-    unsigned mg_tiles_n, mg_tiles_c, mg_Ho, mg_Hp, mg_PW, mg_TW, mg_taps, mg_S, mg_Cin, mg_SC, mg_rowlen;
+    unsigned mg_tiles_n, mg_tiles_c, mg_Ho, mg_Hp, mg_PW, mg_TW, mg_taps, mg_S, mg_Cin, mg_SC, mg_rowlen, mg_UPR, mg_CU;
     // Skipping of all-zero input (Sec. 3.1: the sparsity the low-precision layers produce is there
     // to be skipped).  zin: flags written by the layer that produced x, one byte per (pixel tile,
     // channel tile) of ITS output, 1 = the tile holds a nonzero code; its geometry: z_rh x z_tw

@@ -183,6 +183,35 @@ def test_conv_flat_window(oracle, N, Cin, H, W, Cout, R, S, pad, qy):
     _check(oracle, x, w, QX, QW, qy, relu=False, pad=pad, expect_path=1)
 
 
+@pytest.mark.parametrize("N,Cin,H,W,Cout,R,S,pad", [
+    (2, 16, 30, 30, 16, 7, 7, 1),      # Table 1, layer 2: 112 codes per window row, 4 pieces of which the last is half padding
+    (1, 16, 20, 23, 32, 7, 7, 0),      # layer 3
+    (3, 32, 12, 12, 64, 5, 5, 1),      # layer 4: both 32-channel blocks, 5 whole pieces per row
+    (2, 48, 9, 11, 40, 3, 3, 1),       # 144 codes per row: 4.5 pieces; ragged second block
+    (1, 16, 17, 9, 100, 1, 1, 0),      # 1x1: half a piece per row; two channel tiles
+    (4, 32, 5, 5, 8, 3, 5, 2),         # non-square window, tiles straddling images, 8 channels
+    (2, 16, 6, 40, 24, 5, 3, 2),       # three-piece rows, wide rows
+    (1, 16, 12, 12, 16, 11, 11, 5),    # 44 pieces
+])
+def test_conv_window_row_kernel(oracle, N, Cin, H, W, Cout, R, S, pad):
+    """16-bit codes with 16, 32 or 48 input channels: the reduction runs over window rows of a
+    densely staged patch (positions past a row's S * Cin codes meet zero weight bytes)."""
+    rng = np.random.default_rng(N * 17 + Cin + H * 3 + R)
+    x, w = _codes(rng, (N, Cin, H, W), zero_frac=0.3), _codes(rng, (Cout, Cin, R, S))
+    info = lp.lp_conv_plan_info(lp.ConvDesc(N, H, W, Cin, Cout, R, S, 1, pad), QX, QW)
+    assert info["kernel"] == lp.LP_KERNEL_ROWS
+    _check(oracle, x, w, QX, QW, (16, 12, 4), pad=pad, expect_path=1, modes=("away", "even"))
+    _check(oracle, x, w, QX, QW, (8, 7, 1), relu=False, pad=pad, expect_path=1)
+    # 8-bit weight codes with 16-bit inputs, bias, the 32-bit epilogue
+    xs = np.maximum(_codes(rng, (N, Cin, H, W), full_range=False), 0)
+    w8 = _codes(rng, (Cout, Cin, R, S), n=8)
+    b = _codes(rng, (Cout,), n=16, full_range=False)
+    got = conv(xs, QX, w8, (8, 1, 7), qy=(16, 6, 10), pad=pad, bias=b, qb=(16, 4, 12), want_acc=False)
+    acc = oracle.conv(xs, w8, bias=b, f_acc=19, fb=12, pad=pad, threads=8)
+    y, z, sat = oracle.act(acc, 19, 16, 6, 10, True, oracle.ROUND_AWAY, with_sat=True)
+    assert np.array_equal(got["y"], y) and (got["zeros"], got["sats"]) == (z, sat)
+
+
 @pytest.mark.parametrize("fo", [15, 14, 11, 10, 3, 0])
 def test_conv_requantization_shift_sweep(oracle, fo):
     """Output formats that put the right shift f_acc - fo at 12, 13, 16, 17, 24 and 27 bits, with

@@ -111,7 +111,21 @@ def test_tile_geometry_addresses_the_right_pixels(N, H, W, Cin, Cout, R, S, pad)
     assert info["lds_bytes"] <= 80 * 1024
     NPIXA = PRA * PW
     pitch, pix = info["patch_pitch"], info["patch_pixel"]
-    if Cin >= 16:
+    if info["kernel"] == lp.LP_KERNEL_ROWS:
+        # dense pixels of Cin bytes per limb; 16 lanes = 16 consecutive tile rows read the same
+        # 16-byte slot of their window's first pixel (every piece of every window row shifts them
+        # all by the same amount)
+        assert Cin in (16, 32, 48) and pix == Cin and pitch % 16 == 0 and PW * pix <= pitch < PW * pix + 256
+        assert info["lds_bytes"] <= 40 * 1024
+        worst = 0
+        for m0 in range(0, RH * TW, 16):
+            groups = {}
+            for m in range(m0, min(m0 + 16, RH * TW)):
+                g = (((m // TW) * pitch + (m % TW) * pix) // 16) % 16
+                groups[g] = groups.get(g, 0) + 1
+            worst = max(worst, max(groups.values()))
+        assert worst <= (1 if Cin == 16 and TW in (1, 2, 4, 8, 16) else 3)
+    elif Cin >= 16:
         assert pix == 80 and pitch % 16 == 0 and PW * pix <= pitch < PW * pix + 256
         # fragment reads: 16 lanes = 16 consecutive tile rows m read the same 16-byte slot q of
         # their pixel (patch_row, patch_col) at tap (r, s), stored at patch_row * pitch +
@@ -171,7 +185,7 @@ def test_launch_geometry_covers_every_tile_and_slab_once(N, H, W, Cin, Cout, R, 
     info = lp.lp_conv_plan_info(lp.ConvDesc(N, H, W, Cin, Cout, R, S, 1, pad), Q16, W16)
     total = info["tiles_m"] * info["tiles_n"]
     split, grid = info["split"], info["workgroups"]
-    flat = Cin < 16
+    flat = info["kernel"] != lp.LP_KERNEL_PATCH        # one slab: the flat-window and window-row kernels
     nslabs = 1 if flat else -(-Cin // 64) * R * S
     per_xcd = -(-total // 8)
     assert grid % 8 == 0 and 1 <= split <= max(1, min(nslabs, 8))
