@@ -36,6 +36,7 @@ constexpr int PSP = 80;      // LDS bytes per staged patch pixel and limb: 64 of
 constexpr int kConvThreads = 256;
 
 constexpr int kMaxDevices = 64;
+constexpr int kDirectCountGrid = 2048; // largest grid whose workgroups add to the zero / saturation counters directly
 
 enum { PATH_DIRECT = 0, PATH_MFMA = 1 };
 
@@ -1040,17 +1041,18 @@ __global__ __launch_bounds__(MB == 2 ? 256 : 512)
 
     const TileCounts counts = tile_epilogue<LIMBS, NB, BN, MB, 4>(a, acc, row_sum, outoff, pooloff, ctab, ntile, wm * WROWS,
                                                                   wn * (NB * 32), 0, 0);
-    // one pair of counts per workgroup, no atomics: thousands of same-address atomics would serialise
-    if (a.zero_partial || a.zout) {
+    // one pair of counts per workgroup; on large grids they go to per-workgroup slots, not to the
+    // counters: thousands of same-address atomics would serialise
+    if (a.zero_partial || a.zout || a.direct_counts) {
         if (lane == 0) { // tab[] was last read while staging
             tab[wave] = (int)counts.zeros;
             tab[THREADS / 64 + wave] = (int)counts.sats;
         }
         __syncthreads();
-        if (a.zero_partial && tid < 2) {
+        if (tid < 2) {
             unsigned total = 0;
             for (int w = 0; w < THREADS / 64; ++w) total += (unsigned)tab[tid * (THREADS / 64) + w];
-            a.zero_partial[tid * a.partial_stride + blockIdx.x] = total;
+            publish_count(a, tid, total);
         }
         if (a.zout && wave == 0) {
             // the tile's flag: it holds a code that is not zero (codes that exist: rows x channels)
@@ -1379,16 +1381,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         counts.zeros += c.zeros;
         counts.sats += c.sats;
     }
-    if (a.zero_partial || a.zout) {
+    if (a.zero_partial || a.zout || a.direct_counts) {
         if (lane == 0) {
             wave_counts[0][wave] = counts.zeros;
             wave_counts[1][wave] = counts.sats;
         }
         __syncthreads();
-        if (a.zero_partial && tid < 2) {
+        if (tid < 2) {
             unsigned total = 0;
             for (int w = 0; w < THREADS / 64; ++w) total += wave_counts[tid][w];
-            a.zero_partial[tid * a.partial_stride + blockIdx.x] = total;
+            publish_count(a, tid, total);
         }
         if (a.zout && wave == 0) {
             int rows = 0;
@@ -1570,16 +1572,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         counts.zeros += c.zeros;
         counts.sats += c.sats;
     }
-    if (a.zero_partial || a.zout) {
+    if (a.zero_partial || a.zout || a.direct_counts) {
         if (lane == 0) {
             wave_counts[wave] = counts.zeros;
             wave_counts[THREADS / 64 + wave] = counts.sats;
         }
         __syncthreads();
-        if (a.zero_partial && tid < 2) {
+        if (tid < 2) {
             unsigned total = 0;
             for (int w = 0; w < THREADS / 64; ++w) total += wave_counts[tid * (THREADS / 64) + w];
-            a.zero_partial[tid * a.partial_stride + blockIdx.x] = total;
+            publish_count(a, tid, total);
         }
         if (a.zout && wave == 0) {
             int rows = 0;
@@ -1750,6 +1752,13 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     if (p.pool && !(a.fast && a.y16 && d->Cout % 4 == 0)) return LP_EUNSUPPORTED;
     lp_status st2;
     const int tails = a.split > 1 ? kXCDs * (p.per_xcd - p.full_per_xcd) : 0; // finishing workgroups
+    // A small grid adds its counts to the counters itself: two atomics per workgroup cost less than
+    // the launch of the kernel that sums the per-workgroup slots.
+    const bool direct = counting && !tails && grid <= kDirectCountGrid;
+    if (direct) {
+        a.zero_partial = nullptr;
+        a.direct_counts = ((zero_count || sat_count) && y) ? 1 : 0;
+    }
     if (p.rows) {
         if (p.tiles_n == 1 && d->Cout <= 32) hipLaunchKernelGGL(conv_rows_kernel<1>, dim3(grid), dim3(256), p.lds_bytes, hs, a);
         else hipLaunchKernelGGL(conv_rows_kernel<2>, dim3(grid), dim3(256), p.lds_bytes, hs, a);
@@ -1769,7 +1778,7 @@ static lp_status conv_forward(const lp_conv_desc *d, const void *x, lp_qfmt qx, 
     }
     else if (p.limbs == 2) st2 = launch_mfma<2, 1, 2>(a, p, grid, tails, hs);
     else st2 = p.BN == 128 ? launch_mfma<1, 2, 2>(a, p, grid, tails, hs) : launch_mfma<1, 1, 2>(a, p, grid, tails, hs);
-    if (st2 != LP_OK || tails || !counting) return st2;
+    if (st2 != LP_OK || tails || !counting || direct) return st2;
     return launch_sum_partials(a.zero_partial, grid, (unsigned long long *)zero_count, (unsigned long long *)sat_count, hs);
 }
 

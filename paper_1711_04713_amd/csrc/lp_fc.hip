@@ -425,7 +425,7 @@ __global__ __launch_bounds__(kFcThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     __syncthreads();
     const TileCounts counts = tile_epilogue<LIMBS, 2, FN, 1, 4>(
         f.c, acc, [&](int m) { return rowsum[m]; }, outoff, outoff, ctab, nt, wave * 32, 0, 0, 0);
-    if (f.c.zero_partial) {
+    if (f.c.zero_partial || f.c.direct_counts) {
         if (lane == 0) {
             wave_counts[0][wave] = counts.zeros;
             wave_counts[1][wave] = counts.sats;
@@ -434,7 +434,7 @@ __global__ __launch_bounds__(kFcThreads) __attribute__((amdgpu_waves_per_eu(2, 2
         if (tid < 2) {
             unsigned total = 0;
             for (int w = 0; w < WAVES; ++w) total += wave_counts[tid][w];
-            f.c.zero_partial[tid * f.c.partial_stride + blockIdx.x] = total;
+            publish_count(f.c, tid, total);
         }
     }
 }
@@ -587,7 +587,10 @@ static lp_status fc_forward(int M, int K, int Nout, const void *x, lp_qfmt qx, c
     a.Ho = 1; a.Wo = 1; a.Hp = 1; a.FR = M;
     const bool counting = (zero_count || sat_count) && y;
     unsigned char *ws = (unsigned char *)workspace;
-    if (counting && p.ksplit == 1) a.zero_partial = (unsigned *)ws;
+    // (a small grid adds its counts to the counters itself, a large one leaves per-workgroup slots)
+    const bool direct = counting && p.ksplit == 1 && p.grid <= 2048;
+    a.direct_counts = direct ? 1 : 0;
+    if (counting && p.ksplit == 1 && !direct) a.zero_partial = (unsigned *)ws;
     a.partial_stride = p.grid;
     a.partials = ws + p.ws_counts + p.ws_xs + p.ws_xsum;
     a.part_bytes = (int)p.part_bytes;
@@ -618,7 +621,7 @@ static lp_status fc_forward(int M, int K, int Nout, const void *x, lp_qfmt qx, c
         if (p.ksplit > 1) hipLaunchKernelGGL(fc_finish_kernel<1>, dim3(p.tiles * 8), dim3(kFcThreads), 0, hs, f);
     }
     const lp_status ls = launch_status();
-    if (ls != LP_OK || p.ksplit > 1 || !counting) return ls;
+    if (ls != LP_OK || p.ksplit > 1 || !counting || direct) return ls;
     return launch_sum_partials(a.zero_partial, p.grid, a.zero_count, a.sat_count, hs);
 }
 

@@ -28,6 +28,7 @@ struct ConvArgs {
     unsigned *zero_partial; // per workgroup (MFMA path): [grid] zero counts, then [grid] counts of clipped
                             // values; summed by a second kernel
     int partial_stride;     // = grid
+    int direct_counts;      // no partials: every workgroup adds its counts to zero_count / sat_count itself (small grids)
     int count_sat;          // sat_count is wanted: the epilogue also counts the values it clips
     int N, H, W, Cin, Cout, R, S, stride, pad;
     int Ho, Wo, Hp, FR;
@@ -80,6 +81,18 @@ __device__ __forceinline__ int64_t bias_term(const ConvArgs &a, int co)
     if (!a.bias) return 0;
     const int b = a.bias16 ? (int)((const int16_t *)a.bias)[co] : (int)((const int8_t *)a.bias)[co];
     return (int64_t)b * ((int64_t)1 << a.bias_shift);
+}
+
+// One workgroup's count (which: 0 zero codes, 1 clipped values) goes to its slot of the partials, or,
+// on small grids, straight to the caller's counter.
+__device__ __forceinline__ void publish_count(const ConvArgs &a, int which, unsigned total)
+{
+    if (a.zero_partial) {
+        a.zero_partial[which * a.partial_stride + blockIdx.x] = total;
+    } else if (a.direct_counts && total) {
+        unsigned long long *c = which ? a.sat_count : a.zero_count;
+        if (c) atomicAdd(c, (unsigned long long)total);
+    }
 }
 
 __device__ __forceinline__ v16i mfma_i8(v4i a, v4i b, v16i c)
