@@ -335,8 +335,8 @@ static lp_status make_plan_uncached(const lp_conv_desc *d, lp_qfmt qx, lp_qfmt q
             // workgroup slots per die: what registers and LDS allow
             const int total = p.tiles_m * p.tiles_n, nslabs = p.nchunks * p.taps;
             // (two-limb kernel: three waves per SIMD by registers; one-limb kernels: four)
-            // (window-row kernel: four)
-            const int by_regs = p.rows ? 4 : p.limbs == 2 ? 3 : 4;
+            // (window-row kernel: four, or three where it takes two column blocks)
+            const int by_regs = p.rows ? (d->Cout <= 32 ? 4 : 3) : p.limbs == 2 ? 3 : 4;
             const int wg_per_cu = (int)std::max<size_t>(1, std::min<size_t>(by_regs, (160 * 1024) / p.lds_bytes));
             const int slots = wg_per_cu * (kCUs / kXCDs);
             p.per_xcd = (total + kXCDs - 1) / kXCDs;
@@ -1232,8 +1232,8 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(const unsigned *__res
 // barrier.  The sum of a row's codes (offset correction) is the sum over its lanes' gathers.
 // NCB: 32-channel blocks per tile (1 for layers with at most 32 output channels); KS: K halves (1: K <= 32).
 template <int NCB, int KS>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void conv_flat_kernel(
-    const ConvArgs a)
+__global__ __launch_bounds__(256)
+    __attribute__((amdgpu_waves_per_eu(NCB * KS == 4 ? 3 : 4, NCB * KS == 4 ? 3 : 4))) void conv_flat_kernel(const ConvArgs a)
 {
     constexpr int THREADS = 256, BN = 64;
     __shared__ __align__(16) short raw[kFlatRawBytes / 2]; // the raw input patch, all channels (the planner keeps it within)
@@ -1415,7 +1415,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 // = 16 consecutive codes of a pixel) left by the staging.
 // NCB: 32-channel blocks a workgroup takes (1 for layers with at most 32 output channels).
 template <int NCB>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void conv_rows_kernel(const ConvArgs a)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCB == 1 ? 4 : 3, NCB == 1 ? 4 : 3))) void conv_rows_kernel(
+    const ConvArgs a)
 {
     constexpr int THREADS = 256, BN = 64, NSETS = 4;
     extern __shared__ __align__(16) unsigned char smem[];
