@@ -97,10 +97,13 @@ class ConvStack:
         dt = torch.int16 if self.n_act > 8 else torch.int8
         self.in_shape = (N, H, W, self.w_float[0].shape[3])
         self.x_codes = torch.empty(self.in_shape, dtype=dt, device="cuda")
-        self.zero_counts = torch.zeros(len(self.pool_after), dtype=torch.int64, device="cuda")
-        self.sat_counts = torch.zeros(len(self.pool_after), dtype=torch.int64, device="cuda")
-        self.input_sat = torch.zeros(1, dtype=torch.int64, device="cuda")
-        self.skipped = torch.zeros(len(self.pool_after), dtype=torch.int64, device="cuda")
+        # one buffer for every counter of a pass, so that a pass clears them with one fill
+        nl = len(self.pool_after)
+        self.counters = torch.zeros(3 * nl + 1, dtype=torch.int64, device="cuda")
+        self.zero_counts = self.counters[0:nl]
+        self.sat_counts = self.counters[nl:2 * nl]
+        self.skipped = self.counters[2 * nl:3 * nl]
+        self.input_sat = self.counters[3 * nl:3 * nl + 1]
         self.layers = []
         q_in = self.qx
         for i, pool in enumerate(self.pool_after):
@@ -144,12 +147,7 @@ class ConvStack:
         """One pass over the batch: input quantize + every conv (+fused LPAct/ReLU/zero count) +
         pools.  events (optional): list to which (label, start_event, end_event) are appended."""
         assert tuple(x_float.shape) == self.in_shape
-        self.zero_counts.zero_()
-        if self.zskip:
-            self.skipped.zero_()
-        if self.count_sat:
-            self.sat_counts.zero_()
-            self.input_sat.zero_()
+        self.counters.zero_()
 
         def timed(label, fn):
             if events is None:
