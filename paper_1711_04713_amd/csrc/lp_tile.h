@@ -242,6 +242,9 @@ __device__ __forceinline__ TileCounts tile_epilogue(const ConvArgs &a, v16i (&ac
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                 for (int gl = 0; gl < GL; ++gl) {
+                    // a group of eight channels that lies past Cout altogether has nothing to write
+                    // or count (uniform: a scalar branch)
+                    if (ntile * BN + col0w + nb * 32 + 8 * (g0 + gl) >= a.Cout) continue;
                     const int cl = col0w + nb * 32 + 8 * (g0 + gl) + 4 * kg; // channel within the tile
                     const int col0 = ntile * BN + cl;
                     const bool col_ok = col0 < a.Cout;
