@@ -103,6 +103,36 @@ def test_two_layers_with_structured_zeros(oracle, shape, pool):
     assert torch.equal(b["y"], c["y"]) and c["skipped"] == 0
 
 
+@pytest.mark.parametrize("C0,kernel", [(3, "flat"), (16, "rows"), (32, "rows")])
+def test_flags_from_the_flat_window_and_window_row_kernels(oracle, C0, kernel):
+    """A first layer with few input channels runs on another kernel than the layer it feeds; its flags
+    must describe its codes all the same, and the consumer must skip on them."""
+    N, H, W, C1, C2 = 24, 32, 32, 128, 64
+    rng = np.random.default_rng(C0)
+    x, w1, w2 = _sparse_pair(rng, N, C0, H, W, C1, C2)
+    a = _layer(x, w1, QX, QW, QY)
+    assert a["info"]["kernel"] == {"flat": lp.LP_KERNEL_FLAT, "rows": lp.LP_KERNEL_ROWS}[kernel]
+    y1, z1, s1 = oracle.act(oracle.conv(x, w1, threads=8), 27, *QY, True, oracle.ROUND_AWAY, with_sat=True)
+    assert np.array_equal(a["y_np"], y1) and (a["zeros"], a["sats"]) == (z1, s1)
+    flags = a["flags"].cpu().numpy()
+    assert np.array_equal(flags, _expected_flags(y1, a["info"])) and 0 < flags.sum() < flags.size
+    b = _layer(y1, w2, QY, QW, (16, 9, 7), x_map=lp.zero_map(a["flags"], a["info"], a["W"]))
+    y2, z2, s2 = oracle.act(oracle.conv(y1, w2, threads=8), QY[2] + QW[2], 16, 9, 7, True, oracle.ROUND_AWAY, with_sat=True)
+    assert b["info"]["kernel"] == lp.LP_KERNEL_PATCH
+    assert np.array_equal(b["y_np"], y2) and (b["zeros"], b["sats"]) == (z2, s2)
+    if b["info"]["split"] == 1:
+        assert b["skipped"] > 0
+    # a map handed to a layer that runs on the window-row kernel is accepted and changes nothing
+    if kernel == "rows":
+        w3 = rng.integers(-900, 900, (C0, C0, 3, 3)).astype(np.int32)
+        xs = x[:, :, :16, :16]
+        prev = _layer(rng.integers(0, 50, (N, 64, 16, 16)).astype(np.int32) * 0, rng.integers(-9, 9, (C0, 64, 3, 3)).astype(np.int32),
+                      QX, QW, QY)
+        c = _layer(xs, w3, QX, QW, QY, x_map=lp.zero_map(prev["flags"], prev["info"], prev["W"]))
+        y3, z3 = oracle.act(oracle.conv(xs, w3, threads=8), 27, *QY, True, oracle.ROUND_AWAY)
+        assert c["info"]["kernel"] == lp.LP_KERNEL_ROWS and np.array_equal(c["y_np"], y3) and c["zeros"] == z3 and c["skipped"] == 0
+
+
 def test_flags_from_split_tiles_and_all_zero_input(oracle):
     """A producer whose tail tiles are finished by the second kernel still writes every flag; an input
     that is blank everywhere (every chunk flagged zero) still gives the bias-only output."""
