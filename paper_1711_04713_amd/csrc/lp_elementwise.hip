@@ -204,7 +204,7 @@ __device__ __forceinline__ void count_in(unsigned *h, int bucket)
 static int range_grid(size_t groups)
 {
     size_t blocks = (groups + kThreads - 1) / kThreads;
-    return (int)std::min<size_t>(std::max<size_t>(blocks, 1), 256 * 3); // grid-stride beyond three blocks per CU
+    return (int)std::min<size_t>(std::max<size_t>(blocks, 1), 256 * 2); // grid-stride beyond two blocks per CU
 }
 
 __global__ __launch_bounds__(kThreads) void range_f32_kernel(const float *__restrict__ x, size_t count,
@@ -213,9 +213,24 @@ __global__ __launch_bounds__(kThreads) void range_f32_kernel(const float *__rest
     __shared__ unsigned h[kBuckets * kThreads];
     for (int b = 0; b < kBuckets; ++b) h[b * kThreads + threadIdx.x] = 0;
     // columns are private to a thread: no barrier needed before use
-    const size_t groups = count / 4;
-    for (size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x; g < groups;
-         g += (size_t)gridDim.x * kThreads) {
+    // four 16-byte requests per thread in flight: one per trip leaves the memory system idle most of
+    // the time (a trip's work is a handful of instructions)
+    const size_t groups = count / 4, stride = (size_t)gridDim.x * kThreads;
+    constexpr int U = 4;
+    size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    for (; g + (U - 1) * stride < groups; g += U * stride) {
+        v4f a[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) a[u] = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(x) + g + u * stride);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            count_in(h, bucket_f32(a[u].x));
+            count_in(h, bucket_f32(a[u].y));
+            count_in(h, bucket_f32(a[u].z));
+            count_in(h, bucket_f32(a[u].w));
+        }
+    }
+    for (; g < groups; g += stride) {
         const v4f a = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(x) + g);
         count_in(h, bucket_f32(a.x));
         count_in(h, bucket_f32(a.y));
@@ -235,15 +250,23 @@ __global__ __launch_bounds__(kThreads) void range_i64_kernel(const int64_t *__re
 {
     __shared__ unsigned h[kBuckets * kThreads];
     for (int b = 0; b < kBuckets; ++b) h[b * kThreads + threadIdx.x] = 0;
-    const size_t groups = count / 2;
-    for (size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x; g < groups;
-         g += (size_t)gridDim.x * kThreads) {
-        const v4i a = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(acc) + g);
+    const size_t groups = count / 2, stride = (size_t)gridDim.x * kThreads;
+    constexpr int U = 4; // requests in flight per thread (see range_f32_kernel)
+    auto take = [&](const v4i &a) __attribute__((always_inline)) {
         const int64_t a0 = (int64_t)(((uint64_t)(uint32_t)a.y << 32) | (uint32_t)a.x);
         const int64_t a1 = (int64_t)(((uint64_t)(uint32_t)a.w << 32) | (uint32_t)a.z);
         count_in(h, bucket_i64(a0, f_acc, relu));
         count_in(h, bucket_i64(a1, f_acc, relu));
+    };
+    size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    for (; g + (U - 1) * stride < groups; g += U * stride) {
+        v4i a[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) a[u] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(acc) + g + u * stride);
+#pragma unroll
+        for (int u = 0; u < U; ++u) take(a[u]);
     }
+    for (; g < groups; g += stride) take(__builtin_nontemporal_load(reinterpret_cast<const v4i *>(acc) + g));
     if (blockIdx.x == 0 && threadIdx.x == 0 && (count & 1)) count_in(h, bucket_i64(acc[count - 1], f_acc, relu));
     flush_hist(h, hist_out);
 }
