@@ -97,9 +97,9 @@ lp_status lp_range_acc(const int64_t *acc_dev, size_t count, int f_acc, int relu
  * code = clip(round(x * 2^f)) to the signed n-bit range (Sec. 2.5: values that
  * do not fit saturate).  NaN gives code 0.  codes_dev: int8 (n <= 8) or int16.
  * LP_ROUND_STOCHASTIC (Sec. 2.4): floor(x*2^f) + [u < frac], where u in [0,1)
- * is 2^-32 * the first word of Philox4x32-10 (Salmon et al., SC'11) with key
- * (seed lo, seed hi) and counter (i lo, i hi, 0, 0) for element index i; the
- * other modes ignore `seed`.
+ * is 2^-32 * a word of Philox4x32-10 (Salmon et al., SC'11) with key
+ * (seed lo, seed hi): element i draws word i % 4 of the block with counter
+ * (b lo, b hi, 0, 0), b = i / 4; the other modes ignore `seed`.
  * zero_count_dev / sat_count_dev (nullable): += number of zero codes / clipped values.
  */
 lp_status lp_quantize(const float *x_dev, void *codes_dev, size_t count, lp_qfmt q, lp_round r,
@@ -125,8 +125,8 @@ lp_status lp_act(const int64_t *acc_dev, size_t count, int f_acc, lp_qfmt qy, in
 /*
  * lp_act_stochastic -- lp_act with the stochastic rounding_scheme (Sec. 2.4):
  * with t = max(acc,0) / 2^(f_acc - qy.f) (ReLU only if relu != 0) the code is
- * clip(floor(t) + [u < t - floor(t)]), u as in lp_quantize: 2^-32 * the first
- * word of Philox4x32-10 with key (seed lo, seed hi) and counter (i lo, i hi, 0, 0)
+ * clip(floor(t) + [u < t - floor(t)]), u as in lp_quantize: 2^-32 * word i % 4
+ * of the Philox4x32-10 block with key (seed lo, seed hi) and counter (i / 4, 0)
  * for element index i.  The comparison is exact (integers).  f_acc <= qy.f
  * needs no rounding and gives lp_act's result.  Other arguments, limits and
  * errors as lp_act.  lp_conv_fwd / lp_fc_fwd do not fuse this scheme: pass

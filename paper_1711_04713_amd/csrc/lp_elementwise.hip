@@ -20,8 +20,12 @@ static int grid_for(size_t groups)
 
 // ------------------------------------------------------------------ Philox4x32-10
 // Counter-based generator of Salmon, Moraes, Dror, Shaw (SC'11): ten rounds of two
-// 32x32->64 multiplies and xors, key bumped by the Weyl constants each round.
-__device__ __forceinline__ uint32_t philox4x32_10_word0(uint64_t ctr, uint64_t key)
+// 32x32->64 multiplies and xors, key bumped by the Weyl constants each round.  One block gives four
+// words; element i of a tensor draws word i % 4 of the block with counter (i / 4, 0).
+struct PhiloxBlock {
+    uint32_t w[4];
+};
+__device__ __forceinline__ PhiloxBlock philox4x32_10(uint64_t ctr, uint64_t key)
 {
     uint32_t c0 = (uint32_t)ctr, c1 = (uint32_t)(ctr >> 32), c2 = 0, c3 = 0;
     uint32_t k0 = (uint32_t)key, k1 = (uint32_t)(key >> 32);
@@ -37,14 +41,20 @@ __device__ __forceinline__ uint32_t philox4x32_10_word0(uint64_t ctr, uint64_t k
         k0 += 0x9E3779B9u;
         k1 += 0xBB67AE85u;
     }
-    return c0;
+    return PhiloxBlock{{c0, c1, c2, c3}};
+}
+// the draw of element i by itself (ragged tails)
+__device__ __forceinline__ uint32_t philox_draw(uint64_t i, uint64_t key)
+{
+    const PhiloxBlock b = philox4x32_10(i >> 2, key);
+    const unsigned k = (unsigned)i & 3u;
+    return k == 0 ? b.w[0] : k == 1 ? b.w[1] : k == 2 ? b.w[2] : b.w[3];
 }
 
 // ------------------------------------------------------------------------ quantize
 
 template <int MODE>
-__device__ __forceinline__ int quantize_one(float x, float scale, float lo, float hi, uint64_t index,
-                                            uint64_t seed, bool &sat)
+__device__ __forceinline__ int quantize_one(float x, float scale, float lo, float hi, uint32_t w, bool &sat)
 {
     const float t = x * scale; // exact: scale is a power of two
     float r;
@@ -57,8 +67,7 @@ __device__ __forceinline__ int quantize_one(float x, float scale, float lo, floa
         // below zero t - floor(t) needs more than float holds (-0.25 + 2^-26 -> 0.75 + 2^-26)
         const float fl = floorf(t);
         const double frac = (double)t - (double)fl; // exact
-        const uint32_t w = philox4x32_10_word0(index, seed);
-        r = ((double)w < frac * 4294967296.0) ? fl + 1.0f : fl;
+        r = ((double)w < frac * 4294967296.0) ? fl + 1.0f : fl; // w: the element's draw
     }
     if (t != t) r = 0.0f;
     sat = (r < lo) || (r > hi);
@@ -86,9 +95,15 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restr
             const v4f a = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(x) + 2 * g);
             const v4f b = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(x) + 2 * g + 1);
             const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+            // elements 8g .. 8g+7 draw the words of blocks 2g and 2g+1
+            PhiloxBlock d0 = {}, d1 = {};
+            if constexpr (MODE == LP_ROUND_STOCHASTIC) {
+                d0 = philox4x32_10(2 * g, seed);
+                d1 = philox4x32_10(2 * g + 1, seed);
+            }
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                c[j] = quantize_one<MODE>(v[j], scale, lo, hi, 8 * g + j, seed, s[j]);
+                c[j] = quantize_one<MODE>(v[j], scale, lo, hi, j < 4 ? d0.w[j & 3] : d1.w[j & 3], s[j]);
                 z[j] = (c[j] == 0);
             }
             if (sizeof(OutT) == 2) {
@@ -118,7 +133,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restr
         const size_t i = groups * 8 + threadIdx.x;
         bool z = false, s = false;
         if (threadIdx.x < 8 && i < count) {
-            const int c = quantize_one<MODE>(x[i], scale, lo, hi, i, seed, s);
+            const int c = quantize_one<MODE>(x[i], scale, lo, hi, MODE == LP_ROUND_STOCHASTIC ? philox_draw(i, seed) : 0u, s);
             y[i] = (OutT)c;
             z = (c == 0);
         }
@@ -312,17 +327,16 @@ static lp_status finish_range(unsigned long long *hist_dev, size_t count, int n,
 
 // ----------------------------------------------------------------------------- act
 
-// Sec. 2.4 on an accumulator: floor(v / 2^s) + [u < frac], u = 2^-32 * the first Philox word for
-// the element's index; the comparison u * 2^s < rem is done in integers (rem < 2^s <= 2^62).
-__device__ __forceinline__ int act_one_stochastic(int64_t v, const ActParams &p, uint64_t index, uint64_t seed,
-                                                  bool &sat)
+// Sec. 2.4 on an accumulator: floor(v / 2^s) + [u < frac], u = 2^-32 * the element's Philox draw
+// w32; the comparison u * 2^s < rem is done in integers (rem < 2^s <= 2^62).
+__device__ __forceinline__ int act_one_stochastic(int64_t v, const ActParams &p, uint32_t w32, bool &sat)
 {
     if (p.relu && v < 0) v = 0;
     int64_t r;
     if (p.s > 0) {
         int64_t q = v >> p.s; // floor
         const uint64_t rem = (uint64_t)v & (((uint64_t)1 << p.s) - 1);
-        const uint64_t w = philox4x32_10_word0(index, seed);
+        const uint64_t w = w32;
         const bool up = p.s >= 32 ? (w << (p.s - 32)) < rem : w < (rem << (32 - p.s));
         r = q + (up ? 1 : 0);
     } else {
@@ -347,10 +361,12 @@ __global__ __launch_bounds__(kThreads) void act_kernel(const int64_t *__restrict
     // counts are kept when either counter is wanted; a wave's totals are scalars
     const bool counting = zero_count || sat_count;
     unsigned sats = 0;
-    auto one = [&](int64_t v, size_t index, bool &sat) {
-        if constexpr (STOCH) return act_one_stochastic(v, p, index, seed, sat);
+    // w: the element's draw (stochastic scheme only)
+    auto one = [&](int64_t v, uint32_t w, bool &sat) {
+        if constexpr (STOCH) return act_one_stochastic(v, p, w, sat);
         else return act_one(v, p, sat);
     };
+    auto draw = [&](size_t index) { return STOCH ? philox_draw(index, seed) : 0u; };
     // A block takes 8 * kThreads consecutive accumulators per trip, as four rows of kThreads
     // 16-byte pairs: a lane's loads are 16 bytes apart from its neighbours' (1 KB contiguous per
     // wave and instruction), and it stores the two codes of each pair (4 or 2 bytes, again
@@ -370,7 +386,14 @@ __global__ __launch_bounds__(kThreads) void act_kernel(const int64_t *__restrict
             const int64_t a1 = (int64_t)(((uint64_t)(uint32_t)a[j].w << 32) | (uint32_t)a[j].z);
             const size_t pair = pair0 + j * kThreads;
             bool s0, s1;
-            const int c0 = one(a0, 2 * pair, s0), c1 = one(a1, 2 * pair + 1, s1);
+            // elements 2 * pair and 2 * pair + 1 draw two neighbouring words of block pair / 2
+            uint32_t w0 = 0, w1 = 0;
+            if constexpr (STOCH) {
+                const PhiloxBlock d = philox4x32_10(pair >> 1, seed);
+                w0 = (pair & 1) ? d.w[2] : d.w[0];
+                w1 = (pair & 1) ? d.w[3] : d.w[1];
+            }
+            const int c0 = one(a0, w0, s0), c1 = one(a1, w1, s1);
             if (sizeof(OutT) == 2)
                 reinterpret_cast<int *>(y)[pair] = (c0 & 0xffff) | (c1 << 16);
             else
@@ -389,7 +412,7 @@ __global__ __launch_bounds__(kThreads) void act_kernel(const int64_t *__restrict
         if (g < groups) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const int c = one(acc[8 * g + j], 8 * g + j, st[j]);
+                const int c = one(acc[8 * g + j], draw(8 * g + j), st[j]);
                 y[8 * g + j] = (OutT)c;
                 z[j] = (c == 0);
             }
@@ -406,7 +429,7 @@ __global__ __launch_bounds__(kThreads) void act_kernel(const int64_t *__restrict
         const size_t i = groups * 8 + threadIdx.x;
         bool z = false, st = false;
         if (threadIdx.x < 8 && i < count) {
-            const int c = one(acc[i], i, st);
+            const int c = one(acc[i], draw(i), st);
             y[i] = (OutT)c;
             z = (c == 0);
         }

@@ -64,27 +64,43 @@ def test_quantize_rejects_bad_arguments():
 
 # ------------------------------------------------------------------ stochastic rounding
 
-def _philox4x32_10_word0(index, seed):
-    """First output word of Philox4x32-10 (Salmon et al., SC'11) for counter (index, 0, 0) and
-    key = seed, written from the published round function, vectorised over numpy uint64."""
-    idx = np.asarray(index, dtype=np.uint64)
+def _philox4x32_10(counter, key):
+    """The four output words of Philox4x32-10 (Salmon et al., SC'11), written from the published
+    round function, vectorised over numpy uint64.  counter: four words (arrays or ints), key: two."""
     mask = np.uint64(0xFFFFFFFF)
-    c0, c1 = idx & mask, idx >> np.uint64(32)
-    c2 = np.zeros_like(c0)
-    c3 = np.zeros_like(c0)
-    k0, k1 = np.uint64(seed & 0xFFFFFFFF), np.uint64(seed >> 32)
+    c0, c1, c2, c3 = (np.atleast_1d(np.asarray(c, dtype=np.uint64)) for c in counter)
+    c0, c1, c2, c3 = np.broadcast_arrays(c0, c1, c2, c3)
+    k0, k1 = np.uint64(key[0]), np.uint64(key[1])
     for _ in range(10):
         p0 = np.uint64(0xD2511F53) * c0
         p1 = np.uint64(0xCD9E8D57) * c2
         c0, c1, c2, c3 = (p1 >> np.uint64(32)) ^ c1 ^ k0, p1 & mask, (p0 >> np.uint64(32)) ^ c3 ^ k1, p0 & mask
         k0 = (k0 + np.uint64(0x9E3779B9)) & mask
         k1 = (k1 + np.uint64(0xBB67AE85)) & mask
-    return c0
+    return np.stack([c0, c1, c2, c3], axis=-1)
 
 
-def test_philox_known_answer():
-    """Known-answer vector of the generator's reference distribution: all-zero counter and key."""
-    assert int(_philox4x32_10_word0(np.array([0]), 0)[0]) == 0x6627E8D5
+def _draws(count, seed):
+    """The library's draws for elements 0 .. count-1: element i takes word i % 4 of the block with
+    counter (i / 4 lo, i / 4 hi, 0, 0) and key (seed lo, seed hi)."""
+    blocks = np.arange((count + 3) // 4, dtype=np.uint64)
+    words = _philox4x32_10((blocks & np.uint64(0xFFFFFFFF), blocks >> np.uint64(32), 0, 0),
+                           (seed & 0xFFFFFFFF, seed >> 32))
+    return words.reshape(-1)[:count]
+
+
+def test_philox_known_answers():
+    """The generator's published known-answer vectors: zero counter and key, all ones, and the
+    digits of pi."""
+    kat = [((0, 0, 0, 0), (0, 0), (0x6627E8D5, 0xE169C58D, 0xBC57AC4C, 0x9B00DBD8)),
+           ((0xFFFFFFFF,) * 4, (0xFFFFFFFF,) * 2, (0x408F276D, 0x41C83B0E, 0xA20BC7C6, 0x6D5451FD)),
+           ((0x243F6A88, 0x85A308D3, 0x13198A2E, 0x03707344), (0xA4093822, 0x299F31D0),
+            (0xD16CFE09, 0x94FDCCEB, 0x5001E420, 0x24126EA1))]
+    for counter, key, want in kat:
+        assert tuple(int(w) for w in _philox4x32_10(counter, key)[0]) == want
+    # the element-to-word map: elements 0..3 are the four words of block 0
+    assert tuple(int(w) for w in _draws(4, 0)) == kat[0][2]
+    assert int(_draws(6, 0)[5]) == int(_philox4x32_10((1, 0, 0, 0), (0, 0))[0][1])
 
 
 @pytest.mark.parametrize("q", [(16, 8, 8), (8, 2, 6)])
@@ -93,7 +109,7 @@ def test_quantize_stochastic_matches_oracle(oracle, q):
     count = 70001
     x = _mixed_values(count, 77, 2.0 ** (m - 1))
     seed = 0x1234567ABCDEF01
-    u = _philox4x32_10_word0(np.arange(count), seed).astype(np.float64) * 2.0 ** -32
+    u = _draws(count, seed).astype(np.float64) * 2.0 ** -32
     want, wz, ws = oracle.quantize_stochastic(x, u, n, m, f)
     got, gz, gs = quantize(x, q, lp.LP_ROUND_STOCHASTIC, seed=seed)
     assert np.array_equal(got, want) and (gz, gs) == (wz, ws)
@@ -104,15 +120,15 @@ def test_quantize_stochastic_matches_oracle(oracle, q):
 def test_quantize_stochastic_fraction_needs_more_than_float32(oracle):
     """t = x * 2^f = -0.25 + 2^-26 has the fractional part 0.75 + 2^-26, which float32 cannot
     hold; with a draw in [0.75, 0.75 + 2^-26) the exact decision is "up".  Seed and index were
-    found by searching the test-side generator for a first word in that window."""
-    seed, index, f = 60316096, 5, 8
-    w = int(_philox4x32_10_word0(np.array([index]), seed)[0])
+    found by searching the test-side generator for a draw in that window."""
+    seed, index, f = 15080025, 7, 8
+    w = int(_draws(64, seed)[index])
     assert 3 << 30 <= w < (3 << 30) + 64                    # the draw sits in the window
     t = np.float32(-0.25) + np.float32(2.0 ** -26)
     assert float(t) == -0.25 + 2.0 ** -26                   # representable
     x = np.zeros(64, np.float32)
     x[index] = t * np.float32(2.0 ** -f)
-    u = _philox4x32_10_word0(np.arange(64), seed).astype(np.float64) * 2.0 ** -32
+    u = _draws(64, seed).astype(np.float64) * 2.0 ** -32
     want, _, _ = oracle.quantize_stochastic(x, u, 16, 8, f)
     assert want[index] == 0                                 # floor is -1, rounded up
     got, _, _ = quantize(x, (16, 8, f), lp.LP_ROUND_STOCHASTIC, seed=seed)
@@ -221,7 +237,7 @@ def test_act_stochastic_matches_oracle(oracle, count, f_acc, qy, relu):
     if count > 8 and 0 < s <= 60:
         acc[:4] = [0, (1 << s) - 1, 1 << s, -1]           # remainders 0, 2^s - 1, 0, 2^s - 1
     seed = 0xC0FFEE1234567
-    u = _philox4x32_10_word0(np.arange(count), seed).astype(np.float64) * 2.0 ** -32
+    u = _draws(count, seed).astype(np.float64) * 2.0 ** -32
     want, wz, wsat = oracle.act_stochastic(acc, u, f_acc, n, m, fo, relu, with_sat=True)
     y = torch.empty(count, dtype=code_torch_dtype(n), device="cuda")
     z, sat = counter(), counter()
@@ -254,7 +270,7 @@ def test_act_stochastic_after_conv_accumulators(oracle):
     assert np.array_equal(got["acc"], want_acc)
     acc_nhwc = np.ascontiguousarray(want_acc.transpose(0, 2, 3, 1))
     seed = 77
-    u = _philox4x32_10_word0(np.arange(acc_nhwc.size), seed).astype(np.float64) * 2.0 ** -32
+    u = _draws(acc_nhwc.size, seed).astype(np.float64) * 2.0 ** -32
     want, wz = oracle.act_stochastic(acc_nhwc.reshape(-1), u, 27, *qy, True)
     acc_dev = to_dev(np.ascontiguousarray(got["acc"].transpose(0, 2, 3, 1)).reshape(-1))
     y = torch.empty(acc_nhwc.size, dtype=torch.int16, device="cuda")
