@@ -106,7 +106,7 @@ def measure_extras(lp, torch, lp_inputs, which=EXTRA_SECTIONS, iters=10):
         out["lp_act"] = {"elements": n, "ms": round(ms, 4), "GBps": round(10 * n / ms / 1e6, 1)}
         ms = timed(lambda: lp.lp_act_stochastic(acc.reshape(-1), 27, (16, 6, 10), True, 1, codes))
         out["lp_act_stochastic"] = {"elements": n, "ms": round(ms, 4), "GBps": round(10 * n / ms / 1e6, 1),
-                                    "note": "one Philox4x32-10 block per pair of elements"}
+                                    "note": "two Philox4x32-10 blocks per eight elements"}
         t0 = time.perf_counter()
         for _ in range(iters):
             lp.lp_range_acc(acc.reshape(-1), 27, True, 16, 0.0, rws)

@@ -380,18 +380,31 @@ __global__ __launch_bounds__(kThreads) void act_kernel(const int64_t *__restrict
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             a[j] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(acc) + pair0 + j * kThreads);
+        // Elements 2 * pair and 2 * pair + 1 draw two neighbouring words of block pair / 2, which a
+        // lane shares with its neighbour (lanes 2k and 2k + 1 hold pairs 2m and 2m + 1 in every
+        // row).  The even lane computes the blocks of rows 0 and 2, the odd lane those of rows 1
+        // and 3, and each hands the other its half of the words: two blocks per lane, not four.
+        const unsigned par = threadIdx.x & 1u; // = pair & 1 in every row (kThreads is even)
+        PhiloxBlock blk[2] = {};
+        if constexpr (STOCH) {
+            blk[0] = philox4x32_10((pair0 + par * kThreads) >> 1, seed);
+            blk[1] = philox4x32_10((pair0 + (2 + par) * kThreads) >> 1, seed);
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int64_t a0 = (int64_t)(((uint64_t)(uint32_t)a[j].y << 32) | (uint32_t)a[j].x);
             const int64_t a1 = (int64_t)(((uint64_t)(uint32_t)a[j].w << 32) | (uint32_t)a[j].z);
             const size_t pair = pair0 + j * kThreads;
             bool s0, s1;
-            // elements 2 * pair and 2 * pair + 1 draw two neighbouring words of block pair / 2
             uint32_t w0 = 0, w1 = 0;
             if constexpr (STOCH) {
-                const PhiloxBlock d = philox4x32_10(pair >> 1, seed);
-                w0 = (pair & 1) ? d.w[2] : d.w[0];
-                w1 = (pair & 1) ? d.w[3] : d.w[1];
+                const unsigned pj = j & 1;         // parity of the lanes that hold this row's block
+                const PhiloxBlock &d = blk[j >> 1];
+                // what the other lane needs: the odd lane words 2 and 3, the even lane words 0 and 1
+                const uint32_t x0 = (uint32_t)__builtin_amdgcn_mov_dpp((int)(pj == 0 ? d.w[2] : d.w[0]), 0xB1, 0xF, 0xF, true);
+                const uint32_t x1 = (uint32_t)__builtin_amdgcn_mov_dpp((int)(pj == 0 ? d.w[3] : d.w[1]), 0xB1, 0xF, 0xF, true);
+                w0 = par == pj ? (pj == 0 ? d.w[0] : d.w[2]) : x0;
+                w1 = par == pj ? (pj == 0 ? d.w[1] : d.w[3]) : x1;
             }
             const int c0 = one(a0, w0, s0), c1 = one(a1, w1, s1);
             if (sizeof(OutT) == 2)

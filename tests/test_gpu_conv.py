@@ -212,6 +212,17 @@ def test_conv_window_row_kernel(oracle, N, Cin, H, W, Cout, R, S, pad):
     assert np.array_equal(got["y"], y) and (got["zeros"], got["sats"]) == (z, sat)
 
 
+def test_conv_window_rows_too_large_for_lds_take_the_patch_kernel(oracle):
+    """A 13x13 window over 48 channels: the dense patch of the window-row kernel would not leave
+    room for three workgroups per CU; the planner keeps the patch kernel, same results."""
+    N, Cin, H, W, Cout, R, S, pad = 1, 48, 40, 6, 32, 13, 13, 6
+    info = lp.lp_conv_plan_info(lp.ConvDesc(N, H, W, Cin, Cout, R, S, 1, pad), QX, QW)
+    assert info["kernel"] == lp.LP_KERNEL_PATCH
+    rng = np.random.default_rng(99)
+    x, w = _codes(rng, (N, Cin, H, W), zero_frac=0.3), _codes(rng, (Cout, Cin, R, S))
+    _check(oracle, x, w, QX, QW, (16, 14, 2), pad=pad, expect_path=1)
+
+
 @pytest.mark.parametrize("fo", [15, 14, 11, 10, 3, 0])
 def test_conv_requantization_shift_sweep(oracle, fo):
     """Output formats that put the right shift f_acc - fo at 12, 13, 16, 17, 24 and 27 bits, with
