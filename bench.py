@@ -254,7 +254,7 @@ def main():
                     help="also run a plain 1 GiB device-to-device copy (calibrates FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards by batch, see DESIGN.md",
+        print("bench.py: the library runs on exactly one GPU (--gpus 1); more GPUs would each take a share of the batch",
               file=sys.stderr)
         sys.exit(2)
 
