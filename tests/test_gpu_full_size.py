@@ -75,7 +75,7 @@ def test_config2_conv1_2_layer_full_size(oracle):
     assert 0.3 < zeros / y.numel() < 0.8
 
 
-def _check_layer_over_batch(oracle, x_in, w_codes, G, st, i, samples, rng):
+def _check_layer_over_batch(oracle, x_in, w_codes, G, st, i, samples, rng, pad=1):
     """One layer of a prepared ConvStack against the oracle on outputs drawn from the WHOLE batch:
     the layer's own input codes on the GPU (x_in, NHWC tensor) are handed to the oracle, which
     recomputes the sampled outputs one by one.  Samples are forced into every die's split tiles
@@ -83,6 +83,7 @@ def _check_layer_over_batch(oracle, x_in, w_codes, G, st, i, samples, rng):
     fused are checked on their pooled output: the maximum of the oracle's four codes."""
     N, H, W, _ = x_in.shape
     Cout = w_codes.shape[0]
+    H, W = H + 2 * pad - w_codes.shape[2] + 1, W + 2 * pad - w_codes.shape[3] + 1     # output size
     info = G["info"]
     pos, dies = split_tile_positions(info, N, H, W, Cout, 40, rng)
     if info["split"] > 1:
@@ -96,7 +97,7 @@ def _check_layer_over_batch(oracle, x_in, w_codes, G, st, i, samples, rng):
 
     def oracle_codes(n, yo, xo, co):
         flat = ((n * Cout + co) * H + yo) * W + xo
-        acc = oracle.conv_sampled(x_np, w_codes, flat)
+        acc = oracle.conv_sampled(x_np, w_codes, flat, pad=pad)
         return oracle.act(acc, qx.f + qw.f, qy.n, qy.m, qy.f, True, oracle.ROUND_AWAY)[0]
 
     n, yo, xo, co = pos.T
@@ -159,6 +160,41 @@ def test_config3_vgg16_stack_batch32(oracle):
             assert torch.equal(out, final)            # the whole batch, not only image 0
         del st
     assert np.array_equal(counts[False], counts[True])
+
+
+def test_giga1net_conv_stack_batch32(oracle):
+    """The eleven conv layers of Table 1 in the launch configuration bench.py times (batch 32, pools
+    fused where the tiling allows): the flat-window kernel (layer 1), the window-row kernel (layers
+    2-4) and the patch kernel on small grids.  Image 0 in full against the oracle chain, the rest
+    of the batch on sampled outputs recomputed from each layer's own input codes."""
+    B = 32
+    spec = lp_inputs.GIGA1NET_CONV
+    x = lp_inputs.config3_input(seed=5, batch=B)
+    ws = lp_inputs.giga1net_conv_weights(seed=5)
+    pools = [p for (*_, p) in spec]
+    pads = [pad for (*_, pad, _) in spec]
+    cal = ovgg.conv_stack(x[:1], ws, pools, n=16, threads=16, pads=pads)
+    xd = to_dev(np.ascontiguousarray(x.transpose(0, 2, 3, 1)))
+    st = ConvStack([to_dev(np.ascontiguousarray(w.transpose(0, 2, 3, 1))) for w in ws], pools, pad=pads)
+    st.calibrate(xd[:1])
+    st.prepare(B, 224, 224)
+    out = st.forward(xd)
+    torch.cuda.synchronize()
+    kernels = [G["info"]["kernel"] for G in st.layers]
+    assert kernels[0] == lp.LP_KERNEL_FLAT and kernels[1:4] == [lp.LP_KERNEL_ROWS] * 3
+    assert all(k == lp.LP_KERNEL_PATCH for k in kernels[4:])
+    rng = np.random.default_rng(7)
+    cur = st.x_codes
+    for i, (L, G) in enumerate(zip(cal["layers"], st.layers)):
+        assert (st.qw[i].m, st.qy[i].m) == (L["mw"], L["mo"]), "layer %d formats" % i
+        _check_layer_over_batch(oracle, cur, L["w_codes"], G, st, i, 3000, rng, pad=pads[i])
+        cur = G["pooled"] if G["pooled"] is not None else G["y"]
+        if G["y"] is not None:
+            assert np.array_equal(G["y"][:1].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2), L["codes"]), "layer %d" % i
+            assert int(st.zero_counts[i].item()) == int((G["y"] == 0).sum().item()), "layer %d zero count" % i
+        if G["pooled"] is not None:
+            assert np.array_equal(G["pooled"][:1].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2), L["pooled"]), "layer %d" % i
+    assert np.array_equal(out[:1].cpu().numpy().astype(np.int32).transpose(0, 3, 1, 2), cal["final"])
 
 
 @pytest.mark.parametrize("index", [0, 1, 3, 4, 6, 8])
